@@ -1,0 +1,373 @@
+"""CPU oracle for the ODB-dLLM model step.  TEST INFRASTRUCTURE ONLY.
+
+This file is the slow, plain definition of what the two library calls compute.
+It is imported only by tests, by the smoke check and by the benchmark's
+cpu_baseline leg; the product path never calls it and shares no code with it.
+
+What it follows (ODB-dLLM, arXiv 2511.21759):
+  * Sec. 2.1 (block-wise generation with a dual cache): K/V of every token
+    outside the current block are cached by a full-sequence forward and reused
+    while the block is decoded; the forward is bidirectional (no causal mask).
+  * Sec. 4.1 (adaptive length prediction): the refresh computes every response
+    position and yields a decoding attempt (confidence, token) for all of them.
+  * Sec. 3, Observation 3: masked tokens of the block are decoded in parallel
+    and accepted when their confidence exceeds a threshold.
+  * Sec. 4.2 (jump-share speculative decoding): speculative copies of the block
+    (drafts) see the cached context and themselves, never each other, and keep
+    the position ids of the block they shadow (Fig. 8 caption).
+
+Arithmetic: float64 throughout, on weights whose values are exactly
+representable in bfloat16 (they are stored as bf16 bit patterns).  The model
+step is exact mathematics, so the oracle is the definition written out with
+numpy matmul/einsum as the only library steps; no blocking, fusion or caching
+tricks.  Architecture (pre-norm residual blocks, RMSNorm, rotate-half RoPE,
+SwiGLU, untied LM head, no biases) is not given by the paper, which only names
+the LLaDA models (Sec. 5.1); the choices are recorded as readings in the
+design notes of this repository.
+
+Parity against numbers printed in the paper: unpinned (the paper prints no
+intermediate value of the forward).  Every function is instead pinned by
+closed forms, invariants, brute force and library routines in tests/.
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+
+# --------------------------------------------------------------------------- config
+
+#: tensor ids of the counter-based weight generator (shared *by definition*
+#: with the library, which implements the same generator separately)
+T_EMBED, T_WQ, T_WK, T_WV, T_WO, T_WG, T_WU, T_WD, T_LM, T_G1, T_G2, T_GF = range(12)
+
+TENSOR_NAMES = ("embed", "wq", "wk", "wv", "wo", "wg", "wu", "wd", "lm",
+                "g1", "g2", "gf")
+
+
+@dataclasses.dataclass(frozen=True)
+class Config:
+    n_layers: int
+    d_model: int
+    n_heads: int
+    head_dim: int
+    d_ff: int
+    vocab: int
+    rope_base: float = 10000.0
+    rms_eps: float = 1e-5
+    mask_id: int = -1          # -1 -> vocab - 1
+
+    def __post_init__(self):
+        if self.mask_id < 0:
+            object.__setattr__(self, "mask_id", self.vocab - 1)
+        assert self.n_heads * self.head_dim == self.d_model
+        assert self.head_dim % 2 == 0
+
+    def shape(self, tid: int) -> Tuple[int, ...]:
+        d, f, v = self.d_model, self.d_ff, self.vocab
+        return {T_EMBED: (v, d), T_WQ: (d, d), T_WK: (d, d), T_WV: (d, d),
+                T_WO: (d, d), T_WG: (f, d), T_WU: (f, d), T_WD: (d, f),
+                T_LM: (v, d), T_G1: (d,), T_G2: (d,), T_GF: (d,)}[tid]
+
+
+# --------------------------------------------------------------------------- weight generator
+
+_GAMMA = np.uint64(0x9E3779B97F4A7C15)
+_M1 = np.uint64(0xBF58476D1CE4E5B9)
+_M2 = np.uint64(0x94D049BB133111EB)
+_MASK64 = (1 << 64) - 1
+
+
+def _finalise(z: np.ndarray) -> np.ndarray:
+    """SplitMix64 output function (Steele, Lea & Flood 2014) on uint64 arrays."""
+    z = (z ^ (z >> np.uint64(30))) * _M1
+    z = (z ^ (z >> np.uint64(27))) * _M2
+    return z ^ (z >> np.uint64(31))
+
+
+def splitmix64_stream(state0: int, start: int, n: int) -> np.ndarray:
+    """Outputs number start .. start+n-1 of SplitMix64 seeded with state0.
+
+    Output i is finalise(state0 + (i+1)*GAMMA mod 2^64): the generator is
+    counter based, so any slice can be produced without the ones before it.
+    """
+    with np.errstate(over="ignore"):
+        idx = np.arange(start + 1, start + n + 1, dtype=np.uint64)
+        return _finalise(np.uint64(state0 & _MASK64) + idx * _GAMMA)
+
+
+def stream_key(seed: int, tensor_id: int, layer: int) -> int:
+    """State of the SplitMix64 stream that generates one tensor.
+
+    key = finalise(finalise(seed + GAMMA) + ((tensor_id << 32) | layer) + GAMMA)
+    i.e. the first SplitMix64 output for `seed`, offset by the tensor's tag,
+    pushed through one more SplitMix64 step.
+    """
+    a = int(splitmix64_stream(seed, 0, 1)[0])
+    tag = ((tensor_id & 0xFFFFFFFF) << 32) | (layer & 0xFFFFFFFF)
+    return int(splitmix64_stream((a + tag) & _MASK64, 0, 1)[0])
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 to bfloat16, nearest-even, returning the 16-bit patterns.
+
+    bfloat16 is the upper half of an IEEE binary32; rounding adds 0x7FFF plus
+    the lowest kept bit and truncates.  NaN is not produced by the generator
+    and is not handled here.
+    """
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    return ((u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f64(b: np.ndarray) -> np.ndarray:
+    u = b.astype(np.uint32) << np.uint32(16)
+    return u.view(np.float32).astype(np.float64)
+
+
+def normal_bf16_bits(seed: int, tensor_id: int, layer: int, start: int, n: int,
+                     std: float) -> np.ndarray:
+    """Elements start..start+n-1 (row-major flat index) of one weight tensor.
+
+    z_i   = SplitMix64 output i of the tensor's stream
+    u1    = (high 32 bits of z_i + 0.5) / 2^32,  u2 = (low 32 bits + 0.5) / 2^32
+    x_i   = sqrt(-2 ln u1) * cos(2 pi u2)              (Box-Muller, float64)
+    w_i   = bf16_rne(float32(std * x_i))
+    """
+    z = splitmix64_stream(stream_key(seed, tensor_id, layer), start, n)
+    two32 = 1.0 / 4294967296.0
+    u1 = ((z >> np.uint64(32)).astype(np.float64) + 0.5) * two32
+    u2 = ((z & np.uint64(0xFFFFFFFF)).astype(np.float64) + 0.5) * two32
+    x = np.sqrt(-2.0 * np.log(u1)) * np.cos((2.0 * math.pi) * u2)
+    return f32_to_bf16_bits((std * x).astype(np.float32))
+
+
+class Weights:
+    """Model weights as bf16 bit patterns, generated on demand and cached.
+
+    `overrides[(tensor_id, layer)]` replaces a generated tensor (tests plant
+    weights this way).  Gains (g1, g2, gf) default to 1.0.
+    """
+
+    def __init__(self, cfg: Config, seed: int, std: float = 0.02,
+                 keep: bool = True):
+        self.cfg, self.seed, self.std, self.keep = cfg, seed, std, keep
+        self._bits: Dict[Tuple[int, int], np.ndarray] = {}
+        self.overrides: Dict[Tuple[int, int], np.ndarray] = {}
+
+    def set_bits(self, tensor_id: int, layer: int, bits: np.ndarray) -> None:
+        shape = self.cfg.shape(tensor_id)
+        self.overrides[(tensor_id, layer)] = np.asarray(bits, np.uint16).reshape(shape)
+
+    def set_values(self, tensor_id: int, layer: int, values: np.ndarray) -> None:
+        self.set_bits(tensor_id, layer,
+                      f32_to_bf16_bits(np.asarray(values, np.float32)))
+
+    def bits(self, tensor_id: int, layer: int = 0) -> np.ndarray:
+        key = (tensor_id, layer)
+        if key in self.overrides:
+            return self.overrides[key]
+        if key in self._bits:
+            return self._bits[key]
+        shape = self.cfg.shape(tensor_id)
+        n = int(np.prod(shape))
+        if tensor_id in (T_G1, T_G2, T_GF):
+            out = np.full(shape, 0x3F80, np.uint16)          # 1.0
+        else:
+            out = np.empty(n, np.uint16)
+            step = 1 << 22
+            for s in range(0, n, step):
+                m = min(step, n - s)
+                out[s:s + m] = normal_bf16_bits(self.seed, tensor_id, layer, s, m,
+                                                self.std)
+            out = out.reshape(shape)
+        if self.keep:
+            self._bits[key] = out
+        return out
+
+    def f64(self, tensor_id: int, layer: int = 0) -> np.ndarray:
+        return bf16_bits_to_f64(self.bits(tensor_id, layer))
+
+    def embed_rows(self, tokens: np.ndarray) -> np.ndarray:
+        return bf16_bits_to_f64(self.bits(T_EMBED, 0)[np.asarray(tokens, np.int64)])
+
+
+# --------------------------------------------------------------------------- operators
+
+def rmsnorm(x: np.ndarray, g: np.ndarray, eps: float) -> np.ndarray:
+    """y = x / sqrt(mean(x^2) + eps) * g over the last axis."""
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * g
+
+
+def rope(x: np.ndarray, pos: np.ndarray, base: float) -> np.ndarray:
+    """Rotary embedding, rotate-half pairing, on x[rows, H, dh] at pos[rows].
+
+    Pair j couples channels j and j + dh/2 and turns by pos * base^(-2j/dh):
+      y[j]        = x[j] cos - x[j+dh/2] sin
+      y[j + dh/2] = x[j+dh/2] cos + x[j] sin
+    """
+    dh = x.shape[-1]
+    half = dh // 2
+    inv = base ** (-2.0 * np.arange(half, dtype=np.float64) / dh)
+    ang = np.asarray(pos, np.float64)[:, None] * inv[None, :]
+    c, s = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
+    x1, x2 = x[..., :half], x[..., half:]
+    return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], axis=-1)
+
+
+def silu(x: np.ndarray) -> np.ndarray:
+    return x / (1.0 + np.exp(-x))
+
+
+def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray) -> np.ndarray:
+    """Bidirectional softmax attention: q[R,H,dh], k/v[J,H,dh] -> [R,H,dh].
+
+    Every query row sees every one of the J keys (no mask): Sec. 2.1 of the
+    paper (bidirectional attention).
+    """
+    dh = q.shape[-1]
+    s = np.einsum("rhd,jhd->hrj", q, k) / math.sqrt(dh)
+    s = s - s.max(axis=-1, keepdims=True)
+    p = np.exp(s)
+    p = p / p.sum(axis=-1, keepdims=True)
+    return np.einsum("hrj,jhd->rhd", p, v)
+
+
+def confidence_argmax(z: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Greedy token and its softmax probability for logits z[rows, V].
+
+    conf = max_j softmax(z)_j = 1 / sum_j exp(z_j - max z); ties -> lowest id.
+    """
+    zmax = z.max(axis=-1, keepdims=True)
+    conf = 1.0 / np.exp(z - zmax).sum(axis=-1)
+    return conf, np.argmax(z, axis=-1).astype(np.int32)
+
+
+def threshold_unmask(tokens: np.ndarray, conf: np.ndarray, tau: float,
+                     mask_id: int) -> np.ndarray:
+    """Acceptance rule for one draft (Sec. 3, Observation 3, plus forced progress).
+
+    A position is unmasked iff it currently holds MASK and either its
+    confidence exceeds tau (strictly) or it is the most confident masked
+    position (lowest index on ties).  A draft with no MASK yields all zeros.
+    """
+    masked = np.asarray(tokens) == mask_id
+    out = np.zeros(masked.shape, np.uint8)
+    if not masked.any():
+        return out
+    c = np.where(masked, conf, -np.inf)
+    top = int(np.argmax(c))
+    out[masked & (conf > tau)] = 1
+    out[top] = 1
+    return out
+
+
+# --------------------------------------------------------------------------- the two calls
+
+@dataclasses.dataclass
+class Cache:
+    """K (after RoPE) and V of every position at every layer: [NL, L, H, dh]."""
+    k: np.ndarray
+    v: np.ndarray
+
+    @property
+    def length(self) -> int:
+        return self.k.shape[1]
+
+
+def _layer(cfg: Config, w: Weights, layer: int, h: np.ndarray, pos: np.ndarray,
+           kv_of_rows, rows_group=None):
+    """One pre-norm transformer block on rows h[R, d].
+
+    kv_of_rows(k_new, v_new) -> list of (row_slice, K[J,H,dh], V[J,H,dh]):
+    which keys/values each group of rows attends to, given the fresh K/V the
+    rows themselves produced.  Returns the new h and the fresh (k, v).
+    """
+    H, dh = cfg.n_heads, cfg.head_dim
+    a = rmsnorm(h, w.f64(T_G1, layer), cfg.rms_eps)
+    q = (a @ w.f64(T_WQ, layer).T).reshape(-1, H, dh)
+    k = (a @ w.f64(T_WK, layer).T).reshape(-1, H, dh)
+    v = (a @ w.f64(T_WV, layer).T).reshape(-1, H, dh)
+    q = rope(q, pos, cfg.rope_base)
+    k = rope(k, pos, cfg.rope_base)
+    o = np.empty_like(q)
+    for rows, kk, vv in kv_of_rows(k, v):
+        o[rows] = attention(q[rows], kk, vv)
+    h = h + o.reshape(-1, H * dh) @ w.f64(T_WO, layer).T
+    m = rmsnorm(h, w.f64(T_G2, layer), cfg.rms_eps)
+    gate = m @ w.f64(T_WG, layer).T
+    up = m @ w.f64(T_WU, layer).T
+    h = h + (silu(gate) * up) @ w.f64(T_WD, layer).T
+    return h, k, v
+
+
+def _head(cfg: Config, w: Weights, h: np.ndarray) -> np.ndarray:
+    return rmsnorm(h, w.f64(T_GF, 0), cfg.rms_eps) @ w.f64(T_LM, 0).T
+
+
+def prefill(cfg: Config, w: Weights, tokens: np.ndarray, resp_off: int = 0,
+            pos0: int = 0, return_logits: bool = False):
+    """Cache-refresh forward over one whole sequence (Sec. 2.1; Sec. 4.1).
+
+    tokens[L] -> (Cache over all L positions, conf[L-resp_off],
+    argmax[L-resp_off][, logits]).  Positions are pos0 + i (pos0 is a test
+    hook: RoPE makes the result independent of it).
+    """
+    tokens = np.asarray(tokens, np.int64)
+    L = tokens.shape[0]
+    pos = pos0 + np.arange(L)
+    h = w.embed_rows(tokens)
+    ks, vs = [], []
+    for layer in range(cfg.n_layers):
+        h, k, v = _layer(cfg, w, layer, h, pos,
+                         lambda kn, vn: [(slice(0, L), kn, vn)])
+        ks.append(k)
+        vs.append(v)
+    z = _head(cfg, w, h[resp_off:])
+    conf, amax = confidence_argmax(z)
+    out = (Cache(np.stack(ks), np.stack(vs)), conf, amax)
+    return out + (z,) if return_logits else out
+
+
+def block_step(cfg: Config, w: Weights, cache: Cache, drafts: np.ndarray,
+               block_off: int, tau: float, pos0: int = 0,
+               return_logits: bool = False):
+    """One decode step of S drafts of one block against the cache (Sec. 4.2).
+
+    drafts[S, b] token ids for positions block_off .. block_off+b-1 (every
+    draft uses the same position ids).  Each draft is forwarded on its own;
+    at every layer its rows attend to the cached K/V of all positions outside
+    the block plus the draft's own fresh K/V.  The cache entries at the block's
+    positions are ignored and the cache is not modified.
+    Returns conf[S,b], argmax[S,b], unmask[S,b] (uint8) [, logits[S,b,V]].
+    """
+    drafts = np.asarray(drafts, np.int64)
+    S, b = drafts.shape
+    L = cache.length
+    assert 0 <= block_off and block_off + b <= L
+    pos = pos0 + block_off + np.arange(b)
+    conf = np.empty((S, b))
+    amax = np.empty((S, b), np.int32)
+    unmask = np.empty((S, b), np.uint8)
+    logits = []
+    for s in range(S):
+        h = w.embed_rows(drafts[s])
+        for layer in range(cfg.n_layers):
+            ck, cv = cache.k[layer], cache.v[layer]
+
+            def kv(kn, vn, ck=ck, cv=cv):
+                kk = np.concatenate([ck[:block_off], kn, ck[block_off + b:]])
+                vv = np.concatenate([cv[:block_off], vn, cv[block_off + b:]])
+                return [(slice(0, b), kk, vv)]
+
+            h, _, _ = _layer(cfg, w, layer, h, pos, kv)
+        z = _head(cfg, w, h)
+        conf[s], amax[s] = confidence_argmax(z)
+        unmask[s] = threshold_unmask(drafts[s], conf[s], tau, cfg.mask_id)
+        if return_logits:
+            logits.append(z)
+    out = (conf, amax, unmask)
+    return out + (np.stack(logits),) if return_logits else out

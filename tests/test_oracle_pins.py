@@ -1,0 +1,441 @@
+"""Pins for the CPU oracle: each checks it against something other than itself.
+
+The paper (ODB-dLLM) prints no intermediate value of the forward pass, so the
+pins are closed forms, invariants, brute force, published test vectors of the
+random generator, and PyTorch CPU library routines used as a second opinion.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import odb_oracle as o
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+MICRO = o.Config(n_layers=2, d_model=32, n_heads=2, head_dim=16, d_ff=48, vocab=64)
+TINY = o.Config(n_layers=2, d_model=256, n_heads=4, head_dim=64, d_ff=768,
+                vocab=1024, mask_id=1023)
+
+
+def micro_weights(seed=7, std=0.25):
+    return o.Weights(MICRO, seed, std)
+
+
+# ------------------------------------------------------------------ generator
+
+def test_splitmix64_published_vectors():
+    """SplitMix64 outputs for seeds 0 and 1234567 (vectors in tests/golden)."""
+    for line in open(os.path.join(GOLDEN, "splitmix64_vectors.txt")):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        seed, *vals = line.split()
+        got = o.splitmix64_stream(int(seed, 0), 0, len(vals))
+        assert [int(x) for x in got] == [int(v, 0) for v in vals]
+
+
+def test_splitmix64_is_counter_based():
+    a = o.splitmix64_stream(99, 0, 1000)
+    b = o.splitmix64_stream(99, 500, 100)
+    assert np.array_equal(a[500:600], b)
+
+
+def test_bf16_round_to_nearest_even_bit_patterns():
+    cases = [
+        (0x3F800000, 0x3F80),  # 1.0 exact
+        (0x3F808000, 0x3F80),  # tie, kept bit even -> down
+        (0x3F818000, 0x3F82),  # tie, kept bit odd -> up
+        (0x3F808001, 0x3F81),  # just above tie -> up
+        (0x3F807FFF, 0x3F80),  # just below tie -> down
+        (0xBF818000, 0xBF82),  # sign carried
+        (0x00000000, 0x0000),
+        (0x80000000, 0x8000),
+        (0x00008000, 0x0000),  # subnormal tie -> even (zero)
+        (0x00018000, 0x0002),  # subnormal tie -> up to even
+        (0x3FFFFFFF, 0x4000),  # mantissa carry into exponent
+    ]
+    x = np.array([c[0] for c in cases], np.uint32).view(np.float32)
+    assert list(o.f32_to_bf16_bits(x)) == [c[1] for c in cases]
+    # widening is exact and inverse on representable values
+    bits = np.arange(0, 0x7F80, 37, dtype=np.uint16)
+    back = o.f32_to_bf16_bits(o.bf16_bits_to_f64(bits).astype(np.float32))
+    assert np.array_equal(back, bits)
+
+
+def test_bf16_rounding_agrees_with_torch():
+    rng = np.random.default_rng(0)
+    x = (rng.standard_normal(200000) * np.exp(rng.uniform(-20, 20, 200000))).astype(np.float32)
+    ref = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(o.f32_to_bf16_bits(x), ref)
+
+
+def test_generator_moments_and_independence():
+    n = 4_000_000
+    w = o.bf16_bits_to_f64(o.normal_bf16_bits(5, o.T_WQ, 3, 0, n, 1.0))
+    assert abs(w.mean()) < 4 / math.sqrt(n)
+    assert abs(w.var() - 1.0) < 5e-3           # bf16 rounding adds ~1e-6 relative
+    assert abs((w ** 4).mean() - 3.0) < 3e-2
+    assert abs((w ** 3).mean()) < 2e-2
+    # Box-Muller tail: P(|x|>3) = 2.6998e-3
+    assert abs((np.abs(w) > 3).mean() - 2.6998e-3) < 2e-4
+    # different tensors / layers / seeds decorrelate
+    a = o.bf16_bits_to_f64(o.normal_bf16_bits(5, o.T_WQ, 4, 0, 100000, 1.0))
+    b = o.bf16_bits_to_f64(o.normal_bf16_bits(5, o.T_WK, 3, 0, 100000, 1.0))
+    c = o.bf16_bits_to_f64(o.normal_bf16_bits(6, o.T_WQ, 3, 0, 100000, 1.0))
+    for other in (a, b, c):
+        assert abs(np.corrcoef(w[:100000], other)[0, 1]) < 0.02
+    # lag-1 autocorrelation
+    assert abs(np.corrcoef(w[:-1][:1000000], w[1:][:1000000])[0, 1]) < 5e-3
+    # scaling by std happens before rounding
+    s = o.bf16_bits_to_f64(o.normal_bf16_bits(5, o.T_WQ, 3, 0, 1000, 0.02))
+    assert np.allclose(s, 0.02 * w[:1000], rtol=2 ** -7)
+
+
+def test_generator_slices_agree():
+    full = o.normal_bf16_bits(1, o.T_WD, 2, 0, 5000, 0.02)
+    part = o.normal_bf16_bits(1, o.T_WD, 2, 1234, 100, 0.02)
+    assert np.array_equal(full[1234:1334], part)
+    w = o.Weights(MICRO, 1)
+    assert np.array_equal(w.bits(o.T_WD, 1).ravel(),
+                          o.normal_bf16_bits(1, o.T_WD, 1, 0, 32 * 48, 0.02))
+    assert np.all(w.f64(o.T_G1, 0) == 1.0)
+
+
+# ------------------------------------------------------------------ operators
+
+def test_attention_against_brute_force_loops():
+    rng = np.random.default_rng(1)
+    R, J, H, dh = 5, 9, 2, 4
+    q = rng.standard_normal((R, H, dh)) * 3
+    k = rng.standard_normal((J, H, dh)) * 3
+    v = rng.standard_normal((J, H, dh))
+    got = o.attention(q, k, v)
+    for r in range(R):
+        for h in range(H):
+            sc = [sum(q[r, h, d] * k[j, h, d] for d in range(dh)) / math.sqrt(dh)
+                  for j in range(J)]
+            mx = max(sc)
+            e = [math.exp(s - mx) for s in sc]
+            z = sum(e)
+            for d in range(dh):
+                ref = sum(e[j] / z * v[j, h, d] for j in range(J))
+                assert abs(got[r, h, d] - ref) < 1e-12
+    # sharp softmax really is far from uniform here
+    assert np.abs(got - v.mean(0)).max() > 0.1
+
+
+def test_attention_against_torch_sdpa():
+    rng = np.random.default_rng(2)
+    q = rng.standard_normal((7, 3, 8))
+    k = rng.standard_normal((11, 3, 8))
+    v = rng.standard_normal((11, 3, 8))
+    t = lambda a: torch.from_numpy(a).permute(1, 0, 2)[None]
+    ref = F.scaled_dot_product_attention(t(q), t(k), t(v))[0].permute(1, 0, 2).numpy()
+    assert np.abs(o.attention(q, k, v) - ref).max() < 1e-12
+
+
+def test_rope_closed_form_and_invariants():
+    # dh = 2: a single pair turning by pos * base^0 = pos radians
+    x = np.array([[[1.0, 0.0]], [[0.0, 1.0]]])
+    y = o.rope(x, np.array([1, 2]), 10000.0)
+    assert np.allclose(y[0, 0], [math.cos(1), math.sin(1)], atol=1e-15)
+    assert np.allclose(y[1, 0], [-math.sin(2), math.cos(2)], atol=1e-15)
+    # dh = 4: second pair turns by pos * base^(-1/2); pairing is (j, j + dh/2)
+    x = np.zeros((1, 1, 4)); x[0, 0, 1] = 1.0
+    y = o.rope(x, np.array([3]), 100.0)
+    assert np.allclose(y[0, 0], [0, math.cos(0.3), 0, math.sin(0.3)], atol=1e-15)
+    rng = np.random.default_rng(3)
+    q = rng.standard_normal((6, 2, 16)); k = rng.standard_normal((6, 2, 16))
+    pos = np.array([0, 1, 5, 17, 100, 1000])
+    rq, rk = o.rope(q, pos, 1e4), o.rope(k, pos, 1e4)
+    assert np.allclose(np.linalg.norm(rq, axis=-1), np.linalg.norm(q, axis=-1))
+    rq2, rk2 = o.rope(q, pos + 77, 1e4), o.rope(k, pos + 77, 1e4)
+    assert np.allclose(np.einsum("ahd,bhd->hab", rq, rk),
+                       np.einsum("ahd,bhd->hab", rq2, rk2), atol=1e-11)
+    assert np.allclose(o.rope(q, np.zeros(6), 1e4), q)
+
+
+def test_rmsnorm_and_silu_against_torch():
+    rng = np.random.default_rng(4)
+    x = rng.standard_normal((5, 32)) * 3
+    g = rng.standard_normal(32)
+    ref = F.rms_norm(torch.from_numpy(x), (32,), torch.from_numpy(g), 1e-5).numpy()
+    assert np.abs(o.rmsnorm(x, g, 1e-5) - ref).max() < 1e-13
+    y = o.rmsnorm(x, np.ones(32), 0.0)
+    assert np.allclose(np.sqrt((y * y).mean(-1)), 1.0)
+    assert np.allclose(o.rmsnorm(7.5 * x, g, 0.0), o.rmsnorm(x, g, 0.0))
+    assert np.abs(o.silu(x) - F.silu(torch.from_numpy(x)).numpy()).max() < 1e-14
+
+
+def test_confidence_argmax_definition():
+    z = np.array([[0.0, math.log(3.0), 0.0, 0.0], [2.0, 2.0, 1.0, 2.0]])
+    conf, am = o.confidence_argmax(z)
+    assert np.allclose(conf, [3 / 6, math.e ** 2 / (3 * math.e ** 2 + math.e)])
+    assert list(am) == [1, 0]                       # ties -> lowest id
+    ref = F.softmax(torch.from_numpy(z), -1).max(-1).values.numpy()
+    assert np.allclose(conf, ref)
+
+
+def test_threshold_unmask_rules():
+    M = 9
+    tok = np.array([M, 1, M, M, 2, M])
+    conf = np.array([0.5, 0.99, 0.95, 0.2, 0.99, 0.95])
+    assert list(o.threshold_unmask(tok, conf, 0.9, M)) == [0, 0, 1, 0, 0, 1]
+    # tau >= 1: only the forced top-1 masked position, lowest index on ties
+    assert list(o.threshold_unmask(tok, conf, 1.0, M)) == [0, 0, 1, 0, 0, 0]
+    # tau < 0: every masked position
+    assert list(o.threshold_unmask(tok, conf, -1.0, M)) == [1, 0, 1, 1, 0, 1]
+    # strict comparison
+    assert list(o.threshold_unmask(np.array([M, M]), np.array([0.9, 0.95]), 0.9, M)) == [0, 1]
+    # no masked position -> nothing
+    assert list(o.threshold_unmask(np.array([1, 2]), np.array([0.99, 0.99]), 0.1, M)) == [0, 0]
+    # top-1 is taken among masked positions only
+    assert list(o.threshold_unmask(np.array([1, M]), np.array([0.8, 0.1]), 0.9, M)) == [0, 1]
+
+
+# ------------------------------------------------------------------ whole forward, second opinion
+
+def _torch_rope_complex(x, pos, base):
+    """RoPE as a complex multiplication: (x_j + i x_{j+dh/2}) * exp(i pos w_j)."""
+    half = x.shape[-1] // 2
+    w = torch.tensor([base ** (-2.0 * j / x.shape[-1]) for j in range(half)],
+                     dtype=torch.float64)
+    zc = torch.complex(x[..., :half], x[..., half:])
+    rot = torch.polar(torch.ones(len(pos), half, dtype=torch.float64),
+                      pos.to(torch.float64)[:, None] * w[None])
+    zc = zc * rot[:, None, :]
+    return torch.cat([zc.real, zc.imag], -1)
+
+
+def _torch_forward(cfg, w, tokens, pos, ctx_kv=None, block=None):
+    """Plain PyTorch-CPU float64 forward built from torch.nn.functional calls.
+
+    ctx_kv: per-layer (K, V) tensors [L,H,dh] of a cache, block=(off, b): rows
+    replace cache entries off..off+b-1 by their own K/V.  Returns logits and
+    the per-layer (k, v) of the rows.
+    """
+    T = lambda tid, layer=0: torch.from_numpy(w.f64(tid, layer))
+    H, dh, d = cfg.n_heads, cfg.head_dim, cfg.d_model
+    h = F.embedding(torch.as_tensor(tokens, dtype=torch.long), T(o.T_EMBED))
+    pos = torch.as_tensor(pos)
+    kvs = []
+    for l in range(cfg.n_layers):
+        a = F.rms_norm(h, (d,), T(o.T_G1, l), cfg.rms_eps)
+        q = _torch_rope_complex(F.linear(a, T(o.T_WQ, l)).view(-1, H, dh), pos, cfg.rope_base)
+        k = _torch_rope_complex(F.linear(a, T(o.T_WK, l)).view(-1, H, dh), pos, cfg.rope_base)
+        v = F.linear(a, T(o.T_WV, l)).view(-1, H, dh)
+        kvs.append((k, v))
+        if ctx_kv is not None:
+            off, b = block
+            K = torch.cat([ctx_kv[l][0][:off], k, ctx_kv[l][0][off + b:]])
+            V = torch.cat([ctx_kv[l][1][:off], v, ctx_kv[l][1][off + b:]])
+        else:
+            K, V = k, v
+        att = F.scaled_dot_product_attention(q.permute(1, 0, 2)[None], K.permute(1, 0, 2)[None],
+                                             V.permute(1, 0, 2)[None])[0].permute(1, 0, 2)
+        h = h + F.linear(att.reshape(-1, d), T(o.T_WO, l))
+        m = F.rms_norm(h, (d,), T(o.T_G2, l), cfg.rms_eps)
+        h = h + F.linear(F.silu(F.linear(m, T(o.T_WG, l))) * F.linear(m, T(o.T_WU, l)), T(o.T_WD, l))
+    z = F.linear(F.rms_norm(h, (d,), T(o.T_GF), cfg.rms_eps), T(o.T_LM))
+    return z.numpy(), kvs
+
+
+def _random_gains(w, cfg, rng):
+    for l in range(cfg.n_layers):
+        w.set_values(o.T_G1, l, rng.uniform(0.5, 2.0, cfg.d_model))
+        w.set_values(o.T_G2, l, rng.uniform(0.5, 2.0, cfg.d_model))
+    w.set_values(o.T_GF, 0, rng.uniform(2.0, 6.0, cfg.d_model))
+
+
+@pytest.mark.parametrize("cfg,std", [(MICRO, 0.25), (TINY, 0.05)])
+def test_prefill_and_step_against_torch_functional(cfg, std):
+    rng = np.random.default_rng(11)
+    w = o.Weights(cfg, 3, std)
+    _random_gains(w, cfg, rng)
+    L, off, b, S = 40, 16, 8, 3
+    tokens = rng.integers(0, cfg.vocab, L)
+    cache, conf, am, z = o.prefill(cfg, w, tokens, resp_off=4, return_logits=True)
+    zt, kvs = _torch_forward(cfg, w, tokens, np.arange(L))
+    assert np.abs(z - zt[4:]).max() < 1e-9 * max(1.0, np.abs(zt).max())
+    for l in range(cfg.n_layers):
+        assert np.abs(cache.k[l] - kvs[l][0].numpy()).max() < 1e-10
+        assert np.abs(cache.v[l] - kvs[l][1].numpy()).max() < 1e-10
+    assert np.array_equal(am, zt[4:].argmax(-1))
+    drafts = rng.integers(0, cfg.vocab, (S, b))
+    drafts[:, ::2] = cfg.mask_id
+    c2, a2, u2, z2 = o.block_step(cfg, w, cache, drafts, off, 0.3, return_logits=True)
+    for s in range(S):
+        zs, _ = _torch_forward(cfg, w, drafts[s], off + np.arange(b), ctx_kv=kvs, block=(off, b))
+        assert np.abs(z2[s] - zs).max() < 1e-9 * max(1.0, np.abs(zs).max())
+        p = F.softmax(torch.from_numpy(zs), -1).max(-1).values.numpy()
+        assert np.allclose(c2[s], p, rtol=1e-10)
+    assert c2.shape == (S, b) and a2.dtype == np.int32 and u2.dtype == np.uint8
+
+
+def test_one_layer_against_naive_python_matmul():
+    cfg = o.Config(n_layers=1, d_model=8, n_heads=2, head_dim=4, d_ff=12, vocab=16)
+    w = o.Weights(cfg, 21, 0.5)
+    tokens = [3, 9, 1]
+    _, _, _, z = o.prefill(cfg, w, tokens, return_logits=True)
+
+    def mm(x, W):  # x[R][K] * W[N][K]^T
+        return [[sum(xr[k] * W[n][k] for k in range(len(xr))) for n in range(len(W))] for xr in x]
+
+    def rms(x, eps):
+        return [[v / math.sqrt(sum(u * u for u in r) / len(r) + eps) for v in r] for r in x]
+
+    E = w.f64(o.T_EMBED).tolist()
+    h = [E[t] for t in tokens]
+    a = rms(h, cfg.rms_eps)
+    q, k, v = (mm(a, w.f64(t).tolist()) for t in (o.T_WQ, o.T_WK, o.T_WV))
+
+    def rot(x, p):
+        out = [0.0] * 8
+        for hd in range(2):
+            for j in range(2):
+                th = p * cfg.rope_base ** (-2.0 * j / 4)
+                x1, x2 = x[hd * 4 + j], x[hd * 4 + j + 2]
+                out[hd * 4 + j] = x1 * math.cos(th) - x2 * math.sin(th)
+                out[hd * 4 + j + 2] = x2 * math.cos(th) + x1 * math.sin(th)
+        return out
+
+    q = [rot(q[i], i) for i in range(3)]
+    k = [rot(k[i], i) for i in range(3)]
+    att = [[0.0] * 8 for _ in range(3)]
+    for i in range(3):
+        for hd in range(2):
+            sc = [sum(q[i][hd * 4 + d] * k[j][hd * 4 + d] for d in range(4)) / 2.0 for j in range(3)]
+            e = [math.exp(s - max(sc)) for s in sc]
+            for d in range(4):
+                att[i][hd * 4 + d] = sum(e[j] / sum(e) * v[j][hd * 4 + d] for j in range(3))
+    o_ = mm(att, w.f64(o.T_WO).tolist())
+    h = [[h[i][c] + o_[i][c] for c in range(8)] for i in range(3)]
+    m = rms(h, cfg.rms_eps)
+    g, u = mm(m, w.f64(o.T_WG).tolist()), mm(m, w.f64(o.T_WU).tolist())
+    act = [[g[i][c] / (1 + math.exp(-g[i][c])) * u[i][c] for c in range(12)] for i in range(3)]
+    dn = mm(act, w.f64(o.T_WD).tolist())
+    h = [[h[i][c] + dn[i][c] for c in range(8)] for i in range(3)]
+    zz = mm(rms(h, cfg.rms_eps), w.f64(o.T_LM).tolist())
+    assert np.abs(np.array(zz) - z).max() < 1e-12
+
+
+# ------------------------------------------------------------------ structural properties from the paper
+
+def _setup(seed=5, L=48, off=16, b=8, S=4, cfg=MICRO):
+    rng = np.random.default_rng(seed)
+    w = o.Weights(cfg, seed, 0.25)
+    w.set_values(o.T_GF, 0, np.full(cfg.d_model, 4.0))
+    tokens = rng.integers(0, cfg.vocab - 1, L)
+    tokens[off + 2: off + b] = cfg.mask_id
+    return rng, w, tokens
+
+
+def test_cached_step_equals_full_recompute_on_unchanged_block():
+    """Sec. 2.1: K/V outside the block are what the refresh computed, so a step
+    on the block as it stood at the refresh reproduces the refresh's outputs."""
+    _, w, tokens = _setup()
+    cache, conf, am, z = o.prefill(MICRO, w, tokens, return_logits=True)
+    c, a, u, zs = o.block_step(MICRO, w, cache, tokens[None, 16:24], 16, 0.5, return_logits=True)
+    assert np.abs(zs[0] - z[16:24]).max() < 1e-11
+    assert np.allclose(c[0], conf[16:24], rtol=1e-11) and np.array_equal(a[0], am[16:24])
+    # ... and after a token of the block changed it differs (stale outside K/V aside)
+    d = tokens[None, 16:24].copy(); d[0, 3] = 5
+    assert np.abs(o.block_step(MICRO, w, cache, d, 16, 0.5, return_logits=True)[3][0] - z[16:24]).max() > 1e-3
+
+
+def test_step_ignores_cache_entries_of_the_block_and_leaves_cache_alone():
+    rng, w, tokens = _setup()
+    cache, *_ = o.prefill(MICRO, w, tokens)
+    drafts = rng.integers(0, MICRO.vocab, (2, 8))
+    ref = o.block_step(MICRO, w, cache, drafts, 16, 0.5, return_logits=True)
+    k0, v0 = cache.k.copy(), cache.v.copy()
+    bad = o.Cache(cache.k.copy(), cache.v.copy())
+    bad.k[:, 16:24] = 1e3; bad.v[:, 16:24] = -1e3
+    got = o.block_step(MICRO, w, bad, drafts, 16, 0.5, return_logits=True)
+    assert np.array_equal(ref[3], got[3])
+    assert np.array_equal(cache.k, k0) and np.array_equal(cache.v, v0)
+    # entries outside the block do matter
+    bad.k[:, 30] += 1.0
+    assert np.abs(o.block_step(MICRO, w, bad, drafts, 16, 0.5, return_logits=True)[3] - ref[3]).max() > 1e-6
+
+
+def test_drafts_are_mutually_invisible():
+    """Sec. 4.2: drafts see the cached context and themselves only."""
+    rng, w, tokens = _setup()
+    cache, *_ = o.prefill(MICRO, w, tokens)
+    drafts = rng.integers(0, MICRO.vocab, (4, 8)); drafts[:, 5] = MICRO.mask_id
+    c, a, u, z = o.block_step(MICRO, w, cache, drafts, 16, 0.2, return_logits=True)
+    perm = [2, 0, 3, 1]
+    cp, ap, up, zp = o.block_step(MICRO, w, cache, drafts[perm], 16, 0.2, return_logits=True)
+    assert np.array_equal(zp, z[perm]) and np.array_equal(cp, c[perm])
+    assert np.array_equal(ap, a[perm]) and np.array_equal(up, u[perm])
+    for s in range(4):
+        c1, a1, u1, z1 = o.block_step(MICRO, w, cache, drafts[s:s + 1], 16, 0.2, return_logits=True)
+        assert np.array_equal(z1[0], z[s])
+    dup = np.stack([drafts[1]] * 3)
+    zd = o.block_step(MICRO, w, cache, dup, 16, 0.2, return_logits=True)[3]
+    assert np.array_equal(zd[0], zd[1]) and np.array_equal(zd[0], z[1])
+
+
+def test_attention_is_bidirectional():
+    _, w, tokens = _setup()
+    z = o.prefill(MICRO, w, tokens, return_logits=True)[3]
+    t2 = tokens.copy(); t2[-1] = (t2[-1] + 1) % 60
+    z2 = o.prefill(MICRO, w, t2, return_logits=True)[3]
+    assert np.abs(z2[0] - z[0]).max() > 1e-6      # row 0 depends on the last token
+
+
+def test_prefill_invariant_to_position_offset():
+    _, w, tokens = _setup()
+    z = o.prefill(MICRO, w, tokens, return_logits=True)[3]
+    z2 = o.prefill(MICRO, w, tokens, pos0=123, return_logits=True)[3]
+    assert np.abs(z - z2).max() < 1e-9
+    cache = o.prefill(MICRO, w, tokens, pos0=123)[0]
+    d = tokens[None, 16:24]
+    a = o.block_step(MICRO, w, cache, d, 16, 0.5, pos0=123, return_logits=True)[3]
+    assert np.abs(a[0] - z[16:24]).max() < 1e-9
+
+
+def test_zero_lm_head_gives_uniform_confidence():
+    _, w, tokens = _setup()
+    w.set_values(o.T_LM, 0, np.zeros((MICRO.vocab, MICRO.d_model)))
+    _, conf, am = o.prefill(MICRO, w, tokens)
+    assert np.all(conf == 1.0 / MICRO.vocab) and np.all(am == 0)
+
+
+def test_zero_output_projections_closed_form():
+    """With Wo = Wd = 0 the residual stream is the embedding: logits are
+    rmsnorm(E[tok]) . W_lm^T, and a planted LM row gives a closed-form confidence."""
+    _, w, tokens = _setup()
+    for l in range(MICRO.n_layers):
+        w.set_values(o.T_WO, l, np.zeros((32, 32)))
+        w.set_values(o.T_WD, l, np.zeros((32, 48)))
+    lm = np.zeros((MICRO.vocab, 32)); lm[7, 0] = 2.0
+    w.set_values(o.T_LM, 0, lm)
+    w.set_values(o.T_GF, 0, np.ones(32))
+    emb = np.zeros((MICRO.vocab, 32)); emb[:, 0] = 3.0; emb[:, 1] = 4.0   # rms = sqrt(25/32)
+    w.set_values(o.T_EMBED, 0, emb)
+    _, conf, am, z = o.prefill(MICRO, w, tokens, return_logits=True)
+    x0 = 3.0 / math.sqrt(25.0 / 32 + MICRO.rms_eps)
+    assert np.allclose(z[:, 7], 2.0 * x0, rtol=1e-12) and np.all(am == 7)
+    assert np.allclose(conf, 1.0 / (1.0 + (MICRO.vocab - 1) * math.exp(-2.0 * x0)), rtol=1e-12)
+    cache = o.prefill(MICRO, w, tokens)[0]
+    c, a, u = o.block_step(MICRO, w, cache, tokens[None, 16:24], 16, 0.5)
+    assert np.allclose(c, conf[16:24]) and np.all(a == 7)
+    assert np.array_equal(u[0], (tokens[16:24] == MICRO.mask_id).astype(np.uint8))
+
+
+def test_step_unmask_uses_draft_tokens_and_tau():
+    rng, w, tokens = _setup()
+    cache, *_ = o.prefill(MICRO, w, tokens)
+    drafts = np.stack([tokens[16:24], tokens[16:24]]); drafts[1, :] = 3
+    c, a, u = o.block_step(MICRO, w, cache, drafts, 16, 1.0)
+    assert u[0].sum() == 1 and u[1].sum() == 0
+    masked = drafts[0] == MICRO.mask_id
+    assert u[0][np.argmax(np.where(masked, c[0], -1))] == 1
+    c, a, u = o.block_step(MICRO, w, cache, drafts, 16, -1.0)
+    assert np.array_equal(u[0], masked.astype(np.uint8))
