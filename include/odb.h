@@ -1,0 +1,154 @@
+/* odb.h - C ABI of the MI355X (gfx950) block-decode / cache-refresh library.
+ *
+ * The library computes the model step of ODB-dLLM (arXiv 2511.21759):
+ *   - odb_prefill: the full-sequence bidirectional forward that refreshes the
+ *     K/V cache and yields a decoding attempt for every response position
+ *     (Sec. 2.1 "DualCache" refresh; Sec. 4.1, first paragraph);
+ *   - odb_block_step: the forward of S mutually invisible drafts of one
+ *     response block against the cached K/V of every position outside the
+ *     block, followed by the confidence-threshold acceptance
+ *     (Sec. 3 Observation 3; Sec. 4.2 and Fig. 8 for the drafts).
+ *
+ * Conventions
+ *   - "dev" pointers are device (HBM) addresses on the current HIP device,
+ *     "host" pointers are ordinary host memory.  The caller owns every buffer
+ *     it passes; the library owns models, caches and its internal scratch.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     odb_prefill / odb_block_step are asynchronous on it: outputs are valid
+ *     once the caller has synchronised the stream.  Calls that use the same
+ *     model must be issued on one stream at a time (they share scratch).
+ *   - Every function returns ODB_OK (0) or a negative ODB_E_* code; a message
+ *     for the last failure on the calling thread is kept in odb_last_error().
+ *     Arguments are validated on the host before any kernel is launched, so an
+ *     invalid call launches nothing.
+ *   - There is no CPU fallback: without a usable gfx950 device calls fail with
+ *     ODB_E_HIP.
+ */
+#ifndef ODB_H
+#define ODB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ODB_OK 0
+#define ODB_E_INVALID_ARG (-1)
+#define ODB_E_NOMEM (-2)
+#define ODB_E_HIP (-3)
+#define ODB_E_UNSUPPORTED (-4)
+
+typedef struct odb_model odb_model;
+typedef struct odb_cache odb_cache;
+
+/* Architecture of the masked-diffusion transformer.  The paper names the LLaDA
+ * 8B models (Sec. 5.1) without listing the architecture; this library fixes
+ * pre-norm residual blocks, RMSNorm, rotate-half RoPE on the full head
+ * dimension, SwiGLU, an untied LM head and no biases.
+ * Requirements: d_model = n_heads*head_dim; head_dim is 64 or 128; d_model and
+ * d_ff and vocab are multiples of 32; 0 <= mask_id < vocab. */
+typedef struct {
+    int n_layers, d_model, n_heads, head_dim, d_ff, vocab;
+    float rope_base; /* pair j of a head turns by pos * rope_base^(-2j/head_dim) */
+    float rms_eps;
+    int mask_id;     /* token id of [MASK] */
+} odb_config;
+
+/* Optional device allocator (e.g. backed by torch.empty(device="cuda")).
+ * alloc returns a device pointer aligned to 256 B or NULL. */
+typedef struct {
+    void *(*alloc)(size_t bytes, void *user);
+    void (*free)(void *dev_ptr, void *user);
+    void *user;
+} odb_allocator;
+
+/* Tensor ids for odb_model_set_tensor / odb_model_get_tensor.  Logical shapes
+ * are row-major [out, in]: EMBED and LM [vocab, d]; WQ WK WV WO [d, d]; WG WU
+ * [d_ff, d]; WD [d, d_ff]; the gains G1 (before attention), G2 (before the
+ * MLP) and GF (before the LM head) are [d].  `layer` is ignored for EMBED, LM
+ * and GF. */
+enum {
+    ODB_T_EMBED = 0, ODB_T_WQ, ODB_T_WK, ODB_T_WV, ODB_T_WO, ODB_T_WG, ODB_T_WU,
+    ODB_T_WD, ODB_T_LM, ODB_T_G1, ODB_T_G2, ODB_T_GF, ODB_T_COUNT
+};
+
+/* Creates a model and allocates its weights in HBM (private tiled layout).
+ * allocator may be NULL (hipMalloc/hipFree are used).  Weights are
+ * uninitialised until odb_model_init_random or odb_model_set_tensor. */
+int odb_model_create(const odb_config *cfg, const odb_allocator *allocator,
+                     odb_model **out);
+void odb_model_destroy(odb_model *m);
+
+/* Fills every weight with bf16_rne(float(std * x)), x ~ N(0,1) drawn by the
+ * counter-based generator below from the element's logical flat index, and
+ * sets all gains to 1.  Element i of tensor t at layer l uses
+ *   key = SM(SM(seed) + (t << 32 | l)),   z = SplitMix64 output i of state key,
+ *   u1 = (hi32(z)+0.5)/2^32, u2 = (lo32(z)+0.5)/2^32,
+ *   x = sqrt(-2 ln u1) cos(2 pi u2)   evaluated in binary64,
+ * where SM(s) is the first SplitMix64 output for state s.  Asynchronous on
+ * `stream`. */
+int odb_model_init_random(odb_model *m, uint64_t seed, double std, void *stream);
+
+/* Replaces / reads back one tensor as bf16 bit patterns in logical row-major
+ * order (host memory, n = number of elements, must match the shape).
+ * Synchronous. */
+int odb_model_set_tensor(odb_model *m, int tensor_id, int layer,
+                         const uint16_t *host_bf16, size_t n);
+int odb_model_get_tensor(const odb_model *m, int tensor_id, int layer,
+                         uint16_t *host_bf16, size_t n);
+
+/* K/V cache for `batch` sequences of up to max_len positions: post-RoPE K and
+ * V in bf16 for every layer, head and position (Sec. 2.1). */
+int odb_cache_create(odb_model *m, int batch, int max_len, odb_cache **out);
+void odb_cache_destroy(odb_cache *c);
+/* Current sequence length set by the last odb_prefill (0 before). */
+int odb_cache_length(const odb_cache *c);
+
+/* Cache refresh (Sec. 2.1; Sec. 4.1).  tokens: dev int32 [batch, L], ids in
+ * [0, vocab).  Runs the bidirectional forward over all L positions of every
+ * sequence (positions 0..L-1), stores post-RoPE K and V of all of them in the
+ * cache (its length becomes L) and writes, for response positions i >=
+ * resp_off, conf (dev float [batch, L-resp_off]) = probability of the greedy
+ * token and argmax (dev int32, same shape) = greedy token id, lowest id on
+ * ties.  1 <= L <= max_len, 0 <= resp_off < L. */
+int odb_prefill(odb_model *m, odb_cache *c, const int32_t *tokens_dev, int L,
+                int resp_off, float *conf_dev, int32_t *argmax_dev, void *stream);
+
+/* Block-decode step (Sec. 3 Obs. 3; Sec. 4.2).  drafts: dev int32
+ * [batch, S, b]: S versions of the block at positions block_off ..
+ * block_off+b-1 (all drafts share these position ids).  Each draft's b rows
+ * attend to the cached K/V of positions outside the block and to the draft's
+ * own fresh K/V; the cache entries at the block's positions are ignored and
+ * the cache is not modified.  Outputs, all dev [batch, S, b]: conf (float),
+ * argmax (int32) and unmask (uint8): 1 iff the draft holds mask_id there and
+ * (conf > tau or the position is the draft's most confident masked position,
+ * lowest index on ties).  Requires a prefilled cache, 0 <= block_off,
+ * block_off + b <= cache length, 1 <= b <= 256, 1 <= S. */
+int odb_block_step(odb_model *m, const odb_cache *c, const int32_t *drafts_dev,
+                   int block_off, int b, int S, float tau, float *conf_dev,
+                   int32_t *argmax_dev, uint8_t *unmask_dev, void *stream);
+
+/* Test-only variants that also materialise the logits (dev float, row-major
+ * [batch, L-resp_off, vocab] resp. [batch, S, b, vocab]) through an unfused
+ * store; conf/argmax/unmask pointers may be NULL. */
+int odb_prefill_logits(odb_model *m, odb_cache *c, const int32_t *tokens_dev,
+                       int L, int resp_off, float *logits_dev, void *stream);
+int odb_block_step_logits(odb_model *m, const odb_cache *c,
+                          const int32_t *drafts_dev, int block_off, int b, int S,
+                          float *logits_dev, void *stream);
+
+/* Copies cached K (kv = 0, post-RoPE, logical channel order) or V (kv = 1) of
+ * positions pos0 .. pos0+n-1 of one sequence and layer to host memory as bf16
+ * bit patterns [n, n_heads, head_dim].  Synchronous (device-wide). */
+int odb_cache_read(const odb_cache *c, int layer, int kv, int batch_index,
+                   int pos0, int n, uint16_t *host_bf16);
+
+const char *odb_strerror(int code);
+const char *odb_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ODB_H */

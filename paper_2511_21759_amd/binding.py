@@ -1,0 +1,192 @@
+"""ctypes binding of the C ABI in include/odb.h: argument marshalling only.
+
+Every function has the name of the C entry point it calls.  Device buffers are
+torch CUDA tensors (PyTorch-ROCm is the device allocator and stream provider);
+all arithmetic happens inside libodb.so.  There is no fallback: if the library
+has not been built, or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libodb.so")
+
+#: every symbol include/odb.h declares
+SYMBOLS = (
+    "odb_model_create", "odb_model_destroy", "odb_model_init_random", "odb_model_set_tensor",
+    "odb_model_get_tensor", "odb_cache_create", "odb_cache_destroy", "odb_cache_length", "odb_prefill",
+    "odb_block_step", "odb_prefill_logits", "odb_block_step_logits", "odb_cache_read", "odb_strerror",
+    "odb_last_error",
+)
+
+T_EMBED, T_WQ, T_WK, T_WV, T_WO, T_WG, T_WU, T_WD, T_LM, T_G1, T_G2, T_GF = range(12)
+
+
+class OdbError(RuntimeError):
+    pass
+
+
+class odb_config(ctypes.Structure):
+    _fields_ = [("n_layers", ctypes.c_int), ("d_model", ctypes.c_int), ("n_heads", ctypes.c_int),
+                ("head_dim", ctypes.c_int), ("d_ff", ctypes.c_int), ("vocab", ctypes.c_int),
+                ("rope_base", ctypes.c_float), ("rms_eps", ctypes.c_float), ("mask_id", ctypes.c_int)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libodb.so (built by `__graft_entry__.build()` / build.py) once."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise OdbError("%s is missing: build it with `python -m paper_2511_21759_amd.build` "
+                       "(there is no fallback path)" % LIB_PATH)
+    # PyTorch-ROCm ships its own HIP runtime; import it first so that the library
+    # binds to the runtime torch uses (one runtime per process, shared streams).
+    import torch  # noqa: F401
+    L = ctypes.CDLL(LIB_PATH)
+    vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+    L.odb_model_create.argtypes = [ctypes.POINTER(odb_config), vp, ctypes.POINTER(vp)]
+    L.odb_model_destroy.argtypes = [vp]
+    L.odb_model_destroy.restype = None
+    L.odb_model_init_random.argtypes = [vp, ctypes.c_uint64, ctypes.c_double, vp]
+    L.odb_model_set_tensor.argtypes = [vp, ci, ci, vp, ctypes.c_size_t]
+    L.odb_model_get_tensor.argtypes = [vp, ci, ci, vp, ctypes.c_size_t]
+    L.odb_cache_create.argtypes = [vp, ci, ci, ctypes.POINTER(vp)]
+    L.odb_cache_destroy.argtypes = [vp]
+    L.odb_cache_destroy.restype = None
+    L.odb_cache_length.argtypes = [vp]
+    L.odb_prefill.argtypes = [vp, vp, vp, ci, ci, vp, vp, vp]
+    L.odb_block_step.argtypes = [vp, vp, vp, ci, ci, ci, cf, vp, vp, vp, vp]
+    L.odb_prefill_logits.argtypes = [vp, vp, vp, ci, ci, vp, vp]
+    L.odb_block_step_logits.argtypes = [vp, vp, vp, ci, ci, ci, vp, vp]
+    L.odb_cache_read.argtypes = [vp, ci, ci, ci, ci, ci, vp]
+    L.odb_strerror.argtypes = [ci]
+    L.odb_strerror.restype = ctypes.c_char_p
+    L.odb_last_error.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        L = lib()
+        raise OdbError("%s: %s" % (L.odb_strerror(rc).decode(), L.odb_last_error().decode()))
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev_i32(t):
+    import torch
+    if not (t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()):
+        raise OdbError("expected a contiguous int32 CUDA tensor")
+    return t.data_ptr()
+
+
+# ---- one function per C entry point ---------------------------------------------------------
+
+def odb_model_create(shape: Dict) -> int:
+    cfg = odb_config(**{k: shape[k] for k, _ in odb_config._fields_})
+    out = ctypes.c_void_p()
+    _check(lib().odb_model_create(ctypes.byref(cfg), None, ctypes.byref(out)))
+    return out.value
+
+
+def odb_model_destroy(model: int) -> None:
+    lib().odb_model_destroy(model)
+
+
+def odb_model_init_random(model: int, seed: int, std: float) -> None:
+    _check(lib().odb_model_init_random(model, seed, std, _stream()))
+
+
+def odb_model_set_tensor(model: int, tensor_id: int, layer: int, bits: np.ndarray) -> None:
+    bits = np.ascontiguousarray(bits, np.uint16)
+    _check(lib().odb_model_set_tensor(model, tensor_id, layer, bits.ctypes.data, bits.size))
+
+
+def odb_model_get_tensor(model: int, tensor_id: int, layer: int, n: int) -> np.ndarray:
+    out = np.empty(n, np.uint16)
+    _check(lib().odb_model_get_tensor(model, tensor_id, layer, out.ctypes.data, n))
+    return out
+
+
+def odb_cache_create(model: int, batch: int, max_len: int) -> int:
+    out = ctypes.c_void_p()
+    _check(lib().odb_cache_create(model, batch, max_len, ctypes.byref(out)))
+    return out.value
+
+
+def odb_cache_destroy(cache: int) -> None:
+    lib().odb_cache_destroy(cache)
+
+
+def odb_cache_length(cache: int) -> int:
+    return lib().odb_cache_length(cache)
+
+
+def odb_prefill(model: int, cache: int, tokens, resp_off: int, conf=None, argmax=None):
+    """tokens: int32 CUDA tensor [B, L] -> (conf [B, L-resp_off] f32, argmax int32)."""
+    import torch
+    B, L = tokens.shape
+    if conf is None:
+        conf = torch.empty((B, L - resp_off), dtype=torch.float32, device=tokens.device)
+    if argmax is None:
+        argmax = torch.empty((B, L - resp_off), dtype=torch.int32, device=tokens.device)
+    _check(lib().odb_prefill(model, cache, _dev_i32(tokens), L, resp_off, conf.data_ptr(), argmax.data_ptr(),
+                             _stream()))
+    return conf, argmax
+
+
+def odb_block_step(model: int, cache: int, drafts, block_off: int, tau: float, conf=None, argmax=None, unmask=None):
+    """drafts: int32 CUDA tensor [B, S, b] -> (conf f32, argmax int32, unmask uint8), each [B, S, b]."""
+    import torch
+    B, S, b = drafts.shape
+    if conf is None:
+        conf = torch.empty((B, S, b), dtype=torch.float32, device=drafts.device)
+    if argmax is None:
+        argmax = torch.empty((B, S, b), dtype=torch.int32, device=drafts.device)
+    if unmask is None:
+        unmask = torch.empty((B, S, b), dtype=torch.uint8, device=drafts.device)
+    _check(lib().odb_block_step(model, cache, _dev_i32(drafts), block_off, b, S, tau, conf.data_ptr(),
+                                argmax.data_ptr(), unmask.data_ptr(), _stream()))
+    return conf, argmax, unmask
+
+
+def odb_prefill_logits(model: int, cache: int, tokens, resp_off: int, vocab: int):
+    import torch
+    B, L = tokens.shape
+    logits = torch.empty((B, L - resp_off, vocab), dtype=torch.float32, device=tokens.device)
+    _check(lib().odb_prefill_logits(model, cache, _dev_i32(tokens), L, resp_off, logits.data_ptr(), _stream()))
+    return logits
+
+
+def odb_block_step_logits(model: int, cache: int, drafts, block_off: int, vocab: int):
+    import torch
+    B, S, b = drafts.shape
+    logits = torch.empty((B, S, b, vocab), dtype=torch.float32, device=drafts.device)
+    _check(lib().odb_block_step_logits(model, cache, _dev_i32(drafts), block_off, b, S, logits.data_ptr(),
+                                       _stream()))
+    return logits
+
+
+def odb_cache_read(cache: int, layer: int, kv: int, batch_index: int, pos0: int, n: int, n_heads: int,
+                   head_dim: int) -> np.ndarray:
+    out = np.empty((n, n_heads, head_dim), np.uint16)
+    _check(lib().odb_cache_read(cache, layer, kv, batch_index, pos0, n, out.ctypes.data))
+    return out
+
+
+def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    """Widening of bf16 bit patterns (pure reinterpretation, no arithmetic)."""
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)

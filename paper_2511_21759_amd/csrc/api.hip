@@ -1,0 +1,504 @@
+// C ABI of the library (include/odb.h): argument validation, memory, and the
+// sequence of kernel launches that make up the prefill and the block step.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "model.h"
+
+using namespace odb;
+
+struct odb_model { Model m; };
+struct odb_cache { Cache c; };
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                         \
+    do {                                                                                      \
+        hipError_t e_ = (expr);                                                               \
+        if (e_ != hipSuccess) return fail(ODB_E_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int ru(int x, int a) { return (x + a - 1) / a * a; }
+
+void *dev_alloc(const Model &m, size_t bytes) {
+    if (bytes == 0) bytes = 256;
+    if (m.has_alloc) return m.alloc.alloc(bytes, m.alloc.user);
+    void *p = nullptr;
+    if (hipMalloc(&p, bytes) != hipSuccess) return nullptr;
+    return p;
+}
+
+void dev_free(const Model &m, void *p) {
+    if (!p) return;
+    if (m.has_alloc) m.alloc.free(p, m.alloc.user);
+    else (void)hipFree(p);
+}
+
+constexpr int kCounters = 1 << 16;
+constexpr size_t kGemmPartialBytes = 64u << 20;
+
+// byte offsets of the per-call buffers inside the model's scratch allocation
+struct Plan {
+    size_t h, xa, q, kf, vf, ao, act, stats, gemm_part, attn_part, total;
+};
+
+Plan make_plan(const odb_config &c, int rows_pad, int fresh_rows, int lm_rows_pad, size_t attn_part_bytes,
+               bool need_stats) {
+    Plan p;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    size_t d = c.d_model;
+    p.h = take((size_t)rows_pad * d * 4);
+    p.xa = take((size_t)rows_pad * d * 2);
+    p.q = take((size_t)rows_pad * d * 2);
+    p.kf = take((size_t)fresh_rows * d * 2);
+    p.vf = take((size_t)fresh_rows * d * 2);
+    p.ao = take((size_t)rows_pad * d * 2);
+    p.act = take((size_t)rows_pad * c.d_ff * 2);
+    p.stats = take(need_stats ? (size_t)lm_rows_pad * (c.vocab / 32) * 3 * 4 : 0);
+    p.gemm_part = take(kGemmPartialBytes);
+    p.attn_part = take(attn_part_bytes);
+    p.total = off;
+    return p;
+}
+
+int ensure_scratch(Model &m, size_t bytes, hipStream_t s) {
+    if (bytes <= m.scratch_bytes) return ODB_OK;
+    HIP_TRY(hipStreamSynchronize(s));
+    dev_free(m, m.scratch);
+    m.scratch = nullptr;
+    m.scratch_bytes = 0;
+    size_t want = align_up(bytes + bytes / 8, 1 << 20);
+    m.scratch = dev_alloc(m, want);
+    if (!m.scratch) return fail(ODB_E_NOMEM, "cannot allocate %zu bytes of scratch", want);
+    m.scratch_bytes = want;
+    HIP_TRY(hipMemsetAsync(m.scratch, 0, want, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    return ODB_OK;
+}
+
+int check_config(const odb_config *c) {
+    if (!c) return fail(ODB_E_INVALID_ARG, "config is NULL");
+    if (c->n_layers < 1 || c->d_model < 1 || c->n_heads < 1 || c->d_ff < 1 || c->vocab < 1)
+        return fail(ODB_E_INVALID_ARG, "config: sizes must be positive");
+    if (c->n_heads * c->head_dim != c->d_model) return fail(ODB_E_INVALID_ARG, "config: d_model != n_heads*head_dim");
+    if (c->head_dim != 64 && c->head_dim != 128) return fail(ODB_E_UNSUPPORTED, "config: head_dim must be 64 or 128");
+    if (c->d_model % 32 || c->d_ff % 32) return fail(ODB_E_INVALID_ARG, "config: d_model and d_ff must be multiples of 32");
+    if (c->vocab % 32) return fail(ODB_E_INVALID_ARG, "config: vocab must be a multiple of 32");
+    if (c->mask_id < 0 || c->mask_id >= c->vocab) return fail(ODB_E_INVALID_ARG, "config: mask_id out of range");
+    if (!(c->rope_base > 0.f) || !(c->rms_eps >= 0.f)) return fail(ODB_E_INVALID_ARG, "config: rope_base/rms_eps");
+    return ODB_OK;
+}
+
+size_t tensor_elems(const odb_config &c, int tid) {
+    size_t d = c.d_model, f = c.d_ff, v = c.vocab;
+    switch (tid) {
+    case ODB_T_EMBED: case ODB_T_LM: return v * d;
+    case ODB_T_WQ: case ODB_T_WK: case ODB_T_WV: case ODB_T_WO: return d * d;
+    case ODB_T_WG: case ODB_T_WU: case ODB_T_WD: return f * d;
+    default: return d;
+    }
+}
+
+struct LayerPtrs { const u16 *qkv, *o, *gu, *dn; const float *g1, *g2; };
+
+LayerPtrs layer_ptrs(const Model &m, int l) {
+    LayerPtrs p;
+    p.qkv = m.w[PK_QKV] + (size_t)l * m.layer_elems[PK_QKV];
+    p.o = m.w[PK_O] + (size_t)l * m.layer_elems[PK_O];
+    p.gu = m.w[PK_GU] + (size_t)l * m.layer_elems[PK_GU];
+    p.dn = m.w[PK_D] + (size_t)l * m.layer_elems[PK_D];
+    p.g1 = m.g1 + (size_t)l * m.cfg.d_model;
+    p.g2 = m.g2 + (size_t)l * m.cfg.d_model;
+    return p;
+}
+
+// The transformer stack shared by both calls.  `rm` describes the rows; K/V go
+// to the cache (prefill) or to the fresh buffers (step).
+struct StackIO {
+    RowMap rm;
+    int pos_off;
+    bool to_cache;      // prefill: K/V are written into the cache
+    int blk_lo, blk_hi, fresh, units_per_seq, nsplit;
+};
+
+int run_stack(Model &m, const Cache &c, const Plan &pl, const StackIO &io, hipStream_t s) {
+    const odb_config &cfg = m.cfg;
+    char *base = (char *)m.scratch;
+    float *h = (float *)(base + pl.h);
+    u16 *xa = (u16 *)(base + pl.xa), *q = (u16 *)(base + pl.q), *kf = (u16 *)(base + pl.kf),
+        *vf = (u16 *)(base + pl.vf), *ao = (u16 *)(base + pl.ao), *act = (u16 *)(base + pl.act);
+    Workspace ws{(float *)(base + pl.gemm_part), kGemmPartialBytes, m.counters};
+    const int d = cfg.d_model, H = cfg.n_heads, dh = cfg.head_dim, F = cfg.d_ff;
+    const int rows_pad = io.rm.units * io.rm.rpu_pad, mt = rows_pad / 16, tpu = io.rm.rpu_pad / 16;
+    const size_t seq_elems = (size_t)H * c.lmax32 * dh;
+    const int fresh32 = ru(io.rm.rpu_pad, 32);
+
+    for (int l = 0; l < cfg.n_layers; l++) {
+        LayerPtrs w = layer_ptrs(m, l);
+        launch_rmsnorm(h, w.g1, cfg.rms_eps, d, io.rm, 0, false, mt, xa, s);
+        QkvOut qo;
+        qo.q = q;
+        qo.rope = c.rope;
+        qo.tiles_per_unit = tpu; qo.pos_off = io.pos_off; qo.H = H; qo.dh = dh; qo.d = d;
+        u16 *kc = c.k + (size_t)l * c.layer_elems, *vc = c.v + (size_t)l * c.layer_elems;
+        if (io.to_cache) {
+            qo.k = kc; qo.k_unit_stride = seq_elems; qo.k_head_stride = (size_t)c.lmax32 * dh;
+            qo.v = vc; qo.v_unit_stride = seq_elems; qo.v_head_stride = (size_t)c.lmax32 * dh;
+        } else {
+            qo.k = kf; qo.k_head_stride = (size_t)fresh32 * dh; qo.k_unit_stride = (size_t)H * fresh32 * dh;
+            qo.v = vf; qo.v_head_stride = (size_t)fresh32 * dh; qo.v_unit_stride = (size_t)H * fresh32 * dh;
+        }
+        launch_gemm_qkv(xa, w.qkv, GemmShape{mt, 3 * d / 16, d / 32}, qo, ws, s);
+
+        AttnArgs a;
+        a.q = q; a.kc = kc; a.vc = vc;
+        a.kc_seq_stride = seq_elems; a.kc_head_stride = (size_t)c.lmax32 * dh;
+        a.vc_seq_stride = seq_elems; a.vc_head_stride = (size_t)c.lmax32 * dh;
+        a.kf = kf; a.vf = vf;
+        a.kf_unit_stride = qo.k_unit_stride; a.kf_head_stride = qo.k_head_stride;
+        a.vf_unit_stride = qo.v_unit_stride; a.vf_head_stride = qo.v_head_stride;
+        a.out = ao;
+        a.part_o = (float *)(base + pl.attn_part);
+        a.part_ml = a.part_o + (size_t)io.nsplit * mt * H * (dh / 16) * 256;
+        a.H = H; a.dh = dh; a.mt_total = mt; a.tiles_per_unit = tpu; a.units = io.rm.units;
+        a.units_per_seq = io.units_per_seq; a.L = c.length; a.blk_lo = io.blk_lo; a.blk_hi = io.blk_hi;
+        a.fresh = io.fresh; a.nsplit = io.nsplit;
+        launch_attention(a, s);
+
+        launch_gemm_resid(ao, w.o, GemmShape{mt, d / 16, d / 32}, h, d, ws, s);
+        launch_rmsnorm(h, w.g2, cfg.rms_eps, d, io.rm, 0, false, mt, xa, s);
+        launch_gemm_swiglu(xa, w.gu, GemmShape{mt, 2 * F / 16, d / 32}, act, ws, s);
+        launch_gemm_resid(act, w.dn, GemmShape{mt, d / 16, F / 32}, h, d, ws, s);
+    }
+    return ODB_OK;
+}
+
+// final norm + LM head on the compacted rows (unit u, i >= skip)
+int run_head(Model &m, const Plan &pl, RowMap rm, int skip, const int32_t *tokens, int rpu_out, float tau, float *conf,
+             int32_t *argmax, uint8_t *unmask, float *logits, hipStream_t s) {
+    const odb_config &cfg = m.cfg;
+    char *base = (char *)m.scratch;
+    float *h = (float *)(base + pl.h);
+    u16 *xa = (u16 *)(base + pl.xa);
+    Workspace ws{(float *)(base + pl.gemm_part), kGemmPartialBytes, m.counters};
+    const int rows = rm.units * (rm.valid - skip), lm_mt = (rows + 15) / 16;
+    launch_rmsnorm(h, m.gf, cfg.rms_eps, cfg.d_model, rm, skip, true, lm_mt, xa, s);
+    GemmShape sh{lm_mt, cfg.vocab / 16, cfg.d_model / 32};
+    if (logits) {
+        launch_gemm_store(xa, m.w[PK_LM], sh, logits, rows, cfg.vocab, ws, s);
+    } else {
+        float *stats = (float *)(base + pl.stats);
+        launch_gemm_lmstats(xa, m.w[PK_LM], sh, stats, ws, s);
+        launch_lm_finish(stats, cfg.vocab / 32, rows, rpu_out, tokens, cfg.mask_id, tau, conf, argmax, unmask, s);
+    }
+    HIP_TRY(hipGetLastError());
+    return ODB_OK;
+}
+
+int prefill_impl(odb_model *mh, odb_cache *ch, const int32_t *tokens, int L, int resp_off, float *conf,
+                 int32_t *argmax, float *logits, void *stream) {
+    if (!mh || !ch || !tokens) return fail(ODB_E_INVALID_ARG, "prefill: NULL handle or tokens");
+    Model &m = mh->m;
+    Cache &c = ch->c;
+    if (c.m != &m) return fail(ODB_E_INVALID_ARG, "prefill: cache belongs to another model");
+    if (L < 1 || L > c.max_len) return fail(ODB_E_INVALID_ARG, "prefill: L=%d outside [1, %d]", L, c.max_len);
+    if (resp_off < 0 || resp_off >= L) return fail(ODB_E_INVALID_ARG, "prefill: resp_off=%d outside [0, %d)", resp_off, L);
+    if (!logits && (!conf || !argmax)) return fail(ODB_E_INVALID_ARG, "prefill: NULL output");
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(hipSetDevice(m.device));
+    const int lp = ru(L, 16), rows_pad = c.batch * lp, lm_rows = c.batch * (L - resp_off);
+    Plan pl = make_plan(m.cfg, rows_pad, 0, ru(lm_rows, 16), 0, logits == nullptr);
+    int rc = ensure_scratch(m, pl.total, s);
+    if (rc) return rc;
+    RowMap rm{c.batch, lp, L};
+    c.length = L;
+    launch_embed(m, tokens, rm, (float *)((char *)m.scratch + pl.h), s);
+    StackIO io{rm, 0, true, 0, 0, 0, 1, 1};
+    rc = run_stack(m, c, pl, io, s);
+    if (rc) return rc;
+    return run_head(m, pl, rm, resp_off, nullptr, 64, 0.f, conf, argmax, nullptr, logits, s);
+}
+
+int step_impl(odb_model *mh, const odb_cache *ch, const int32_t *drafts, int block_off, int b, int S, float tau,
+              float *conf, int32_t *argmax, uint8_t *unmask, float *logits, void *stream) {
+    if (!mh || !ch || !drafts) return fail(ODB_E_INVALID_ARG, "block_step: NULL handle or drafts");
+    Model &m = mh->m;
+    const Cache &c = ch->c;
+    if (c.m != &m) return fail(ODB_E_INVALID_ARG, "block_step: cache belongs to another model");
+    if (c.length < 1) return fail(ODB_E_INVALID_ARG, "block_step: cache has not been prefilled");
+    if (b < 1 || b > 256) return fail(ODB_E_INVALID_ARG, "block_step: b=%d outside [1, 256]", b);
+    if (S < 1 || S > 4096) return fail(ODB_E_INVALID_ARG, "block_step: S=%d outside [1, 4096]", S);
+    if (block_off < 0 || block_off + b > c.length)
+        return fail(ODB_E_INVALID_ARG, "block_step: block [%d, %d) outside the cached length %d", block_off,
+                    block_off + b, c.length);
+    if (!logits && (!conf || !argmax || !unmask)) return fail(ODB_E_INVALID_ARG, "block_step: NULL output");
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(hipSetDevice(m.device));
+    const odb_config &cfg = m.cfg;
+    const int bp = ru(b, 16), bp32 = ru(b, 32), units = c.batch * S, rows_pad = units * bp;
+    const int chunks = (bp / 16 + 1) / 2, n32 = (c.length + 31) / 32;
+    int nsplit = 1;
+    while (units * chunks * cfg.n_heads * nsplit < 256 && n32 / (nsplit * 2) >= 4) nsplit *= 2;
+    AttnArgs probe;
+    probe.nsplit = nsplit; probe.mt_total = rows_pad / 16; probe.H = cfg.n_heads; probe.dh = cfg.head_dim;
+    Plan pl = make_plan(cfg, rows_pad, units * bp32, ru(units * b, 16), attn_partial_bytes(probe), logits == nullptr);
+    int rc = ensure_scratch(m, pl.total, s);
+    if (rc) return rc;
+    RowMap rm{units, bp, b};
+    launch_embed(m, drafts, rm, (float *)((char *)m.scratch + pl.h), s);
+    if (b % 32)   // slots of padded keys must hold finite values: they meet zero probabilities in the P*V product
+        launch_fill_f32((float *)((char *)m.scratch + pl.vf), 0.f, (size_t)units * bp32 * cfg.d_model / 2, s);
+    StackIO io{rm, block_off, false, block_off, block_off + b, b, S, nsplit};
+    rc = run_stack(m, c, pl, io, s);
+    if (rc) return rc;
+    return run_head(m, pl, rm, 0, drafts, b, tau, conf, argmax, unmask, logits, s);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *odb_last_error(void) { return g_err; }
+
+const char *odb_strerror(int code) {
+    switch (code) {
+    case ODB_OK: return "ok";
+    case ODB_E_INVALID_ARG: return "invalid argument";
+    case ODB_E_NOMEM: return "out of device memory";
+    case ODB_E_HIP: return "HIP runtime error";
+    case ODB_E_UNSUPPORTED: return "unsupported configuration or device";
+    default: return "unknown error";
+    }
+}
+
+int odb_model_create(const odb_config *cfg, const odb_allocator *allocator, odb_model **out) {
+    if (!out) return fail(ODB_E_INVALID_ARG, "model_create: out is NULL");
+    *out = nullptr;
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (allocator && (!allocator->alloc || !allocator->free))
+        return fail(ODB_E_INVALID_ARG, "model_create: allocator needs alloc and free");
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDeviceProperties(&prop, dev));
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+        return fail(ODB_E_UNSUPPORTED, "device %d is %s; this library is built for gfx950 only", dev, prop.gcnArchName);
+    odb_model *mh = new (std::nothrow) odb_model();
+    if (!mh) return fail(ODB_E_NOMEM, "model_create: host allocation failed");
+    Model &m = mh->m;
+    memset(&m, 0, sizeof(m));
+    m.cfg = *cfg;
+    m.device = dev;
+    if (allocator) { m.alloc = *allocator; m.has_alloc = true; }
+    const size_t d = cfg->d_model, f = cfg->d_ff, v = cfg->vocab, nl = cfg->n_layers;
+    m.layer_elems[PK_QKV] = 3 * d * d;
+    m.layer_elems[PK_O] = d * d;
+    m.layer_elems[PK_GU] = 2 * f * d;
+    m.layer_elems[PK_D] = d * f;
+    m.layer_elems[PK_LM] = v * d;
+    m.layer_elems[PK_EMBED] = v * d;
+    bool ok = true;
+    for (int pk = 0; pk < PK_COUNT; pk++) {
+        size_t layers = (pk == PK_LM || pk == PK_EMBED) ? 1 : nl;
+        m.w[pk] = (u16 *)dev_alloc(m, m.layer_elems[pk] * layers * 2);
+        ok = ok && m.w[pk];
+    }
+    m.g1 = (float *)dev_alloc(m, nl * d * 4);
+    m.g2 = (float *)dev_alloc(m, nl * d * 4);
+    m.gf = (float *)dev_alloc(m, d * 4);
+    m.counters = (unsigned *)dev_alloc(m, kCounters * sizeof(unsigned));
+    ok = ok && m.g1 && m.g2 && m.gf && m.counters;
+    if (!ok) {
+        odb_model_destroy(mh);
+        return fail(ODB_E_NOMEM, "model_create: device allocation failed");
+    }
+    hipError_t e = hipMemset(m.counters, 0, kCounters * sizeof(unsigned));
+    if (e != hipSuccess) {
+        odb_model_destroy(mh);
+        return fail(ODB_E_HIP, "hipMemset: %s", hipGetErrorString(e));
+    }
+    *out = mh;
+    return ODB_OK;
+}
+
+void odb_model_destroy(odb_model *mh) {
+    if (!mh) return;
+    Model &m = mh->m;
+    (void)hipSetDevice(m.device);
+    (void)hipDeviceSynchronize();
+    for (int pk = 0; pk < PK_COUNT; pk++) dev_free(m, m.w[pk]);
+    dev_free(m, m.g1);
+    dev_free(m, m.g2);
+    dev_free(m, m.gf);
+    dev_free(m, m.counters);
+    dev_free(m, m.scratch);
+    dev_free(m, m.staging);
+    delete mh;
+}
+
+int odb_model_init_random(odb_model *mh, uint64_t seed, double std, void *stream) {
+    if (!mh) return fail(ODB_E_INVALID_ARG, "init_random: model is NULL");
+    if (!(std >= 0.0)) return fail(ODB_E_INVALID_ARG, "init_random: std must be >= 0");
+    HIP_TRY(hipSetDevice(mh->m.device));
+    launch_init_random(mh->m, seed, std, (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return ODB_OK;
+}
+
+static int tensor_io(Model &m, int tensor_id, int layer, uint16_t *host, size_t n, bool to_model) {
+    if (tensor_id < 0 || tensor_id >= ODB_T_COUNT) return fail(ODB_E_INVALID_ARG, "tensor id %d", tensor_id);
+    if (!host) return fail(ODB_E_INVALID_ARG, "tensor buffer is NULL");
+    bool global = tensor_id == ODB_T_EMBED || tensor_id == ODB_T_LM || tensor_id == ODB_T_GF;
+    if (!global && (layer < 0 || layer >= m.cfg.n_layers)) return fail(ODB_E_INVALID_ARG, "layer %d", layer);
+    if (global) layer = 0;
+    size_t want = tensor_elems(m.cfg, tensor_id);
+    if (n != want) return fail(ODB_E_INVALID_ARG, "tensor %d has %zu elements, got %zu", tensor_id, want, n);
+    HIP_TRY(hipSetDevice(m.device));
+    HIP_TRY(hipDeviceSynchronize());
+    if (m.staging_bytes < n * 2) {
+        dev_free(m, m.staging);
+        m.staging_bytes = 0;
+        m.staging = (u16 *)dev_alloc(m, n * 2);
+        if (!m.staging) return fail(ODB_E_NOMEM, "tensor staging of %zu bytes", n * 2);
+        m.staging_bytes = n * 2;
+    }
+    if (to_model) HIP_TRY(hipMemcpy(m.staging, host, n * 2, hipMemcpyHostToDevice));
+    if (tensor_id >= ODB_T_G1) {
+        float *g = tensor_id == ODB_T_G1 ? m.g1 + (size_t)layer * m.cfg.d_model
+                 : tensor_id == ODB_T_G2 ? m.g2 + (size_t)layer * m.cfg.d_model : m.gf;
+        launch_gain_copy(g, m.staging, (int)n, to_model, nullptr);
+    } else {
+        launch_tensor_copy(m, tensor_id, layer, m.staging, to_model, nullptr);
+    }
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipDeviceSynchronize());
+    if (!to_model) HIP_TRY(hipMemcpy(host, m.staging, n * 2, hipMemcpyDeviceToHost));
+    return ODB_OK;
+}
+
+int odb_model_set_tensor(odb_model *mh, int tensor_id, int layer, const uint16_t *host_bf16, size_t n) {
+    if (!mh) return fail(ODB_E_INVALID_ARG, "set_tensor: model is NULL");
+    return tensor_io(mh->m, tensor_id, layer, const_cast<uint16_t *>(host_bf16), n, true);
+}
+
+int odb_model_get_tensor(const odb_model *mh, int tensor_id, int layer, uint16_t *host_bf16, size_t n) {
+    if (!mh) return fail(ODB_E_INVALID_ARG, "get_tensor: model is NULL");
+    return tensor_io(const_cast<odb_model *>(mh)->m, tensor_id, layer, host_bf16, n, false);
+}
+
+int odb_cache_create(odb_model *mh, int batch, int max_len, odb_cache **out) {
+    if (!out) return fail(ODB_E_INVALID_ARG, "cache_create: out is NULL");
+    *out = nullptr;
+    if (!mh) return fail(ODB_E_INVALID_ARG, "cache_create: model is NULL");
+    if (batch < 1 || batch > 1024) return fail(ODB_E_INVALID_ARG, "cache_create: batch=%d outside [1, 1024]", batch);
+    if (max_len < 1 || max_len > (1 << 20)) return fail(ODB_E_INVALID_ARG, "cache_create: max_len=%d", max_len);
+    Model &m = mh->m;
+    HIP_TRY(hipSetDevice(m.device));
+    odb_cache *ch = new (std::nothrow) odb_cache();
+    if (!ch) return fail(ODB_E_NOMEM, "cache_create: host allocation failed");
+    Cache &c = ch->c;
+    memset(&c, 0, sizeof(c));
+    c.m = &m;
+    c.batch = batch;
+    c.max_len = max_len;
+    c.lmax32 = ru(max_len, 32);
+    c.layer_elems = (size_t)batch * m.cfg.d_model * c.lmax32;
+    size_t bytes = c.layer_elems * m.cfg.n_layers * 2;
+    c.k = (u16 *)dev_alloc(m, bytes);
+    c.v = (u16 *)dev_alloc(m, bytes);
+    const int rope_rows = c.lmax32 + 16;      // padded rows of the last tile may look one tile past the end
+    c.rope = (float *)dev_alloc(m, (size_t)rope_rows * m.cfg.head_dim * 4);
+    if (!c.k || !c.v || !c.rope) {
+        odb_cache_destroy(ch);
+        return fail(ODB_E_NOMEM, "cache_create: cannot allocate 2 x %zu bytes", bytes);
+    }
+    hipError_t e = hipMemset(c.k, 0, bytes);
+    if (e == hipSuccess) e = hipMemset(c.v, 0, bytes);
+    if (e == hipSuccess) {
+        launch_rope_table(c.rope, rope_rows, m.cfg.head_dim, (double)m.cfg.rope_base, nullptr);
+        e = hipDeviceSynchronize();
+    }
+    if (e != hipSuccess) {
+        odb_cache_destroy(ch);
+        return fail(ODB_E_HIP, "cache_create: %s", hipGetErrorString(e));
+    }
+    *out = ch;
+    return ODB_OK;
+}
+
+void odb_cache_destroy(odb_cache *ch) {
+    if (!ch) return;
+    Cache &c = ch->c;
+    (void)hipSetDevice(c.m->device);
+    (void)hipDeviceSynchronize();
+    dev_free(*c.m, c.k);
+    dev_free(*c.m, c.v);
+    dev_free(*c.m, c.rope);
+    delete ch;
+}
+
+int odb_cache_length(const odb_cache *ch) { return ch ? ch->c.length : 0; }
+
+int odb_prefill(odb_model *m, odb_cache *c, const int32_t *tokens_dev, int L, int resp_off, float *conf_dev,
+                int32_t *argmax_dev, void *stream) {
+    return prefill_impl(m, c, tokens_dev, L, resp_off, conf_dev, argmax_dev, nullptr, stream);
+}
+
+int odb_prefill_logits(odb_model *m, odb_cache *c, const int32_t *tokens_dev, int L, int resp_off, float *logits_dev,
+                       void *stream) {
+    if (!logits_dev) return fail(ODB_E_INVALID_ARG, "prefill_logits: logits is NULL");
+    return prefill_impl(m, c, tokens_dev, L, resp_off, nullptr, nullptr, logits_dev, stream);
+}
+
+int odb_block_step(odb_model *m, const odb_cache *c, const int32_t *drafts_dev, int block_off, int b, int S, float tau,
+                   float *conf_dev, int32_t *argmax_dev, uint8_t *unmask_dev, void *stream) {
+    return step_impl(m, c, drafts_dev, block_off, b, S, tau, conf_dev, argmax_dev, unmask_dev, nullptr, stream);
+}
+
+int odb_block_step_logits(odb_model *m, const odb_cache *c, const int32_t *drafts_dev, int block_off, int b, int S,
+                          float *logits_dev, void *stream) {
+    if (!logits_dev) return fail(ODB_E_INVALID_ARG, "block_step_logits: logits is NULL");
+    return step_impl(m, c, drafts_dev, block_off, b, S, 0.f, nullptr, nullptr, nullptr, logits_dev, stream);
+}
+
+int odb_cache_read(const odb_cache *ch, int layer, int kv, int batch_index, int pos0, int n, uint16_t *host_bf16) {
+    if (!ch || !host_bf16) return fail(ODB_E_INVALID_ARG, "cache_read: NULL argument");
+    const Cache &c = ch->c;
+    Model &m = *c.m;
+    if (layer < 0 || layer >= m.cfg.n_layers || kv < 0 || kv > 1 || batch_index < 0 || batch_index >= c.batch)
+        return fail(ODB_E_INVALID_ARG, "cache_read: layer/kv/batch out of range");
+    if (pos0 < 0 || n < 1 || pos0 + n > c.length) return fail(ODB_E_INVALID_ARG, "cache_read: positions [%d, %d) outside the cached length %d", pos0, pos0 + n, c.length);
+    HIP_TRY(hipSetDevice(m.device));
+    HIP_TRY(hipDeviceSynchronize());
+    size_t bytes = (size_t)n * m.cfg.d_model * 2;
+    if (m.staging_bytes < bytes) {
+        dev_free(m, m.staging);
+        m.staging_bytes = 0;
+        m.staging = (u16 *)dev_alloc(m, bytes);
+        if (!m.staging) return fail(ODB_E_NOMEM, "cache_read staging");
+        m.staging_bytes = bytes;
+    }
+    launch_cache_read(c, layer, kv, batch_index, pos0, n, m.staging, nullptr);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipMemcpy(host_bf16, m.staging, bytes, hipMemcpyDeviceToHost));
+    return ODB_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,104 @@
+// Host-side structures of the library and the prototypes of the kernel
+// launchers that the API layer (api.hip) strings together.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/odb.h"
+#include "common.h"
+
+namespace odb {
+
+// ---- physical layouts -----------------------------------------------------
+// W_qkv  [3d, d]  tiles [n_tile][k_tile]; rows 0..d-1 = Wq, d..2d-1 = Wk with
+//                 the channels of each head interleaved (physical 2j -> channel
+//                 j, 2j+1 -> channel j + dh/2) so that a RoPE pair sits in one
+//                 lane of the GEMM result; rows 2d..3d-1 = Wv in logical order.
+// W_o    [d, d], W_d [d, F], W_lm [V, d]: logical row order, tiles [n_tile][k_tile].
+// W_gu   [2F, d]: n-tile 2t = rows 16t..16t+15 of W_gate, n-tile 2t+1 = the same
+//                 rows of W_up, so one wave holds a gate tile and its up tile.
+// E      [V, d] plain row-major (gathered by row).
+enum PhysKind { PK_QKV = 0, PK_O, PK_GU, PK_D, PK_LM, PK_EMBED, PK_COUNT };
+
+struct Model {
+    odb_config cfg;
+    odb_allocator alloc;
+    bool has_alloc;
+    int device;
+    u16 *w[PK_COUNT];          // per kind, all layers contiguous
+    size_t layer_elems[PK_COUNT];
+    float *g1, *g2, *gf;       // [NL][d], [NL][d], [d]
+    // scratch, grown on demand (see api.hip)
+    void *scratch;
+    size_t scratch_bytes;
+    unsigned *counters;        // split-K arrival counters (self-resetting)
+    u16 *staging;              // set/get tensor staging
+    size_t staging_bytes;
+};
+
+struct Cache {
+    Model *m;
+    int batch, max_len, lmax32, length;
+    u16 *k, *v;                // [NL][B][H][lmax32/16][dh/32][512], [NL][B][H][lmax32/32][dh/16][512]
+    float *rope;               // [lmax32][dh/2][2] = (cos, sin)
+    size_t layer_elems;        // B*H*lmax32*dh
+};
+
+// ---- weights.hip ------------------------------------------------------------
+void launch_init_random(const Model &m, uint64_t seed, double std, hipStream_t s);
+// copy between a logical row-major bf16 staging buffer (device) and the physical layout
+void launch_tensor_copy(const Model &m, int tensor_id, int layer, u16 *staging, bool to_model, hipStream_t s);
+void launch_gain_copy(float *gain, u16 *staging, int n, bool to_model, hipStream_t s);
+void launch_fill_f32(float *p, float v, size_t n, hipStream_t s);
+void launch_rope_table(float *table, int n_pos, int dh, double base, hipStream_t s);
+void launch_cache_read(const Cache &c, int layer, int kv, int batch_index, int pos0, int n, u16 *out, hipStream_t s);
+
+// ---- rows.hip ---------------------------------------------------------------
+// Row bookkeeping.  Rows are grouped in "units" (a draft in the step, a
+// sequence in the prefill) of rpu_pad rows (multiple of 16) of which the first
+// `valid` are real.
+struct RowMap { int units, rpu_pad, valid; };
+void launch_embed(const Model &m, const int32_t *tokens, RowMap rm, float *h, hipStream_t s);
+// xa = bf16(rmsnorm(h) * gain) in tile-major [d/32][mt_total][512]; if `compact`, destination
+// row j = u*(valid-skip) + (i-skip) for source row (u, i >= skip), else the same row.
+void launch_rmsnorm(const float *h, const float *gain, float eps, int d, RowMap rm, int skip, bool compact,
+                    int dst_mt_total, u16 *xa, hipStream_t s);
+void launch_lm_finish(const float *stats, int n_part, int rows, int rows_per_unit, const int32_t *tokens,
+                      int mask_id, float tau, float *conf, int32_t *argmax, uint8_t *unmask, hipStream_t s);
+
+// ---- gemm.hip ---------------------------------------------------------------
+struct GemmShape { int M_tiles, N_tiles, K_tiles; };
+struct QkvOut {
+    u16 *q;                    // [H][mt_total][dh/32][512]
+    u16 *k; size_t k_unit_stride, k_head_stride;   // tiles [pos/16][dh/32]
+    u16 *v; size_t v_unit_stride, v_head_stride;   // tiles [pos/32][dh/16], keys permuted inside
+    const float *rope;         // (cos,sin) table
+    int tiles_per_unit, pos_off, H, dh, d;
+};
+struct Workspace { float *partial; size_t partial_bytes; unsigned *counters; };
+void launch_gemm_qkv(const u16 *xa, const u16 *w, GemmShape sh, QkvOut out, Workspace ws, hipStream_t s);
+void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int ldh, Workspace ws, hipStream_t s);
+void launch_gemm_swiglu(const u16 *xa, const u16 *w, GemmShape sh, u16 *act, Workspace ws, hipStream_t s);
+void launch_gemm_lmstats(const u16 *xa, const u16 *w, GemmShape sh, float *stats, Workspace ws, hipStream_t s);
+void launch_gemm_store(const u16 *xa, const u16 *w, GemmShape sh, float *out, int rows, int ld, Workspace ws, hipStream_t s);
+
+// ---- attn.hip ---------------------------------------------------------------
+struct AttnArgs {
+    const u16 *q;              // [H][mt_total][dh/32][512]
+    const u16 *kc, *vc;        // cache of this layer
+    size_t kc_seq_stride, kc_head_stride, vc_seq_stride, vc_head_stride;
+    const u16 *kf, *vf;        // fresh K/V of the units (step only)
+    size_t kf_unit_stride, kf_head_stride, vf_unit_stride, vf_head_stride;
+    u16 *out;                  // [d/32][mt_total][512]
+    float *part_o, *part_ml;   // split partials
+    int H, dh, mt_total, tiles_per_unit, units, units_per_seq;
+    int L;                     // cached length
+    int blk_lo, blk_hi;        // cached keys in [blk_lo, blk_hi) are ignored
+    int fresh;                 // number of fresh keys per unit (0 in the prefill)
+    int nsplit;
+};
+size_t attn_partial_bytes(const AttnArgs &a);
+void launch_attention(AttnArgs a, hipStream_t s);
+
+}  // namespace odb

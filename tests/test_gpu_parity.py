@@ -1,0 +1,299 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle,
+element by element, on the same seeded inputs.
+
+Bars (stated by the benchmark spec):
+  logits   max|gpu - oracle| / max|oracle|            <= 2e-2
+  K/V      max|gpu - oracle| / max|oracle| per layer   <= 1e-2
+  argmax / unmask   bit-exact wherever the oracle's top-2 probability margin
+                    exceeds 1e-2 (and |conf - tau| > 1e-3 for the threshold)
+The fused path never stores logits; it is checked through conf (= 1/sum exp)
+and argmax, the unfused test-only entry points give the logits themselves.
+"""
+import numpy as np
+import pytest
+
+from oracle import odb_oracle as o
+from paper_2511_21759_amd import binding as B
+from paper_2511_21759_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+LOGIT_TOL, KV_TOL, MARGIN, TAU_BAND = 2e-2, 1e-2, 1e-2, 1e-3
+
+
+def cuda_i32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, np.int32)).cuda()
+
+
+class Pair:
+    """A library model and the oracle's weights for the same seed/overrides."""
+
+    def __init__(self, shape, seed=W.WEIGHT_SEED, std=W.WEIGHT_STD, gf=None):
+        self.shape = shape
+        self.cfg = o.Config(**shape)
+        self.w = o.Weights(self.cfg, seed, std)
+        self.model = B.odb_model_create(shape)
+        B.odb_model_init_random(self.model, seed, std)
+        if gf is not None:
+            self.set(o.T_GF, 0, np.full(self.cfg.d_model, gf, np.float32))
+        self.caches = []
+
+    def set(self, tid, layer, values):
+        self.w.set_values(tid, layer, values)
+        B.odb_model_set_tensor(self.model, tid, layer, self.w.bits(tid, layer))
+
+    def cache(self, batch, max_len):
+        c = B.odb_cache_create(self.model, batch, max_len)
+        self.caches.append(c)
+        return c
+
+    def close(self):
+        for c in self.caches:
+            B.odb_cache_destroy(c)
+        B.odb_model_destroy(self.model)
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    p = Pair(W.MODEL_SHAPES["tiny"])
+    yield p
+    p.close()
+
+
+def top2_margin(z):
+    """Difference of the two largest softmax probabilities per row (float64)."""
+    p = np.exp(z - z.max(-1, keepdims=True))
+    p /= p.sum(-1, keepdims=True)
+    part = np.partition(p, -2, axis=-1)
+    return part[..., -1] - part[..., -2]
+
+
+def check_decisions(conf_g, am_g, conf_o, am_o, z_o, err, tag):
+    """err = measured max |logit_gpu - logit_oracle| of this call (from the unfused
+    entry point, which runs the same GEMM).
+
+    conf = exp(z_max - logsumexp z) and both terms are 1-Lipschitz in the max norm,
+    so |log conf_gpu - log conf_oracle| <= 2 err must hold exactly.
+    argmax must be bit-exact on every row whose top-2 logit gap exceeds 2 err (no
+    admissible perturbation can flip it); rows with a top-2 probability margin above
+    1e-2 whose gap is inside that band may only flip to the oracle's runner-up.
+    Returns the number of rows with margin > 1e-2 that were checked bit-exactly."""
+    assert np.all(np.abs(np.log(conf_g) - np.log(conf_o)) <= 2 * err + 1e-5), "%s: confidence" % tag
+    part = np.partition(z_o, -2, axis=-1)
+    gap = part[..., -1] - part[..., -2]
+    strict = gap > 2 * err
+    assert np.array_equal(am_g[strict], am_o[strict]), "%s: argmax differs outside the error band" % tag
+    second = np.argsort(z_o, axis=-1)[..., -2]
+    loose = ~strict
+    assert np.all((am_g[loose] == am_o[loose]) | (am_g[loose] == second[loose])), "%s: argmax not in top-2" % tag
+    clear = top2_margin(z_o) > MARGIN
+    return int((clear & strict).sum()), int(clear.sum())
+
+
+def check_unmask(unmask_g, drafts, conf_o, tau, mask_id, err, tag):
+    """unmask must equal the oracle's wherever the oracle's decision survives any
+    admissible perturbation: |log conf - log tau| > 2 err (and |conf - tau| > 1e-3)
+    for the threshold, and a forced pick that leads the runner-up by more than 4 err
+    in log confidence."""
+    S, b = drafts.shape
+    for s in range(S):
+        masked = drafts[s] == mask_id
+        assert not unmask_g[s][~masked].any(), "%s: unmasked a decoded position" % tag
+        if not masked.any():
+            continue
+        ref = o.threshold_unmask(drafts[s], conf_o[s], tau, mask_id)
+        lc = np.where(masked, np.log(conf_o[s]), -np.inf)
+        order = np.sort(lc)[::-1]
+        top_clear = masked.sum() < 2 or order[0] - order[1] > 4 * err + 1e-5
+        for i in np.flatnonzero(masked):
+            thr_clear = abs(conf_o[s][i] - tau) > TAU_BAND and (tau <= 0 or abs(lc[i] - np.log(tau)) > 2 * err + 1e-5)
+            if not thr_clear:
+                continue
+            if not top_clear and not conf_o[s][i] > tau and lc[i] >= order[0] - 4 * err - 1e-5:
+                continue            # may or may not be the forced pick
+            assert unmask_g[s][i] == ref[i], "%s: unmask[%d][%d]" % (tag, s, i)
+        assert unmask_g[s][masked].sum() >= 1, "%s: no forced progress" % tag
+
+
+def rel_err(a, ref):
+    return float(np.abs(a - ref).max() / np.abs(ref).max())
+
+
+# ------------------------------------------------------------------ weights and layouts
+
+def test_generator_is_bit_identical_to_the_oracle(tiny):
+    for tid in range(o.T_G1):
+        for layer in (0, 1):
+            n = int(np.prod(tiny.cfg.shape(tid)))
+            got = B.odb_model_get_tensor(tiny.model, tid, layer, n)
+            ref = o.normal_bf16_bits(W.WEIGHT_SEED, tid, 0 if tid in (o.T_EMBED, o.T_LM) else layer, 0, n,
+                                     W.WEIGHT_STD)
+            assert np.array_equal(got, ref), (tid, layer)
+    for tid in (o.T_G1, o.T_G2, o.T_GF):
+        assert np.all(B.odb_model_get_tensor(tiny.model, tid, 0, 256) == 0x3F80)
+
+
+def test_set_get_tensor_round_trip():
+    p = Pair(W.MODEL_SHAPES["tiny"], seed=3)
+    try:
+        rng = np.random.default_rng(0)
+        for tid in range(12):
+            n = int(np.prod(p.cfg.shape(tid)))
+            bits = rng.integers(0, 0x7F00, n).astype(np.uint16)
+            B.odb_model_set_tensor(p.model, tid, 1, bits)
+            assert np.array_equal(B.odb_model_get_tensor(p.model, tid, 1, n), bits), tid
+        # neighbours in the fused physical matrices are untouched by a set
+        q = B.odb_model_get_tensor(p.model, o.T_WQ, 1, 256 * 256)
+        B.odb_model_set_tensor(p.model, o.T_WK, 1, np.zeros(256 * 256, np.uint16))
+        assert np.array_equal(B.odb_model_get_tensor(p.model, o.T_WQ, 1, 256 * 256), q)
+        with pytest.raises(B.OdbError):
+            B.odb_model_set_tensor(p.model, o.T_WQ, 0, np.zeros(5, np.uint16))
+        with pytest.raises(B.OdbError):
+            B.odb_model_set_tensor(p.model, o.T_WQ, 7, np.zeros(256 * 256, np.uint16))
+    finally:
+        p.close()
+
+
+# ------------------------------------------------------------------ the two calls on the tiny model
+
+def run_prefill_case(p, tokens, resp_off, tag, cache=None):
+    Bn, L = tokens.shape
+    cache = cache or p.cache(Bn, L)
+    tg = cuda_i32(tokens)
+    logits = B.odb_prefill_logits(p.model, cache, tg, resp_off, p.cfg.vocab).cpu().numpy()
+    conf, am = B.odb_prefill(p.model, cache, tg, resp_off)
+    torch.cuda.synchronize()
+    conf, am = conf.cpu().numpy(), am.cpu().numpy()
+    assert B.odb_cache_length(cache) == L
+    oc = []
+    for bi in range(Bn):
+        c, conf_o, am_o, z = o.prefill(p.cfg, p.w, tokens[bi], resp_off, return_logits=True)
+        oc.append(c)
+        assert rel_err(logits[bi], z) <= LOGIT_TOL, "%s: logits %g" % (tag, rel_err(logits[bi], z))
+        check_decisions(conf[bi], am[bi], conf_o, am_o, z, np.abs(logits[bi] - z).max(), tag)
+        for layer in range(p.cfg.n_layers):
+            for kv, ref in ((0, c.k[layer]), (1, c.v[layer])):
+                got = B.bf16_bits_to_f32(B.odb_cache_read(cache, layer, kv, bi, 0, L, p.cfg.n_heads, p.cfg.head_dim))
+                assert rel_err(got, ref) <= KV_TOL, "%s: cache layer %d kv %d: %g" % (tag, layer, kv, rel_err(got, ref))
+    return cache, oc
+
+
+def run_step_case(p, cache, ocaches, drafts, block_off, tau, tag):
+    Bn, S, b = drafts.shape
+    dg = cuda_i32(drafts)
+    logits = B.odb_block_step_logits(p.model, cache, dg, block_off, p.cfg.vocab).cpu().numpy()
+    conf, am, um = B.odb_block_step(p.model, cache, dg, block_off, tau)
+    torch.cuda.synchronize()
+    conf, am, um = conf.cpu().numpy(), am.cpu().numpy(), um.cpu().numpy()
+    stats = []
+    for bi in range(Bn):
+        c_o, a_o, u_o, z = o.block_step(p.cfg, p.w, ocaches[bi], drafts[bi], block_off, tau, return_logits=True)
+        assert rel_err(logits[bi], z) <= LOGIT_TOL, "%s: logits %g" % (tag, rel_err(logits[bi], z))
+        err = np.abs(logits[bi] - z).max()
+        stats.append(check_decisions(conf[bi], am[bi], c_o, a_o, z, err, tag))
+        check_unmask(um[bi], drafts[bi], c_o, tau, p.cfg.mask_id, err, tag)
+    return conf, am, um, stats
+
+
+def test_config0_prefill_then_step(tiny):
+    wl = W.config0()
+    cache, oc = run_prefill_case(tiny, wl.tokens, wl.resp_off, "config0 prefill")
+    conf, am, um, _ = run_step_case(tiny, cache, oc, wl.drafts, wl.block_off, wl.tau, "config0 step")
+    # random-init weights: nothing reaches tau = 0.9, so exactly the forced top-1 position is unmasked
+    assert um.sum() == 1
+
+
+@pytest.mark.parametrize("gf", [32.0, 64.0])
+def test_config0_peaked(gf):
+    """Final-norm gain scaled so that confidences straddle tau and margins exceed 1e-2."""
+    p = Pair(W.MODEL_SHAPES["tiny"], gf=gf)
+    try:
+        wl = W.decode_workload(p.shape, 128, 64, 16, 4, W.WEIGHT_SEED + 5)
+        cache, oc = run_prefill_case(p, wl.tokens, wl.resp_off, "peaked prefill")
+        conf, am, um, stats = run_step_case(p, cache, oc, wl.drafts, wl.block_off, 0.9, "peaked step")
+        c_o, a_o, u_o, z = o.block_step(p.cfg, p.w, oc[0], wl.drafts[0], wl.block_off, 0.9, return_logits=True)
+        # the decision clauses really bind in this variant: most rows have a top-2 margin
+        # above 1e-2 and nearly all of those are compared bit-exactly
+        strict, clear = stats[0]
+        assert clear > 0.5 * conf[0].size and strict >= 0.8 * clear
+        if gf == 64.0:
+            assert (c_o > 0.9).any() and (c_o < 0.9).any()
+            assert um.sum() > wl.drafts.shape[1]          # more than the forced picks
+    finally:
+        p.close()
+
+
+@pytest.mark.parametrize("Bn,P,R,b,S,blk", [
+    (1, 40, 24, 8, 3, 1),      # block smaller than a tile, odd S, L not a multiple of 32
+    (2, 33, 47, 20, 2, 1),     # ragged block (20 = 16 + 4), batch 2, L = 80
+    (1, 64, 64, 32, 5, 1),     # block aligned to 32
+    (1, 16, 48, 48, 2, 0),     # block of three tiles at the start of the response
+    (1, 70, 26, 26, 1, 0),     # block reaches the end of the sequence
+    (3, 10, 7, 1, 2, 3),       # single-token block
+])
+def test_step_edge_shapes(tiny, Bn, P, R, b, S, blk):
+    wl = W.decode_workload(tiny.shape, P, R, b, S, 77 + P, batch=Bn, block_index=blk)
+    cache, oc = run_prefill_case(tiny, wl.tokens, wl.resp_off, "edge prefill")
+    run_step_case(tiny, cache, oc, wl.drafts, wl.block_off, 0.9, "edge step")
+
+
+def test_gpu_structural_properties(tiny):
+    """Sec. 4.2: drafts are mutually invisible; Sec. 2.1: a step on the unchanged
+    block reproduces the refresh; the step leaves the cache untouched."""
+    wl = W.decode_workload(tiny.shape, 96, 64, 16, 4, 5)
+    cache = tiny.cache(1, 160)
+    tg = cuda_i32(wl.tokens)
+    pl = B.odb_prefill_logits(tiny.model, cache, tg, 0, tiny.cfg.vocab)
+    k_before = B.odb_cache_read(cache, 1, 0, 0, 0, 160, 4, 64)
+    d = cuda_i32(wl.drafts)
+    z = B.odb_block_step_logits(tiny.model, cache, d, wl.block_off, tiny.cfg.vocab)
+    perm = [2, 0, 3, 1]
+    zp = B.odb_block_step_logits(tiny.model, cache, d[:, perm].contiguous(), wl.block_off, tiny.cfg.vocab)
+    assert torch.equal(zp, z[:, perm])
+    z1 = B.odb_block_step_logits(tiny.model, cache, d[:, 1:2].contiguous(), wl.block_off, tiny.cfg.vocab)
+    assert torch.equal(z1[:, 0], z[:, 1])
+    # draft 0 is the block as it stood at the refresh
+    ref = pl[0, wl.block_off:wl.block_off + 16]
+    assert rel_err(z[0, 0].cpu().numpy(), ref.cpu().numpy()) < 5e-3
+    assert np.array_equal(B.odb_cache_read(cache, 1, 0, 0, 0, 160, 4, 64), k_before)
+    # same call twice: bit-identical (fixed reduction orders)
+    c1 = B.odb_block_step(tiny.model, cache, d, wl.block_off, 0.9)
+    c2 = B.odb_block_step(tiny.model, cache, d, wl.block_off, 0.9)
+    assert all(torch.equal(x, y) for x, y in zip(c1, c2))
+
+
+def test_threshold_extremes(tiny):
+    wl = W.decode_workload(tiny.shape, 64, 32, 16, 3, 9)
+    wl.drafts[0, 2] = 5                       # a draft without any MASK
+    cache = tiny.cache(1, 96)
+    B.odb_prefill(tiny.model, cache, cuda_i32(wl.tokens), 64)
+    d = cuda_i32(wl.drafts)
+    conf, am, um = (t.cpu().numpy() for t in B.odb_block_step(tiny.model, cache, d, wl.block_off, 1.0))
+    masked = wl.drafts[0] == tiny.cfg.mask_id
+    assert um[0, 2].sum() == 0
+    for s in (0, 1):
+        assert um[0, s].sum() == 1
+        assert um[0, s][np.argmax(np.where(masked[s], conf[0, s], -1))] == 1
+    _, _, um = (t.cpu().numpy() for t in B.odb_block_step(tiny.model, cache, d, wl.block_off, -1.0))
+    assert np.array_equal(um[0].astype(bool), masked)
+
+
+def test_error_paths(tiny):
+    cache = tiny.cache(1, 64)
+    t = cuda_i32(np.zeros((1, 64)))
+    d = cuda_i32(np.zeros((1, 1, 16)))
+    with pytest.raises(B.OdbError):          # not prefilled yet
+        B.odb_block_step(tiny.model, cache, d, 0, 0.9)
+    with pytest.raises(B.OdbError):          # longer than the cache
+        B.odb_prefill(tiny.model, cache, cuda_i32(np.zeros((1, 65))), 0)
+    with pytest.raises(B.OdbError):
+        B.odb_prefill(tiny.model, cache, t, 64)
+    B.odb_prefill(tiny.model, cache, t, 0)
+    with pytest.raises(B.OdbError):          # block sticks out of the sequence
+        B.odb_block_step(tiny.model, cache, d, 49, 0.9)
+    with pytest.raises(B.OdbError):
+        B.odb_cache_read(cache, 0, 0, 0, 60, 8, 4, 64)
+    with pytest.raises(B.OdbError):
+        B.odb_cache_create(tiny.model, 0, 16)
+    torch.cuda.synchronize()
