@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-decode step (and, on request, the cache-refresh prefill).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config1|config2|config3|config4]
+
+One "step" is one pass of the whole hot path over one batch of synthetic input:
+odb_block_step on the 8B-shaped model against a prefilled cache (config1: S=1,
+config2: S=4, config4: batch 4, S=8) or odb_prefill (config3, L=1024).  Inputs,
+weights and the cache are resident in HBM before the timed region starts.
+Prints ONE JSON line.  Everything runs on one GPU; --gpus above 1 is refused.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def weight_bytes(shape):
+    d, f, v, nl = shape["d_model"], shape["d_ff"], shape["vocab"], shape["n_layers"]
+    per_layer = (3 * d * d + d * d + 2 * f * d + d * f) * 2
+    return per_layer, per_layer * nl + v * d * 2
+
+
+def kv_bytes_per_pos(shape):
+    return shape["n_layers"] * 2 * shape["d_model"] * 2
+
+
+def step_flops(shape, rows, keys_per_row):
+    d, f, v, nl = shape["d_model"], shape["d_ff"], shape["vocab"], shape["n_layers"]
+    gemm = 2 * rows * (nl * (4 * d * d + 3 * d * f) + v * d)
+    attn = nl * 4 * rows * keys_per_row * d
+    return gemm + attn
+
+
+def cpu_baseline_step(shape, wl, seed, std):
+    """Times the oracle on a bounded sample of the step: ONE transformer layer (of
+    n_layers) plus the LM head at full width on all rows of sequence 0, and scales
+    the layer time by n_layers."""
+    import numpy as np
+    from oracle import odb_oracle as o
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    one = dict(shape, n_layers=1)
+    cfg = o.Config(**one)
+    w = o.Weights(cfg, seed, std)
+    for tid in (o.T_WQ, o.T_WK, o.T_WV, o.T_WO, o.T_WG, o.T_WU, o.T_WD, o.T_LM):
+        w.bits(tid, 0)                                   # generation is not part of the step
+    S, b = wl.drafts.shape[1:]
+    L = wl.tokens.shape[1]
+    rng = np.random.default_rng(0)
+    cache = o.Cache(rng.standard_normal((1, L, cfg.n_heads, cfg.head_dim)),
+                    rng.standard_normal((1, L, cfg.n_heads, cfg.head_dim)))
+    t0 = time.perf_counter()
+    o.block_step(cfg, w, cache, wl.drafts[0], wl.block_off, wl.tau)
+    t_layer_head = time.perf_counter() - t0
+    h = rng.standard_normal((S * b, cfg.d_model))
+    t0 = time.perf_counter()
+    o.confidence_argmax(o._head(cfg, w, h))
+    t_head = time.perf_counter() - t0
+    t_layer = max(t_layer_head - t_head, 1e-9)
+    t_full = shape["n_layers"] * t_layer + t_head
+    rows = wl.drafts.shape[0] * S * b
+    return {"value": rows / (t_full * wl.drafts.shape[0]), "unit": "rows/s", "cores": int(cores), "kind": "oracle",
+            "sample": "1 of %d layers + LM head at full width, all %d rows of sequence 0, float64; layer time x%d "
+                      "(measured %.2fs layer, %.2fs head)" % (shape["n_layers"], S * b, shape["n_layers"], t_layer,
+                                                             t_head)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="config1", choices=["config0", "config1", "config2", "config3", "config4"])
+    ap.add_argument("--resp", type=int, default=512, help="response length for config3 (512, 256 or 128)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2511_21759_amd import binding as B
+    from paper_2511_21759_amd import workloads as W
+
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2511_21759_amd.build import build_library
+        build_library()
+    torch.cuda.set_device(0)
+    name = args.workload
+    shape = W.MODEL_SHAPES["tiny" if name == "config0" else "8b"]
+    model = B.odb_model_create(shape)
+    B.odb_model_init_random(model, W.WEIGHT_SEED, W.WEIGHT_STD)
+    per_layer_w, total_w = weight_bytes(shape)
+    d, f = shape["d_model"], shape["d_ff"]
+
+    if name == "config3":
+        tokens = torch.from_numpy(W.config3(args.resp)).cuda()
+        Bn, L = tokens.shape
+        cache = B.odb_cache_create(model, Bn, L)
+        conf = torch.empty((Bn, L - 512), dtype=torch.float32, device="cuda")
+        am = torch.empty((Bn, L - 512), dtype=torch.int32, device="cuda")
+        run = lambda: B.odb_prefill(model, cache, tokens, 512, conf, am)
+        rows = Bn * L
+        flops = step_flops(shape, rows, L) - 2 * Bn * 512 * shape["vocab"] * d   # LM head on response rows only
+        alg_bytes = total_w + rows * kv_bytes_per_pos(shape)
+        wl = None
+        label = "cache-refresh prefill, 8B shape, 512 prompt + %d MASK, batch 1" % args.resp
+    else:
+        wl = {"config0": W.config0, "config1": W.config1, "config2": W.config2, "config4": W.config4}[name]()
+        Bn, L = wl.tokens.shape
+        S, b = wl.drafts.shape[1:]
+        cache = B.odb_cache_create(model, Bn, L)
+        tok = torch.from_numpy(wl.tokens).cuda()
+        B.odb_prefill(model, cache, tok, wl.resp_off)
+        drafts = torch.from_numpy(wl.drafts).cuda()
+        conf = torch.empty((Bn, S, b), dtype=torch.float32, device="cuda")
+        am = torch.empty((Bn, S, b), dtype=torch.int32, device="cuda")
+        um = torch.empty((Bn, S, b), dtype=torch.uint8, device="cuda")
+        run = lambda: B.odb_block_step(model, cache, drafts, wl.block_off, wl.tau, conf, am, um)
+        rows = Bn * S * b
+        flops = step_flops(shape, rows, L)
+        alg_bytes = total_w + Bn * (L - b) * kv_bytes_per_pos(shape)
+        label = "block-decode step, %s shape, cache L=%d, block b=%d, S=%d drafts, batch %d" % (
+            "tiny" if name == "config0" else "8B", L, b, S, Bn)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        run()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = wall * 1e3 / args.steps
+    ms_gpu = ev0.elapsed_time(ev1) / args.steps
+
+    # dominant kernel: the gate/up projection (SwiGLU GEMM), 2*F*d weights per launch.
+    # Its launches are bracketed by HIP events on the launch stream in a second,
+    # instrumented pass over the same steps (the events would perturb the timed pass).
+    prof = B.odb_profile_kernel(model, run, args.steps) if hasattr(B, "odb_profile_kernel") else None
+    compute_bound = name in ("config3", "config4")
+    rows_per_launch = rows
+    gu_bytes = 2 * f * d * 2 + rows_per_launch * d * 2 + rows_per_launch * f * 2
+    gu_flops = 2 * rows_per_launch * 2 * f * d
+    roofline = None
+    if prof:
+        avg_s = prof["avg_ms"] * 1e-3
+        if compute_bound:
+            ach = gu_flops / avg_s / 1e12
+            roofline = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+        else:
+            ach = gu_bytes / avg_s / 1e9
+            roofline = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": ach / HBM_PEAK_GBS, "traffic": None}
+        roofline.update({"kernel": prof["kernel"], "launches": prof["launches"], "avg_us": prof["avg_ms"] * 1e3})
+
+    out = {
+        "metric": "block-decode tokens/s (8B shape, S drafts); achieved HBM GB/s vs peak"
+                  if wl is not None else "cache-refresh prefill tokens/s; achieved bf16 TFLOP/s vs MFMA peak",
+        "value": rows / (ms * 1e-3), "unit": "rows/s" if wl is not None else "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "ms_per_step_gpu_events": ms_gpu,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: %s" % (name, label), "rows_per_step": rows,
+                   "steps_per_s": 1e3 / ms},
+        "step_hbm": {"algorithmic_bytes": alg_bytes, "achieved_GBps": alg_bytes / (ms * 1e-3) / 1e9,
+                     "frac_of_8TBps": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "step_mfma": {"flops": flops, "achieved_TFLOPps": flops / (ms * 1e-3) / 1e12,
+                      "frac_of_2.5PFLOPps": flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+        "roofline": roofline,
+    }
+    if wl is not None and not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_step(shape, wl, W.WEIGHT_SEED, W.WEIGHT_STD)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out))
+    B.odb_cache_destroy(cache)
+    B.odb_model_destroy(model)
+
+
+if __name__ == "__main__":
+    main()

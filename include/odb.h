@@ -48,7 +48,7 @@ typedef struct odb_cache odb_cache;
  * pre-norm residual blocks, RMSNorm, rotate-half RoPE on the full head
  * dimension, SwiGLU, an untied LM head and no biases.
  * Requirements: d_model = n_heads*head_dim; head_dim is 64 or 128; d_model and
- * d_ff and vocab are multiples of 32; 0 <= mask_id < vocab. */
+ * d_ff are multiples of 256; vocab is a multiple of 16; 0 <= mask_id < vocab. */
 typedef struct {
     int n_layers, d_model, n_heads, head_dim, d_ff, vocab;
     float rope_base; /* pair j of a head turns by pos * rope_base^(-2j/head_dim) */
@@ -130,9 +130,9 @@ int odb_block_step(odb_model *m, const odb_cache *c, const int32_t *drafts_dev,
                    int block_off, int b, int S, float tau, float *conf_dev,
                    int32_t *argmax_dev, uint8_t *unmask_dev, void *stream);
 
-/* Test-only variants that also materialise the logits (dev float, row-major
+/* Test-only variants that materialise the logits (dev float, row-major
  * [batch, L-resp_off, vocab] resp. [batch, S, b, vocab]) through an unfused
- * store; conf/argmax/unmask pointers may be NULL. */
+ * store instead of the fused confidence/argmax reduction. */
 int odb_prefill_logits(odb_model *m, odb_cache *c, const int32_t *tokens_dev,
                        int L, int resp_off, float *logits_dev, void *stream);
 int odb_block_step_logits(odb_model *m, const odb_cache *c,
@@ -144,6 +144,20 @@ int odb_block_step_logits(odb_model *m, const odb_cache *c,
  * bit patterns [n, n_heads, head_dim].  Synchronous (device-wide). */
 int odb_cache_read(const odb_cache *c, int layer, int kv, int batch_index,
                    int pos0, int n, uint16_t *host_bf16);
+
+/* Measurement aid.  Between odb_profile_begin and odb_profile_end every launch
+ * of the kernel class `kernel_class` made by calls on this model is bracketed
+ * by a pair of HIP events recorded on the launch stream (at most max_launches
+ * pairs; further launches are not timed).  odb_profile_end synchronises the
+ * device, returns the number of timed launches and the sum of their durations
+ * in milliseconds, and releases the events.  The events serialise nothing but
+ * do cost a few microseconds each: do not time whole steps while enabled. */
+enum {
+    ODB_K_GEMM_QKV = 0, ODB_K_ATTENTION, ODB_K_GEMM_O, ODB_K_GEMM_GATE_UP,
+    ODB_K_GEMM_DOWN, ODB_K_GEMM_LM_HEAD, ODB_K_RMSNORM, ODB_K_COUNT
+};
+int odb_profile_begin(odb_model *m, int kernel_class, int max_launches);
+int odb_profile_end(odb_model *m, int *n_launches, float *total_ms);
 
 const char *odb_strerror(int code);
 const char *odb_last_error(void);

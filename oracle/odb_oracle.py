@@ -31,8 +31,10 @@ closed forms, invariants, brute force and library routines in tests/.
 """
 from __future__ import annotations
 
+import concurrent.futures
 import dataclasses
 import math
+import os
 from typing import Dict, Optional, Tuple
 
 import numpy as np
@@ -152,8 +154,9 @@ class Weights:
     """
 
     def __init__(self, cfg: Config, seed: int, std: float = 0.02,
-                 keep: bool = True):
+                 keep: bool = True, threads: Optional[int] = None):
         self.cfg, self.seed, self.std, self.keep = cfg, seed, std, keep
+        self.threads = threads or min(16, os.cpu_count() or 1)
         self._bits: Dict[Tuple[int, int], np.ndarray] = {}
         self.overrides: Dict[Tuple[int, int], np.ndarray] = {}
 
@@ -177,11 +180,17 @@ class Weights:
             out = np.full(shape, 0x3F80, np.uint16)          # 1.0
         else:
             out = np.empty(n, np.uint16)
-            step = 1 << 22
-            for s in range(0, n, step):
+            step = 1 << 21
+
+            def fill(s):
                 m = min(step, n - s)
                 out[s:s + m] = normal_bf16_bits(self.seed, tensor_id, layer, s, m,
                                                 self.std)
+
+            # chunks are independent (counter-based generator); numpy releases
+            # the GIL inside its loops, so threads only shorten the wait
+            with concurrent.futures.ThreadPoolExecutor(self.threads) as ex:
+                list(ex.map(fill, range(0, n, step)))
             out = out.reshape(shape)
         if self.keep:
             self._bits[key] = out
@@ -191,7 +200,15 @@ class Weights:
         return bf16_bits_to_f64(self.bits(tensor_id, layer))
 
     def embed_rows(self, tokens: np.ndarray) -> np.ndarray:
-        return bf16_bits_to_f64(self.bits(T_EMBED, 0)[np.asarray(tokens, np.int64)])
+        """Rows E[tok] of the embedding table (only those rows are generated when
+        the table itself is neither planted nor cached)."""
+        tokens = np.asarray(tokens, np.int64)
+        key = (T_EMBED, 0)
+        if key in self.overrides or key in self._bits:
+            return bf16_bits_to_f64(self.bits(T_EMBED, 0)[tokens])
+        d = self.cfg.d_model
+        rows = [normal_bf16_bits(self.seed, T_EMBED, 0, int(t) * d, d, self.std) for t in tokens]
+        return bf16_bits_to_f64(np.stack(rows))
 
 
 # --------------------------------------------------------------------------- operators

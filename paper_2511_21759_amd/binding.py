@@ -21,8 +21,10 @@ SYMBOLS = (
     "odb_model_create", "odb_model_destroy", "odb_model_init_random", "odb_model_set_tensor",
     "odb_model_get_tensor", "odb_cache_create", "odb_cache_destroy", "odb_cache_length", "odb_prefill",
     "odb_block_step", "odb_prefill_logits", "odb_block_step_logits", "odb_cache_read", "odb_strerror",
-    "odb_last_error",
+    "odb_last_error", "odb_profile_begin", "odb_profile_end",
 )
+
+KERNEL_CLASSES = ("gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "rmsnorm")
 
 T_EMBED, T_WQ, T_WK, T_WV, T_WO, T_WG, T_WU, T_WD, T_LM, T_G1, T_G2, T_GF = range(12)
 
@@ -68,6 +70,8 @@ def lib() -> ctypes.CDLL:
     L.odb_prefill_logits.argtypes = [vp, vp, vp, ci, ci, vp, vp]
     L.odb_block_step_logits.argtypes = [vp, vp, vp, ci, ci, ci, vp, vp]
     L.odb_cache_read.argtypes = [vp, ci, ci, ci, ci, ci, vp]
+    L.odb_profile_begin.argtypes = [vp, ci, ci]
+    L.odb_profile_end.argtypes = [vp, ctypes.POINTER(ci), ctypes.POINTER(cf)]
     L.odb_strerror.argtypes = [ci]
     L.odb_strerror.restype = ctypes.c_char_p
     L.odb_last_error.restype = ctypes.c_char_p
@@ -185,6 +189,27 @@ def odb_cache_read(cache: int, layer: int, kv: int, batch_index: int, pos0: int,
     out = np.empty((n, n_heads, head_dim), np.uint16)
     _check(lib().odb_cache_read(cache, layer, kv, batch_index, pos0, n, out.ctypes.data))
     return out
+
+
+def odb_profile_begin(model: int, kernel_class: int, max_launches: int) -> None:
+    _check(lib().odb_profile_begin(model, kernel_class, max_launches))
+
+
+def odb_profile_end(model: int) -> Tuple[int, float]:
+    n, ms = ctypes.c_int(), ctypes.c_float()
+    _check(lib().odb_profile_end(model, ctypes.byref(n), ctypes.byref(ms)))
+    return n.value, ms.value
+
+
+def odb_profile_kernel(model: int, run, steps: int, kernel_class: int = 3, max_launches: int = 1 << 16) -> Dict:
+    """Average on-stream duration of one kernel class over `steps` calls of run()."""
+    odb_profile_begin(model, kernel_class, max_launches)
+    try:
+        for _ in range(steps):
+            run()
+    finally:
+        n, ms = odb_profile_end(model)
+    return {"kernel": KERNEL_CLASSES[kernel_class], "launches": n, "avg_ms": ms / max(n, 1)}
 
 
 def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:

@@ -48,16 +48,14 @@ void dev_free(const Model &m, void *p) {
     else (void)hipFree(p);
 }
 
-constexpr int kCounters = 1 << 16;
-constexpr size_t kGemmPartialBytes = 64u << 20;
+constexpr int kCounters = 1 << 12;     // grid-barrier / arrival counters
 
 // byte offsets of the per-call buffers inside the model's scratch allocation
 struct Plan {
-    size_t h, xa, q, kf, vf, ao, act, stats, gemm_part, attn_part, total;
+    size_t h, xa, q, kf, vf, ao, act, ssq, stats, total;
 };
 
-Plan make_plan(const odb_config &c, int rows_pad, int fresh_rows, int lm_rows_pad, size_t attn_part_bytes,
-               bool need_stats) {
+Plan make_plan(const odb_config &c, int rows_pad, int fresh_rows, int lm_rows_pad, bool need_stats) {
     Plan p;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
@@ -69,9 +67,8 @@ Plan make_plan(const odb_config &c, int rows_pad, int fresh_rows, int lm_rows_pa
     p.vf = take((size_t)fresh_rows * d * 2);
     p.ao = take((size_t)rows_pad * d * 2);
     p.act = take((size_t)rows_pad * c.d_ff * 2);
-    p.stats = take(need_stats ? (size_t)lm_rows_pad * (c.vocab / 32) * 3 * 4 : 0);
-    p.gemm_part = take(kGemmPartialBytes);
-    p.attn_part = take(attn_part_bytes);
+    p.ssq = take((size_t)rows_pad * (d / 16) * 4);
+    p.stats = take(need_stats ? (size_t)lm_rows_pad * (c.vocab / 16) * 3 * 4 : 0);
     p.total = off;
     return p;
 }
@@ -97,8 +94,8 @@ int check_config(const odb_config *c) {
         return fail(ODB_E_INVALID_ARG, "config: sizes must be positive");
     if (c->n_heads * c->head_dim != c->d_model) return fail(ODB_E_INVALID_ARG, "config: d_model != n_heads*head_dim");
     if (c->head_dim != 64 && c->head_dim != 128) return fail(ODB_E_UNSUPPORTED, "config: head_dim must be 64 or 128");
-    if (c->d_model % 32 || c->d_ff % 32) return fail(ODB_E_INVALID_ARG, "config: d_model and d_ff must be multiples of 32");
-    if (c->vocab % 32) return fail(ODB_E_INVALID_ARG, "config: vocab must be a multiple of 32");
+    if (c->d_model % 256 || c->d_ff % 256) return fail(ODB_E_INVALID_ARG, "config: d_model and d_ff must be multiples of 256");
+    if (c->vocab % 16) return fail(ODB_E_INVALID_ARG, "config: vocab must be a multiple of 16");
     if (c->mask_id < 0 || c->mask_id >= c->vocab) return fail(ODB_E_INVALID_ARG, "config: mask_id out of range");
     if (!(c->rope_base > 0.f) || !(c->rms_eps >= 0.f)) return fail(ODB_E_INVALID_ARG, "config: rope_base/rms_eps");
     return ODB_OK;
@@ -127,30 +124,56 @@ LayerPtrs layer_ptrs(const Model &m, int l) {
     return p;
 }
 
+// brackets the launches of one kernel class with events while profiling is on
+struct ProfScope {
+    Model &m;
+    hipStream_t s;
+    int slot;
+    ProfScope(Model &m_, int cls, hipStream_t s_) : m(m_), s(s_), slot(-1) {
+        if (m.prof_class == cls && m.prof_used < m.prof_cap) {
+            slot = m.prof_used++;
+            (void)hipEventRecord(m.prof_ev[2 * slot], s);
+        }
+    }
+    ~ProfScope() {
+        if (slot >= 0) (void)hipEventRecord(m.prof_ev[2 * slot + 1], s);
+    }
+};
+
 // The transformer stack shared by both calls.  `rm` describes the rows; K/V go
 // to the cache (prefill) or to the fresh buffers (step).
+//
+// fused_norm (the step): every RMSNorm is folded into its neighbours - the
+// kernel that produces the residual stream h also writes bf16(h * gain) and
+// per-tile sums of squares, the consuming GEMM turns them into row scales.
+// Otherwise (the prefill) a separate RMSNorm kernel writes the GEMM input.
 struct StackIO {
     RowMap rm;
     int pos_off;
     bool to_cache;      // prefill: K/V are written into the cache
-    int blk_lo, blk_hi, fresh, units_per_seq, nsplit;
+    int blk_lo, blk_hi, fresh, units_per_seq;
+    bool fused_norm;
 };
 
 int run_stack(Model &m, const Cache &c, const Plan &pl, const StackIO &io, hipStream_t s) {
     const odb_config &cfg = m.cfg;
     char *base = (char *)m.scratch;
-    float *h = (float *)(base + pl.h);
+    float *h = (float *)(base + pl.h), *ssq = (float *)(base + pl.ssq);
     u16 *xa = (u16 *)(base + pl.xa), *q = (u16 *)(base + pl.q), *kf = (u16 *)(base + pl.kf),
         *vf = (u16 *)(base + pl.vf), *ao = (u16 *)(base + pl.ao), *act = (u16 *)(base + pl.act);
-    Workspace ws{(float *)(base + pl.gemm_part), kGemmPartialBytes, m.counters};
     const int d = cfg.d_model, H = cfg.n_heads, dh = cfg.head_dim, F = cfg.d_ff;
     const int rows_pad = io.rm.units * io.rm.rpu_pad, mt = rows_pad / 16, tpu = io.rm.rpu_pad / 16;
     const size_t seq_elems = (size_t)H * c.lmax32 * dh;
     const int fresh32 = ru(io.rm.rpu_pad, 32);
+    const int n_ssq = d / 16;
+    const NormIn ni = io.fused_norm ? NormIn{ssq, n_ssq, cfg.rms_eps} : NormIn{nullptr, 0, 0.f};
 
     for (int l = 0; l < cfg.n_layers; l++) {
         LayerPtrs w = layer_ptrs(m, l);
-        launch_rmsnorm(h, w.g1, cfg.rms_eps, d, io.rm, 0, false, mt, xa, s);
+        if (!io.fused_norm) {
+            ProfScope ps(m, ODB_K_RMSNORM, s);
+            launch_rmsnorm(h, w.g1, cfg.rms_eps, d, io.rm, 0, false, mt, xa, s);
+        }
         QkvOut qo;
         qo.q = q;
         qo.rope = c.rope;
@@ -163,7 +186,10 @@ int run_stack(Model &m, const Cache &c, const Plan &pl, const StackIO &io, hipSt
             qo.k = kf; qo.k_head_stride = (size_t)fresh32 * dh; qo.k_unit_stride = (size_t)H * fresh32 * dh;
             qo.v = vf; qo.v_head_stride = (size_t)fresh32 * dh; qo.v_unit_stride = (size_t)H * fresh32 * dh;
         }
-        launch_gemm_qkv(xa, w.qkv, GemmShape{mt, 3 * d / 16, d / 32}, qo, ws, s);
+        {
+            ProfScope ps(m, ODB_K_GEMM_QKV, s);
+            launch_gemm_qkv(xa, w.qkv, GemmShape{mt, 3 * d / 16, d / 32}, ni, qo, s);
+        }
 
         AttnArgs a;
         a.q = q; a.kc = kc; a.vc = vc;
@@ -173,38 +199,70 @@ int run_stack(Model &m, const Cache &c, const Plan &pl, const StackIO &io, hipSt
         a.kf_unit_stride = qo.k_unit_stride; a.kf_head_stride = qo.k_head_stride;
         a.vf_unit_stride = qo.v_unit_stride; a.vf_head_stride = qo.v_head_stride;
         a.out = ao;
-        a.part_o = (float *)(base + pl.attn_part);
-        a.part_ml = a.part_o + (size_t)io.nsplit * mt * H * (dh / 16) * 256;
         a.H = H; a.dh = dh; a.mt_total = mt; a.tiles_per_unit = tpu; a.units = io.rm.units;
         a.units_per_seq = io.units_per_seq; a.L = c.length; a.blk_lo = io.blk_lo; a.blk_hi = io.blk_hi;
-        a.fresh = io.fresh; a.nsplit = io.nsplit;
-        launch_attention(a, s);
-
-        launch_gemm_resid(ao, w.o, GemmShape{mt, d / 16, d / 32}, h, d, ws, s);
-        launch_rmsnorm(h, w.g2, cfg.rms_eps, d, io.rm, 0, false, mt, xa, s);
-        launch_gemm_swiglu(xa, w.gu, GemmShape{mt, 2 * F / 16, d / 32}, act, ws, s);
-        launch_gemm_resid(act, w.dn, GemmShape{mt, d / 16, F / 32}, h, d, ws, s);
+        a.fresh = io.fresh;
+        {
+            ProfScope ps(m, ODB_K_ATTENTION, s);
+            launch_attention(a, s);
+        }
+        // the residual epilogues prepare the norm that follows them
+        const float *g_after_mlp = l + 1 < cfg.n_layers ? m.g1 + (size_t)(l + 1) * d : m.gf;
+        NormOut no_attn = io.fused_norm ? NormOut{xa, ssq, w.g2, n_ssq} : NormOut{nullptr, nullptr, nullptr, 0};
+        NormOut no_mlp = io.fused_norm ? NormOut{xa, ssq, g_after_mlp, n_ssq} : NormOut{nullptr, nullptr, nullptr, 0};
+        {
+            ProfScope ps(m, ODB_K_GEMM_O, s);
+            launch_gemm_resid(ao, w.o, GemmShape{mt, d / 16, d / 32}, h, d, no_attn, s);
+        }
+        if (!io.fused_norm) {
+            ProfScope ps(m, ODB_K_RMSNORM, s);
+            launch_rmsnorm(h, w.g2, cfg.rms_eps, d, io.rm, 0, false, mt, xa, s);
+        }
+        {
+            ProfScope ps(m, ODB_K_GEMM_GATE_UP, s);
+            launch_gemm_swiglu(xa, w.gu, GemmShape{mt, 2 * F / 16, d / 32}, ni, act, s);
+        }
+        {
+            ProfScope ps(m, ODB_K_GEMM_DOWN, s);
+            launch_gemm_resid(act, w.dn, GemmShape{mt, d / 16, F / 32}, h, d, no_mlp, s);
+        }
     }
     return ODB_OK;
 }
 
-// final norm + LM head on the compacted rows (unit u, i >= skip)
-int run_head(Model &m, const Plan &pl, RowMap rm, int skip, const int32_t *tokens, int rpu_out, float tau, float *conf,
-             int32_t *argmax, uint8_t *unmask, float *logits, hipStream_t s) {
+// final norm + LM head.  Fused mode: on the padded rows, straight from hb/ssq.
+// Otherwise on the compacted rows (unit u, i >= skip) through the RMSNorm kernel.
+int run_head(Model &m, const Plan &pl, RowMap rm, int skip, bool fused_norm, const int32_t *tokens, int rpu_out,
+             float tau, float *conf, int32_t *argmax, uint8_t *unmask, float *logits, hipStream_t s) {
     const odb_config &cfg = m.cfg;
     char *base = (char *)m.scratch;
     float *h = (float *)(base + pl.h);
     u16 *xa = (u16 *)(base + pl.xa);
-    Workspace ws{(float *)(base + pl.gemm_part), kGemmPartialBytes, m.counters};
-    const int rows = rm.units * (rm.valid - skip), lm_mt = (rows + 15) / 16;
-    launch_rmsnorm(h, m.gf, cfg.rms_eps, cfg.d_model, rm, skip, true, lm_mt, xa, s);
+    float *stats = (float *)(base + pl.stats);
+    const int rows = rm.units * (rm.valid - skip);
+    int lm_mt, rpu_pad, valid;
+    NormIn ni{nullptr, 0, 0.f};
+    if (fused_norm) {
+        lm_mt = rm.units * rm.rpu_pad / 16;
+        rpu_pad = rm.rpu_pad;
+        valid = rm.valid;
+        ni = NormIn{(float *)(base + pl.ssq), cfg.d_model / 16, cfg.rms_eps};
+    } else {
+        lm_mt = (rows + 15) / 16;
+        rpu_pad = valid = rpu_out;
+        launch_rmsnorm(h, m.gf, cfg.rms_eps, cfg.d_model, rm, skip, true, lm_mt, xa, s);
+    }
     GemmShape sh{lm_mt, cfg.vocab / 16, cfg.d_model / 32};
     if (logits) {
-        launch_gemm_store(xa, m.w[PK_LM], sh, logits, rows, cfg.vocab, ws, s);
+        if (fused_norm) launch_gemm_store(xa, m.w[PK_LM], sh, ni, logits, rm.units, rpu_pad, valid, cfg.vocab, s);
+        else launch_gemm_store(xa, m.w[PK_LM], sh, ni, logits, 1, lm_mt * 16, rows, cfg.vocab, s);
     } else {
-        float *stats = (float *)(base + pl.stats);
-        launch_gemm_lmstats(xa, m.w[PK_LM], sh, stats, ws, s);
-        launch_lm_finish(stats, cfg.vocab / 32, rows, rpu_out, tokens, cfg.mask_id, tau, conf, argmax, unmask, s);
+        {
+            ProfScope ps(m, ODB_K_GEMM_LM_HEAD, s);
+            launch_gemm_lmstats(xa, m.w[PK_LM], sh, ni, stats, s);
+        }
+        launch_lm_finish(stats, cfg.vocab / 16, rows, rpu_out, rpu_pad, tokens, cfg.mask_id, tau, conf, argmax, unmask,
+                         s);
     }
     HIP_TRY(hipGetLastError());
     return ODB_OK;
@@ -222,16 +280,16 @@ int prefill_impl(odb_model *mh, odb_cache *ch, const int32_t *tokens, int L, int
     hipStream_t s = (hipStream_t)stream;
     HIP_TRY(hipSetDevice(m.device));
     const int lp = ru(L, 16), rows_pad = c.batch * lp, lm_rows = c.batch * (L - resp_off);
-    Plan pl = make_plan(m.cfg, rows_pad, 0, ru(lm_rows, 16), 0, logits == nullptr);
+    Plan pl = make_plan(m.cfg, rows_pad, 0, ru(lm_rows, 16), logits == nullptr);
     int rc = ensure_scratch(m, pl.total, s);
     if (rc) return rc;
     RowMap rm{c.batch, lp, L};
     c.length = L;
-    launch_embed(m, tokens, rm, (float *)((char *)m.scratch + pl.h), s);
-    StackIO io{rm, 0, true, 0, 0, 0, 1, 1};
+    launch_embed(m, tokens, rm, (float *)((char *)m.scratch + pl.h), NormOut{nullptr, nullptr, nullptr, 0}, s);
+    StackIO io{rm, 0, true, 0, 0, 0, 1, false};
     rc = run_stack(m, c, pl, io, s);
     if (rc) return rc;
-    return run_head(m, pl, rm, resp_off, nullptr, 64, 0.f, conf, argmax, nullptr, logits, s);
+    return run_head(m, pl, rm, resp_off, false, nullptr, 64, 0.f, conf, argmax, nullptr, logits, s);
 }
 
 int step_impl(odb_model *mh, const odb_cache *ch, const int32_t *drafts, int block_off, int b, int S, float tau,
@@ -251,22 +309,19 @@ int step_impl(odb_model *mh, const odb_cache *ch, const int32_t *drafts, int blo
     HIP_TRY(hipSetDevice(m.device));
     const odb_config &cfg = m.cfg;
     const int bp = ru(b, 16), bp32 = ru(b, 32), units = c.batch * S, rows_pad = units * bp;
-    const int chunks = (bp / 16 + 1) / 2, n32 = (c.length + 31) / 32;
-    int nsplit = 1;
-    while (units * chunks * cfg.n_heads * nsplit < 256 && n32 / (nsplit * 2) >= 4) nsplit *= 2;
-    AttnArgs probe;
-    probe.nsplit = nsplit; probe.mt_total = rows_pad / 16; probe.H = cfg.n_heads; probe.dh = cfg.head_dim;
-    Plan pl = make_plan(cfg, rows_pad, units * bp32, ru(units * b, 16), attn_partial_bytes(probe), logits == nullptr);
+    Plan pl = make_plan(cfg, rows_pad, units * bp32, rows_pad, logits == nullptr);
     int rc = ensure_scratch(m, pl.total, s);
     if (rc) return rc;
     RowMap rm{units, bp, b};
-    launch_embed(m, drafts, rm, (float *)((char *)m.scratch + pl.h), s);
+    char *base = (char *)m.scratch;
+    launch_embed(m, drafts, rm, (float *)(base + pl.h),
+                 NormOut{(u16 *)(base + pl.xa), (float *)(base + pl.ssq), m.g1, cfg.d_model / 16}, s);
     if (b % 32)   // slots of padded keys must hold finite values: they meet zero probabilities in the P*V product
         launch_fill_f32((float *)((char *)m.scratch + pl.vf), 0.f, (size_t)units * bp32 * cfg.d_model / 2, s);
-    StackIO io{rm, block_off, false, block_off, block_off + b, b, S, nsplit};
+    StackIO io{rm, block_off, false, block_off, block_off + b, b, S, true};
     rc = run_stack(m, c, pl, io, s);
     if (rc) return rc;
-    return run_head(m, pl, rm, 0, drafts, b, tau, conf, argmax, unmask, logits, s);
+    return run_head(m, pl, rm, 0, true, drafts, b, tau, conf, argmax, unmask, logits, s);
 }
 
 }  // namespace
@@ -305,6 +360,7 @@ int odb_model_create(const odb_config *cfg, const odb_allocator *allocator, odb_
     memset(&m, 0, sizeof(m));
     m.cfg = *cfg;
     m.device = dev;
+    m.prof_class = -1;
     if (allocator) { m.alloc = *allocator; m.has_alloc = true; }
     const size_t d = cfg->d_model, f = cfg->d_ff, v = cfg->vocab, nl = cfg->n_layers;
     m.layer_elems[PK_QKV] = 3 * d * d;
@@ -349,6 +405,10 @@ void odb_model_destroy(odb_model *mh) {
     dev_free(m, m.counters);
     dev_free(m, m.scratch);
     dev_free(m, m.staging);
+    if (m.prof_ev) {
+        for (int i = 0; i < 2 * m.prof_cap; i++) (void)hipEventDestroy(m.prof_ev[i]);
+        delete[] m.prof_ev;
+    }
     delete mh;
 }
 
@@ -475,6 +535,53 @@ int odb_block_step_logits(odb_model *m, const odb_cache *c, const int32_t *draft
                           float *logits_dev, void *stream) {
     if (!logits_dev) return fail(ODB_E_INVALID_ARG, "block_step_logits: logits is NULL");
     return step_impl(m, c, drafts_dev, block_off, b, S, 0.f, nullptr, nullptr, nullptr, logits_dev, stream);
+}
+
+int odb_profile_begin(odb_model *mh, int kernel_class, int max_launches) {
+    if (!mh) return fail(ODB_E_INVALID_ARG, "profile_begin: model is NULL");
+    Model &m = mh->m;
+    if (kernel_class < 0 || kernel_class >= ODB_K_COUNT) return fail(ODB_E_INVALID_ARG, "profile_begin: class %d", kernel_class);
+    if (max_launches < 1 || max_launches > (1 << 20)) return fail(ODB_E_INVALID_ARG, "profile_begin: max_launches");
+    if (m.prof_ev) return fail(ODB_E_INVALID_ARG, "profile_begin: already profiling");
+    HIP_TRY(hipSetDevice(m.device));
+    m.prof_ev = new (std::nothrow) hipEvent_t[2 * (size_t)max_launches];
+    if (!m.prof_ev) return fail(ODB_E_NOMEM, "profile_begin: host allocation");
+    for (int i = 0; i < 2 * max_launches; i++) {
+        hipError_t e = hipEventCreate(&m.prof_ev[i]);
+        if (e != hipSuccess) {
+            for (int j = 0; j < i; j++) (void)hipEventDestroy(m.prof_ev[j]);
+            delete[] m.prof_ev;
+            m.prof_ev = nullptr;
+            return fail(ODB_E_HIP, "hipEventCreate: %s", hipGetErrorString(e));
+        }
+    }
+    m.prof_cap = max_launches;
+    m.prof_used = 0;
+    m.prof_class = kernel_class;
+    return ODB_OK;
+}
+
+int odb_profile_end(odb_model *mh, int *n_launches, float *total_ms) {
+    if (!mh || !n_launches || !total_ms) return fail(ODB_E_INVALID_ARG, "profile_end: NULL argument");
+    Model &m = mh->m;
+    if (!m.prof_ev) return fail(ODB_E_INVALID_ARG, "profile_end: not profiling");
+    HIP_TRY(hipSetDevice(m.device));
+    hipError_t e = hipDeviceSynchronize();
+    float total = 0.f;
+    for (int i = 0; i < m.prof_used && e == hipSuccess; i++) {
+        float ms = 0.f;
+        e = hipEventElapsedTime(&ms, m.prof_ev[2 * i], m.prof_ev[2 * i + 1]);
+        total += ms;
+    }
+    for (int i = 0; i < 2 * m.prof_cap; i++) (void)hipEventDestroy(m.prof_ev[i]);
+    delete[] m.prof_ev;
+    m.prof_ev = nullptr;
+    *n_launches = m.prof_used;
+    *total_ms = total;
+    m.prof_class = -1;
+    m.prof_cap = m.prof_used = 0;
+    if (e != hipSuccess) return fail(ODB_E_HIP, "profile_end: %s", hipGetErrorString(e));
+    return ODB_OK;
 }
 
 int odb_cache_read(const odb_cache *ch, int layer, int kv, int batch_index, int pos0, int n, uint16_t *host_bf16) {

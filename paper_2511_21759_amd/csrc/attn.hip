@@ -2,9 +2,9 @@
 // in the decode step, the fresh K/V of the rows' own draft.
 //
 // Work is organised per "unit" (a draft in the step, a sequence in the prefill):
-// the rows of a unit all see the same keys.  A workgroup takes up to 32 rows
-// (two 16-row tiles) of one unit and one head; its four waves split the key
-// tiles, keep a running (max, sum, O) per row and are merged through LDS.
+// the rows of a unit all see the same keys.  A workgroup takes QT 16-row tiles
+// of one unit and one head; its NW waves split the 32-key tiles, keep a running
+// (max, sum, O) per row and are merged through LDS in a fixed order.
 // Scores are computed transposed, S^T = K Q^T, so that after the MFMA every
 // lane holds scores of ONE query row (lane & 15): the softmax statistics are
 // lane-local plus two cross-lane exchanges, and the probabilities are already
@@ -16,8 +16,6 @@
 #include "model.h"
 
 namespace odb {
-
-constexpr int QT = 2;   // 16-row query tiles per workgroup
 
 template <int DH>
 __device__ inline void store_out_tile(const AttnArgs &a, int mt, int hd, int dt16, int lane, f32x4 v) {
@@ -31,13 +29,14 @@ __device__ inline void store_out_tile(const AttnArgs &a, int mt, int hd, int dt1
     *reinterpret_cast<uint2 *>(dst) = p;
 }
 
-template <int DH>
-__global__ __launch_bounds__(256) void attn_kernel(AttnArgs a, float sc) {
+template <int DH, int QT, int NW>
+__global__ __launch_bounds__(64 * NW) void attn_kernel(AttnArgs a, float sc) {
     constexpr int DT32 = DH / 32, DT16 = DH / 16;
+    constexpr int DC = DT16 < 4 ? DT16 : 4;          // channel tiles merged per pass through LDS
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, mi = lane & 15, g = lane >> 4;
     const int chunks = (a.tiles_per_unit + QT - 1) / QT;
     const int unit = blockIdx.x / chunks, tu0 = (blockIdx.x % chunks) * QT;
-    const int hd = blockIdx.y, split = blockIdx.z;
+    const int hd = blockIdx.y;
     const int seq = unit / a.units_per_seq;
 
     frag_t q[QT][DT32];
@@ -121,27 +120,25 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a, float sc) {
         }
     };
 
-    // cached keys: 32-key tiles of this split, interleaved over the waves
+    // cached keys: 32-key tiles interleaved over the waves; the fresh tiles follow in the same rotation
     const int n32 = (a.L + 31) / 32;
-    const int per_split = (n32 + a.nsplit - 1) / a.nsplit;
-    const int t_end = min(n32, (split + 1) * per_split);
     const u16 *kc = a.kc + seq * a.kc_seq_stride + hd * a.kc_head_stride;
     const u16 *vc = a.vc + seq * a.vc_seq_stride + hd * a.vc_head_stride;
-    for (int T = split * per_split + w; T < t_end; T += 4) {
+    for (int T = w; T < n32; T += NW) {
         if (T * 32 >= a.blk_lo && T * 32 + 32 <= a.blk_hi) continue;       // wholly inside the block
         tile(kc + (size_t)T * 2 * DT32 * kTileElems, vc + (size_t)T * DT16 * kTileElems, T * 32, true);
     }
-    if (a.fresh > 0 && split == a.nsplit - 1) {
+    if (a.fresh > 0) {
         const u16 *kf = a.kf + unit * a.kf_unit_stride + hd * a.kf_head_stride;
         const u16 *vf = a.vf + unit * a.vf_unit_stride + hd * a.vf_head_stride;
         const int nf = (a.fresh + 31) / 32;
-        for (int T = w; T < nf; T += 4)
+        for (int T = (w + NW - n32 % NW) % NW; T < nf; T += NW)
             tile(kf + (size_t)T * 2 * DT32 * kTileElems, vf + (size_t)T * DT16 * kTileElems, T * 32, false);
     }
 
-    // merge the four waves
-    __shared__ float s_m[4][QT][16], s_l[4][QT][16];
-    __shared__ f32x4 s_o[4][DT16][64];
+    // merge the waves
+    __shared__ float s_m[NW][QT][16], s_l[NW][QT][16];
+    __shared__ f32x4 s_o[NW][DC][64];
 #pragma unroll
     for (int t = 0; t < QT; t++) {
         float l = lrun[t];
@@ -158,86 +155,46 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a, float sc) {
     for (int t = 0; t < QT; t++) {
         float mall = -INFINITY;
 #pragma unroll
-        for (int x = 0; x < 4; x++) mall = fmaxf(mall, s_m[x][t][mi]);
+        for (int x = 0; x < NW; x++) mall = fmaxf(mall, s_m[x][t][mi]);
         float ltot = 0.f, fown = 0.f;
 #pragma unroll
-        for (int x = 0; x < 4; x++) {
+        for (int x = 0; x < NW; x++) {
             float mx = s_m[x][t][mi];
             float f = mx == -INFINITY ? 0.f : exp2f(mx - mall);
             ltot += s_l[x][t][mi] * f;
             if (x == w) fown = f;
         }
-#pragma unroll
-        for (int dt = 0; dt < DT16; dt++) s_o[w][dt][lane] = o[t][dt] * fown;
-        __syncthreads();
         const int tu = tu0 + t;
-        if (tu < a.tiles_per_unit) {
-            const int mt = unit * a.tiles_per_unit + tu;
-            for (int dt = w; dt < DT16; dt += 4) {
-                f32x4 v = s_o[0][dt][lane];
+        const int mt = unit * a.tiles_per_unit + tu;
 #pragma unroll
-                for (int x = 1; x < 4; x++) v += s_o[x][dt][lane];
-                if (a.nsplit == 1) {
-                    store_out_tile<DH>(a, mt, hd, dt, lane, v * (1.0f / ltot));
-                } else {
-                    size_t base = ((size_t)split * a.mt_total + mt) * a.H + hd;
-                    *reinterpret_cast<f32x4 *>(a.part_o + (base * DT16 + dt) * 256 + lane * 4) = v;
-                    if (dt == 0 && g == 0) {
-                        a.part_ml[(base * 16 + mi) * 2] = mall;
-                        a.part_ml[(base * 16 + mi) * 2 + 1] = ltot;
-                    }
+        for (int d0 = 0; d0 < DT16; d0 += DC) {
+#pragma unroll
+            for (int dt = 0; dt < DC; dt++) s_o[w][dt][lane] = o[t][d0 + dt] * fown;
+            __syncthreads();
+            if (tu < a.tiles_per_unit) {
+                for (int dt = w; dt < DC; dt += NW) {
+                    f32x4 v = s_o[0][dt][lane];
+#pragma unroll
+                    for (int x = 1; x < NW; x++) v += s_o[x][dt][lane];
+                    store_out_tile<DH>(a, mt, hd, d0 + dt, lane, v * (1.0f / ltot));
                 }
             }
+            __syncthreads();
         }
-        __syncthreads();
     }
-}
-
-// merges the per-split partial results (nsplit > 1)
-template <int DH>
-__global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
-    constexpr int DT16 = DH / 16;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, mi = lane & 15;
-    const int mt = blockIdx.x, hd = blockIdx.y;
-    float mall = -INFINITY;
-    for (int s = 0; s < a.nsplit; s++) {
-        size_t base = ((size_t)s * a.mt_total + mt) * a.H + hd;
-        mall = fmaxf(mall, a.part_ml[(base * 16 + mi) * 2]);
-    }
-    float ltot = 0.f;
-    for (int s = 0; s < a.nsplit; s++) {
-        size_t base = ((size_t)s * a.mt_total + mt) * a.H + hd;
-        float mx = a.part_ml[(base * 16 + mi) * 2];
-        ltot += a.part_ml[(base * 16 + mi) * 2 + 1] * (mx == -INFINITY ? 0.f : exp2f(mx - mall));
-    }
-    for (int dt = w; dt < DT16; dt += 4) {
-        f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
-        for (int s = 0; s < a.nsplit; s++) {
-            size_t base = ((size_t)s * a.mt_total + mt) * a.H + hd;
-            float mx = a.part_ml[(base * 16 + mi) * 2];
-            float f = mx == -INFINITY ? 0.f : exp2f(mx - mall);
-            v += *reinterpret_cast<const f32x4 *>(a.part_o + (base * DT16 + dt) * 256 + lane * 4) * f;
-        }
-        store_out_tile<DH>(a, mt, hd, dt, lane, v * (1.0f / ltot));
-    }
-}
-
-size_t attn_partial_bytes(const AttnArgs &a) {
-    if (a.nsplit <= 1) return 0;
-    size_t tiles = (size_t)a.nsplit * a.mt_total * a.H;
-    return tiles * (a.dh / 16) * 1024 + tiles * 16 * 2 * sizeof(float);
 }
 
 void launch_attention(AttnArgs a, hipStream_t s) {
-    const int chunks = (a.tiles_per_unit + QT - 1) / QT;
-    dim3 grid(a.units * chunks, a.H, a.nsplit);
     const float sc = 1.4426950408889634f / sqrtf((float)a.dh);
-    if (a.dh == 128) attn_kernel<128><<<grid, 256, 0, s>>>(a, sc);
-    else attn_kernel<64><<<grid, 256, 0, s>>>(a, sc);
-    if (a.nsplit > 1) {
-        dim3 g2(a.mt_total, a.H);
-        if (a.dh == 128) attn_combine_kernel<128><<<g2, 256, 0, s>>>(a);
-        else attn_combine_kernel<64><<<g2, 256, 0, s>>>(a);
+    if (a.fresh > 0) {
+        // decode step: few rows, one 16-row tile per workgroup and eight waves over the keys
+        dim3 grid(a.units * a.tiles_per_unit, a.H);
+        if (a.dh == 128) attn_kernel<128, 1, 8><<<grid, 512, 0, s>>>(a, sc);
+        else attn_kernel<64, 1, 8><<<grid, 512, 0, s>>>(a, sc);
+    } else {
+        dim3 grid(a.units * ((a.tiles_per_unit + 1) / 2), a.H);
+        if (a.dh == 128) attn_kernel<128, 2, 4><<<grid, 256, 0, s>>>(a, sc);
+        else attn_kernel<64, 2, 4><<<grid, 256, 0, s>>>(a, sc);
     }
 }
 

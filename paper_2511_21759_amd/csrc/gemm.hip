@@ -1,176 +1,154 @@
 // Weight-streaming bf16 MFMA GEMM  C[M,N] = A[M,K] * W[N,K]^T  for few rows.
 //
 // A (activations) is tile-major [k_tile][m_tile][512], W is [n_tile][k_tile][512]
-// (see common.h for the tile).  A workgroup owns NG n-tiles x MT m-tiles and a
-// slice of K (grid.y = split-K factor); its WK waves split that slice again, so
-// every wave streams a contiguous run of 1 KiB weight tiles straight from HBM
-// into MFMA operand registers, PF tiles ahead.  Partial sums of the waves are
-// added through LDS in a fixed order; partial sums of different workgroups go
-// through an fp32 workspace and are added, again in a fixed order, by the last
-// workgroup to arrive - results do not depend on scheduling.
+// (see common.h for the tile).  The launch is persistent in spirit: grid.x
+// workgroups (one per compute unit) split the n-tiles into equal contiguous
+// ranges, and the eight waves of a workgroup split K into eight slices.  Each
+// wave therefore walks, NG n-tiles at a time, along contiguous runs of 1 KiB
+// weight tiles, loading them straight into MFMA operand registers through a
+// ring of PF stages that keeps running across the boundary between one group of
+// n-tiles and the next, so the HBM stream never drains inside a launch.  The
+// eight K-slices of an output tile are added through LDS in a fixed order, so
+// results do not depend on scheduling.
 //
 // The epilogues fuse what follows each projection in the transformer block:
-// RoPE + scatter of Q/K/V into attention layouts, residual add, SiLU(gate)*up,
-// and the per-row softmax statistics of the LM head (logits are never stored).
+// RoPE + scatter of Q/K/V into the attention layouts, the residual add,
+// SiLU(gate)*up, and the per-row softmax statistics of the LM head (logits are
+// never stored).
 #include "model.h"
 
 namespace odb {
 
+constexpr int WK = 8;    // waves per workgroup = K slices
+
 struct GemmArgs {
     const u16 *A, *W;
-    int KT, MT_total, NT, ksplit;
-    float *partial;
-    unsigned *counters;
+    int KT, MT_total, NT;
+    // fused RMSNorm of the input rows: A holds bf16(x * gain) and ssq[row][0..n_ssq) partial sums
+    // of x^2; the result rows are scaled by 1/sqrt(sum/d + eps).  ssq == nullptr: A is used as is.
+    const float *ssq;
+    int n_ssq;
+    float eps, inv_d;
 };
 
-template <int MT, int NG, int PF, bool SWAP>
-__device__ inline void mainloop(const GemmArgs &g, int nt0, int mt0, int k0, int k1, int lane, f32x4 (&acc)[MT][NG]) {
-    const u16 *wp[NG];
+template <int MT, int NG, int PF, class Epi>
+__global__ __launch_bounds__(64 * WK) void gemm_stream_kernel(GemmArgs g, Epi epi) {
+    constexpr int MC = NG >= 3 ? 2 : (MT < 4 ? MT : 4);    // m-tiles reduced per pass through LDS (<= 48 KiB)
+    static_assert(MT % MC == 0 && MC * NG <= 6, "m chunking");
+    __shared__ f32x4 red[WK][MC * NG][64];
+    __shared__ float s_rstd[MT * 16];
+
+    const int lane = threadIdx.x & 63, wk = threadIdx.x >> 6;
+    const int n_lo = (int)(((long)blockIdx.x * g.NT) / gridDim.x);
+    const int n_hi = (int)(((long)(blockIdx.x + 1) * g.NT) / gridDim.x);
+    if (n_lo >= n_hi) return;
+    const int mt0 = blockIdx.y * MT;
+    const int KW = g.KT / WK;
+    const int ngroups = (n_hi - n_lo + NG - 1) / NG;
+
+    const u16 *wbase = g.W + (size_t)(wk * KW) * kTileElems + lane * 8;
     const u16 *ap[MT];
-#pragma unroll
-    for (int n = 0; n < NG; n++) wp[n] = g.W + ((size_t)(nt0 + n) * g.KT) * kTileElems + lane * 8;
 #pragma unroll
     for (int m = 0; m < MT; m++) {
         int mt = mt0 + m < g.MT_total ? mt0 + m : g.MT_total - 1;
-        ap[m] = g.A + (size_t)mt * kTileElems + lane * 8;
+        ap[m] = g.A + ((size_t)(wk * KW) * g.MT_total + mt) * kTileElems + lane * 8;
     }
     const size_t a_step = (size_t)g.MT_total * kTileElems;
+
     frag_t wb[PF][NG], ab[PF][MT];
+    auto load_stage = [&](int slot, int grp, int kk) __attribute__((always_inline)) {
 #pragma unroll
-    for (int s = 0; s < PF - 1; s++) {
-        int kt = k0 + s;
-        if (kt < k1) {
-#pragma unroll
-            for (int n = 0; n < NG; n++) wb[s][n] = ld_frag(wp[n] + (size_t)kt * kTileElems);
-#pragma unroll
-            for (int m = 0; m < MT; m++) ab[s][m] = ld_frag(ap[m] + kt * a_step);
+        for (int n = 0; n < NG; n++) {
+            int nt = n_lo + grp * NG + n;
+            nt = nt < n_hi ? nt : n_hi - 1;
+            wb[slot][n] = ld_frag(wbase + ((size_t)nt * g.KT + kk) * kTileElems);
         }
+#pragma unroll
+        for (int m = 0; m < MT; m++) ab[slot][m] = ld_frag(ap[m] + kk * a_step);
+    };
+
+#pragma unroll
+    for (int s = 0; s < PF; s++) load_stage(s, 0, s);
+
+    // row scales of the fused RMSNorm (after the first weight loads are in flight)
+    for (int r = wk; r < MT * 16; r += WK) {
+        float rs = 1.0f;
+        if (g.ssq) {
+            int row = mt0 * 16 + r;
+            row = row < g.MT_total * 16 ? row : g.MT_total * 16 - 1;
+            float q = 0.f;
+            for (int i = lane; i < g.n_ssq; i += 64) q += g.ssq[(size_t)row * g.n_ssq + i];
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o);
+            rs = 1.0f / sqrtf(q * g.inv_d + g.eps);
+        }
+        if (lane == 0) s_rstd[r] = rs;
     }
-    for (int kb = k0; kb < k1; kb += PF) {
+
+    for (int grp = 0; grp < ngroups; grp++) {
+        f32x4 acc[MT][NG];
 #pragma unroll
-        for (int s = 0; s < PF; s++) {
-            const int ls = (s + PF - 1) % PF;
-            int kl = kb + s + PF - 1;
-            if (kl < k1) {
+        for (int m = 0; m < MT; m++)
 #pragma unroll
-                for (int n = 0; n < NG; n++) wb[ls][n] = ld_frag(wp[n] + (size_t)kl * kTileElems);
+            for (int n = 0; n < NG; n++) acc[m][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        for (int kb = 0; kb < KW; kb += PF) {
 #pragma unroll
-                for (int m = 0; m < MT; m++) ab[ls][m] = ld_frag(ap[m] + kl * a_step);
-            }
-            if (kb + s < k1) {
+            for (int s = 0; s < PF; s++) {
 #pragma unroll
                 for (int m = 0; m < MT; m++)
 #pragma unroll
-                    for (int n = 0; n < NG; n++)
-                        acc[m][n] = SWAP ? mfma16(ab[s][m], wb[s][n], acc[m][n]) : mfma16(wb[s][n], ab[s][m], acc[m][n]);
+                    for (int n = 0; n < NG; n++) acc[m][n] = mfma16(wb[s][n], ab[s][m], acc[m][n]);
+                // refill this slot with the step PF ahead, which may belong to the next group
+                int kn = kb + s + PF, gn = grp;
+                if (kn >= KW) { kn -= KW; gn++; }
+                if (gn < ngroups) load_stage(s, gn, kn);
             }
         }
-    }
-}
 
-template <int MT, int NG, int WK, int PF, class Epi>
-__global__ __launch_bounds__(64 * WK) void gemm_skinny_kernel(GemmArgs g, Epi epi) {
-    constexpr int TP = Epi::kTP;
-    constexpr int GP = NG / TP;               // epilogue groups per m-tile
-    static_assert(NG % TP == 0 && GP <= WK, "tile grouping");
-    const int lane = threadIdx.x & 63, wk = threadIdx.x >> 6;
-    const int nt0 = blockIdx.x * NG, ks = blockIdx.y, mt0 = blockIdx.z * MT;
-    const int kt_split = g.KT / g.ksplit;
-    const int per_wave = (kt_split + WK - 1) / WK;
-    const int k0 = ks * kt_split + wk * per_wave;
-    const int k1 = min(k0 + per_wave, (ks + 1) * kt_split);
-
-    f32x4 acc[MT][NG];
+        // add the eight K-slices through LDS, MC m-tiles at a time; the wave that owns a tile runs its epilogue
 #pragma unroll
-    for (int m = 0; m < MT; m++)
+        for (int mc = 0; mc < MT; mc += MC) {
 #pragma unroll
-        for (int n = 0; n < NG; n++) acc[m][n] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    if (epi.swapped(nt0)) mainloop<MT, NG, PF, true>(g, nt0, mt0, k0, k1, lane, acc);
-    else mainloop<MT, NG, PF, false>(g, nt0, mt0, k0, k1, lane, acc);
-
-    __shared__ f32x4 red[WK > 1 ? WK : 1][NG][64];
-    __shared__ unsigned s_last;
-    const bool split = g.ksplit > 1;
-
+            for (int m = 0; m < MC; m++)
 #pragma unroll
-    for (int m = 0; m < MT; m++) {
-        const int mt = mt0 + m;
-        f32x4 c[TP];
-        bool mine;
-        int grp;
-        if (WK > 1) {
-#pragma unroll
-            for (int n = 0; n < NG; n++) red[wk][n][lane] = acc[m][n];
+                for (int n = 0; n < NG; n++) red[wk][m * NG + n][lane] = acc[mc + m][n];
             __syncthreads();
-            mine = wk < GP;
-            grp = wk;
-            if (mine) {
+            for (int t = wk; t < MC * NG; t += WK) {
+                const int m = t / NG, n = t % NG;
+                const int mt = mt0 + mc + m, nt = n_lo + grp * NG + n;
+                if (mt < g.MT_total && nt < n_hi) {
+                    f32x4 c;
+                    if (!epi.transposed(nt)) {
+                        c = red[0][t][lane];
 #pragma unroll
-                for (int t = 0; t < TP; t++) {
-                    f32x4 sum = red[0][grp * TP + t][lane];
+                        for (int w = 1; w < WK; w++) c += red[w][t][lane];
+                        c *= s_rstd[(mc + m) * 16 + (lane & 15)];
+                    } else {
+                        // hand lane (g, ni) the four rows 4g..4g+3 of column ni instead of four columns of one row
+                        const int ni = lane & 15, gq = lane >> 4;
+                        const float *base = reinterpret_cast<const float *>(&red[0][t][0]);
+                        const int stride = MC * NG * 64 * 4;        // floats between the waves' copies
 #pragma unroll
-                    for (int w = 1; w < WK; w++) sum += red[w][grp * TP + t][lane];
-                    c[t] = sum;
-                }
-            }
-        }
+                        for (int r = 0; r < 4; r++) {
+                            const int src = ((ni >> 2) * 16 + 4 * gq + r) * 4 + (ni & 3);
+                            float v = base[src];
 #pragma unroll
-        for (int gp = 0; gp < (WK > 1 ? 1 : GP); gp++) {
-            if (WK == 1) {
-                mine = true;
-                grp = gp;
-#pragma unroll
-                for (int t = 0; t < TP; t++) c[t] = acc[m][gp * TP + t];
-            }
-            if (mine && mt < g.MT_total) {
-                if (!split) {
-                    epi(mt, nt0 + grp * TP, c, lane);
-                } else {
-#pragma unroll
-                    for (int t = 0; t < TP; t++) {
-                        size_t tile = ((size_t)ks * g.MT_total + mt) * g.NT + nt0 + grp * TP + t;
-                        *reinterpret_cast<f32x4 *>(g.partial + tile * 256 + lane * 4) = c[t];
+                            for (int w = 1; w < WK; w++) v += base[w * stride + src];
+                            c[r] = v * s_rstd[(mc + m) * 16 + 4 * gq + r];
+                        }
                     }
+                    epi(mt, nt, c, lane);
                 }
             }
+            __syncthreads();
         }
-        if (WK > 1) __syncthreads();
     }
-    if (!split) return;
-
-    // split-K: the last workgroup to arrive for this (m-block, n-group) adds the partials
-    const unsigned cidx = blockIdx.z * gridDim.x + blockIdx.x;
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        unsigned old = atomicAdd(&g.counters[cidx], 1u);
-        s_last = (old == (unsigned)g.ksplit - 1) ? 1u : 0u;
-    }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    for (int tp = wk; tp < MT * GP; tp += WK) {
-        const int m = tp / GP, grp = tp % GP, mt = mt0 + m;
-        if (mt >= g.MT_total) continue;
-        f32x4 c[TP];
-#pragma unroll
-        for (int t = 0; t < TP; t++) {
-            f32x4 sum = f32x4{0.f, 0.f, 0.f, 0.f};
-            for (int s = 0; s < g.ksplit; s++) {
-                size_t tile = ((size_t)s * g.MT_total + mt) * g.NT + nt0 + grp * TP + t;
-                sum += *reinterpret_cast<const f32x4 *>(g.partial + tile * 256 + lane * 4);
-            }
-            c[t] = sum;
-        }
-        epi(mt, nt0 + grp * TP, c, lane);
-    }
-    if (threadIdx.x == 0) g.counters[cidx] = 0;
 }
 
 // ---- epilogues ------------------------------------------------------------------
-// Not swapped: lane l holds C[row = 16*mt + (l&15)][col = 16*nt + 4*(l>>4) + r], r = 0..3.
-// Swapped:     lane l holds C[row = 16*mt + 4*(l>>4) + r][col = 16*nt + (l&15)].
+// Default:    lane l holds C[row = 16*mt + (l&15)][col = 16*nt + 4*(l>>4) + r], r = 0..3.
+// Transposed: lane l holds C[row = 16*mt + 4*(l>>4) + r][col = 16*nt + (l&15)].
 
 __device__ inline void st_bf16x4(u16 *p, float a, float b, float c, float d) {
     uint2 v;
@@ -180,15 +158,14 @@ __device__ inline void st_bf16x4(u16 *p, float a, float b, float c, float d) {
 }
 
 struct EpiQKV {
-    static constexpr int kTP = 2;
     QkvOut o;
     int mt_total;
-    __device__ bool swapped(int nt) const { return nt * 16 >= 2 * o.d; }
-    __device__ void operator()(int mt, int nt, const f32x4 *c, int lane) const {
+    __device__ bool transposed(int nt) const { return nt * 16 >= 2 * o.d; }
+    __device__ void operator()(int mt, int nt, f32x4 c, int lane) const {
         const int mi = lane & 15, g = lane >> 4;
         const int unit = mt / o.tiles_per_unit, tu = mt % o.tiles_per_unit;
         const int n = nt * 16, sec = n / o.d, rr = n % o.d;
-        const int hd = rr / o.dh, p0 = rr % o.dh;            // p0 is a multiple of 32
+        const int hd = rr / o.dh, p0 = rr % o.dh;            // p0 is a multiple of 16
         if (sec < 2) {
             // physical channel 2j is logical j, 2j+1 is j + dh/2: each adjacent pair is a RoPE pair
             const int pos = o.pos_off + tu * 16 + mi;
@@ -196,81 +173,80 @@ struct EpiQKV {
             u16 *dst = sec == 0
                 ? o.q + (((size_t)hd * mt_total + mt) * (o.dh / 32) + p0 / 32) * kTileElems
                 : o.k + unit * o.k_unit_stride + hd * o.k_head_stride + ((size_t)tu * (o.dh / 32) + p0 / 32) * kTileElems;
-#pragma unroll
-            for (int t = 0; t < 2; t++) {
-                const int j = (p0 + t * 16 + 4 * g) >> 1;
-                float2 cs0 = tab[j], cs1 = tab[j + 1];
-                float y0 = c[t][0] * cs0.x - c[t][1] * cs0.y;
-                float y1 = c[t][1] * cs0.x + c[t][0] * cs0.y;
-                float y2 = c[t][2] * cs1.x - c[t][3] * cs1.y;
-                float y3 = c[t][3] * cs1.x + c[t][2] * cs1.y;
-                st_bf16x4(dst + ((t * 2 + (g >> 1)) * 16 + mi) * 8 + (g & 1) * 4, y0, y1, y2, y3);
-            }
+            const int j = (p0 + 4 * g) >> 1;
+            float2 cs0 = tab[j], cs1 = tab[j + 1];
+            float y0 = c[0] * cs0.x - c[1] * cs0.y;
+            float y1 = c[1] * cs0.x + c[0] * cs0.y;
+            float y2 = c[2] * cs1.x - c[3] * cs1.y;
+            float y3 = c[3] * cs1.x + c[2] * cs1.y;
+            const int kk = (p0 & 16) + 4 * g;                 // k-element of y0 inside the 32-wide tile
+            st_bf16x4(dst + ((kk >> 3) * 16 + mi) * 8 + (kk & 7), y0, y1, y2, y3);
         } else {
             // V^T tile: row = channel, the 32 keys of a tile sit in k-slot 8*g + 4*half + r
-#pragma unroll
-            for (int t = 0; t < 2; t++) {
-                const int dt16 = p0 / 16 + t;
-                u16 *dst = o.v + unit * o.v_unit_stride + hd * o.v_head_stride +
-                           ((size_t)(tu >> 1) * (o.dh / 16) + dt16) * kTileElems + lane * 8 + 4 * (tu & 1);
-                st_bf16x4(dst, c[t][0], c[t][1], c[t][2], c[t][3]);
-            }
+            u16 *dst = o.v + unit * o.v_unit_stride + hd * o.v_head_stride +
+                       ((size_t)(tu >> 1) * (o.dh / 16) + p0 / 16) * kTileElems + lane * 8 + 4 * (tu & 1);
+            st_bf16x4(dst, c[0], c[1], c[2], c[3]);
         }
     }
 };
 
+// h += C.  With a NormOut it also prepares the next RMSNorm: hb = bf16(h * gain) in the
+// operand layout and the sum of squares of this tile's 16 columns per row.
 struct EpiResid {
-    static constexpr int kTP = 1;
     float *h;
     int ld;
-    __device__ bool swapped(int) const { return false; }
-    __device__ void operator()(int mt, int nt, const f32x4 *c, int lane) const {
-        float *p = h + (size_t)(mt * 16 + (lane & 15)) * ld + nt * 16 + 4 * (lane >> 4);
-        f32x4 v = *reinterpret_cast<f32x4 *>(p);
-        *reinterpret_cast<f32x4 *>(p) = v + c[0];
+    NormOut no;
+    int mt_total;
+    __device__ bool transposed(int) const { return false; }
+    __device__ void operator()(int mt, int nt, f32x4 c, int lane) const {
+        const int mi = lane & 15, g = lane >> 4, row = mt * 16 + mi, col = nt * 16 + 4 * g;
+        float *p = h + (size_t)row * ld + col;
+        f32x4 v = *reinterpret_cast<f32x4 *>(p) + c;
+        *reinterpret_cast<f32x4 *>(p) = v;
+        if (no.hb) {
+            f32x4 gn = *reinterpret_cast<const f32x4 *>(no.gain + col);
+            const int kk = (nt & 1) * 16 + 4 * g;
+            st_bf16x4(no.hb + ((size_t)(nt >> 1) * mt_total + mt) * kTileElems + ((kk >> 3) * 16 + mi) * 8 + (kk & 7),
+                      v[0] * gn[0], v[1] * gn[1], v[2] * gn[2], v[3] * gn[3]);
+            float q = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+            q += __shfl_xor(q, 16);
+            q += __shfl_xor(q, 32);
+            if (g == 0) no.ssq[(size_t)row * no.n_ssq + nt] = q;
+        }
     }
 };
 
+// W_gu interleaves the rows of W_gate and W_up (physical row 2j = gate j, 2j+1 = up j)
 struct EpiSwiGLU {
-    static constexpr int kTP = 2;
     u16 *act;
     int mt_total;
-    __device__ bool swapped(int) const { return false; }
-    __device__ void operator()(int mt, int nt, const f32x4 *c, int lane) const {
-        const int mi = lane & 15, g = lane >> 4, t = nt >> 1;
-        float y[4];
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-            float x = c[0][r];
-            y[r] = x / (1.0f + expf(-x)) * c[1][r];
-        }
-        u16 *dst = act + ((size_t)(t >> 1) * mt_total + mt) * kTileElems + (((t & 1) * 2 + (g >> 1)) * 16 + mi) * 8 +
-                   (g & 1) * 4;
-        st_bf16x4(dst, y[0], y[1], y[2], y[3]);
+    __device__ bool transposed(int) const { return false; }
+    __device__ void operator()(int mt, int nt, f32x4 c, int lane) const {
+        const int mi = lane & 15, g = lane >> 4;
+        const int j = nt * 8 + 2 * g;                         // channel of the first (gate, up) pair
+        float y0 = c[0] / (1.0f + expf(-c[0])) * c[1];
+        float y1 = c[2] / (1.0f + expf(-c[2])) * c[3];
+        const int kk = j & 31;
+        u16 *dst = act + ((size_t)(j >> 5) * mt_total + mt) * kTileElems + ((kk >> 3) * 16 + mi) * 8 + (kk & 7);
+        *reinterpret_cast<uint32_t *>(dst) = pack2bf(y0, y1);
     }
 };
 
+// stats[row][nt] = (max, sum exp(z - max), argmax) over the 16 columns of n-tile nt
 struct EpiLMStats {
-    static constexpr int kTP = 2;
     float *stats;
     int n_part;
-    __device__ bool swapped(int) const { return false; }
-    __device__ void operator()(int mt, int nt, const f32x4 *c, int lane) const {
+    __device__ bool transposed(int) const { return false; }
+    __device__ void operator()(int mt, int nt, f32x4 c, int lane) const {
         const int mi = lane & 15, g = lane >> 4;
-        float m = -INFINITY;
-        int a = 0;
+        float m = c[0];
+        int a = nt * 16 + 4 * g;
 #pragma unroll
-        for (int t = 0; t < 2; t++)
-#pragma unroll
-            for (int r = 0; r < 4; r++) {
-                float z = c[t][r];
-                if (z > m) { m = z; a = nt * 16 + t * 16 + 4 * g + r; }
-            }
+        for (int r = 1; r < 4; r++)
+            if (c[r] > m) { m = c[r]; a = nt * 16 + 4 * g + r; }
         float s = 0.f;
 #pragma unroll
-        for (int t = 0; t < 2; t++)
-#pragma unroll
-            for (int r = 0; r < 4; r++) s += expf(c[t][r] - m);
+        for (int r = 0; r < 4; r++) s += expf(c[r] - m);
 #pragma unroll
         for (int o = 16; o <= 32; o <<= 1) {
             float om = __shfl_xor(m, o), os = __shfl_xor(s, o);
@@ -281,7 +257,7 @@ struct EpiLMStats {
             m = nm;
         }
         if (g == 0) {
-            float *p = stats + ((size_t)(mt * 16 + mi) * n_part + (nt >> 1)) * 3;
+            float *p = stats + ((size_t)(mt * 16 + mi) * n_part + nt) * 3;
             p[0] = m;
             p[1] = s;
             p[2] = __int_as_float(a);
@@ -289,60 +265,56 @@ struct EpiLMStats {
     }
 };
 
+// plain fp32 store of the valid rows (unit u, i < valid) to a compact row-major matrix
 struct EpiStore {
-    static constexpr int kTP = 1;
     float *out;
-    int rows, ld;
-    __device__ bool swapped(int) const { return false; }
-    __device__ void operator()(int mt, int nt, const f32x4 *c, int lane) const {
+    int units, rpu_pad, valid, ld;
+    __device__ bool transposed(int) const { return false; }
+    __device__ void operator()(int mt, int nt, f32x4 c, int lane) const {
         int row = mt * 16 + (lane & 15);
-        if (row < rows) *reinterpret_cast<f32x4 *>(out + (size_t)row * ld + nt * 16 + 4 * (lane >> 4)) = c[0];
+        int u = row / rpu_pad, i = row % rpu_pad;
+        if (u < units && i < valid)
+            *reinterpret_cast<f32x4 *>(out + ((size_t)u * valid + i) * ld + nt * 16 + 4 * (lane >> 4)) = c;
     }
 };
 
 // ---- launch ---------------------------------------------------------------------
-template <class Epi>
-static void launch(const u16 *a, const u16 *w, GemmShape sh, Epi epi, Workspace ws, hipStream_t s) {
+constexpr int kStreamWGs = 256;      // one workgroup per compute unit
+
+template <int NG, class Epi>
+static void launch(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi epi, hipStream_t s) {
     GemmArgs g;
     g.A = a; g.W = w; g.KT = sh.K_tiles; g.MT_total = sh.M_tiles; g.NT = sh.N_tiles;
-    g.partial = ws.partial; g.counters = ws.counters;
-    const int mt_blk = sh.M_tiles <= 2 ? 2 : (sh.M_tiles <= 4 ? 4 : 8);
-    const int ng = (mt_blk == 8 && sh.N_tiles % 4 == 0) ? 4 : 2;
-    const int wk = mt_blk == 8 ? 4 : 8;
-    const int mblocks = (sh.M_tiles + mt_blk - 1) / mt_blk;
-    const int wgs = (sh.N_tiles / ng) * mblocks;
-    int ksplit = 1;
-    while (wgs * ksplit < 256 && sh.K_tiles % (ksplit * 2) == 0 && sh.K_tiles / (ksplit * 2) >= wk &&
-           (size_t)(ksplit * 2) * sh.M_tiles * sh.N_tiles * 1024 <= ws.partial_bytes)
-        ksplit *= 2;
-    g.ksplit = ksplit;
-    dim3 grid(sh.N_tiles / ng, ksplit, mblocks);
-    if (mt_blk == 2) gemm_skinny_kernel<2, 2, 8, 4, Epi><<<grid, 512, 0, s>>>(g, epi);
-    else if (mt_blk == 4) gemm_skinny_kernel<4, 2, 8, 3, Epi><<<grid, 512, 0, s>>>(g, epi);
-    else if (ng == 4) gemm_skinny_kernel<8, 4, 4, 2, Epi><<<grid, 256, 0, s>>>(g, epi);
-    else gemm_skinny_kernel<8, 2, 4, 2, Epi><<<grid, 256, 0, s>>>(g, epi);
+    g.ssq = ni.ssq; g.n_ssq = ni.n_ssq; g.eps = ni.eps; g.inv_d = 1.0f / (float)(sh.K_tiles * 32);
+    const int kw = sh.K_tiles / WK;                 // K_tiles is a multiple of 8 (checked at model creation)
+    const int groups = (sh.N_tiles + NG - 1) / NG;
+    const int wgs = groups < kStreamWGs ? groups : kStreamWGs;
+    if (sh.M_tiles <= 2) {
+        dim3 grid(wgs, 1);
+        if (kw % 8 == 0) gemm_stream_kernel<2, NG, 8, Epi><<<grid, 64 * WK, 0, s>>>(g, epi);
+        else gemm_stream_kernel<2, NG, 1, Epi><<<grid, 64 * WK, 0, s>>>(g, epi);
+    } else {
+        dim3 grid(wgs, (sh.M_tiles + 7) / 8);
+        if (kw % 2 == 0) gemm_stream_kernel<8, NG, 2, Epi><<<grid, 64 * WK, 0, s>>>(g, epi);
+        else gemm_stream_kernel<8, NG, 1, Epi><<<grid, 64 * WK, 0, s>>>(g, epi);
+    }
 }
 
-void launch_gemm_qkv(const u16 *xa, const u16 *w, GemmShape sh, QkvOut out, Workspace ws, hipStream_t s) {
-    EpiQKV e{out, sh.M_tiles};
-    launch(xa, w, sh, e, ws, s);
+void launch_gemm_qkv(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, QkvOut out, hipStream_t s) {
+    launch<3>(xa, w, sh, ni, EpiQKV{out, sh.M_tiles}, s);
 }
-void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int ldh, Workspace ws, hipStream_t s) {
-    EpiResid e{h, ldh};
-    launch(a, w, sh, e, ws, s);
+void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int ldh, NormOut no, hipStream_t s) {
+    launch<1>(a, w, sh, NormIn{nullptr, 0, 0.f}, EpiResid{h, ldh, no, sh.M_tiles}, s);
 }
-void launch_gemm_swiglu(const u16 *xa, const u16 *w, GemmShape sh, u16 *act, Workspace ws, hipStream_t s) {
-    EpiSwiGLU e{act, sh.M_tiles};
-    launch(xa, w, sh, e, ws, s);
+void launch_gemm_swiglu(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, u16 *act, hipStream_t s) {
+    launch<3>(xa, w, sh, ni, EpiSwiGLU{act, sh.M_tiles}, s);
 }
-void launch_gemm_lmstats(const u16 *xa, const u16 *w, GemmShape sh, float *stats, Workspace ws, hipStream_t s) {
-    EpiLMStats e{stats, sh.N_tiles / 2};
-    launch(xa, w, sh, e, ws, s);
+void launch_gemm_lmstats(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, float *stats, hipStream_t s) {
+    launch<3>(xa, w, sh, ni, EpiLMStats{stats, sh.N_tiles}, s);
 }
-void launch_gemm_store(const u16 *xa, const u16 *w, GemmShape sh, float *out, int rows, int ld, Workspace ws,
-                       hipStream_t s) {
-    EpiStore e{out, rows, ld};
-    launch(xa, w, sh, e, ws, s);
+void launch_gemm_store(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, float *out, int units, int rpu_pad,
+                       int valid, int ld, hipStream_t s) {
+    launch<3>(xa, w, sh, ni, EpiStore{out, units, rpu_pad, valid, ld}, s);
 }
 
 }  // namespace odb

@@ -16,8 +16,8 @@ namespace odb {
 //                 j, 2j+1 -> channel j + dh/2) so that a RoPE pair sits in one
 //                 lane of the GEMM result; rows 2d..3d-1 = Wv in logical order.
 // W_o    [d, d], W_d [d, F], W_lm [V, d]: logical row order, tiles [n_tile][k_tile].
-// W_gu   [2F, d]: n-tile 2t = rows 16t..16t+15 of W_gate, n-tile 2t+1 = the same
-//                 rows of W_up, so one wave holds a gate tile and its up tile.
+// W_gu   [2F, d]: physical row 2j = row j of W_gate, 2j+1 = row j of W_up, so a
+//                 lane of the GEMM result holds (gate, up) pairs.
 // E      [V, d] plain row-major (gathered by row).
 enum PhysKind { PK_QKV = 0, PK_O, PK_GU, PK_D, PK_LM, PK_EMBED, PK_COUNT };
 
@@ -35,6 +35,9 @@ struct Model {
     unsigned *counters;        // split-K arrival counters (self-resetting)
     u16 *staging;              // set/get tensor staging
     size_t staging_bytes;
+    // optional per-kernel-class timing (odb_profile_begin / odb_profile_end)
+    int prof_class, prof_cap, prof_used;
+    hipEvent_t *prof_ev;       // 2 * prof_cap events
 };
 
 struct Cache {
@@ -54,17 +57,25 @@ void launch_fill_f32(float *p, float v, size_t n, hipStream_t s);
 void launch_rope_table(float *table, int n_pos, int dh, double base, hipStream_t s);
 void launch_cache_read(const Cache &c, int layer, int kv, int batch_index, int pos0, int n, u16 *out, hipStream_t s);
 
+// Fused RMSNorm.  NormIn: the GEMM input holds bf16(x * gain) and ssq[row][0..n_ssq) are partial
+// sums of x^2 over the row; output rows are scaled by 1/sqrt(sum/d + eps) (ssq == nullptr: off).
+// NormOut: the residual epilogue also emits that pair for the next norm (hb == nullptr: off).
+struct NormIn { const float *ssq; int n_ssq; float eps; };
+struct NormOut { u16 *hb; float *ssq; const float *gain; int n_ssq; };
+
 // ---- rows.hip ---------------------------------------------------------------
 // Row bookkeeping.  Rows are grouped in "units" (a draft in the step, a
 // sequence in the prefill) of rpu_pad rows (multiple of 16) of which the first
 // `valid` are real.
 struct RowMap { int units, rpu_pad, valid; };
-void launch_embed(const Model &m, const int32_t *tokens, RowMap rm, float *h, hipStream_t s);
+// h = E[token] (fp32); with a NormOut also hb = bf16(h * gain) and the per-tile sums of squares
+void launch_embed(const Model &m, const int32_t *tokens, RowMap rm, float *h, NormOut no, hipStream_t s);
 // xa = bf16(rmsnorm(h) * gain) in tile-major [d/32][mt_total][512]; if `compact`, destination
 // row j = u*(valid-skip) + (i-skip) for source row (u, i >= skip), else the same row.
 void launch_rmsnorm(const float *h, const float *gain, float eps, int d, RowMap rm, int skip, bool compact,
                     int dst_mt_total, u16 *xa, hipStream_t s);
-void launch_lm_finish(const float *stats, int n_part, int rows, int rows_per_unit, const int32_t *tokens,
+// stats rows come in units of rpu_pad rows of which the first rpu are real; the `rows` outputs are compact
+void launch_lm_finish(const float *stats, int n_part, int rows, int rpu, int rpu_pad, const int32_t *tokens,
                       int mask_id, float tau, float *conf, int32_t *argmax, uint8_t *unmask, hipStream_t s);
 
 // ---- gemm.hip ---------------------------------------------------------------
@@ -76,12 +87,13 @@ struct QkvOut {
     const float *rope;         // (cos,sin) table
     int tiles_per_unit, pos_off, H, dh, d;
 };
-struct Workspace { float *partial; size_t partial_bytes; unsigned *counters; };
-void launch_gemm_qkv(const u16 *xa, const u16 *w, GemmShape sh, QkvOut out, Workspace ws, hipStream_t s);
-void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int ldh, Workspace ws, hipStream_t s);
-void launch_gemm_swiglu(const u16 *xa, const u16 *w, GemmShape sh, u16 *act, Workspace ws, hipStream_t s);
-void launch_gemm_lmstats(const u16 *xa, const u16 *w, GemmShape sh, float *stats, Workspace ws, hipStream_t s);
-void launch_gemm_store(const u16 *xa, const u16 *w, GemmShape sh, float *out, int rows, int ld, Workspace ws, hipStream_t s);
+void launch_gemm_qkv(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, QkvOut out, hipStream_t s);
+void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int ldh, NormOut no, hipStream_t s);
+void launch_gemm_swiglu(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, u16 *act, hipStream_t s);
+void launch_gemm_lmstats(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, float *stats, hipStream_t s);
+// fp32 store of the valid rows (unit u, i < valid of rpu_pad) to a compact row-major [units*valid, ld]
+void launch_gemm_store(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, float *out, int units, int rpu_pad,
+                       int valid, int ld, hipStream_t s);
 
 // ---- attn.hip ---------------------------------------------------------------
 struct AttnArgs {
@@ -91,14 +103,11 @@ struct AttnArgs {
     const u16 *kf, *vf;        // fresh K/V of the units (step only)
     size_t kf_unit_stride, kf_head_stride, vf_unit_stride, vf_head_stride;
     u16 *out;                  // [d/32][mt_total][512]
-    float *part_o, *part_ml;   // split partials
     int H, dh, mt_total, tiles_per_unit, units, units_per_seq;
     int L;                     // cached length
     int blk_lo, blk_hi;        // cached keys in [blk_lo, blk_hi) are ignored
     int fresh;                 // number of fresh keys per unit (0 in the prefill)
-    int nsplit;
 };
-size_t attn_partial_bytes(const AttnArgs &a);
 void launch_attention(AttnArgs a, hipStream_t s);
 
 }  // namespace odb

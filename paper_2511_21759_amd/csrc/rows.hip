@@ -4,8 +4,9 @@
 
 namespace odb {
 
-// h[r, :] = E[token(r), :] as fp32 (the residual stream stays in fp32).
-__global__ void embed_kernel(const u16 *embed, const int32_t *tokens, RowMap rm, int d, int vocab, float *h) {
+// h[r, :] = E[token(r), :] as fp32 (the residual stream stays in fp32).  One thread per 16 columns.
+__global__ void embed_kernel(const u16 *embed, const int32_t *tokens, RowMap rm, int d, int vocab, float *h,
+                             NormOut no, int mt_total) {
     int r = blockIdx.x;
     int u = r / rm.rpu_pad, i = r % rm.rpu_pad;
     int tok = 0;
@@ -13,22 +14,46 @@ __global__ void embed_kernel(const u16 *embed, const int32_t *tokens, RowMap rm,
     tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
     const u16 *src = embed + (size_t)tok * d;
     float *dst = h + (size_t)r * d;
-    for (int c = threadIdx.x * 8; c < d; c += blockDim.x * 8) {
-        frag_t f = ld_frag(src + c);
-        float4 a, b;
-        a.x = bf2f(f.w[0] & 0xffff); a.y = bf2f(f.w[0] >> 16);
-        a.z = bf2f(f.w[1] & 0xffff); a.w = bf2f(f.w[1] >> 16);
-        b.x = bf2f(f.w[2] & 0xffff); b.y = bf2f(f.w[2] >> 16);
-        b.z = bf2f(f.w[3] & 0xffff); b.w = bf2f(f.w[3] >> 16);
-        *reinterpret_cast<float4 *>(dst + c) = a;
-        *reinterpret_cast<float4 *>(dst + c + 4) = b;
+    for (int nt = threadIdx.x; nt < d / 16; nt += blockDim.x) {
+        float x[16];
+#pragma unroll
+        for (int half = 0; half < 2; half++) {
+            frag_t f = ld_frag(src + nt * 16 + half * 8);
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                x[half * 8 + 2 * j] = bf2f(f.w[j] & 0xffff);
+                x[half * 8 + 2 * j + 1] = bf2f(f.w[j] >> 16);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 16; j += 4)
+            *reinterpret_cast<float4 *>(dst + nt * 16 + j) = make_float4(x[j], x[j + 1], x[j + 2], x[j + 3]);
+        if (no.hb) {
+            float q = 0.f;
+#pragma unroll
+            for (int j = 0; j < 16; j++) q += x[j] * x[j];
+            no.ssq[(size_t)r * no.n_ssq + nt] = q;
+            const float *gn = no.gain + nt * 16;
+#pragma unroll
+            for (int half = 0; half < 2; half++) {
+                frag_t f;
+#pragma unroll
+                for (int j = 0; j < 4; j++)
+                    f.w[j] = pack2bf(x[half * 8 + 2 * j] * gn[half * 8 + 2 * j],
+                                     x[half * 8 + 2 * j + 1] * gn[half * 8 + 2 * j + 1]);
+                const int chunk = (nt & 1) * 2 + half;
+                *reinterpret_cast<frag_t *>(no.hb + ((size_t)(nt >> 1) * mt_total + (r >> 4)) * kTileElems +
+                                            (chunk * 16 + (r & 15)) * 8) = f;
+            }
+        }
     }
 }
 
-void launch_embed(const Model &m, const int32_t *tokens, RowMap rm, float *h, hipStream_t s) {
+void launch_embed(const Model &m, const int32_t *tokens, RowMap rm, float *h, NormOut no, hipStream_t s) {
     int rows = rm.units * rm.rpu_pad;
-    int threads = m.cfg.d_model / 8 < 256 ? 64 : 256;
-    embed_kernel<<<dim3(rows), threads, 0, s>>>(m.w[PK_EMBED], tokens, rm, m.cfg.d_model, m.cfg.vocab, h);
+    int threads = m.cfg.d_model / 16 < 256 ? 64 : 256;
+    embed_kernel<<<dim3(rows), threads, 0, s>>>(m.w[PK_EMBED], tokens, rm, m.cfg.d_model, m.cfg.vocab, h, no,
+                                                rows / 16);
 }
 
 __device__ inline float wave_sum(float v) {
@@ -89,7 +114,7 @@ void launch_rmsnorm(const float *h, const float *gain, float eps, int d, RowMap 
 
 // ---- LM-head statistics -> confidence, argmax, unmask ------------------------
 // stats[row][part] = (max logit, sum exp(logit - max), argmax as int bits) over
-// the 32 vocabulary columns of part.  Merging keeps the lowest id on equal maxima.
+// the 16 vocabulary columns of part.  Merging keeps the lowest id on equal maxima.
 struct Stat { float m, s; int a; };
 
 __device__ inline Stat merge(Stat x, Stat y) {
@@ -103,16 +128,16 @@ __device__ inline Stat merge(Stat x, Stat y) {
     return o;
 }
 
-__global__ __launch_bounds__(256) void lm_finish_kernel(const float *stats, int n_part, int rows, int rpu,
+__global__ __launch_bounds__(256) void lm_finish_kernel(const float *stats, int n_part, int rows, int rpu, int rpu_pad,
                                                         const int32_t *tokens, int mask_id, float tau, float *conf,
                                                         int32_t *argmax, uint8_t *unmask) {
     __shared__ float s_conf[256];
     int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int u = blockIdx.x;
     for (int i = wave; i < rpu; i += 4) {
-        int row = u * rpu + i;
+        int row = u * rpu + i;                                  // compact output row
         if (row >= rows) break;
-        const float *p = stats + (size_t)row * n_part * 3;
+        const float *p = stats + ((size_t)u * rpu_pad + i) * n_part * 3;
         Stat acc = {-INFINITY, 0.f, 0x7fffffff};
         for (int q = lane; q < n_part; q += 64) {
             Stat t = {p[q * 3], p[q * 3 + 1], __float_as_int(p[q * 3 + 2])};
@@ -153,11 +178,11 @@ __global__ __launch_bounds__(256) void lm_finish_kernel(const float *stats, int 
     }
 }
 
-void launch_lm_finish(const float *stats, int n_part, int rows, int rows_per_unit, const int32_t *tokens, int mask_id,
-                      float tau, float *conf, int32_t *argmax, uint8_t *unmask, hipStream_t s) {
-    int units = (rows + rows_per_unit - 1) / rows_per_unit;
-    lm_finish_kernel<<<dim3(units), 256, 0, s>>>(stats, n_part, rows, rows_per_unit, tokens, mask_id, tau, conf, argmax,
-                                                 unmask);
+void launch_lm_finish(const float *stats, int n_part, int rows, int rpu, int rpu_pad, const int32_t *tokens,
+                      int mask_id, float tau, float *conf, int32_t *argmax, uint8_t *unmask, hipStream_t s) {
+    int units = (rows + rpu - 1) / rpu;
+    lm_finish_kernel<<<dim3(units), 256, 0, s>>>(stats, n_part, rows, rpu, rpu_pad, tokens, mask_id, tau, conf,
+                                                 argmax, unmask);
 }
 
 }  // namespace odb

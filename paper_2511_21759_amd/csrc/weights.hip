@@ -20,9 +20,8 @@ __host__ __device__ inline void phys_to_logical(int pk, int prow, int d, int dh,
         break;
     }
     case PK_GU: {
-        int t = prow >> 4;
-        lrow = (t >> 1) * 16 + (prow & 15);
-        tid = (t & 1) ? ODB_T_WU : ODB_T_WG;
+        lrow = prow >> 1;
+        tid = (prow & 1) ? ODB_T_WU : ODB_T_WG;
         break;
     }
     case PK_O: tid = ODB_T_WO; lrow = prow; break;
