@@ -130,6 +130,27 @@ int odb_block_step(odb_model *m, const odb_cache *c, const int32_t *drafts_dev,
                    int block_off, int b, int S, float tau, float *conf_dev,
                    int32_t *argmax_dev, uint8_t *unmask_dev, void *stream);
 
+/* How odb_block_step runs.  ODB_STEP_KERNELS (default): one kernel per
+ * projection / attention.  ODB_STEP_FUSED: one persistent kernel for the whole
+ * step whenever it has at most 128 rows (batch*S*ceil16(b)); same results bit
+ * for bit.  On MI355X the grid barriers of the fused kernel currently cost more
+ * than kernel boundaries, so it is the slower of the two and stays opt-in. */
+#define ODB_STEP_FUSED 0
+#define ODB_STEP_KERNELS 1
+int odb_set_step_mode(odb_model *m, int mode);
+
+/* Synchronises the device and returns ODB_OK, or ODB_E_HIP if a fused step
+ * kernel gave up waiting at one of its grid barriers (its outputs are then
+ * invalid); clears the condition. */
+int odb_model_status(odb_model *m);
+
+/* Debug aid: while dev_u64 is non-NULL the fused step kernel stores, for every
+ * workgroup w, the 100 MHz wall-clock time at which it arrives at and leaves each
+ * of its grid barriers into dev_u64[w*stride + 2*i], [.. + 2*i + 1] (dev uint64,
+ * number of workgroups = number of compute units, stride >= 2*(2 + 5*n_layers)).
+ * NULL switches it off. */
+int odb_debug_step_trace(odb_model *m, void *dev_u64, int stride);
+
 /* Test-only variants that materialise the logits (dev float, row-major
  * [batch, L-resp_off, vocab] resp. [batch, S, b, vocab]) through an unfused
  * store instead of the fused confidence/argmax reduction. */
@@ -154,7 +175,7 @@ int odb_cache_read(const odb_cache *c, int layer, int kv, int batch_index,
  * do cost a few microseconds each: do not time whole steps while enabled. */
 enum {
     ODB_K_GEMM_QKV = 0, ODB_K_ATTENTION, ODB_K_GEMM_O, ODB_K_GEMM_GATE_UP,
-    ODB_K_GEMM_DOWN, ODB_K_GEMM_LM_HEAD, ODB_K_RMSNORM, ODB_K_COUNT
+    ODB_K_GEMM_DOWN, ODB_K_GEMM_LM_HEAD, ODB_K_RMSNORM, ODB_K_STEP_FUSED, ODB_K_COUNT
 };
 int odb_profile_begin(odb_model *m, int kernel_class, int max_launches);
 int odb_profile_end(odb_model *m, int *n_launches, float *total_ms);

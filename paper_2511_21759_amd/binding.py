@@ -21,10 +21,13 @@ SYMBOLS = (
     "odb_model_create", "odb_model_destroy", "odb_model_init_random", "odb_model_set_tensor",
     "odb_model_get_tensor", "odb_cache_create", "odb_cache_destroy", "odb_cache_length", "odb_prefill",
     "odb_block_step", "odb_prefill_logits", "odb_block_step_logits", "odb_cache_read", "odb_strerror",
-    "odb_last_error", "odb_profile_begin", "odb_profile_end",
+    "odb_last_error", "odb_profile_begin", "odb_profile_end", "odb_set_step_mode", "odb_model_status",
+    "odb_debug_step_trace",
 )
 
-KERNEL_CLASSES = ("gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "rmsnorm")
+KERNEL_CLASSES = ("gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "rmsnorm",
+                  "step_fused")
+STEP_FUSED, STEP_KERNELS = 0, 1
 
 T_EMBED, T_WQ, T_WK, T_WV, T_WO, T_WG, T_WU, T_WD, T_LM, T_G1, T_G2, T_GF = range(12)
 
@@ -72,6 +75,9 @@ def lib() -> ctypes.CDLL:
     L.odb_cache_read.argtypes = [vp, ci, ci, ci, ci, ci, vp]
     L.odb_profile_begin.argtypes = [vp, ci, ci]
     L.odb_profile_end.argtypes = [vp, ctypes.POINTER(ci), ctypes.POINTER(cf)]
+    L.odb_set_step_mode.argtypes = [vp, ci]
+    L.odb_model_status.argtypes = [vp]
+    L.odb_debug_step_trace.argtypes = [vp, vp, ci]
     L.odb_strerror.argtypes = [ci]
     L.odb_strerror.restype = ctypes.c_char_p
     L.odb_last_error.restype = ctypes.c_char_p
@@ -189,6 +195,19 @@ def odb_cache_read(cache: int, layer: int, kv: int, batch_index: int, pos0: int,
     out = np.empty((n, n_heads, head_dim), np.uint16)
     _check(lib().odb_cache_read(cache, layer, kv, batch_index, pos0, n, out.ctypes.data))
     return out
+
+
+def odb_set_step_mode(model: int, mode: int) -> None:
+    _check(lib().odb_set_step_mode(model, mode))
+
+
+def odb_model_status(model: int) -> None:
+    _check(lib().odb_model_status(model))
+
+
+def odb_debug_step_trace(model: int, buf, stride: int) -> None:
+    """buf: int64 CUDA tensor [n_workgroups, stride] or None."""
+    _check(lib().odb_debug_step_trace(model, buf.data_ptr() if buf is not None else None, stride))
 
 
 def odb_profile_begin(model: int, kernel_class: int, max_launches: int) -> None:

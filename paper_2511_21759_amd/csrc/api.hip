@@ -319,6 +319,48 @@ int step_impl(odb_model *mh, const odb_cache *ch, const int32_t *drafts, int blo
     if (b % 32)   // slots of padded keys must hold finite values: they meet zero probabilities in the P*V product
         launch_fill_f32((float *)((char *)m.scratch + pl.vf), 0.f, (size_t)units * bp32 * cfg.d_model / 2, s);
     StackIO io{rm, block_off, false, block_off, block_off + b, b, S, true};
+    if (!logits && m.step_mode == ODB_STEP_FUSED && rows_pad <= 128) {
+        // the whole step as one persistent kernel
+        StepArgs a;
+        memset(&a, 0, sizeof(a));
+        const int d = cfg.d_model, H = cfg.n_heads, dh = cfg.head_dim;
+        a.embed = m.w[PK_EMBED]; a.wqkv = m.w[PK_QKV]; a.wo = m.w[PK_O]; a.wgu = m.w[PK_GU]; a.wd = m.w[PK_D];
+        a.wlm = m.w[PK_LM];
+        a.qkv_stride = m.layer_elems[PK_QKV]; a.o_stride = m.layer_elems[PK_O]; a.gu_stride = m.layer_elems[PK_GU];
+        a.d_stride = m.layer_elems[PK_D];
+        a.g1 = m.g1; a.g2 = m.g2; a.gf = m.gf;
+        a.n_layers = cfg.n_layers; a.d = d; a.H = H; a.dh = dh; a.F = cfg.d_ff; a.V = cfg.vocab; a.mask_id = cfg.mask_id;
+        a.eps = cfg.rms_eps; a.tau = tau;
+        a.tokens = drafts; a.rm = rm; a.mt_total = rows_pad / 16;
+        a.h = (float *)(base + pl.h); a.ssq = (float *)(base + pl.ssq); a.stats = (float *)(base + pl.stats);
+        a.hb = (u16 *)(base + pl.xa); a.ao = (u16 *)(base + pl.ao); a.act = (u16 *)(base + pl.act);
+        const size_t seq_elems = (size_t)H * c.lmax32 * dh;
+        QkvOut &qo = a.qo;
+        qo.q = (u16 *)(base + pl.q); qo.rope = c.rope;
+        qo.tiles_per_unit = bp / 16; qo.pos_off = block_off; qo.H = H; qo.dh = dh; qo.d = d;
+        qo.k = (u16 *)(base + pl.kf); qo.k_head_stride = (size_t)bp32 * dh; qo.k_unit_stride = (size_t)H * bp32 * dh;
+        qo.v = (u16 *)(base + pl.vf); qo.v_head_stride = (size_t)bp32 * dh; qo.v_unit_stride = (size_t)H * bp32 * dh;
+        AttnArgs &at = a.attn;
+        at.q = qo.q; at.kc = c.k; at.vc = c.v;
+        at.kc_seq_stride = seq_elems; at.kc_head_stride = (size_t)c.lmax32 * dh;
+        at.vc_seq_stride = seq_elems; at.vc_head_stride = (size_t)c.lmax32 * dh;
+        at.kf = qo.k; at.vf = qo.v;
+        at.kf_unit_stride = qo.k_unit_stride; at.kf_head_stride = qo.k_head_stride;
+        at.vf_unit_stride = qo.v_unit_stride; at.vf_head_stride = qo.v_head_stride;
+        at.out = a.ao;
+        at.H = H; at.dh = dh; at.mt_total = a.mt_total; at.tiles_per_unit = bp / 16; at.units = units;
+        at.units_per_seq = S; at.L = c.length; at.blk_lo = block_off; at.blk_hi = block_off + b; at.fresh = b;
+        a.cache_layer_stride = c.layer_elems;
+        a.conf = conf; a.argmax = argmax; a.unmask = unmask;
+        a.trace = m.trace; a.trace_stride = m.trace_stride;
+        a.barrier = m.counters + 64; a.status = m.counters; a.barrier_base = m.barrier_epoch;
+        {
+            ProfScope ps(m, ODB_K_STEP_FUSED, s);
+            HIP_TRY(launch_step_kernel(a, m.n_cu, s));
+        }
+        m.barrier_epoch += step_kernel_barriers(cfg.n_layers);
+        return ODB_OK;
+    }
     rc = run_stack(m, c, pl, io, s);
     if (rc) return rc;
     return run_head(m, pl, rm, 0, true, drafts, b, tau, conf, argmax, unmask, logits, s);
@@ -361,6 +403,8 @@ int odb_model_create(const odb_config *cfg, const odb_allocator *allocator, odb_
     m.cfg = *cfg;
     m.device = dev;
     m.prof_class = -1;
+    m.n_cu = prop.multiProcessorCount;
+    m.step_mode = ODB_STEP_KERNELS;
     if (allocator) { m.alloc = *allocator; m.has_alloc = true; }
     const size_t d = cfg->d_model, f = cfg->d_ff, v = cfg->vocab, nl = cfg->n_layers;
     m.layer_elems[PK_QKV] = 3 * d * d;
@@ -535,6 +579,38 @@ int odb_block_step_logits(odb_model *m, const odb_cache *c, const int32_t *draft
                           float *logits_dev, void *stream) {
     if (!logits_dev) return fail(ODB_E_INVALID_ARG, "block_step_logits: logits is NULL");
     return step_impl(m, c, drafts_dev, block_off, b, S, 0.f, nullptr, nullptr, nullptr, logits_dev, stream);
+}
+
+int odb_set_step_mode(odb_model *mh, int mode) {
+    if (!mh) return fail(ODB_E_INVALID_ARG, "set_step_mode: model is NULL");
+    if (mode != ODB_STEP_FUSED && mode != ODB_STEP_KERNELS) return fail(ODB_E_INVALID_ARG, "set_step_mode: mode %d", mode);
+    mh->m.step_mode = mode;
+    return ODB_OK;
+}
+
+int odb_debug_step_trace(odb_model *mh, void *dev_u64, int stride) {
+    if (!mh) return fail(ODB_E_INVALID_ARG, "debug_step_trace: model is NULL");
+    if (dev_u64 && stride < 2 * (int)step_kernel_barriers(mh->m.cfg.n_layers))
+        return fail(ODB_E_INVALID_ARG, "debug_step_trace: stride %d too small", stride);
+    mh->m.trace = (unsigned long long *)dev_u64;
+    mh->m.trace_stride = stride;
+    return ODB_OK;
+}
+
+int odb_model_status(odb_model *mh) {
+    if (!mh) return fail(ODB_E_INVALID_ARG, "model_status: model is NULL");
+    Model &m = mh->m;
+    HIP_TRY(hipSetDevice(m.device));
+    HIP_TRY(hipDeviceSynchronize());
+    unsigned host = 0;
+    HIP_TRY(hipMemcpy(&host, m.counters, sizeof(host), hipMemcpyDeviceToHost));
+    if (host != 0) {
+        // a barrier gave up: bring flags, epoch and status back to a clean state
+        HIP_TRY(hipMemset(m.counters, 0, kCounters * sizeof(unsigned)));
+        m.barrier_epoch = 0;
+        return fail(ODB_E_HIP, "a fused step kernel timed out at a grid barrier");
+    }
+    return ODB_OK;
 }
 
 int odb_profile_begin(odb_model *mh, int kernel_class, int max_launches) {

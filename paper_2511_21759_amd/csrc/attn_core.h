@@ -1,0 +1,194 @@
+// Device-side core of the attention kernels (attn.hip) and of the fused step kernel (step.hip).
+//
+// Bidirectional attention of a group of query rows against the K/V cache plus,
+// in the decode step, the fresh K/V of the rows' own draft.
+//
+// Work is organised per "unit" (a draft in the step, a sequence in the prefill):
+// the rows of a unit all see the same keys.  A workgroup takes QT 16-row tiles
+// of one unit and one head; its NW waves split the 32-key tiles, keep a running
+// (max, sum, O) per row and are merged through LDS in a fixed order.
+// Scores are computed transposed, S^T = K Q^T, so that after the MFMA every
+// lane holds scores of ONE query row (lane & 15): the softmax statistics are
+// lane-local plus two cross-lane exchanges, and the probabilities are already
+// in the register order the second MFMA (O^T = V^T P^T) wants, because V^T is
+// stored with the 32 keys of a tile permuted to match (see gemm.hip, EpiQKV).
+//
+// Visibility (ODB-dLLM Sec. 4.2): cached keys of the block itself are skipped,
+// a draft's rows see only that draft's fresh keys; there is no causal mask.
+#pragma once
+#include "model.h"
+
+namespace odb {
+
+template <int DH>
+__device__ inline void store_out_tile(const AttnArgs &a, int mt, int hd, int dt16, int lane, f32x4 v) {
+    const int mi = lane & 15, g = lane >> 4;
+    const int kt = hd * (DH / 32) + (dt16 >> 1);
+    u16 *dst = a.out + ((size_t)kt * a.mt_total + mt) * kTileElems + (((dt16 & 1) * 2 + (g >> 1)) * 16 + mi) * 8 +
+               (g & 1) * 4;
+    uint2 p;
+    p.x = pack2bf(v[0], v[1]);
+    p.y = pack2bf(v[2], v[3]);
+    *reinterpret_cast<uint2 *>(dst) = p;
+}
+
+template <int QT, int NW>
+constexpr int attn_smem_bytes() { return NW * 4 * 1024 + 2 * NW * QT * 16 * 4; }
+
+// One work item: QT row tiles (chunk `item` of the units' tiles) of head hd.  sc = log2(e)/sqrt(dh).
+template <int DH, int QT, int NW>
+__device__ __forceinline__ void attn_wg(const AttnArgs &a, float sc, int item, int hd, char *smem) {
+    constexpr int DT32 = DH / 32, DT16 = DH / 16;
+    constexpr int DC = DT16 < 4 ? DT16 : 4;          // channel tiles merged per pass through LDS
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, mi = lane & 15, g = lane >> 4;
+    const int chunks = (a.tiles_per_unit + QT - 1) / QT;
+    const int unit = item / chunks, tu0 = (item % chunks) * QT;
+    const int seq = unit / a.units_per_seq;
+    f32x4 (*s_o)[DC][64] = reinterpret_cast<f32x4 (*)[DC][64]>(smem);
+    float (*s_m)[QT][16] = reinterpret_cast<float (*)[QT][16]>(smem + NW * 4 * 1024);
+    float (*s_l)[QT][16] = s_m + NW;
+
+    frag_t q[QT][DT32];
+#pragma unroll
+    for (int t = 0; t < QT; t++) {
+        int tu = tu0 + t < a.tiles_per_unit ? tu0 + t : a.tiles_per_unit - 1;
+        int mt = unit * a.tiles_per_unit + tu;
+#pragma unroll
+        for (int dt = 0; dt < DT32; dt++)
+            q[t][dt] = ld_frag(a.q + (((size_t)hd * a.mt_total + mt) * DT32 + dt) * kTileElems + lane * 8);
+    }
+    f32x4 o[QT][DT16];
+    float mrun[QT], lrun[QT];
+#pragma unroll
+    for (int t = 0; t < QT; t++) {
+        mrun[t] = -INFINITY;
+        lrun[t] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < DT16; dt++) o[t][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    auto tile = [&](const u16 *kp, const u16 *vp, int key0, bool cached) __attribute__((always_inline)) {
+        frag_t kf[2][DT32];
+#pragma unroll
+        for (int s = 0; s < 2; s++)
+#pragma unroll
+            for (int dt = 0; dt < DT32; dt++) kf[s][dt] = ld_frag(kp + (size_t)(s * DT32 + dt) * kTileElems + lane * 8);
+        frag_t vf[DT16];
+#pragma unroll
+        for (int dt = 0; dt < DT16; dt++) vf[dt] = ld_frag(vp + (size_t)dt * kTileElems + lane * 8);
+        bool ok[2][4];
+#pragma unroll
+        for (int s = 0; s < 2; s++)
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                int key = key0 + s * 16 + 4 * g + r;
+                ok[s][r] = cached ? (key < a.L && !(key >= a.blk_lo && key < a.blk_hi)) : key < a.fresh;
+            }
+#pragma unroll
+        for (int t = 0; t < QT; t++) {
+            f32x4 st[2];
+#pragma unroll
+            for (int s = 0; s < 2; s++) {
+                st[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int dt = 0; dt < DT32; dt++) st[s] = mfma16(kf[s][dt], q[t][dt], st[s]);
+            }
+            float tm = -INFINITY;
+#pragma unroll
+            for (int s = 0; s < 2; s++)
+#pragma unroll
+                for (int r = 0; r < 4; r++) {
+                    st[s][r] = ok[s][r] ? st[s][r] * sc : -INFINITY;
+                    tm = fmaxf(tm, st[s][r]);
+                }
+            tm = fmaxf(tm, __shfl_xor(tm, 16));
+            tm = fmaxf(tm, __shfl_xor(tm, 32));
+            const float mnew = fmaxf(mrun[t], tm);
+            const float mref = mnew == -INFINITY ? 0.f : mnew;
+            const float alpha = exp2f(mrun[t] - mref);
+            float p[2][4], ps = 0.f;
+#pragma unroll
+            for (int s = 0; s < 2; s++)
+#pragma unroll
+                for (int r = 0; r < 4; r++) {
+                    p[s][r] = exp2f(st[s][r] - mref);
+                    ps += p[s][r];
+                }
+            lrun[t] = lrun[t] * alpha + ps;
+            mrun[t] = mnew;
+            frag_t pf;
+            pf.w[0] = pack2bf(p[0][0], p[0][1]);
+            pf.w[1] = pack2bf(p[0][2], p[0][3]);
+            pf.w[2] = pack2bf(p[1][0], p[1][1]);
+            pf.w[3] = pack2bf(p[1][2], p[1][3]);
+#pragma unroll
+            for (int dt = 0; dt < DT16; dt++) {
+                o[t][dt] *= alpha;
+                o[t][dt] = mfma16(vf[dt], pf, o[t][dt]);
+            }
+        }
+    };
+
+    // cached keys: 32-key tiles interleaved over the waves; the fresh tiles follow in the same rotation
+    const int n32 = (a.L + 31) / 32;
+    const u16 *kc = a.kc + seq * a.kc_seq_stride + hd * a.kc_head_stride;
+    const u16 *vc = a.vc + seq * a.vc_seq_stride + hd * a.vc_head_stride;
+    for (int T = w; T < n32; T += NW) {
+        if (T * 32 >= a.blk_lo && T * 32 + 32 <= a.blk_hi) continue;       // wholly inside the block
+        tile(kc + (size_t)T * 2 * DT32 * kTileElems, vc + (size_t)T * DT16 * kTileElems, T * 32, true);
+    }
+    if (a.fresh > 0) {
+        const u16 *kf = a.kf + unit * a.kf_unit_stride + hd * a.kf_head_stride;
+        const u16 *vf = a.vf + unit * a.vf_unit_stride + hd * a.vf_head_stride;
+        const int nf = (a.fresh + 31) / 32;
+        for (int T = (w + NW - n32 % NW) % NW; T < nf; T += NW)
+            tile(kf + (size_t)T * 2 * DT32 * kTileElems, vf + (size_t)T * DT16 * kTileElems, T * 32, false);
+    }
+
+    // merge the waves
+#pragma unroll
+    for (int t = 0; t < QT; t++) {
+        float l = lrun[t];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        lrun[t] = l;
+        if (g == 0) {
+            s_m[w][t][mi] = mrun[t];
+            s_l[w][t][mi] = l;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < QT; t++) {
+        float mall = -INFINITY;
+#pragma unroll
+        for (int x = 0; x < NW; x++) mall = fmaxf(mall, s_m[x][t][mi]);
+        float ltot = 0.f, fown = 0.f;
+#pragma unroll
+        for (int x = 0; x < NW; x++) {
+            float mx = s_m[x][t][mi];
+            float f = mx == -INFINITY ? 0.f : exp2f(mx - mall);
+            ltot += s_l[x][t][mi] * f;
+            if (x == w) fown = f;
+        }
+        const int tu = tu0 + t;
+        const int mt = unit * a.tiles_per_unit + tu;
+#pragma unroll
+        for (int d0 = 0; d0 < DT16; d0 += DC) {
+#pragma unroll
+            for (int dt = 0; dt < DC; dt++) s_o[w][dt][lane] = o[t][d0 + dt] * fown;
+            __syncthreads();
+            if (tu < a.tiles_per_unit) {
+                for (int dt = w; dt < DC; dt += NW) {
+                    f32x4 v = s_o[0][dt][lane];
+#pragma unroll
+                    for (int x = 1; x < NW; x++) v += s_o[x][dt][lane];
+                    store_out_tile<DH>(a, mt, hd, d0 + dt, lane, v * (1.0f / ltot));
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+}  // namespace odb

@@ -1,0 +1,337 @@
+// Device-side core of the weight-streaming bf16 MFMA GEMM  C[M,N] = A[M,K] * W[N,K]^T
+// for few rows, shared by the stand-alone GEMM kernels (gemm.hip) and the fused
+// decode-step kernel (step.hip).
+//
+// A (activations) is tile-major [k_tile][m_tile][512], W is [n_tile][k_tile][512]
+// (see common.h for the tile).  The work is persistent in spirit: nwg workgroups
+// (one per compute unit) split the n-tiles into equal contiguous ranges, and the
+// eight waves of a workgroup split K into eight slices.  Each wave therefore
+// walks, NG n-tiles at a time, along contiguous runs of 1 KiB weight tiles,
+// loading them straight into MFMA operand registers through a ring of PF stages
+// that keeps running across the boundary between one group of n-tiles and the
+// next, so the HBM stream never drains.  The eight K-slices of an output tile
+// are added through LDS in a fixed order, so results do not depend on scheduling.
+//
+// The epilogues fuse what follows each projection in the transformer block:
+// RoPE + scatter of Q/K/V into the attention layouts, the residual add (plus the
+// input of the next RMSNorm), SiLU(gate)*up, and the per-row softmax statistics
+// of the LM head (logits are never stored).
+#pragma once
+#include "model.h"
+
+
+namespace odb {
+
+constexpr int WK = 8;    // waves per workgroup = K slices
+
+struct GemmArgs {
+    const u16 *A, *W;
+    int KT, MT_total, NT;
+    // fused RMSNorm of the input rows: A holds bf16(x * gain) and ssq[row][0..n_ssq) partial sums
+    // of x^2; the result rows are scaled by 1/sqrt(sum/d + eps).  ssq == nullptr: A is used as is.
+    const float *ssq;
+    int n_ssq;
+    float eps, inv_d;
+};
+
+constexpr int kGemmSmemBytes = WK * 6 * 1024 + 8 * 16 * 4;    // LDS one workgroup needs (red + row scales)
+
+// Weight tiles of the first PF k-steps of workgroup `wg`'s first group of n-tiles.  Weights do not
+// depend on the previous kernel phase, so a caller may issue these loads early (before it waits
+// for its input rows) and hand the ring to gemm_wg<..., true>.
+template <int NG, int PF>
+__device__ __forceinline__ void gemm_prefetch_w(const GemmArgs &g, int wg, int nwg, frag_t (&wb)[PF][NG]) {
+    const int lane = threadIdx.x & 63, wk = threadIdx.x >> 6;
+    const int n_lo = (int)(((long)wg * g.NT) / nwg);
+    int n_hi = (int)(((long)(wg + 1) * g.NT) / nwg);
+    // a workgroup without n-tiles still loads (tile 0, discarded) so that the ring is always
+    // fully redefined here and never has to be kept alive across phases
+    if (n_hi <= n_lo) n_hi = n_lo + 1 <= g.NT ? n_lo + 1 : g.NT;
+    const int KW = g.KT / WK;
+    const u16 *wbase = g.W + (size_t)(wk * KW) * kTileElems + lane * 8;
+#pragma unroll
+    for (int s = 0; s < PF; s++)
+#pragma unroll
+        for (int n = 0; n < NG; n++) {
+            int nt = n_lo + n;
+            nt = nt < n_hi ? nt : n_hi - 1;
+            wb[s][n] = ld_frag(wbase + ((size_t)nt * g.KT + s) * kTileElems);
+        }
+}
+
+// One workgroup's share of the GEMM: n-tiles [wg*NT/nwg, (wg+1)*NT/nwg), m-tiles mt0 .. mt0+MT-1.
+// HAVE_W: wb already holds (or is receiving) the tiles gemm_prefetch_w loads.
+template <int MT, int NG, int PF, bool HAVE_W, class Epi>
+__device__ __forceinline__ void gemm_wg(const GemmArgs &g, const Epi &epi, int wg, int nwg, int mt0,
+                                        frag_t (&wb)[PF][NG], char *smem) {
+    constexpr int MC = NG >= 3 ? 2 : (MT < 4 ? MT : 4);    // m-tiles reduced per pass through LDS (<= 48 KiB)
+    static_assert(MT % MC == 0 && MC * NG <= 6 && MT <= 8, "m chunking");
+    f32x4 (*red)[MC * NG][64] = reinterpret_cast<f32x4 (*)[MC * NG][64]>(smem);
+    float *s_rstd = reinterpret_cast<float *>(smem + WK * 6 * 1024);
+
+    const int lane = threadIdx.x & 63, wk = threadIdx.x >> 6;
+    const int n_lo = (int)(((long)wg * g.NT) / nwg);
+    const int n_hi = (int)(((long)(wg + 1) * g.NT) / nwg);
+    if (n_lo >= n_hi) return;
+    const int KW = g.KT / WK;
+    const int ngroups = (n_hi - n_lo + NG - 1) / NG;
+
+    const u16 *wbase = g.W + (size_t)(wk * KW) * kTileElems + lane * 8;
+    const u16 *ap[MT];
+#pragma unroll
+    for (int m = 0; m < MT; m++) {
+        int mt = mt0 + m < g.MT_total ? mt0 + m : g.MT_total - 1;
+        ap[m] = g.A + ((size_t)(wk * KW) * g.MT_total + mt) * kTileElems + lane * 8;
+    }
+    const size_t a_step = (size_t)g.MT_total * kTileElems;
+
+    frag_t ab[PF][MT];
+    auto load_stage = [&](int slot, int grp, int kk) __attribute__((always_inline)) {
+#pragma unroll
+        for (int n = 0; n < NG; n++) {
+            int nt = n_lo + grp * NG + n;
+            nt = nt < n_hi ? nt : n_hi - 1;
+            wb[slot][n] = ld_frag(wbase + ((size_t)nt * g.KT + kk) * kTileElems);
+        }
+#pragma unroll
+        for (int m = 0; m < MT; m++) ab[slot][m] = ld_frag(ap[m] + kk * a_step);
+    };
+
+    // Row scales of the fused RMSNorm.  Their loads are issued before the first stage so that
+    // waiting for them does not wait for the weight stream (loads return in order).
+    constexpr int RPW = MT * 16 / WK;                       // rows per wave
+    float q[RPW];
+#pragma unroll
+    for (int j = 0; j < RPW; j++) {
+        q[j] = 0.f;
+        if (g.ssq) {
+            int row = mt0 * 16 + wk + j * WK;
+            row = row < g.MT_total * 16 ? row : g.MT_total * 16 - 1;
+            const float *p = g.ssq + (size_t)row * g.n_ssq;
+            for (int i0 = 0; i0 < g.n_ssq; i0 += 256) {     // four independent loads per pass, not a dependent chain
+                float v[4];
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    int i = i0 + lane + 64 * u;
+                    v[u] = i < g.n_ssq ? p[i] : 0.f;
+                }
+                q[j] += (v[0] + v[1]) + (v[2] + v[3]);
+            }
+        }
+    }
+    if (HAVE_W) {
+#pragma unroll
+        for (int s = 0; s < PF; s++)
+#pragma unroll
+            for (int m = 0; m < MT; m++) ab[s][m] = ld_frag(ap[m] + s * a_step);
+    } else {
+#pragma unroll
+        for (int s = 0; s < PF; s++) load_stage(s, 0, s);
+    }
+#pragma unroll
+    for (int j = 0; j < RPW; j++) {
+        float rs = 1.0f;
+        if (g.ssq) {
+            float t = q[j];
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) t += __shfl_xor(t, o);
+            rs = 1.0f / sqrtf(t * g.inv_d + g.eps);
+        }
+        if (lane == 0) s_rstd[wk + j * WK] = rs;
+    }
+
+    for (int grp = 0; grp < ngroups; grp++) {
+        f32x4 acc[MT][NG];
+#pragma unroll
+        for (int m = 0; m < MT; m++)
+#pragma unroll
+            for (int n = 0; n < NG; n++) acc[m][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        for (int kb = 0; kb < KW; kb += PF) {
+#pragma unroll
+            for (int s = 0; s < PF; s++) {
+#pragma unroll
+                for (int m = 0; m < MT; m++)
+#pragma unroll
+                    for (int n = 0; n < NG; n++) acc[m][n] = mfma16(wb[s][n], ab[s][m], acc[m][n]);
+                // refill this slot with the step PF ahead, which may belong to the next group
+                int kn = kb + s + PF, gn = grp;
+                if (kn >= KW) { kn -= KW; gn++; }
+                if (gn < ngroups) load_stage(s, gn, kn);
+            }
+        }
+
+        // add the eight K-slices through LDS, MC m-tiles at a time; the wave that owns a tile runs its epilogue
+#pragma unroll
+        for (int mc = 0; mc < MT; mc += MC) {
+#pragma unroll
+            for (int m = 0; m < MC; m++)
+#pragma unroll
+                for (int n = 0; n < NG; n++) red[wk][m * NG + n][lane] = acc[mc + m][n];
+            __syncthreads();
+            for (int t = wk; t < MC * NG; t += WK) {
+                const int m = t / NG, n = t % NG;
+                const int mt = mt0 + mc + m, nt = n_lo + grp * NG + n;
+                if (mt < g.MT_total && nt < n_hi) {
+                    f32x4 c;
+                    if (!epi.transposed(nt)) {
+                        c = red[0][t][lane];
+#pragma unroll
+                        for (int w = 1; w < WK; w++) c += red[w][t][lane];
+                        c *= s_rstd[(mc + m) * 16 + (lane & 15)];
+                    } else {
+                        // hand lane (g, ni) the four rows 4g..4g+3 of column ni instead of four columns of one row
+                        const int ni = lane & 15, gq = lane >> 4;
+                        const float *base = reinterpret_cast<const float *>(&red[0][t][0]);
+                        const int stride = MC * NG * 64 * 4;        // floats between the waves' copies
+#pragma unroll
+                        for (int r = 0; r < 4; r++) {
+                            const int src = ((ni >> 2) * 16 + 4 * gq + r) * 4 + (ni & 3);
+                            float v = base[src];
+#pragma unroll
+                            for (int w = 1; w < WK; w++) v += base[w * stride + src];
+                            c[r] = v * s_rstd[(mc + m) * 16 + 4 * gq + r];
+                        }
+                    }
+                    epi(mt, nt, c, lane);
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// ---- epilogues ------------------------------------------------------------------
+// Default:    lane l holds C[row = 16*mt + (l&15)][col = 16*nt + 4*(l>>4) + r], r = 0..3.
+// Transposed: lane l holds C[row = 16*mt + 4*(l>>4) + r][col = 16*nt + (l&15)].
+
+__device__ inline void st_bf16x4(u16 *p, float a, float b, float c, float d) {
+    uint2 v;
+    v.x = pack2bf(a, b);
+    v.y = pack2bf(c, d);
+    *reinterpret_cast<uint2 *>(p) = v;
+}
+
+struct EpiQKV {
+    QkvOut o;
+    int mt_total;
+    __device__ bool transposed(int nt) const { return nt * 16 >= 2 * o.d; }
+    __device__ void operator()(int mt, int nt, f32x4 c, int lane) const {
+        const int mi = lane & 15, g = lane >> 4;
+        const int unit = mt / o.tiles_per_unit, tu = mt % o.tiles_per_unit;
+        const int n = nt * 16, sec = n / o.d, rr = n % o.d;
+        const int hd = rr / o.dh, p0 = rr % o.dh;            // p0 is a multiple of 16
+        if (sec < 2) {
+            // physical channel 2j is logical j, 2j+1 is j + dh/2: each adjacent pair is a RoPE pair
+            const int pos = o.pos_off + tu * 16 + mi;
+            const float2 *tab = reinterpret_cast<const float2 *>(o.rope) + (size_t)pos * (o.dh / 2);
+            u16 *dst = sec == 0
+                ? o.q + (((size_t)hd * mt_total + mt) * (o.dh / 32) + p0 / 32) * kTileElems
+                : o.k + unit * o.k_unit_stride + hd * o.k_head_stride + ((size_t)tu * (o.dh / 32) + p0 / 32) * kTileElems;
+            const int j = (p0 + 4 * g) >> 1;
+            float2 cs0 = tab[j], cs1 = tab[j + 1];
+            float y0 = c[0] * cs0.x - c[1] * cs0.y;
+            float y1 = c[1] * cs0.x + c[0] * cs0.y;
+            float y2 = c[2] * cs1.x - c[3] * cs1.y;
+            float y3 = c[3] * cs1.x + c[2] * cs1.y;
+            const int kk = (p0 & 16) + 4 * g;                 // k-element of y0 inside the 32-wide tile
+            st_bf16x4(dst + ((kk >> 3) * 16 + mi) * 8 + (kk & 7), y0, y1, y2, y3);
+        } else {
+            // V^T tile: row = channel, the 32 keys of a tile sit in k-slot 8*g + 4*half + r
+            u16 *dst = o.v + unit * o.v_unit_stride + hd * o.v_head_stride +
+                       ((size_t)(tu >> 1) * (o.dh / 16) + p0 / 16) * kTileElems + lane * 8 + 4 * (tu & 1);
+            st_bf16x4(dst, c[0], c[1], c[2], c[3]);
+        }
+    }
+};
+
+// h += C.  With a NormOut it also prepares the next RMSNorm: hb = bf16(h * gain) in the
+// operand layout and the sum of squares of this tile's 16 columns per row.
+struct EpiResid {
+    float *h;
+    int ld;
+    NormOut no;
+    int mt_total;
+    __device__ bool transposed(int) const { return false; }
+    __device__ void operator()(int mt, int nt, f32x4 c, int lane) const {
+        const int mi = lane & 15, g = lane >> 4, row = mt * 16 + mi, col = nt * 16 + 4 * g;
+        float *p = h + (size_t)row * ld + col;
+        f32x4 v = *reinterpret_cast<f32x4 *>(p) + c;
+        *reinterpret_cast<f32x4 *>(p) = v;
+        if (no.hb) {
+            f32x4 gn = *reinterpret_cast<const f32x4 *>(no.gain + col);
+            const int kk = (nt & 1) * 16 + 4 * g;
+            st_bf16x4(no.hb + ((size_t)(nt >> 1) * mt_total + mt) * kTileElems + ((kk >> 3) * 16 + mi) * 8 + (kk & 7),
+                      v[0] * gn[0], v[1] * gn[1], v[2] * gn[2], v[3] * gn[3]);
+            float q = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+            q += __shfl_xor(q, 16);
+            q += __shfl_xor(q, 32);
+            if (g == 0) no.ssq[(size_t)row * no.n_ssq + nt] = q;
+        }
+    }
+};
+
+// W_gu interleaves the rows of W_gate and W_up (physical row 2j = gate j, 2j+1 = up j)
+struct EpiSwiGLU {
+    u16 *act;
+    int mt_total;
+    __device__ bool transposed(int) const { return false; }
+    __device__ void operator()(int mt, int nt, f32x4 c, int lane) const {
+        const int mi = lane & 15, g = lane >> 4;
+        const int j = nt * 8 + 2 * g;                         // channel of the first (gate, up) pair
+        float y0 = c[0] / (1.0f + expf(-c[0])) * c[1];
+        float y1 = c[2] / (1.0f + expf(-c[2])) * c[3];
+        const int kk = j & 31;
+        u16 *dst = act + ((size_t)(j >> 5) * mt_total + mt) * kTileElems + ((kk >> 3) * 16 + mi) * 8 + (kk & 7);
+        *reinterpret_cast<uint32_t *>(dst) = pack2bf(y0, y1);
+    }
+};
+
+// stats[row][nt] = (max, sum exp(z - max), argmax) over the 16 columns of n-tile nt
+struct EpiLMStats {
+    float *stats;
+    int n_part;
+    __device__ bool transposed(int) const { return false; }
+    __device__ void operator()(int mt, int nt, f32x4 c, int lane) const {
+        const int mi = lane & 15, g = lane >> 4;
+        float m = c[0];
+        int a = nt * 16 + 4 * g;
+#pragma unroll
+        for (int r = 1; r < 4; r++)
+            if (c[r] > m) { m = c[r]; a = nt * 16 + 4 * g + r; }
+        float s = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; r++) s += expf(c[r] - m);
+#pragma unroll
+        for (int o = 16; o <= 32; o <<= 1) {
+            float om = __shfl_xor(m, o), os = __shfl_xor(s, o);
+            int oa = __shfl_xor(a, o);
+            float nm = fmaxf(m, om);
+            s = s * (m == nm ? 1.f : expf(m - nm)) + os * (om == nm ? 1.f : expf(om - nm));
+            a = m > om ? a : (om > m ? oa : (a < oa ? a : oa));
+            m = nm;
+        }
+        if (g == 0) {
+            float *p = stats + ((size_t)(mt * 16 + mi) * n_part + nt) * 3;
+            p[0] = m;
+            p[1] = s;
+            p[2] = __int_as_float(a);
+        }
+    }
+};
+
+// plain fp32 store of the valid rows (unit u, i < valid) to a compact row-major matrix
+struct EpiStore {
+    float *out;
+    int units, rpu_pad, valid, ld;
+    __device__ bool transposed(int) const { return false; }
+    __device__ void operator()(int mt, int nt, f32x4 c, int lane) const {
+        int row = mt * 16 + (lane & 15);
+        int u = row / rpu_pad, i = row % rpu_pad;
+        if (u < units && i < valid)
+            *reinterpret_cast<f32x4 *>(out + ((size_t)u * valid + i) * ld + nt * 16 + 4 * (lane >> 4)) = c;
+    }
+};
+
+
+}  // namespace odb

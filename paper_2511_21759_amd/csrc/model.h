@@ -32,7 +32,12 @@ struct Model {
     // scratch, grown on demand (see api.hip)
     void *scratch;
     size_t scratch_bytes;
-    unsigned *counters;        // split-K arrival counters (self-resetting)
+    unsigned *counters;        // [0] status word of the fused step kernel, [64..] its per-workgroup barrier flags
+    unsigned barrier_epoch;    // barrier epoch reached once all launched step kernels have finished
+    unsigned long long *trace; // debug: barrier timestamps of the fused step kernel (device memory of the caller)
+    int trace_stride;
+    int step_mode;             // 0: fused persistent kernel when the shape allows, 1: separate kernels
+    int n_cu;
     u16 *staging;              // set/get tensor staging
     size_t staging_bytes;
     // optional per-kernel-class timing (odb_profile_begin / odb_profile_end)
@@ -109,5 +114,35 @@ struct AttnArgs {
     int fresh;                 // number of fresh keys per unit (0 in the prefill)
 };
 void launch_attention(AttnArgs a, hipStream_t s);
+
+// ---- step.hip ---------------------------------------------------------------
+// Everything the fused decode-step kernel needs (pointers into the model, the cache and the
+// scratch of one call).
+struct StepArgs {
+    const u16 *embed, *wqkv, *wo, *wgu, *wd, *wlm;      // layer 0 of each kind
+    size_t qkv_stride, o_stride, gu_stride, d_stride;   // elements per layer
+    const float *g1, *g2, *gf;
+    int n_layers, d, H, dh, F, V, mask_id;
+    float eps, tau;
+    const int32_t *tokens;
+    RowMap rm;
+    int mt_total;
+    float *h, *ssq, *stats;
+    u16 *hb, *ao, *act;
+    QkvOut qo;                 // q / fresh K / fresh V destinations
+    AttnArgs attn;             // kc, vc point at layer 0
+    size_t cache_layer_stride;
+    float *conf;
+    int32_t *argmax;
+    uint8_t *unmask;
+    unsigned *barrier, *status;
+    unsigned barrier_base;
+    unsigned long long *trace;  // optional [nwg][trace_stride] timestamps, two per barrier
+    int trace_stride;
+};
+bool step_kernel_supports(const StepArgs &a);
+size_t step_kernel_max_wgs(int device);
+hipError_t launch_step_kernel(const StepArgs &a, int nwg, hipStream_t s);
+inline unsigned step_kernel_barriers(int n_layers) { return 2u + 5u * (unsigned)n_layers; }
 
 }  // namespace odb

@@ -1,52 +1,12 @@
 // Row-wise kernels: embedding gather, RMSNorm into the tiled operand layout,
 // and the final reduction of the LM-head statistics with the threshold unmask.
-#include "model.h"
+#include "rows_core.h"
 
 namespace odb {
 
-// h[r, :] = E[token(r), :] as fp32 (the residual stream stays in fp32).  One thread per 16 columns.
 __global__ void embed_kernel(const u16 *embed, const int32_t *tokens, RowMap rm, int d, int vocab, float *h,
                              NormOut no, int mt_total) {
-    int r = blockIdx.x;
-    int u = r / rm.rpu_pad, i = r % rm.rpu_pad;
-    int tok = 0;
-    if (i < rm.valid) tok = tokens[(size_t)u * rm.valid + i];
-    tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
-    const u16 *src = embed + (size_t)tok * d;
-    float *dst = h + (size_t)r * d;
-    for (int nt = threadIdx.x; nt < d / 16; nt += blockDim.x) {
-        float x[16];
-#pragma unroll
-        for (int half = 0; half < 2; half++) {
-            frag_t f = ld_frag(src + nt * 16 + half * 8);
-#pragma unroll
-            for (int j = 0; j < 4; j++) {
-                x[half * 8 + 2 * j] = bf2f(f.w[j] & 0xffff);
-                x[half * 8 + 2 * j + 1] = bf2f(f.w[j] >> 16);
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < 16; j += 4)
-            *reinterpret_cast<float4 *>(dst + nt * 16 + j) = make_float4(x[j], x[j + 1], x[j + 2], x[j + 3]);
-        if (no.hb) {
-            float q = 0.f;
-#pragma unroll
-            for (int j = 0; j < 16; j++) q += x[j] * x[j];
-            no.ssq[(size_t)r * no.n_ssq + nt] = q;
-            const float *gn = no.gain + nt * 16;
-#pragma unroll
-            for (int half = 0; half < 2; half++) {
-                frag_t f;
-#pragma unroll
-                for (int j = 0; j < 4; j++)
-                    f.w[j] = pack2bf(x[half * 8 + 2 * j] * gn[half * 8 + 2 * j],
-                                     x[half * 8 + 2 * j + 1] * gn[half * 8 + 2 * j + 1]);
-                const int chunk = (nt & 1) * 2 + half;
-                *reinterpret_cast<frag_t *>(no.hb + ((size_t)(nt >> 1) * mt_total + (r >> 4)) * kTileElems +
-                                            (chunk * 16 + (r & 15)) * 8) = f;
-            }
-        }
-    }
+    embed_row(blockIdx.x, embed, tokens, rm, d, vocab, h, no, mt_total);
 }
 
 void launch_embed(const Model &m, const int32_t *tokens, RowMap rm, float *h, NormOut no, hipStream_t s) {
@@ -112,70 +72,11 @@ void launch_rmsnorm(const float *h, const float *gain, float eps, int d, RowMap 
                                                           dst_mt_total, xa);
 }
 
-// ---- LM-head statistics -> confidence, argmax, unmask ------------------------
-// stats[row][part] = (max logit, sum exp(logit - max), argmax as int bits) over
-// the 16 vocabulary columns of part.  Merging keeps the lowest id on equal maxima.
-struct Stat { float m, s; int a; };
-
-__device__ inline Stat merge(Stat x, Stat y) {
-    Stat o;
-    o.m = fmaxf(x.m, y.m);
-    // equal maxima (including two empty -inf partials) must not evaluate inf - inf
-    float ex = x.m == o.m ? 1.f : expf(x.m - o.m);
-    float ey = y.m == o.m ? 1.f : expf(y.m - o.m);
-    o.s = x.s * ex + y.s * ey;
-    o.a = x.m > y.m ? x.a : (y.m > x.m ? y.a : (x.a < y.a ? x.a : y.a));
-    return o;
-}
-
 __global__ __launch_bounds__(256) void lm_finish_kernel(const float *stats, int n_part, int rows, int rpu, int rpu_pad,
                                                         const int32_t *tokens, int mask_id, float tau, float *conf,
                                                         int32_t *argmax, uint8_t *unmask) {
     __shared__ float s_conf[256];
-    int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int u = blockIdx.x;
-    for (int i = wave; i < rpu; i += 4) {
-        int row = u * rpu + i;                                  // compact output row
-        if (row >= rows) break;
-        const float *p = stats + ((size_t)u * rpu_pad + i) * n_part * 3;
-        Stat acc = {-INFINITY, 0.f, 0x7fffffff};
-        for (int q = lane; q < n_part; q += 64) {
-            Stat t = {p[q * 3], p[q * 3 + 1], __float_as_int(p[q * 3 + 2])};
-            acc = merge(acc, t);
-        }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            Stat t = {__shfl_xor(acc.m, o), __shfl_xor(acc.s, o), __shfl_xor(acc.a, o)};
-            acc = merge(acc, t);
-        }
-        if (lane == 0) {
-            float c = 1.0f / acc.s;
-            if (conf) conf[row] = c;
-            if (argmax) argmax[row] = acc.a;
-            s_conf[i & 255] = c;
-        }
-    }
-    if (!unmask) return;
-    __syncthreads();
-    if (wave != 0) return;
-    // most confident masked position of this draft, lowest index on ties
-    float best = -1.f;
-    int best_i = 0x7fffffff;
-    for (int i = lane; i < rpu; i += 64) {
-        bool masked = tokens[(size_t)u * rpu + i] == mask_id;
-        float c = s_conf[i];
-        if (masked && c > best) { best = c; best_i = i; }
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        float ob = __shfl_xor(best, o);
-        int oi = __shfl_xor(best_i, o);
-        if (ob > best || (ob == best && oi < best_i)) { best = ob; best_i = oi; }
-    }
-    for (int i = lane; i < rpu; i += 64) {
-        bool masked = tokens[(size_t)u * rpu + i] == mask_id;
-        unmask[(size_t)u * rpu + i] = (masked && (s_conf[i] > tau || i == best_i)) ? 1 : 0;
-    }
+    lm_finish_wg(blockIdx.x, stats, n_part, rows, rpu, rpu_pad, tokens, mask_id, tau, conf, argmax, unmask, s_conf);
 }
 
 void launch_lm_finish(const float *stats, int n_part, int rows, int rpu, int rpu_pad, const int32_t *tokens,

@@ -263,6 +263,27 @@ def test_gpu_structural_properties(tiny):
     assert all(torch.equal(x, y) for x, y in zip(c1, c2))
 
 
+@pytest.mark.parametrize("P,R,b,S,Bn", [(128, 64, 16, 1, 1), (96, 64, 32, 4, 1), (40, 24, 20, 3, 2), (64, 64, 48, 2, 1)])
+def test_fused_step_kernel_equals_separate_kernels(tiny, P, R, b, S, Bn):
+    """The persistent one-kernel step and the kernel-per-projection path run the same arithmetic
+    in the same order: their outputs must agree bit for bit, and no grid barrier may time out."""
+    wl = W.decode_workload(tiny.shape, P, R, b, S, 31 + b, batch=Bn)
+    cache = tiny.cache(Bn, P + R)
+    B.odb_prefill(tiny.model, cache, cuda_i32(wl.tokens), wl.resp_off)
+    d = cuda_i32(wl.drafts)
+    try:
+        B.odb_set_step_mode(tiny.model, B.STEP_KERNELS)
+        ref = [t.clone() for t in B.odb_block_step(tiny.model, cache, d, wl.block_off, 0.002)]
+        B.odb_set_step_mode(tiny.model, B.STEP_FUSED)
+        for _ in range(3):
+            got = B.odb_block_step(tiny.model, cache, d, wl.block_off, 0.002)
+            B.odb_model_status(tiny.model)
+            for x, y in zip(got, ref):
+                assert torch.equal(x, y)
+    finally:
+        B.odb_set_step_mode(tiny.model, B.STEP_KERNELS)
+
+
 def test_threshold_extremes(tiny):
     wl = W.decode_workload(tiny.shape, 64, 32, 16, 3, 9)
     wl.drafts[0, 2] = 5                       # a draft without any MASK
