@@ -85,6 +85,9 @@ def main():
     ap.add_argument("--workload", default="config1", choices=["config0", "config1", "config2", "config3", "config4"])
     ap.add_argument("--resp", type=int, default=512, help="response length for config3 (512, 256 or 128)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="after the timed region also run three 1 GiB device-to-device copies (a kernel of known "
+                         "traffic, used to scale the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc runs)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -192,6 +195,12 @@ def main():
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out))
+    if args.calib_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     B.odb_cache_destroy(cache)
     B.odb_model_destroy(model)
 

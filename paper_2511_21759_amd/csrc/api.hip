@@ -68,7 +68,7 @@ Plan make_plan(const odb_config &c, int rows_pad, int fresh_rows, int lm_rows_pa
     p.ao = take((size_t)rows_pad * d * 2);
     p.act = take((size_t)rows_pad * c.d_ff * 2);
     p.ssq = take((size_t)rows_pad * (d / 16) * 4);
-    p.stats = take(need_stats ? (size_t)lm_rows_pad * (c.vocab / 16) * 3 * 4 : 0);
+    p.stats = take(need_stats ? (size_t)lm_rows_pad * lm_stats_parts(c.vocab / 16) * 3 * 4 : 0);
     p.total = off;
     return p;
 }
@@ -261,7 +261,7 @@ int run_head(Model &m, const Plan &pl, RowMap rm, int skip, bool fused_norm, con
             ProfScope ps(m, ODB_K_GEMM_LM_HEAD, s);
             launch_gemm_lmstats(xa, m.w[PK_LM], sh, ni, stats, s);
         }
-        launch_lm_finish(stats, cfg.vocab / 16, rows, rpu_out, rpu_pad, tokens, cfg.mask_id, tau, conf, argmax, unmask,
+        launch_lm_finish(stats, lm_stats_parts(cfg.vocab / 16), rows, rpu_out, rpu_pad, tokens, cfg.mask_id, tau, conf, argmax, unmask,
                          s);
     }
     HIP_TRY(hipGetLastError());

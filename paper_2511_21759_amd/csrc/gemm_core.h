@@ -62,7 +62,7 @@ __device__ __forceinline__ void gemm_prefetch_w(const GemmArgs &g, int wg, int n
 // One workgroup's share of the GEMM: n-tiles [wg*NT/nwg, (wg+1)*NT/nwg), m-tiles mt0 .. mt0+MT-1.
 // HAVE_W: wb already holds (or is receiving) the tiles gemm_prefetch_w loads.
 template <int MT, int NG, int PF, bool HAVE_W, class Epi>
-__device__ __forceinline__ void gemm_wg(const GemmArgs &g, const Epi &epi, int wg, int nwg, int mt0,
+__device__ __forceinline__ void gemm_wg(const GemmArgs &g, Epi epi, int wg, int nwg, int mt0,
                                         frag_t (&wb)[PF][NG], char *smem) {
     constexpr int MC = NG >= 3 ? 2 : (MT < 4 ? MT : 4);    // m-tiles reduced per pass through LDS (<= 48 KiB)
     static_assert(MT % MC == 0 && MC * NG <= 6 && MT <= 8, "m chunking");
@@ -193,11 +193,17 @@ __device__ __forceinline__ void gemm_wg(const GemmArgs &g, const Epi &epi, int w
                             c[r] = v * s_rstd[(mc + m) * 16 + 4 * gq + r];
                         }
                     }
-                    epi(mt, nt, c, lane);
+                    epi(mt, nt, c, lane, mc / MC);
                 }
             }
             __syncthreads();
         }
+    }
+    // epilogues that accumulate over the n-tiles of the workgroup write their result now
+#pragma unroll
+    for (int mc = 0; mc < MT; mc += MC) {
+        const int t = wk;                       // the tile slot this wave served in every pass
+        if (t < MC * NG && mt0 + mc + t / NG < g.MT_total) epi.finish(mt0 + mc + t / NG, wg * NG + t % NG, lane, mc / MC);
     }
 }
 
@@ -216,7 +222,8 @@ struct EpiQKV {
     QkvOut o;
     int mt_total;
     __device__ bool transposed(int nt) const { return nt * 16 >= 2 * o.d; }
-    __device__ void operator()(int mt, int nt, f32x4 c, int lane) const {
+    __device__ void finish(int, int, int, int) const {}
+    __device__ void operator()(int mt, int nt, f32x4 c, int lane, int) const {
         const int mi = lane & 15, g = lane >> 4;
         const int unit = mt / o.tiles_per_unit, tu = mt % o.tiles_per_unit;
         const int n = nt * 16, sec = n / o.d, rr = n % o.d;
@@ -253,7 +260,8 @@ struct EpiResid {
     NormOut no;
     int mt_total;
     __device__ bool transposed(int) const { return false; }
-    __device__ void operator()(int mt, int nt, f32x4 c, int lane) const {
+    __device__ void finish(int, int, int, int) const {}
+    __device__ void operator()(int mt, int nt, f32x4 c, int lane, int) const {
         const int mi = lane & 15, g = lane >> 4, row = mt * 16 + mi, col = nt * 16 + 4 * g;
         float *p = h + (size_t)row * ld + col;
         f32x4 v = *reinterpret_cast<f32x4 *>(p) + c;
@@ -276,7 +284,8 @@ struct EpiSwiGLU {
     u16 *act;
     int mt_total;
     __device__ bool transposed(int) const { return false; }
-    __device__ void operator()(int mt, int nt, f32x4 c, int lane) const {
+    __device__ void finish(int, int, int, int) const {}
+    __device__ void operator()(int mt, int nt, f32x4 c, int lane, int) const {
         const int mi = lane & 15, g = lane >> 4;
         const int j = nt * 8 + 2 * g;                         // channel of the first (gate, up) pair
         float y0 = c[0] / (1.0f + expf(-c[0])) * c[1];
@@ -287,13 +296,23 @@ struct EpiSwiGLU {
     }
 };
 
-// stats[row][nt] = (max, sum exp(z - max), argmax) over the 16 columns of n-tile nt
+// Softmax statistics of the LM head without ever storing logits.  A wave serves the same
+// (m-tile, n-slot) in every group of n-tiles of its workgroup, so it keeps a running
+// (max, sum exp(z - max), argmax) per row in registers and writes ONE partial per row at the end:
+// stats[row][part], part = workgroup * NG + n-slot.  Ties keep the lowest token id.
+template <int PASSES>
 struct EpiLMStats {
     float *stats;
     int n_part;
+    float rm[PASSES], rs[PASSES];
+    int ra[PASSES];
+    __host__ __device__ EpiLMStats(float *st, int np) : stats(st), n_part(np) {
+#pragma unroll
+        for (int p = 0; p < PASSES; p++) { rm[p] = -INFINITY; rs[p] = 0.f; ra[p] = 0x7fffffff; }
+    }
     __device__ bool transposed(int) const { return false; }
-    __device__ void operator()(int mt, int nt, f32x4 c, int lane) const {
-        const int mi = lane & 15, g = lane >> 4;
+    __device__ void operator()(int mt, int nt, f32x4 c, int lane, int pass) {
+        const int g = lane >> 4;
         float m = c[0];
         int a = nt * 16 + 4 * g;
 #pragma unroll
@@ -302,6 +321,22 @@ struct EpiLMStats {
         float s = 0.f;
 #pragma unroll
         for (int r = 0; r < 4; r++) s += expf(c[r] - m);
+#pragma unroll
+        for (int p = 0; p < PASSES; p++)
+            if (p == pass) {
+                float nm = fmaxf(rm[p], m);
+                rs[p] = rs[p] * (rm[p] == nm ? 1.f : expf(rm[p] - nm)) + s * (m == nm ? 1.f : expf(m - nm));
+                ra[p] = rm[p] > m ? ra[p] : (m > rm[p] ? a : (ra[p] < a ? ra[p] : a));
+                rm[p] = nm;
+            }
+    }
+    __device__ void finish(int mt, int part, int lane, int pass) const {
+        const int mi = lane & 15, g = lane >> 4;
+        float m = -INFINITY, s = 0.f;
+        int a = 0x7fffffff;
+#pragma unroll
+        for (int p = 0; p < PASSES; p++)
+            if (p == pass) { m = rm[p]; s = rs[p]; a = ra[p]; }
 #pragma unroll
         for (int o = 16; o <= 32; o <<= 1) {
             float om = __shfl_xor(m, o), os = __shfl_xor(s, o);
@@ -312,7 +347,7 @@ struct EpiLMStats {
             m = nm;
         }
         if (g == 0) {
-            float *p = stats + ((size_t)(mt * 16 + mi) * n_part + nt) * 3;
+            float *p = stats + ((size_t)(mt * 16 + mi) * n_part + part) * 3;
             p[0] = m;
             p[1] = s;
             p[2] = __int_as_float(a);
@@ -325,7 +360,8 @@ struct EpiStore {
     float *out;
     int units, rpu_pad, valid, ld;
     __device__ bool transposed(int) const { return false; }
-    __device__ void operator()(int mt, int nt, f32x4 c, int lane) const {
+    __device__ void finish(int, int, int, int) const {}
+    __device__ void operator()(int mt, int nt, f32x4 c, int lane, int) const {
         int row = mt * 16 + (lane & 15);
         int u = row / rpu_pad, i = row % rpu_pad;
         if (u < units && i < valid)

@@ -95,6 +95,8 @@ struct QkvOut {
 void launch_gemm_qkv(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, QkvOut out, hipStream_t s);
 void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int ldh, NormOut no, hipStream_t s);
 void launch_gemm_swiglu(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, u16 *act, hipStream_t s);
+// stats[row][lm_stats_parts(N_tiles)][3]: one partial (max, sum exp, argmax) per row and (workgroup, n-slot)
+int lm_stats_parts(int n_tiles);
 void launch_gemm_lmstats(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, float *stats, hipStream_t s);
 // fp32 store of the valid rows (unit u, i < valid of rpu_pad) to a compact row-major [units*valid, ld]
 void launch_gemm_store(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, float *out, int units, int rpu_pad,

@@ -77,6 +77,7 @@ __global__ __launch_bounds__(64 * WK) void step_kernel(StepArgs a) {
     Trace tr{a.trace ? a.trace + (size_t)wg0 * a.trace_stride : nullptr, 0};
     const int d = a.d, F = a.F, mt = a.mt_total;
     const int n_ssq = d / 16;
+    const int lm_groups = (a.V / 16 + 2) / 3, lm_wgs = lm_groups < nwg ? lm_groups : nwg;   // as the stand-alone launch
     const float sc = 1.4426950408889634f * rsqrtf((float)DH);
 
     GemmArgs gq{a.hb, a.wqkv, d / 32, mt, 3 * d / 16, a.ssq, n_ssq, a.eps, 1.0f / (float)d};
@@ -127,17 +128,21 @@ __global__ __launch_bounds__(64 * WK) void step_kernel(StepArgs a) {
         const float *gnext = last ? a.gf : a.g1 + (size_t)(l + 1) * d;
         gemm_wg<MT, 1, PF, true>(gd, EpiResid{a.h, d, NormOut{a.hb, a.ssq, gnext, n_ssq}, mt}, wg, nwg, 0, w1, smem);
         gq.W += a.qkv_stride; go.W += a.o_stride; gg.W += a.gu_stride; gd.W += a.d_stride;
-        if (last) gq = GemmArgs{a.hb, a.wlm, d / 32, mt, a.V / 16, a.ssq, n_ssq, a.eps, 1.0f / (float)d};
-        gemm_prefetch_w<3, PF>(gq, wg, nwg, w3);
+        if (last) {
+            gq = GemmArgs{a.hb, a.wlm, d / 32, mt, a.V / 16, a.ssq, n_ssq, a.eps, 1.0f / (float)d};
+            gemm_prefetch_w<3, PF>(gq, wg < lm_wgs ? wg : lm_wgs - 1, lm_wgs, w3);
+        } else {
+            gemm_prefetch_w<3, PF>(gq, wg, nwg, w3);
+        }
         grid_sync(a.barrier, target, wg0, nwg, a.status, tr);
     }
 
     // LM head: softmax statistics per (row, 16 vocabulary columns), then the per-draft finish
-    gemm_wg<MT, 3, PF, true>(gq, EpiLMStats{a.stats, a.V / 16}, wg0, nwg, 0, w3, smem);
+    if (wg0 < lm_wgs) gemm_wg<MT, 3, PF, true>(gq, EpiLMStats<MT / 2>(a.stats, lm_wgs * 3), wg0, lm_wgs, 0, w3, smem);
     grid_sync(a.barrier, target, wg0, nwg, a.status, tr);
     for (int u = wg0; u < a.rm.units; u += nwg) {
         __syncthreads();
-        lm_finish_wg(u, a.stats, a.V / 16, a.rm.units * a.rm.valid, a.rm.valid, a.rm.rpu_pad, a.tokens, a.mask_id, a.tau,
+        lm_finish_wg(u, a.stats, lm_wgs * 3, a.rm.units * a.rm.valid, a.rm.valid, a.rm.rpu_pad, a.tokens, a.mask_id, a.tau,
                      a.conf, a.argmax, a.unmask, reinterpret_cast<float *>(smem));
     }
 }

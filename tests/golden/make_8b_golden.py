@@ -1,0 +1,62 @@
+"""Writes tests/golden/config12_oracle.npz: the CPU oracle's outputs for the
+8B-shaped decode workloads (config1: S=1, config2: S=4 drafts; same cache).
+
+Calls only the oracle and the seeded workload generator; nothing here touches
+the HIP library.  Takes the better part of an hour on 8 cores and ~25 GB of RAM
+(the oracle widens every weight to float64 on use), which is why its outputs are
+stored instead of being recomputed inside the GPU tests.
+
+    python tests/golden/make_8b_golden.py [n_layers]   (n_layers defaults to 32)
+"""
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, ROOT)
+from oracle import odb_oracle as o                       # noqa: E402
+from paper_2511_21759_amd import workloads as W          # noqa: E402
+
+
+def main():
+    n_layers = int(sys.argv[1]) if len(sys.argv) > 1 else 32
+    shape = dict(W.MODEL_SHAPES["8b"], n_layers=n_layers)
+    cfg = o.Config(**shape)
+    w = o.Weights(cfg, W.WEIGHT_SEED, W.WEIGHT_STD, keep=True)
+    wl = W.config2()
+    assert np.array_equal(wl.tokens, W.config1().tokens) and np.array_equal(wl.drafts[0, :1], W.config1().drafts[0])
+    t0 = time.time()
+    cache, conf_p, am_p, z_p = o.prefill(cfg, w, wl.tokens[0], wl.resp_off, return_logits=True)
+    print("prefill done %.0fs" % (time.time() - t0), flush=True)
+    conf, am, um, z = o.block_step(cfg, w, cache, wl.drafts[0], wl.block_off, wl.tau, return_logits=True)
+    print("step done %.0fs" % (time.time() - t0), flush=True)
+    rng = np.random.default_rng(123)
+    cols = np.sort(rng.choice(cfg.vocab, 256, replace=False))
+    top = np.argsort(z, axis=-1)[..., -8:]
+    top_p = np.argsort(z_p, axis=-1)[..., -8:]
+    layers = sorted(set([0, n_layers // 2, n_layers - 1]))
+    pos = np.sort(rng.choice(wl.tokens.shape[1], 48, replace=False))
+    out = dict(
+        n_layers=n_layers, tau=wl.tau, block_off=wl.block_off,
+        step_conf=conf, step_argmax=am, step_unmask=um,
+        step_logit_cols=cols, step_logits_sample=z[..., cols].astype(np.float32),
+        step_top_ids=top.astype(np.int32), step_top_logits=np.take_along_axis(z, top, -1).astype(np.float32),
+        step_logit_absmax=np.abs(z).max(), step_lse=np.log(np.exp(z - z.max(-1, keepdims=True)).sum(-1)) + z.max(-1),
+        prefill_conf=conf_p, prefill_argmax=am_p,
+        prefill_logits_sample=z_p[..., cols].astype(np.float32),
+        prefill_top_ids=top_p.astype(np.int32),
+        prefill_top_logits=np.take_along_axis(z_p, top_p, -1).astype(np.float32),
+        prefill_logit_absmax=np.abs(z_p).max(),
+        kv_layers=np.array(layers), kv_pos=pos,
+        k_sample=cache.k[layers][:, pos].astype(np.float32), v_sample=cache.v[layers][:, pos].astype(np.float32),
+        k_absmax=np.abs(cache.k[layers]).max(axis=(1, 2, 3)), v_absmax=np.abs(cache.v[layers]).max(axis=(1, 2, 3)),
+    )
+    name = "config12_oracle.npz" if n_layers == 32 else "config12_oracle_%dL.npz" % n_layers
+    np.savez_compressed(os.path.join(os.path.dirname(os.path.abspath(__file__)), name), **out)
+    print("wrote", name, "%.0fs" % (time.time() - t0), flush=True)
+
+
+if __name__ == "__main__":
+    main()
