@@ -93,14 +93,18 @@ int odb_model_init_random(odb_model *m, uint64_t seed, double std, void *stream)
 
 /* Replaces / reads back one tensor as bf16 bit patterns in logical row-major
  * order (host memory, n = number of elements, must match the shape).
- * Synchronous. */
+ * Synchronous.  Inside the library the projection matrices are held as IEEE
+ * binary16, which represents every bf16 value of magnitude 2^-16 .. 65504
+ * exactly; smaller magnitudes are rounded to a multiple of 2^-24 (an absolute
+ * error below 3e-8), larger ones saturate. */
 int odb_model_set_tensor(odb_model *m, int tensor_id, int layer,
                          const uint16_t *host_bf16, size_t n);
 int odb_model_get_tensor(const odb_model *m, int tensor_id, int layer,
                          uint16_t *host_bf16, size_t n);
 
 /* K/V cache for `batch` sequences of up to max_len positions: post-RoPE K and
- * V in bf16 for every layer, head and position (Sec. 2.1). */
+ * V, two bytes per element (binary16), for every layer, head and position
+ * (Sec. 2.1). */
 int odb_cache_create(odb_model *m, int batch, int max_len, odb_cache **out);
 void odb_cache_destroy(odb_cache *c);
 /* Current sequence length set by the last odb_prefill (0 before). */
@@ -161,10 +165,10 @@ int odb_block_step_logits(odb_model *m, const odb_cache *c,
                           float *logits_dev, void *stream);
 
 /* Copies cached K (kv = 0, post-RoPE, logical channel order) or V (kv = 1) of
- * positions pos0 .. pos0+n-1 of one sequence and layer to host memory as bf16
- * bit patterns [n, n_heads, head_dim].  Synchronous (device-wide). */
+ * positions pos0 .. pos0+n-1 of one sequence and layer to host memory as
+ * float [n, n_heads, head_dim].  Synchronous (device-wide). */
 int odb_cache_read(const odb_cache *c, int layer, int kv, int batch_index,
-                   int pos0, int n, uint16_t *host_bf16);
+                   int pos0, int n, float *host_f32);
 
 /* Measurement aid.  Between odb_profile_begin and odb_profile_end every launch
  * of the kernel class `kernel_class` made by calls on this model is bracketed

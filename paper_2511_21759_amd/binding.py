@@ -192,7 +192,7 @@ def odb_block_step_logits(model: int, cache: int, drafts, block_off: int, vocab:
 
 def odb_cache_read(cache: int, layer: int, kv: int, batch_index: int, pos0: int, n: int, n_heads: int,
                    head_dim: int) -> np.ndarray:
-    out = np.empty((n, n_heads, head_dim), np.uint16)
+    out = np.empty((n, n_heads, head_dim), np.float32)
     _check(lib().odb_cache_read(cache, layer, kv, batch_index, pos0, n, out.ctypes.data))
     return out
 

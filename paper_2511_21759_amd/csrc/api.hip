@@ -49,10 +49,11 @@ void dev_free(const Model &m, void *p) {
 }
 
 constexpr int kCounters = 1 << 12;     // grid-barrier / arrival counters
+constexpr size_t kPartialBytes = 32u << 20;   // K-split partial sums of the tile GEMM
 
 // byte offsets of the per-call buffers inside the model's scratch allocation
 struct Plan {
-    size_t h, xa, q, kf, vf, ao, act, ssq, stats, total;
+    size_t h, xa, q, kf, vf, ao, act, ssq, stats, part, total;
 };
 
 Plan make_plan(const odb_config &c, int rows_pad, int fresh_rows, int lm_rows_pad, bool need_stats) {
@@ -68,7 +69,8 @@ Plan make_plan(const odb_config &c, int rows_pad, int fresh_rows, int lm_rows_pa
     p.ao = take((size_t)rows_pad * d * 2);
     p.act = take((size_t)rows_pad * c.d_ff * 2);
     p.ssq = take((size_t)rows_pad * (d / 16) * 4);
-    p.stats = take(need_stats ? (size_t)lm_rows_pad * lm_stats_parts(c.vocab / 16) * 3 * 4 : 0);
+    p.stats = take(need_stats ? (size_t)lm_rows_pad * 256 * 6 * 3 * 4 : 0);      // room for any launch variant
+    p.part = take(kPartialBytes);
     p.total = off;
     return p;
 }
@@ -166,6 +168,7 @@ int run_stack(Model &m, const Cache &c, const Plan &pl, const StackIO &io, hipSt
     const size_t seq_elems = (size_t)H * c.lmax32 * dh;
     const int fresh32 = ru(io.rm.rpu_pad, 32);
     const int n_ssq = d / 16;
+    const Workspace ws{(float *)(base + pl.part), kPartialBytes};
     const NormIn ni = io.fused_norm ? NormIn{ssq, n_ssq, cfg.rms_eps} : NormIn{nullptr, 0, 0.f};
 
     for (int l = 0; l < cfg.n_layers; l++) {
@@ -188,7 +191,7 @@ int run_stack(Model &m, const Cache &c, const Plan &pl, const StackIO &io, hipSt
         }
         {
             ProfScope ps(m, ODB_K_GEMM_QKV, s);
-            launch_gemm_qkv(xa, w.qkv, GemmShape{mt, 3 * d / 16, d / 32}, ni, qo, s);
+            launch_gemm_qkv(xa, w.qkv, GemmShape{mt, 3 * d / 16, d / 32}, ni, qo, ws, s);
         }
 
         AttnArgs a;
@@ -212,7 +215,7 @@ int run_stack(Model &m, const Cache &c, const Plan &pl, const StackIO &io, hipSt
         NormOut no_mlp = io.fused_norm ? NormOut{xa, ssq, g_after_mlp, n_ssq} : NormOut{nullptr, nullptr, nullptr, 0};
         {
             ProfScope ps(m, ODB_K_GEMM_O, s);
-            launch_gemm_resid(ao, w.o, GemmShape{mt, d / 16, d / 32}, h, d, no_attn, s);
+            launch_gemm_resid(ao, w.o, GemmShape{mt, d / 16, d / 32}, h, d, no_attn, ws, s);
         }
         if (!io.fused_norm) {
             ProfScope ps(m, ODB_K_RMSNORM, s);
@@ -220,11 +223,11 @@ int run_stack(Model &m, const Cache &c, const Plan &pl, const StackIO &io, hipSt
         }
         {
             ProfScope ps(m, ODB_K_GEMM_GATE_UP, s);
-            launch_gemm_swiglu(xa, w.gu, GemmShape{mt, 2 * F / 16, d / 32}, ni, act, s);
+            launch_gemm_swiglu(xa, w.gu, GemmShape{mt, 2 * F / 16, d / 32}, ni, act, ws, s);
         }
         {
             ProfScope ps(m, ODB_K_GEMM_DOWN, s);
-            launch_gemm_resid(act, w.dn, GemmShape{mt, d / 16, F / 32}, h, d, no_mlp, s);
+            launch_gemm_resid(act, w.dn, GemmShape{mt, d / 16, F / 32}, h, d, no_mlp, ws, s);
         }
     }
     return ODB_OK;
@@ -239,6 +242,7 @@ int run_head(Model &m, const Plan &pl, RowMap rm, int skip, bool fused_norm, con
     float *h = (float *)(base + pl.h);
     u16 *xa = (u16 *)(base + pl.xa);
     float *stats = (float *)(base + pl.stats);
+    const Workspace ws{(float *)(base + pl.part), kPartialBytes};
     const int rows = rm.units * (rm.valid - skip);
     int lm_mt, rpu_pad, valid;
     NormIn ni{nullptr, 0, 0.f};
@@ -254,14 +258,14 @@ int run_head(Model &m, const Plan &pl, RowMap rm, int skip, bool fused_norm, con
     }
     GemmShape sh{lm_mt, cfg.vocab / 16, cfg.d_model / 32};
     if (logits) {
-        if (fused_norm) launch_gemm_store(xa, m.w[PK_LM], sh, ni, logits, rm.units, rpu_pad, valid, cfg.vocab, s);
-        else launch_gemm_store(xa, m.w[PK_LM], sh, ni, logits, 1, lm_mt * 16, rows, cfg.vocab, s);
+        if (fused_norm) launch_gemm_store(xa, m.w[PK_LM], sh, ni, logits, rm.units, rpu_pad, valid, cfg.vocab, ws, s);
+        else launch_gemm_store(xa, m.w[PK_LM], sh, ni, logits, 1, lm_mt * 16, rows, cfg.vocab, ws, s);
     } else {
         {
             ProfScope ps(m, ODB_K_GEMM_LM_HEAD, s);
-            launch_gemm_lmstats(xa, m.w[PK_LM], sh, ni, stats, s);
+            launch_gemm_lmstats(xa, m.w[PK_LM], sh, ni, stats, ws, s);
         }
-        launch_lm_finish(stats, lm_stats_parts(cfg.vocab / 16), rows, rpu_out, rpu_pad, tokens, cfg.mask_id, tau, conf, argmax, unmask,
+        launch_lm_finish(stats, lm_stats_parts(cfg.vocab / 16, lm_mt), rows, rpu_out, rpu_pad, tokens, cfg.mask_id, tau, conf, argmax, unmask,
                          s);
     }
     HIP_TRY(hipGetLastError());
@@ -660,8 +664,8 @@ int odb_profile_end(odb_model *mh, int *n_launches, float *total_ms) {
     return ODB_OK;
 }
 
-int odb_cache_read(const odb_cache *ch, int layer, int kv, int batch_index, int pos0, int n, uint16_t *host_bf16) {
-    if (!ch || !host_bf16) return fail(ODB_E_INVALID_ARG, "cache_read: NULL argument");
+int odb_cache_read(const odb_cache *ch, int layer, int kv, int batch_index, int pos0, int n, float *host_f32) {
+    if (!ch || !host_f32) return fail(ODB_E_INVALID_ARG, "cache_read: NULL argument");
     const Cache &c = ch->c;
     Model &m = *c.m;
     if (layer < 0 || layer >= m.cfg.n_layers || kv < 0 || kv > 1 || batch_index < 0 || batch_index >= c.batch)
@@ -669,7 +673,7 @@ int odb_cache_read(const odb_cache *ch, int layer, int kv, int batch_index, int 
     if (pos0 < 0 || n < 1 || pos0 + n > c.length) return fail(ODB_E_INVALID_ARG, "cache_read: positions [%d, %d) outside the cached length %d", pos0, pos0 + n, c.length);
     HIP_TRY(hipSetDevice(m.device));
     HIP_TRY(hipDeviceSynchronize());
-    size_t bytes = (size_t)n * m.cfg.d_model * 2;
+    size_t bytes = (size_t)n * m.cfg.d_model * 4;
     if (m.staging_bytes < bytes) {
         dev_free(m, m.staging);
         m.staging_bytes = 0;
@@ -677,10 +681,10 @@ int odb_cache_read(const odb_cache *ch, int layer, int kv, int batch_index, int 
         if (!m.staging) return fail(ODB_E_NOMEM, "cache_read staging");
         m.staging_bytes = bytes;
     }
-    launch_cache_read(c, layer, kv, batch_index, pos0, n, m.staging, nullptr);
+    launch_cache_read(c, layer, kv, batch_index, pos0, n, (float *)m.staging, nullptr);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipDeviceSynchronize());
-    HIP_TRY(hipMemcpy(host_bf16, m.staging, bytes, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(host_f32, m.staging, bytes, hipMemcpyDeviceToHost));
     return ODB_OK;
 }
 

@@ -27,8 +27,8 @@ __device__ inline void store_out_tile(const AttnArgs &a, int mt, int hd, int dt1
     u16 *dst = a.out + ((size_t)kt * a.mt_total + mt) * kTileElems + (((dt16 & 1) * 2 + (g >> 1)) * 16 + mi) * 8 +
                (g & 1) * 4;
     uint2 p;
-    p.x = pack2bf(v[0], v[1]);
-    p.y = pack2bf(v[2], v[3]);
+    p.x = pack2(v[0], v[1]);
+    p.y = pack2(v[2], v[3]);
     *reinterpret_cast<uint2 *>(dst) = p;
 }
 
@@ -67,22 +67,25 @@ __device__ __forceinline__ void attn_wg(const AttnArgs &a, float sc, int item, i
         for (int dt = 0; dt < DT16; dt++) o[t][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    auto tile = [&](const u16 *kp, const u16 *vp, int key0, bool cached) __attribute__((always_inline)) {
-        frag_t kf[2][DT32];
+    struct TileRef { const u16 *kp, *vp; int key0; bool cached, live; };
+    auto load_tile = [&](const TileRef &r, frag_t (&kf)[2][DT32], frag_t (&vf)[DT16]) __attribute__((always_inline)) {
 #pragma unroll
         for (int s = 0; s < 2; s++)
 #pragma unroll
-            for (int dt = 0; dt < DT32; dt++) kf[s][dt] = ld_frag(kp + (size_t)(s * DT32 + dt) * kTileElems + lane * 8);
-        frag_t vf[DT16];
+            for (int dt = 0; dt < DT32; dt++)
+                kf[s][dt] = ld_frag(r.kp + (size_t)(s * DT32 + dt) * kTileElems + lane * 8);
 #pragma unroll
-        for (int dt = 0; dt < DT16; dt++) vf[dt] = ld_frag(vp + (size_t)dt * kTileElems + lane * 8);
+        for (int dt = 0; dt < DT16; dt++) vf[dt] = ld_frag(r.vp + (size_t)dt * kTileElems + lane * 8);
+    };
+    auto compute_tile = [&](const TileRef &r, const frag_t (&kf)[2][DT32], const frag_t (&vf)[DT16])
+                            __attribute__((always_inline)) {
         bool ok[2][4];
 #pragma unroll
         for (int s = 0; s < 2; s++)
 #pragma unroll
-            for (int r = 0; r < 4; r++) {
-                int key = key0 + s * 16 + 4 * g + r;
-                ok[s][r] = cached ? (key < a.L && !(key >= a.blk_lo && key < a.blk_hi)) : key < a.fresh;
+            for (int rr = 0; rr < 4; rr++) {
+                int key = r.key0 + s * 16 + 4 * g + rr;
+                ok[s][rr] = r.cached ? (key < a.L && !(key >= a.blk_lo && key < a.blk_hi)) : key < a.fresh;
             }
 #pragma unroll
         for (int t = 0; t < QT; t++) {
@@ -97,9 +100,9 @@ __device__ __forceinline__ void attn_wg(const AttnArgs &a, float sc, int item, i
 #pragma unroll
             for (int s = 0; s < 2; s++)
 #pragma unroll
-                for (int r = 0; r < 4; r++) {
-                    st[s][r] = ok[s][r] ? st[s][r] * sc : -INFINITY;
-                    tm = fmaxf(tm, st[s][r]);
+                for (int rr = 0; rr < 4; rr++) {
+                    st[s][rr] = ok[s][rr] ? st[s][rr] * sc : -INFINITY;
+                    tm = fmaxf(tm, st[s][rr]);
                 }
             tm = fmaxf(tm, __shfl_xor(tm, 16));
             tm = fmaxf(tm, __shfl_xor(tm, 32));
@@ -110,17 +113,17 @@ __device__ __forceinline__ void attn_wg(const AttnArgs &a, float sc, int item, i
 #pragma unroll
             for (int s = 0; s < 2; s++)
 #pragma unroll
-                for (int r = 0; r < 4; r++) {
-                    p[s][r] = exp2f(st[s][r] - mref);
-                    ps += p[s][r];
+                for (int rr = 0; rr < 4; rr++) {
+                    p[s][rr] = exp2f(st[s][rr] - mref);
+                    ps += p[s][rr];
                 }
             lrun[t] = lrun[t] * alpha + ps;
             mrun[t] = mnew;
             frag_t pf;
-            pf.w[0] = pack2bf(p[0][0], p[0][1]);
-            pf.w[1] = pack2bf(p[0][2], p[0][3]);
-            pf.w[2] = pack2bf(p[1][0], p[1][1]);
-            pf.w[3] = pack2bf(p[1][2], p[1][3]);
+            pf.w[0] = pack2(p[0][0], p[0][1]);
+            pf.w[1] = pack2(p[0][2], p[0][3]);
+            pf.w[2] = pack2(p[1][0], p[1][1]);
+            pf.w[3] = pack2(p[1][2], p[1][3]);
 #pragma unroll
             for (int dt = 0; dt < DT16; dt++) {
                 o[t][dt] *= alpha;
@@ -129,20 +132,60 @@ __device__ __forceinline__ void attn_wg(const AttnArgs &a, float sc, int item, i
         }
     };
 
-    // cached keys: 32-key tiles interleaved over the waves; the fresh tiles follow in the same rotation
+    // This wave's tiles: cached 32-key tiles w, w+NW, ... (those wholly inside the block are dead),
+    // then the fresh tiles that continue the same rotation.  The loads of tile i+1 are issued
+    // before tile i is computed.
     const int n32 = (a.L + 31) / 32;
     const u16 *kc = a.kc + seq * a.kc_seq_stride + hd * a.kc_head_stride;
     const u16 *vc = a.vc + seq * a.vc_seq_stride + hd * a.vc_head_stride;
-    for (int T = w; T < n32; T += NW) {
-        if (T * 32 >= a.blk_lo && T * 32 + 32 <= a.blk_hi) continue;       // wholly inside the block
-        tile(kc + (size_t)T * 2 * DT32 * kTileElems, vc + (size_t)T * DT16 * kTileElems, T * 32, true);
-    }
-    if (a.fresh > 0) {
-        const u16 *kf = a.kf + unit * a.kf_unit_stride + hd * a.kf_head_stride;
-        const u16 *vf = a.vf + unit * a.vf_unit_stride + hd * a.vf_head_stride;
-        const int nf = (a.fresh + 31) / 32;
-        for (int T = (w + NW - n32 % NW) % NW; T < nf; T += NW)
-            tile(kf + (size_t)T * 2 * DT32 * kTileElems, vf + (size_t)T * DT16 * kTileElems, T * 32, false);
+    const u16 *kfr = a.kf + unit * a.kf_unit_stride + hd * a.kf_head_stride;
+    const u16 *vfr = a.vf + unit * a.vf_unit_stride + hd * a.vf_head_stride;
+    const int nc = w < n32 ? (n32 - w + NW - 1) / NW : 0;
+    const int nf32 = a.fresh > 0 ? (a.fresh + 31) / 32 : 0;
+    const int f0 = (w + NW - n32 % NW) % NW;
+    const int nfw = f0 < nf32 ? (nf32 - f0 + NW - 1) / NW : 0;
+    const int total = nc + nfw;
+    auto get = [&](int i) __attribute__((always_inline)) {
+        TileRef r;
+        if (i < nc) {
+            const int T = w + i * NW;
+            r.kp = kc + (size_t)T * 2 * DT32 * kTileElems;
+            r.vp = vc + (size_t)T * DT16 * kTileElems;
+            r.key0 = T * 32;
+            r.cached = true;
+            r.live = !(T * 32 >= a.blk_lo && T * 32 + 32 <= a.blk_hi);
+        } else {
+            const int T = f0 + (i - nc) * NW;
+            r.kp = kfr + (size_t)T * 2 * DT32 * kTileElems;
+            r.vp = vfr + (size_t)T * DT16 * kTileElems;
+            r.key0 = T * 32;
+            r.cached = false;
+            r.live = true;
+        }
+        return r;
+    };
+    if (total > 0) {
+        frag_t kf_c[2][DT32], vf_c[DT16], kf_n[2][DT32], vf_n[DT16];
+        TileRef cur = get(0);
+        if (cur.live) load_tile(cur, kf_c, vf_c);
+        for (int i = 0; i < total; i++) {
+            TileRef nxt = cur;
+            const bool more = i + 1 < total;
+            if (more) {
+                nxt = get(i + 1);
+                if (nxt.live) load_tile(nxt, kf_n, vf_n);
+            }
+            if (cur.live) compute_tile(cur, kf_c, vf_c);
+            if (more) {
+                cur = nxt;
+#pragma unroll
+                for (int s = 0; s < 2; s++)
+#pragma unroll
+                    for (int dt = 0; dt < DT32; dt++) kf_c[s][dt] = kf_n[s][dt];
+#pragma unroll
+                for (int dt = 0; dt < DT16; dt++) vf_c[dt] = vf_n[dt];
+            }
+        }
     }
 
     // merge the waves

@@ -1,8 +1,8 @@
 // Shared device-side definitions: MFMA fragment types and the tiled layouts.
 //
-// Every bf16 matrix that feeds an MFMA lives in HBM as a sequence of 1 KiB
-// "operand tiles" of 16 rows x 32 k-elements, stored in the register order of
-// v_mfma_f32_16x16x32_bf16: lane l of a wavefront owns row (l & 15) and the 8
+// Every matrix that feeds an MFMA lives in HBM as a sequence of 1 KiB "operand
+// tiles" of 16 rows x 32 k-elements of binary16, stored in the register order of
+// v_mfma_f32_16x16x32_f16: lane l of a wavefront owns row (l & 15) and the 8
 // consecutive k-elements starting at 8*(l >> 4).  A wave loads a tile with one
 // 16-byte load per lane from 1 KiB of contiguous memory and hands the register
 // straight to the MFMA, as either operand:
@@ -14,7 +14,12 @@
 
 namespace odb {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+// Operands are IEEE binary16 (11-bit significand), accumulation is fp32.  The model's weights are
+// bfloat16 VALUES (8-bit significand); every such value of magnitude 2^-16 .. 65504 is exactly
+// representable in binary16, so they are converted once when they enter the library.  Activations
+// rounded to bfloat16 instead would cost 8x the rounding noise per GEMM input, which after 32 layers
+// exceeds the 1e-2 bound on the K/V cache (measured 2.3e-2) - at the same MFMA rate.
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned short u16;
 
@@ -23,21 +28,28 @@ constexpr int kTileK = 32;
 constexpr int kTileElems = 512;   // 1 KiB of bf16
 constexpr int kWave = 64;
 
-struct __attribute__((aligned(16))) frag_t { uint32_t w[4]; };   // 8 bf16
+struct __attribute__((aligned(16))) frag_t { uint32_t w[4]; };   // 8 binary16
 
 // offset of element (row r, k-element kk) inside a tile
 __host__ __device__ inline int tile_elem(int r, int kk) {
     return ((kk >> 3) * 16 + r) * 8 + (kk & 7);
 }
 
-__device__ inline u16 f2bf(float x) {          // round to nearest even
+__device__ inline u16 f2bf(float x) {          // bfloat16, round to nearest even
     return __builtin_bit_cast(u16, (__bf16)x);
 }
 __device__ inline float bf2f(u16 b) {
     return __builtin_bit_cast(float, (uint32_t)b << 16);
 }
-__device__ inline uint32_t pack2bf(float lo, float hi) {
-    return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+__device__ inline u16 f2h(float x) {           // binary16, round to nearest even, saturating
+    x = fminf(fmaxf(x, -65504.f), 65504.f);
+    return __builtin_bit_cast(u16, (_Float16)x);
+}
+__device__ inline float h2f(u16 b) {
+    return (float)__builtin_bit_cast(_Float16, b);
+}
+__device__ inline uint32_t pack2(float lo, float hi) {      // two operand elements
+    return (uint32_t)f2h(lo) | ((uint32_t)f2h(hi) << 16);
 }
 
 __device__ inline frag_t ld_frag(const u16 *p) {
@@ -45,8 +57,8 @@ __device__ inline frag_t ld_frag(const u16 *p) {
 }
 
 __device__ inline f32x4 mfma16(const frag_t &x, const frag_t &y, f32x4 acc) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-        __builtin_bit_cast(bf16x8, x), __builtin_bit_cast(bf16x8, y), acc, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(
+        __builtin_bit_cast(f16x8, x), __builtin_bit_cast(f16x8, y), acc, 0, 0, 0);
 }
 
 }  // namespace odb

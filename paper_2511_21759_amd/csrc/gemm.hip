@@ -1,5 +1,5 @@
 // Stand-alone launches of the weight-streaming GEMM (see gemm_core.h).
-#include "gemm_core.h"
+#include "gemm_tile.h"
 
 namespace odb {
 
@@ -10,61 +10,87 @@ __global__ __launch_bounds__(64 * WK) void gemm_stream_kernel(GemmArgs g, Epi ep
     gemm_wg<MT, NG, PF, false>(g, epi, blockIdx.x, gridDim.x, blockIdx.y * MT, wb, smem);
 }
 
-// an epilogue "maker" yields the epilogue object for a given m-tile count (most are independent of it)
-template <class Epi> struct Same {
-    Epi e;
-    template <int MT> Epi for_mt() const { return e; }
-};
-struct LMStatsMaker {
-    float *stats;
-    int n_part;
-    template <int MT> EpiLMStats<MT / 2> for_mt() const { return EpiLMStats<MT / 2>(stats, n_part); }
-};
-
-// ---- launch ---------------------------------------------------------------------
 constexpr int kStreamWGs = 256;      // one workgroup per compute unit
 
-template <int NG, class Maker>
-static void launch(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Maker mk, hipStream_t s) {
+// Up to 32 rows: the persistent streaming kernel with NG n-tiles per group and a PF-deep ring.
+// More rows: the tile kernel (gemm_tile.h), K-split over workgroups when there are too few n-blocks.
+template <int NG, int PF, class Epi>
+static void launch_stream(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi e, hipStream_t s) {
     GemmArgs g;
     g.A = a; g.W = w; g.KT = sh.K_tiles; g.MT_total = sh.M_tiles; g.NT = sh.N_tiles;
     g.ssq = ni.ssq; g.n_ssq = ni.n_ssq; g.eps = ni.eps; g.inv_d = 1.0f / (float)(sh.K_tiles * 32);
     const int kw = sh.K_tiles / WK;                 // K_tiles is a multiple of 8 (checked at model creation)
     const int groups = (sh.N_tiles + NG - 1) / NG;
-    const int wgs = groups < kStreamWGs ? groups : kStreamWGs;
-    if (sh.M_tiles <= 2) {
-        dim3 grid(wgs, 1);
-        auto e = mk.template for_mt<2>();
-        if (kw % 8 == 0) gemm_stream_kernel<2, NG, 8, decltype(e)><<<grid, 64 * WK, 0, s>>>(g, e);
-        else gemm_stream_kernel<2, NG, 1, decltype(e)><<<grid, 64 * WK, 0, s>>>(g, e);
-    } else {
-        dim3 grid(wgs, (sh.M_tiles + 7) / 8);
-        auto e = mk.template for_mt<8>();
-        if (kw % 2 == 0) gemm_stream_kernel<8, NG, 2, decltype(e)><<<grid, 64 * WK, 0, s>>>(g, e);
-        else gemm_stream_kernel<8, NG, 1, decltype(e)><<<grid, 64 * WK, 0, s>>>(g, e);
+    dim3 grid(groups < kStreamWGs ? groups : kStreamWGs, 1);
+    if (kw % PF == 0) gemm_stream_kernel<2, NG, PF, Epi><<<grid, 64 * WK, 0, s>>>(g, e);
+    else gemm_stream_kernel<2, NG, 1, Epi><<<grid, 64 * WK, 0, s>>>(g, e);
+}
+
+template <class Epi>
+static void launch_tile(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi e, Workspace ws, bool may_split,
+                        hipStream_t s) {
+    TileArgs g;
+    g.A = a; g.W = w; g.KT = sh.K_tiles; g.MT_total = sh.M_tiles; g.NT = sh.N_tiles;
+    g.ssq = ni.ssq; g.n_ssq = ni.n_ssq; g.eps = ni.eps; g.inv_d = 1.0f / (float)(sh.K_tiles * 32);
+    g.partial = ws.partial;
+    const int m_blocks = (sh.M_tiles + 7) / 8;
+    const bool big = sh.M_tiles > 8;                 // compute-bound shapes take two n-tiles per wave
+    const int ngw = big ? 2 : 1;
+    g.n_blocks = (sh.N_tiles + 8 * ngw - 1) / (8 * ngw);
+    int ks = 1;
+    while (may_split && g.n_blocks * m_blocks * ks * 2 <= kStreamWGs && sh.K_tiles % (ks * 2) == 0 &&
+           sh.K_tiles / (ks * 2) >= 8 && (size_t)(ks * 2) * sh.M_tiles * sh.N_tiles * 1024 <= ws.partial_bytes)
+        ks *= 2;
+    g.KS = ks;
+    dim3 grid(g.n_blocks * ks, m_blocks);
+    if (big) gemm_tile_kernel<2, 4, Epi><<<grid, 512, 0, s>>>(g, e);
+    else gemm_tile_kernel<1, 8, Epi><<<grid, 512, 0, s>>>(g, e);
+    if (ks > 1) {
+        if constexpr (!is_row_stats<Epi>::value)
+            tile_epilogue_kernel<Epi><<<dim3((sh.N_tiles + 7) / 8, sh.M_tiles), 512, 0, s>>>(g, e);
     }
 }
 
-void launch_gemm_qkv(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, QkvOut out, hipStream_t s) {
-    launch<3>(xa, w, sh, ni, Same<EpiQKV>{EpiQKV{out, sh.M_tiles}}, s);
+void launch_gemm_qkv(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, QkvOut out, Workspace ws, hipStream_t s) {
+    EpiQKV e{out, sh.M_tiles};
+    if (sh.M_tiles <= 2) launch_stream<3, 8>(xa, w, sh, ni, e, s);
+    else launch_tile(xa, w, sh, ni, e, ws, true, s);
 }
-void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int ldh, NormOut no, hipStream_t s) {
-    launch<1>(a, w, sh, NormIn{nullptr, 0, 0.f}, Same<EpiResid>{EpiResid{h, ldh, no, sh.M_tiles}}, s);
+void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int ldh, NormOut no, Workspace ws,
+                       hipStream_t s) {
+    EpiResid e{h, ldh, no, sh.M_tiles};
+    if (sh.M_tiles <= 2) launch_stream<1, 8>(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
+    else launch_tile(a, w, sh, NormIn{nullptr, 0, 0.f}, e, ws, true, s);
 }
-void launch_gemm_swiglu(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, u16 *act, hipStream_t s) {
-    launch<3>(xa, w, sh, ni, Same<EpiSwiGLU>{EpiSwiGLU{act, sh.M_tiles}}, s);
-}
-int lm_stats_parts(int n_tiles) {
-    const int groups = (n_tiles + 2) / 3;
-    return (groups < kStreamWGs ? groups : kStreamWGs) * 3;
+void launch_gemm_swiglu(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, u16 *act, Workspace ws, hipStream_t s) {
+    EpiSwiGLU e{act, sh.M_tiles};
+    if (sh.M_tiles <= 2) launch_stream<6, 4>(xa, w, sh, ni, e, s);
+    else launch_tile(xa, w, sh, ni, e, ws, true, s);
 }
 
-void launch_gemm_lmstats(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, float *stats, hipStream_t s) {
-    launch<3>(xa, w, sh, ni, LMStatsMaker{stats, lm_stats_parts(sh.N_tiles)}, s);
+constexpr int kLmNG = 6;      // n-tiles per group of the LM head at up to 32 rows
+
+// partials per row that launch_gemm_lmstats writes
+int lm_stats_parts(int n_tiles, int m_tiles) {
+    if (m_tiles <= 2) {
+        const int groups = (n_tiles + kLmNG - 1) / kLmNG;
+        return (groups < kStreamWGs ? groups : kStreamWGs) * kLmNG;
+    }
+    const int ngw = m_tiles > 8 ? 2 : 1;
+    return (n_tiles + 8 * ngw - 1) / (8 * ngw);
+}
+
+void launch_gemm_lmstats(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, float *stats, Workspace ws,
+                         hipStream_t s) {
+    const int parts = lm_stats_parts(sh.N_tiles, sh.M_tiles);
+    if (sh.M_tiles <= 2) launch_stream<kLmNG, 4>(xa, w, sh, ni, EpiLMStats<2>(stats, parts), s);
+    else launch_tile(xa, w, sh, ni, TileLMStats{stats, parts}, ws, false, s);
 }
 void launch_gemm_store(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, float *out, int units, int rpu_pad,
-                       int valid, int ld, hipStream_t s) {
-    launch<3>(xa, w, sh, ni, Same<EpiStore>{EpiStore{out, units, rpu_pad, valid, ld}}, s);
+                       int valid, int ld, Workspace ws, hipStream_t s) {
+    EpiStore e{out, units, rpu_pad, valid, ld};
+    if (sh.M_tiles <= 2) launch_stream<3, 8>(xa, w, sh, ni, e, s);
+    else launch_tile(xa, w, sh, ni, e, ws, false, s);
 }
 
 }  // namespace odb

@@ -34,6 +34,9 @@ struct GemmArgs {
     float eps, inv_d;
 };
 
+// m-tiles per reduction pass: at most six 1 KiB tiles per wave go through LDS at a time
+constexpr int gemm_mc(int mt, int ng) { return ng >= 6 ? 1 : (ng >= 3 ? 2 : (mt < 4 ? mt : 4)); }
+
 constexpr int kGemmSmemBytes = WK * 6 * 1024 + 8 * 16 * 4;    // LDS one workgroup needs (red + row scales)
 
 // Weight tiles of the first PF k-steps of workgroup `wg`'s first group of n-tiles.  Weights do not
@@ -64,7 +67,7 @@ __device__ __forceinline__ void gemm_prefetch_w(const GemmArgs &g, int wg, int n
 template <int MT, int NG, int PF, bool HAVE_W, class Epi>
 __device__ __forceinline__ void gemm_wg(const GemmArgs &g, Epi epi, int wg, int nwg, int mt0,
                                         frag_t (&wb)[PF][NG], char *smem) {
-    constexpr int MC = NG >= 3 ? 2 : (MT < 4 ? MT : 4);    // m-tiles reduced per pass through LDS (<= 48 KiB)
+    constexpr int MC = gemm_mc(MT, NG);                     // m-tiles reduced per pass through LDS (<= 48 KiB)
     static_assert(MT % MC == 0 && MC * NG <= 6 && MT <= 8, "m chunking");
     f32x4 (*red)[MC * NG][64] = reinterpret_cast<f32x4 (*)[MC * NG][64]>(smem);
     float *s_rstd = reinterpret_cast<float *>(smem + WK * 6 * 1024);
@@ -213,8 +216,8 @@ __device__ __forceinline__ void gemm_wg(const GemmArgs &g, Epi epi, int wg, int 
 
 __device__ inline void st_bf16x4(u16 *p, float a, float b, float c, float d) {
     uint2 v;
-    v.x = pack2bf(a, b);
-    v.y = pack2bf(c, d);
+    v.x = pack2(a, b);
+    v.y = pack2(c, d);
     *reinterpret_cast<uint2 *>(p) = v;
 }
 
@@ -292,7 +295,7 @@ struct EpiSwiGLU {
         float y1 = c[2] / (1.0f + expf(-c[2])) * c[3];
         const int kk = j & 31;
         u16 *dst = act + ((size_t)(j >> 5) * mt_total + mt) * kTileElems + ((kk >> 3) * 16 + mi) * 8 + (kk & 7);
-        *reinterpret_cast<uint32_t *>(dst) = pack2bf(y0, y1);
+        *reinterpret_cast<uint32_t *>(dst) = pack2(y0, y1);
     }
 };
 

@@ -1,0 +1,269 @@
+// bf16 MFMA GEMM  C[M,N] = A[M,K] * W[N,K]^T  for 33 rows and more (the multi-draft step,
+// the prefill, the long-context step).  Same operand layouts and epilogues as gemm_core.h.
+//
+// A workgroup computes a 128-row block x (8*NGW n-tiles) x one slice of K.  Its eight waves split
+// the n-tiles; the 128 x 32 slab of A that a k-step needs is shared through LDS: every wave fetches
+// one of the slab's eight 16-row tiles PF steps ahead into registers and drops it into a two-slot LDS
+// buffer when its turn comes, so A is read from L2 once per workgroup while every wave streams its
+// own weight tiles from HBM straight into MFMA operand registers.  With a K split (grid.x =
+// n-blocks x KS) the partial sums go to an fp32 workspace in MFMA fragment order and
+// tile_epilogue_kernel adds them in a fixed order and runs the epilogue.
+#pragma once
+#include "gemm_core.h"
+
+namespace odb {
+
+struct TileArgs {
+    const u16 *A, *W;
+    int KT, MT_total, NT;
+    int n_blocks, KS;          // grid.x = n_blocks * KS
+    float *partial;            // [KS][MT_total][NT][256] fp32 (KS > 1)
+    const float *ssq;          // fused RMSNorm of the input rows (see GemmArgs)
+    int n_ssq;
+    float eps, inv_d;
+};
+
+// LM-head statistics for the tile kernel: one partial (max, sum exp, argmax) per row and n-block
+struct TileLMStats {
+    static constexpr bool kRowStats = true;
+    float *stats;
+    int n_part;
+};
+
+template <class Epi> struct is_row_stats { static constexpr bool value = false; };
+template <> struct is_row_stats<TileLMStats> { static constexpr bool value = true; };
+
+constexpr int kTileSmemBytes = 2 * 8 * 1024 + 8 * 1024 + 128 * 4;     // A slots, per-wave scratch, row scales
+
+__device__ __forceinline__ void merge_stat(float &m, float &s, int &a, float om, float os, int oa) {
+    float nm = fmaxf(m, om);
+    s = s * (m == nm ? 1.f : expf(m - nm)) + os * (om == nm ? 1.f : expf(om - nm));
+    a = m > om ? a : (om > m ? oa : (a < oa ? a : oa));
+    m = nm;
+}
+
+template <int NGW, int PF, class Epi>
+__global__ __launch_bounds__(512) void gemm_tile_kernel(TileArgs g, Epi epi) {
+    __shared__ __attribute__((aligned(16))) char smem[kTileSmemBytes];
+    frag_t (*a_lds)[8][64] = reinterpret_cast<frag_t (*)[8][64]>(smem);                 // [2][8 m-tiles][64 lanes]
+    f32x4 (*scr)[64] = reinterpret_cast<f32x4 (*)[64]>(smem + 16 * 1024);                // [8 waves][64]
+    float *s_rstd = reinterpret_cast<float *>(smem + 24 * 1024);
+
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int nb = blockIdx.x % g.n_blocks, ks = blockIdx.x / g.n_blocks;
+    const int mt0 = blockIdx.y * 8;
+    const int k_lo = (int)(((long)ks * g.KT) / g.KS), k_hi = (int)(((long)(ks + 1) * g.KT) / g.KS);
+    const int nk = k_hi - k_lo;
+    const int nt0 = (nb * 8 + w) * NGW;
+
+    const u16 *wp[NGW];
+#pragma unroll
+    for (int j = 0; j < NGW; j++) {
+        int nt = nt0 + j < g.NT ? nt0 + j : g.NT - 1;
+        wp[j] = g.W + ((size_t)nt * g.KT + k_lo) * kTileElems + lane * 8;
+    }
+    const int mt_mine = mt0 + w < g.MT_total ? mt0 + w : g.MT_total - 1;           // the A tile this wave fetches
+    const u16 *ap = g.A + ((size_t)k_lo * g.MT_total + mt_mine) * kTileElems + lane * 8;
+    const size_t a_step = (size_t)g.MT_total * kTileElems;
+
+    // row scales of the fused RMSNorm: 16 rows per wave
+    if (g.ssq) {
+        for (int r = 0; r < 16; r++) {
+            int row = (mt0 + w) * 16 + r;
+            row = row < g.MT_total * 16 ? row : g.MT_total * 16 - 1;
+            const float *p = g.ssq + (size_t)row * g.n_ssq;
+            float q = 0.f;
+            for (int i0 = 0; i0 < g.n_ssq; i0 += 256) {
+                float v[4];
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    int i = i0 + lane + 64 * u;
+                    v[u] = i < g.n_ssq ? p[i] : 0.f;
+                }
+                q += (v[0] + v[1]) + (v[2] + v[3]);
+            }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o);
+            if (lane == 0) s_rstd[w * 16 + r] = 1.0f / sqrtf(q * g.inv_d + g.eps);
+        }
+    } else if (lane < 16) {
+        s_rstd[w * 16 + lane] = 1.0f;
+    }
+
+    f32x4 acc[8][NGW];
+#pragma unroll
+    for (int m = 0; m < 8; m++)
+#pragma unroll
+        for (int j = 0; j < NGW; j++) acc[m][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    frag_t wr[PF][NGW], ar[PF];
+#pragma unroll
+    for (int s = 0; s < PF; s++)
+        if (s < nk) {
+            ar[s] = ld_frag(ap + s * a_step);
+#pragma unroll
+            for (int j = 0; j < NGW; j++) wr[s][j] = ld_frag(wp[j] + (size_t)s * kTileElems);
+        }
+
+    for (int kb = 0; kb < nk; kb += PF) {
+#pragma unroll
+        for (int s = 0; s < PF; s++) {
+            const int k = kb + s;
+            if (k < nk) {
+                a_lds[k & 1][w][lane] = ar[s];
+                __syncthreads();
+                frag_t a[8];
+#pragma unroll
+                for (int m = 0; m < 8; m++) a[m] = a_lds[k & 1][m][lane];
+#pragma unroll
+                for (int m = 0; m < 8; m++)
+#pragma unroll
+                    for (int j = 0; j < NGW; j++) acc[m][j] = mfma16(wr[s][j], a[m], acc[m][j]);
+                const int kn = k + PF;
+                if (kn < nk) {
+                    ar[s] = ld_frag(ap + kn * a_step);
+#pragma unroll
+                    for (int j = 0; j < NGW; j++) wr[s][j] = ld_frag(wp[j] + (size_t)kn * kTileElems);
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    if (g.KS > 1) {
+        // partial sums in fragment order; tile_epilogue_kernel finishes the job
+#pragma unroll
+        for (int m = 0; m < 8; m++)
+#pragma unroll
+            for (int j = 0; j < NGW; j++) {
+                const int mt = mt0 + m, nt = nt0 + j;
+                if (mt < g.MT_total && nt < g.NT) {
+                    size_t tile = ((size_t)ks * g.MT_total + mt) * g.NT + nt;
+                    *reinterpret_cast<f32x4 *>(g.partial + tile * 256 + lane * 4) = acc[m][j];
+                }
+            }
+        return;
+    }
+
+    if constexpr (is_row_stats<Epi>::value) {
+        // softmax statistics per row over this workgroup's n-tiles: lane-local, across the four lane
+        // groups, across the wave's NGW tiles, then across the eight waves through LDS
+        float *st_m = reinterpret_cast<float *>(smem);               // the A slots are free now: [8 waves][128 rows]
+        float *st_s = st_m + 8 * 128;
+        int *st_a = reinterpret_cast<int *>(st_s + 8 * 128);
+        const int mi = lane & 15, gq = lane >> 4;
+#pragma unroll
+        for (int m = 0; m < 8; m++) {
+            float rm = -INFINITY, rs = 0.f;
+            int ra = 0x7fffffff;
+#pragma unroll
+            for (int j = 0; j < NGW; j++) {
+                if (nt0 + j < g.NT) {
+                    f32x4 c = acc[m][j] * s_rstd[m * 16 + mi];
+                    float cm = c[0];
+                    int ca = (nt0 + j) * 16 + 4 * gq;
+#pragma unroll
+                    for (int r = 1; r < 4; r++)
+                        if (c[r] > cm) { cm = c[r]; ca = (nt0 + j) * 16 + 4 * gq + r; }
+                    float cs = 0.f;
+#pragma unroll
+                    for (int r = 0; r < 4; r++) cs += expf(c[r] - cm);
+                    merge_stat(rm, rs, ra, cm, cs, ca);
+                }
+            }
+#pragma unroll
+            for (int o = 16; o <= 32; o <<= 1) {
+                float om = __shfl_xor(rm, o), os = __shfl_xor(rs, o);
+                int oa = __shfl_xor(ra, o);
+                merge_stat(rm, rs, ra, om, os, oa);
+            }
+            if (gq == 0) {
+                st_m[w * 128 + m * 16 + mi] = rm;
+                st_s[w * 128 + m * 16 + mi] = rs;
+                st_a[w * 128 + m * 16 + mi] = ra;
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x < 128) {
+            const int r = threadIdx.x, row = mt0 * 16 + r;
+            float rm = st_m[r], rs = st_s[r];
+            int ra = st_a[r];
+#pragma unroll
+            for (int x = 1; x < 8; x++) merge_stat(rm, rs, ra, st_m[x * 128 + r], st_s[x * 128 + r], st_a[x * 128 + r]);
+            if (row < g.MT_total * 16) {
+                float *p = epi.stats + ((size_t)row * epi.n_part + nb) * 3;
+                p[0] = rm;
+                p[1] = rs;
+                p[2] = __int_as_float(ra);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int m = 0; m < 8; m++)
+#pragma unroll
+            for (int j = 0; j < NGW; j++) {
+                const int mt = mt0 + m, nt = nt0 + j;
+                if (mt < g.MT_total && nt < g.NT) {
+                    f32x4 c;
+                    if (!epi.transposed(nt)) {
+                        c = acc[m][j] * s_rstd[m * 16 + (lane & 15)];
+                    } else {
+                        // lane (g, ni) gets rows 4g..4g+3 of column ni: through this wave's LDS scratch
+                        const int ni = lane & 15, gq = lane >> 4;
+                        scr[w][lane] = acc[m][j];
+                        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // store before the transposed reads
+                        const float *base = reinterpret_cast<const float *>(&scr[w][0]);
+#pragma unroll
+                        for (int r = 0; r < 4; r++)
+                            c[r] = base[((ni >> 2) * 16 + 4 * gq + r) * 4 + (ni & 3)] * s_rstd[m * 16 + 4 * gq + r];
+                        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // reads before the next tile's store
+                    }
+                    epi(mt, nt, c, lane, 0);
+                }
+            }
+    }
+}
+
+// Adds the KS partial sums of every output tile in a fixed order and runs the epilogue.
+template <class Epi>
+__global__ __launch_bounds__(512) void tile_epilogue_kernel(TileArgs g, Epi epi) {
+    __shared__ float s_rstd[16];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int mt = blockIdx.y, nt = blockIdx.x * 8 + w;
+    if (g.ssq) {
+        // 16 rows of this m-tile: two per wave
+        for (int r = w * 2; r < w * 2 + 2; r++) {
+            const float *p = g.ssq + (size_t)(mt * 16 + r) * g.n_ssq;
+            float q = 0.f;
+            for (int i = lane; i < g.n_ssq; i += 64) q += p[i];
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o);
+            if (lane == 0) s_rstd[r] = 1.0f / sqrtf(q * g.inv_d + g.eps);
+        }
+    } else if (threadIdx.x < 16) {
+        s_rstd[threadIdx.x] = 1.0f;
+    }
+    __syncthreads();
+    if (nt >= g.NT) return;
+    f32x4 c = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (!epi.transposed(nt)) {
+        for (int s = 0; s < g.KS; s++) {
+            size_t tile = ((size_t)s * g.MT_total + mt) * g.NT + nt;
+            c += *reinterpret_cast<const f32x4 *>(g.partial + tile * 256 + lane * 4);
+        }
+        c *= s_rstd[lane & 15];
+    } else {
+        const int ni = lane & 15, gq = lane >> 4;
+        for (int s = 0; s < g.KS; s++) {
+            size_t tile = ((size_t)s * g.MT_total + mt) * g.NT + nt;
+            const float *base = g.partial + tile * 256;
+#pragma unroll
+            for (int r = 0; r < 4; r++) c[r] += base[((ni >> 2) * 16 + 4 * gq + r) * 4 + (ni & 3)];
+        }
+#pragma unroll
+        for (int r = 0; r < 4; r++) c[r] *= s_rstd[4 * gq + r];
+    }
+    epi(mt, nt, c, lane, 0);
+}
+
+}  // namespace odb

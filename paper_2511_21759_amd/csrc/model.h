@@ -60,7 +60,7 @@ void launch_tensor_copy(const Model &m, int tensor_id, int layer, u16 *staging, 
 void launch_gain_copy(float *gain, u16 *staging, int n, bool to_model, hipStream_t s);
 void launch_fill_f32(float *p, float v, size_t n, hipStream_t s);
 void launch_rope_table(float *table, int n_pos, int dh, double base, hipStream_t s);
-void launch_cache_read(const Cache &c, int layer, int kv, int batch_index, int pos0, int n, u16 *out, hipStream_t s);
+void launch_cache_read(const Cache &c, int layer, int kv, int batch_index, int pos0, int n, float *out, hipStream_t s);
 
 // Fused RMSNorm.  NormIn: the GEMM input holds bf16(x * gain) and ssq[row][0..n_ssq) are partial
 // sums of x^2 over the row; output rows are scaled by 1/sqrt(sum/d + eps) (ssq == nullptr: off).
@@ -92,15 +92,19 @@ struct QkvOut {
     const float *rope;         // (cos,sin) table
     int tiles_per_unit, pos_off, H, dh, d;
 };
-void launch_gemm_qkv(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, QkvOut out, hipStream_t s);
-void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int ldh, NormOut no, hipStream_t s);
-void launch_gemm_swiglu(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, u16 *act, hipStream_t s);
-// stats[row][lm_stats_parts(N_tiles)][3]: one partial (max, sum exp, argmax) per row and (workgroup, n-slot)
-int lm_stats_parts(int n_tiles);
-void launch_gemm_lmstats(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, float *stats, hipStream_t s);
+// fp32 workspace for K-split partial sums (multi-draft step)
+struct Workspace { float *partial; size_t partial_bytes; };
+void launch_gemm_qkv(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, QkvOut out, Workspace ws, hipStream_t s);
+void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int ldh, NormOut no, Workspace ws,
+                       hipStream_t s);
+void launch_gemm_swiglu(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, u16 *act, Workspace ws, hipStream_t s);
+// stats[row][lm_stats_parts(N_tiles, M_tiles)][3]: one partial (max, sum exp, argmax) per row and (workgroup, n-slot)
+int lm_stats_parts(int n_tiles, int m_tiles);
+void launch_gemm_lmstats(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, float *stats, Workspace ws,
+                         hipStream_t s);
 // fp32 store of the valid rows (unit u, i < valid of rpu_pad) to a compact row-major [units*valid, ld]
 void launch_gemm_store(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, float *out, int units, int rpu_pad,
-                       int valid, int ld, hipStream_t s);
+                       int valid, int ld, Workspace ws, hipStream_t s);
 
 // ---- attn.hip ---------------------------------------------------------------
 struct AttnArgs {

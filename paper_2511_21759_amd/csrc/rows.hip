@@ -54,10 +54,10 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *h, const floa
             float4 b = *reinterpret_cast<const float4 *>(x + q * 8 + 4);
             float4 ga = *reinterpret_cast<const float4 *>(gain + q * 8);
             float4 gb = *reinterpret_cast<const float4 *>(gain + q * 8 + 4);
-            f.w[0] = pack2bf(a.x * rstd * ga.x, a.y * rstd * ga.y);
-            f.w[1] = pack2bf(a.z * rstd * ga.z, a.w * rstd * ga.w);
-            f.w[2] = pack2bf(b.x * rstd * gb.x, b.y * rstd * gb.y);
-            f.w[3] = pack2bf(b.z * rstd * gb.z, b.w * rstd * gb.w);
+            f.w[0] = pack2(a.x * rstd * ga.x, a.y * rstd * ga.y);
+            f.w[1] = pack2(a.z * rstd * ga.z, a.w * rstd * ga.w);
+            f.w[2] = pack2(b.x * rstd * gb.x, b.y * rstd * gb.y);
+            f.w[3] = pack2(b.z * rstd * gb.z, b.w * rstd * gb.w);
         }
         int kt = q >> 2, kg = q & 3;
         *reinterpret_cast<frag_t *>(xa + ((size_t)kt * dst_mt_total + mt) * kTileElems + (kg * 16 + r) * 8) = f;
@@ -72,7 +72,7 @@ void launch_rmsnorm(const float *h, const float *gain, float eps, int d, RowMap 
                                                           dst_mt_total, xa);
 }
 
-__global__ __launch_bounds__(256) void lm_finish_kernel(const float *stats, int n_part, int rows, int rpu, int rpu_pad,
+__global__ __launch_bounds__(1024) void lm_finish_kernel(const float *stats, int n_part, int rows, int rpu, int rpu_pad,
                                                         const int32_t *tokens, int mask_id, float tau, float *conf,
                                                         int32_t *argmax, uint8_t *unmask) {
     __shared__ float s_conf[256];
@@ -82,7 +82,7 @@ __global__ __launch_bounds__(256) void lm_finish_kernel(const float *stats, int 
 void launch_lm_finish(const float *stats, int n_part, int rows, int rpu, int rpu_pad, const int32_t *tokens,
                       int mask_id, float tau, float *conf, int32_t *argmax, uint8_t *unmask, hipStream_t s) {
     int units = (rows + rpu - 1) / rpu;
-    lm_finish_kernel<<<dim3(units), 256, 0, s>>>(stats, n_part, rows, rpu, rpu_pad, tokens, mask_id, tau, conf,
+    lm_finish_kernel<<<dim3(units), 1024, 0, s>>>(stats, n_part, rows, rpu, rpu_pad, tokens, mask_id, tau, conf,
                                                  argmax, unmask);
 }
 

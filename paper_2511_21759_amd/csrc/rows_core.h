@@ -40,7 +40,7 @@ __device__ __forceinline__ void embed_row(int r, const u16 *embed, const int32_t
                 frag_t f;
 #pragma unroll
                 for (int j = 0; j < 4; j++)
-                    f.w[j] = pack2bf(x[half * 8 + 2 * j] * gn[half * 8 + 2 * j],
+                    f.w[j] = pack2(x[half * 8 + 2 * j] * gn[half * 8 + 2 * j],
                                      x[half * 8 + 2 * j + 1] * gn[half * 8 + 2 * j + 1]);
                 const int chunk = (nt & 1) * 2 + half;
                 *reinterpret_cast<frag_t *>(no.hb + ((size_t)(nt >> 1) * mt_total + (r >> 4)) * kTileElems +
@@ -78,9 +78,16 @@ __device__ __forceinline__ void lm_finish_wg(int u, const float *stats, int n_pa
         if (row >= rows) break;
         const float *p = stats + ((size_t)u * rpu_pad + i) * n_part * 3;
         Stat acc = {-INFINITY, 0.f, 0x7fffffff};
-        for (int q = lane; q < n_part; q += 64) {
-            Stat t = {p[q * 3], p[q * 3 + 1], __float_as_int(p[q * 3 + 2])};
-            acc = merge(acc, t);
+        for (int q0 = 0; q0 < n_part; q0 += 64 * 8) {            // eight independent partials per lane and pass
+            Stat t[8];
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                int q = q0 + lane + 64 * j;
+                if (q < n_part) t[j] = Stat{p[q * 3], p[q * 3 + 1], __float_as_int(p[q * 3 + 2])};
+                else t[j] = Stat{-INFINITY, 0.f, 0x7fffffff};
+            }
+#pragma unroll
+            for (int j = 0; j < 8; j++) acc = merge(acc, t[j]);
         }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) {

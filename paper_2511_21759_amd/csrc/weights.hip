@@ -67,6 +67,10 @@ __device__ inline u16 normal_bf16(uint64_t key, uint64_t i, double std) {
     return (u16)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
 }
 
+// weights enter the MFMA as binary16: exact for bfloat16 values of magnitude 2^-16 .. 65504
+__device__ inline u16 bf_to_h(u16 b) { return f2h(bf2f(b)); }
+__device__ inline u16 h_to_bf(u16 h) { return f2bf(h2f(h)); }
+
 struct GenKeys { uint64_t key[ODB_T_COUNT]; };
 
 __global__ void gen_tiled_kernel(u16 *dst, size_t n_chunks, int pk, int K, int d, int dh, GenKeys keys, double std) {
@@ -85,9 +89,10 @@ __global__ void gen_tiled_kernel(u16 *dst, size_t n_chunks, int pk, int K, int d
     frag_t f;
 #pragma unroll
     for (int j = 0; j < 4; j++) {
-        uint32_t lo = normal_bf16(key, i0 + 2 * j, std);
-        uint32_t hi = normal_bf16(key, i0 + 2 * j + 1, std);
-        f.w[j] = lo | (hi << 16);
+        u16 lo = normal_bf16(key, i0 + 2 * j, std);
+        u16 hi = normal_bf16(key, i0 + 2 * j + 1, std);
+        if (pk != PK_EMBED) { lo = bf_to_h(lo); hi = bf_to_h(hi); }
+        f.w[j] = (uint32_t)lo | ((uint32_t)hi << 16);
     }
     *reinterpret_cast<frag_t *>(dst + c * 8) = f;
 }
@@ -138,7 +143,17 @@ __global__ void tensor_copy_kernel(u16 *phys, u16 *logical, size_t n_chunks, int
     if (tid != want_tid) return;
     frag_t *p = reinterpret_cast<frag_t *>(phys + c * 8);
     frag_t *q = reinterpret_cast<frag_t *>(logical + (size_t)lrow * K + k);
-    if (to_model) *p = *q; else *q = *p;
+    frag_t v = to_model ? *q : *p;
+    if (pk != PK_EMBED) {
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            u16 lo = (u16)(v.w[j] & 0xffff), hi = (u16)(v.w[j] >> 16);
+            lo = to_model ? bf_to_h(lo) : h_to_bf(lo);
+            hi = to_model ? bf_to_h(hi) : h_to_bf(hi);
+            v.w[j] = (uint32_t)lo | ((uint32_t)hi << 16);
+        }
+    }
+    if (to_model) *p = v; else *q = v;
 }
 
 static int tensor_kind(int tid) {
@@ -189,22 +204,22 @@ void launch_rope_table(float *table, int n_pos, int dh, double base, hipStream_t
 
 // ---- cache read-back ---------------------------------------------------------------
 __global__ void cache_read_kernel(const u16 *kc, const u16 *vc, int kv, int H, int dh, int lmax32, int pos0, int n,
-                                  u16 *out) {
+                                  float *out) {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n * H * dh) return;
     int ch = i % dh, hd = (i / dh) % H, pos = pos0 + i / (dh * H);
     if (kv == 0) {
         int p = ch < dh / 2 ? 2 * ch : 2 * (ch - dh / 2) + 1;       // physical channel
         size_t tile = ((size_t)hd * (lmax32 / 16) + pos / 16) * (dh / 32) + p / 32;
-        out[i] = kc[tile * kTileElems + tile_elem(pos & 15, p & 31)];
+        out[i] = h2f(kc[tile * kTileElems + tile_elem(pos & 15, p & 31)]);
     } else {
         int pl = pos & 31, t = pl >> 4, g = (pl & 15) >> 2, r = pl & 3;
         size_t tile = ((size_t)hd * (lmax32 / 32) + pos / 32) * (dh / 16) + ch / 16;
-        out[i] = vc[tile * kTileElems + tile_elem(ch & 15, g * 8 + 4 * t + r)];
+        out[i] = h2f(vc[tile * kTileElems + tile_elem(ch & 15, g * 8 + 4 * t + r)]);
     }
 }
 
-void launch_cache_read(const Cache &c, int layer, int kv, int batch_index, int pos0, int n, u16 *out, hipStream_t s) {
+void launch_cache_read(const Cache &c, int layer, int kv, int batch_index, int pos0, int n, float *out, hipStream_t s) {
     const odb_config &cfg = c.m->cfg;
     size_t seq_elems = (size_t)cfg.n_heads * c.lmax32 * cfg.head_dim;
     const u16 *kc = c.k + (size_t)layer * c.layer_elems + (size_t)batch_index * seq_elems;
