@@ -26,6 +26,10 @@ static void launch_stream(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, E
     else gemm_stream_kernel<2, NG, 1, Epi><<<grid, 64 * WK, 0, s>>>(g, e);
 }
 
+// workgroup shapes of the tile kernel: (waves, n-tiles per wave, ring depth)
+struct TileCfg { int nw, ngw, max_wgs; };
+static TileCfg tile_cfg(int m_tiles) { return m_tiles > 8 ? TileCfg{8, 2, 256} : TileCfg{8, 1, 256}; }
+
 template <class Epi>
 static void launch_tile(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi e, Workspace ws, bool may_split,
                         hipStream_t s) {
@@ -34,17 +38,20 @@ static void launch_tile(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi
     g.ssq = ni.ssq; g.n_ssq = ni.n_ssq; g.eps = ni.eps; g.inv_d = 1.0f / (float)(sh.K_tiles * 32);
     g.partial = ws.partial;
     const int m_blocks = (sh.M_tiles + 7) / 8;
-    const bool big = sh.M_tiles > 8;                 // compute-bound shapes take two n-tiles per wave
-    const int ngw = big ? 2 : 1;
-    g.n_blocks = (sh.N_tiles + 8 * ngw - 1) / (8 * ngw);
+    const TileCfg c = tile_cfg(sh.M_tiles);
+    const int per_wg = c.nw * c.ngw;
+    g.n_blocks = (sh.N_tiles + per_wg - 1) / per_wg;
     int ks = 1;
-    while (may_split && g.n_blocks * m_blocks * ks * 2 <= kStreamWGs && sh.K_tiles % (ks * 2) == 0 &&
+    while (may_split && g.n_blocks * m_blocks * ks * 2 <= c.max_wgs && sh.K_tiles % (ks * 2) == 0 &&
            sh.K_tiles / (ks * 2) >= 8 && (size_t)(ks * 2) * sh.M_tiles * sh.N_tiles * 1024 <= ws.partial_bytes)
         ks *= 2;
     g.KS = ks;
     dim3 grid(g.n_blocks * ks, m_blocks);
-    if (big) gemm_tile_kernel<2, 4, Epi><<<grid, 512, 0, s>>>(g, e);
-    else gemm_tile_kernel<1, 8, Epi><<<grid, 512, 0, s>>>(g, e);
+    // (8 waves x 1 n-tile, ring of 8) for the multi-draft step, (8 x 2, ring of 4) for compute-bound shapes:
+    // the best of the shapes tried on MI355X (4-wave workgroups, 4 n-tiles per wave and 2 or 4 k-tiles
+    // per barrier were all slower - occupancy beats wider tiles here)
+    if (c.ngw == 1) gemm_tile_kernel<8, 1, 1, 8, Epi><<<grid, 512, 0, s>>>(g, e);
+    else gemm_tile_kernel<8, 2, 1, 4, Epi><<<grid, 512, 0, s>>>(g, e);
     if (ks > 1) {
         if constexpr (!is_row_stats<Epi>::value)
             tile_epilogue_kernel<Epi><<<dim3((sh.N_tiles + 7) / 8, sh.M_tiles), 512, 0, s>>>(g, e);
@@ -76,8 +83,8 @@ int lm_stats_parts(int n_tiles, int m_tiles) {
         const int groups = (n_tiles + kLmNG - 1) / kLmNG;
         return (groups < kStreamWGs ? groups : kStreamWGs) * kLmNG;
     }
-    const int ngw = m_tiles > 8 ? 2 : 1;
-    return (n_tiles + 8 * ngw - 1) / (8 * ngw);
+    const TileCfg c = tile_cfg(m_tiles);
+    return (n_tiles + c.nw * c.ngw - 1) / (c.nw * c.ngw);
 }
 
 void launch_gemm_lmstats(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, float *stats, Workspace ws,

@@ -33,7 +33,6 @@ struct TileLMStats {
 template <class Epi> struct is_row_stats { static constexpr bool value = false; };
 template <> struct is_row_stats<TileLMStats> { static constexpr bool value = true; };
 
-constexpr int kTileSmemBytes = 2 * 8 * 1024 + 8 * 1024 + 128 * 4;     // A slots, per-wave scratch, row scales
 
 __device__ __forceinline__ void merge_stat(float &m, float &s, int &a, float om, float os, int oa) {
     float nm = fmaxf(m, om);
@@ -42,19 +41,26 @@ __device__ __forceinline__ void merge_stat(float &m, float &s, int &a, float om,
     m = nm;
 }
 
-template <int NGW, int PF, class Epi>
-__global__ __launch_bounds__(512) void gemm_tile_kernel(TileArgs g, Epi epi) {
-    __shared__ __attribute__((aligned(16))) char smem[kTileSmemBytes];
-    frag_t (*a_lds)[8][64] = reinterpret_cast<frag_t (*)[8][64]>(smem);                 // [2][8 m-tiles][64 lanes]
-    f32x4 (*scr)[64] = reinterpret_cast<f32x4 (*)[64]>(smem + 16 * 1024);                // [8 waves][64]
-    float *s_rstd = reinterpret_cast<float *>(smem + 24 * 1024);
+// NW waves per workgroup, each NGW n-tiles wide: the workgroup covers NW*NGW n-tiles.  A stage of the
+// pipeline is a chunk of KC k-tiles (one barrier per chunk); PF chunks are in flight.
+constexpr int tile_smem_bytes(int kc) { return 2 * kc * 8 * 1024 + 8 * 1024 + 128 * 4; }
+
+template <int NW, int NGW, int KC, int PF, class Epi>
+__global__ __launch_bounds__(64 * NW) void gemm_tile_kernel(TileArgs g, Epi epi) {
+    constexpr int AW = 8 / NW;                 // A tiles (per k-tile) of the slab each wave fetches
+    static_assert(NW == 4 || NW == 8, "waves per workgroup");
+    __shared__ __attribute__((aligned(16))) char smem[tile_smem_bytes(KC)];
+    frag_t (*a_lds)[KC][8][64] = reinterpret_cast<frag_t (*)[KC][8][64]>(smem);         // [2][KC][8 m-tiles][64 lanes]
+    f32x4 (*scr)[64] = reinterpret_cast<f32x4 (*)[64]>(smem + 2 * KC * 8 * 1024);        // [8 waves][64]
+    float *s_rstd = reinterpret_cast<float *>(smem + 2 * KC * 8 * 1024 + 8 * 1024);
 
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int nb = blockIdx.x % g.n_blocks, ks = blockIdx.x / g.n_blocks;
     const int mt0 = blockIdx.y * 8;
     const int k_lo = (int)(((long)ks * g.KT) / g.KS), k_hi = (int)(((long)(ks + 1) * g.KT) / g.KS);
-    const int nk = k_hi - k_lo;
-    const int nt0 = (nb * 8 + w) * NGW;
+    const int nk = k_hi - k_lo;                 // k-tiles of this slice
+    const int nc = (nk + KC - 1) / KC;          // chunks
+    const int nt0 = (nb * NW + w) * NGW;
 
     const u16 *wp[NGW];
 #pragma unroll
@@ -62,14 +68,18 @@ __global__ __launch_bounds__(512) void gemm_tile_kernel(TileArgs g, Epi epi) {
         int nt = nt0 + j < g.NT ? nt0 + j : g.NT - 1;
         wp[j] = g.W + ((size_t)nt * g.KT + k_lo) * kTileElems + lane * 8;
     }
-    const int mt_mine = mt0 + w < g.MT_total ? mt0 + w : g.MT_total - 1;           // the A tile this wave fetches
-    const u16 *ap = g.A + ((size_t)k_lo * g.MT_total + mt_mine) * kTileElems + lane * 8;
+    const u16 *ap[AW];                                                             // the A tiles this wave fetches
+#pragma unroll
+    for (int i = 0; i < AW; i++) {
+        int mt = mt0 + w * AW + i < g.MT_total ? mt0 + w * AW + i : g.MT_total - 1;
+        ap[i] = g.A + ((size_t)k_lo * g.MT_total + mt) * kTileElems + lane * 8;
+    }
     const size_t a_step = (size_t)g.MT_total * kTileElems;
 
-    // row scales of the fused RMSNorm: 16 rows per wave
+    // row scales of the fused RMSNorm: 128 / NW rows per wave
     if (g.ssq) {
-        for (int r = 0; r < 16; r++) {
-            int row = (mt0 + w) * 16 + r;
+        for (int r = 0; r < 16 * AW; r++) {
+            int row = (mt0 + w * AW) * 16 + r;
             row = row < g.MT_total * 16 ? row : g.MT_total * 16 - 1;
             const float *p = g.ssq + (size_t)row * g.n_ssq;
             float q = 0.f;
@@ -84,10 +94,10 @@ __global__ __launch_bounds__(512) void gemm_tile_kernel(TileArgs g, Epi epi) {
             }
 #pragma unroll
             for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o);
-            if (lane == 0) s_rstd[w * 16 + r] = 1.0f / sqrtf(q * g.inv_d + g.eps);
+            if (lane == 0) s_rstd[w * 16 * AW + r] = 1.0f / sqrtf(q * g.inv_d + g.eps);
         }
-    } else if (lane < 16) {
-        s_rstd[w * 16 + lane] = 1.0f;
+    } else if (lane < 16 * AW) {
+        s_rstd[w * 16 * AW + lane] = 1.0f;
     }
 
     f32x4 acc[8][NGW];
@@ -96,35 +106,46 @@ __global__ __launch_bounds__(512) void gemm_tile_kernel(TileArgs g, Epi epi) {
 #pragma unroll
         for (int j = 0; j < NGW; j++) acc[m][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    frag_t wr[PF][NGW], ar[PF];
+    // k-tiles past the end of the slice are clamped to its last tile and contribute nothing (see below)
+    frag_t wr[PF][KC][NGW], ar[PF][KC][AW];
+    auto load_chunk = [&](int slot, int c) __attribute__((always_inline)) {
+#pragma unroll
+        for (int kk = 0; kk < KC; kk++) {
+            int k = c * KC + kk;
+            k = k < nk ? k : nk - 1;
+#pragma unroll
+            for (int i = 0; i < AW; i++) ar[slot][kk][i] = ld_frag(ap[i] + k * a_step);
+#pragma unroll
+            for (int j = 0; j < NGW; j++) wr[slot][kk][j] = ld_frag(wp[j] + (size_t)k * kTileElems);
+        }
+    };
 #pragma unroll
     for (int s = 0; s < PF; s++)
-        if (s < nk) {
-            ar[s] = ld_frag(ap + s * a_step);
-#pragma unroll
-            for (int j = 0; j < NGW; j++) wr[s][j] = ld_frag(wp[j] + (size_t)s * kTileElems);
-        }
+        if (s < nc) load_chunk(s, s);
 
-    for (int kb = 0; kb < nk; kb += PF) {
+    for (int cb = 0; cb < nc; cb += PF) {
 #pragma unroll
         for (int s = 0; s < PF; s++) {
-            const int k = kb + s;
-            if (k < nk) {
-                a_lds[k & 1][w][lane] = ar[s];
+            const int c = cb + s;
+            if (c < nc) {
+#pragma unroll
+                for (int kk = 0; kk < KC; kk++)
+#pragma unroll
+                    for (int i = 0; i < AW; i++) a_lds[c & 1][kk][w * AW + i][lane] = ar[s][kk][i];
                 __syncthreads();
-                frag_t a[8];
 #pragma unroll
-                for (int m = 0; m < 8; m++) a[m] = a_lds[k & 1][m][lane];
+                for (int kk = 0; kk < KC; kk++) {
+                    if (c * KC + kk < nk) {
+                        frag_t a[8];
 #pragma unroll
-                for (int m = 0; m < 8; m++)
+                        for (int m = 0; m < 8; m++) a[m] = a_lds[c & 1][kk][m][lane];
 #pragma unroll
-                    for (int j = 0; j < NGW; j++) acc[m][j] = mfma16(wr[s][j], a[m], acc[m][j]);
-                const int kn = k + PF;
-                if (kn < nk) {
-                    ar[s] = ld_frag(ap + kn * a_step);
+                        for (int m = 0; m < 8; m++)
 #pragma unroll
-                    for (int j = 0; j < NGW; j++) wr[s][j] = ld_frag(wp[j] + (size_t)kn * kTileElems);
+                            for (int j = 0; j < NGW; j++) acc[m][j] = mfma16(wr[s][kk][j], a[m], acc[m][j]);
+                    }
                 }
+                if (c + PF < nc) load_chunk(s, c + PF);
             }
         }
     }
@@ -148,9 +169,9 @@ __global__ __launch_bounds__(512) void gemm_tile_kernel(TileArgs g, Epi epi) {
     if constexpr (is_row_stats<Epi>::value) {
         // softmax statistics per row over this workgroup's n-tiles: lane-local, across the four lane
         // groups, across the wave's NGW tiles, then across the eight waves through LDS
-        float *st_m = reinterpret_cast<float *>(smem);               // the A slots are free now: [8 waves][128 rows]
-        float *st_s = st_m + 8 * 128;
-        int *st_a = reinterpret_cast<int *>(st_s + 8 * 128);
+        float *st_m = reinterpret_cast<float *>(smem);               // the A slots are free now: [NW waves][128 rows]
+        float *st_s = st_m + NW * 128;
+        int *st_a = reinterpret_cast<int *>(st_s + NW * 128);
         const int mi = lane & 15, gq = lane >> 4;
 #pragma unroll
         for (int m = 0; m < 8; m++) {
@@ -189,7 +210,7 @@ __global__ __launch_bounds__(512) void gemm_tile_kernel(TileArgs g, Epi epi) {
             float rm = st_m[r], rs = st_s[r];
             int ra = st_a[r];
 #pragma unroll
-            for (int x = 1; x < 8; x++) merge_stat(rm, rs, ra, st_m[x * 128 + r], st_s[x * 128 + r], st_a[x * 128 + r]);
+            for (int x = 1; x < NW; x++) merge_stat(rm, rs, ra, st_m[x * 128 + r], st_s[x * 128 + r], st_a[x * 128 + r]);
             if (row < g.MT_total * 16) {
                 float *p = epi.stats + ((size_t)row * epi.n_part + nb) * 3;
                 p[0] = rm;
