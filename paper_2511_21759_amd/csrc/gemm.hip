@@ -3,27 +3,27 @@
 
 namespace odb {
 
-template <int MT, int NG, int PF, class Epi>
-__global__ __launch_bounds__(64 * WK) void gemm_stream_kernel(GemmArgs g, Epi epi) {
+template <int MT, int NG, int PF, class Epi, int WKT = WK, bool IL = false>
+__global__ __launch_bounds__(64 * WKT) void gemm_stream_kernel(GemmArgs g, Epi epi) {
     __shared__ __attribute__((aligned(16))) char smem[kGemmSmemBytes];
     frag_t wb[PF][NG];
-    gemm_wg<MT, NG, PF, false>(g, epi, blockIdx.x, gridDim.x, blockIdx.y * MT, wb, smem);
+    gemm_wg<MT, NG, PF, false, Epi, WKT, IL>(g, epi, blockIdx.x, gridDim.x, blockIdx.y * MT, wb, smem);
 }
 
 constexpr int kStreamWGs = 256;      // one workgroup per compute unit
 
 // Up to 32 rows: the persistent streaming kernel with NG n-tiles per group and a PF-deep ring.
 // More rows: the tile kernel (gemm_tile.h), K-split over workgroups when there are too few n-blocks.
-template <int NG, int PF, class Epi>
+template <int MT, int NG, int PF, int WKT, bool IL, class Epi>
 static void launch_stream(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi e, hipStream_t s) {
     GemmArgs g;
     g.A = a; g.W = w; g.KT = sh.K_tiles; g.MT_total = sh.M_tiles; g.NT = sh.N_tiles;
     g.ssq = ni.ssq; g.n_ssq = ni.n_ssq; g.eps = ni.eps; g.inv_d = 1.0f / (float)(sh.K_tiles * 32);
-    const int kw = sh.K_tiles / WK;                 // K_tiles is a multiple of 8 (checked at model creation)
+    const int kw = sh.K_tiles / WKT;                // K_tiles is a multiple of 8 (checked at model creation)
     const int groups = (sh.N_tiles + NG - 1) / NG;
     dim3 grid(groups < kStreamWGs ? groups : kStreamWGs, 1);
-    if (kw % PF == 0) gemm_stream_kernel<2, NG, PF, Epi><<<grid, 64 * WK, 0, s>>>(g, e);
-    else gemm_stream_kernel<2, NG, 1, Epi><<<grid, 64 * WK, 0, s>>>(g, e);
+    if (kw % PF == 0) gemm_stream_kernel<MT, NG, PF, Epi, WKT, IL><<<grid, 64 * WKT, 0, s>>>(g, e);
+    else gemm_stream_kernel<MT, NG, 1, Epi, WKT, IL><<<grid, 64 * WKT, 0, s>>>(g, e);
 }
 
 // workgroup shapes of the tile kernel: (waves, n-tiles per wave, ring depth)
@@ -60,18 +60,21 @@ static void launch_tile(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi
 
 void launch_gemm_qkv(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, QkvOut out, Workspace ws, hipStream_t s) {
     EpiQKV e{out, sh.M_tiles};
-    if (sh.M_tiles <= 2) launch_stream<3, 8>(xa, w, sh, ni, e, s);
+    if (sh.M_tiles <= 2) launch_stream<2, 3, 8, 8, true>(xa, w, sh, ni, e, s);
+    else if (sh.M_tiles <= 8) launch_stream<8, 3, 2, 8, false>(xa, w, sh, ni, e, s);
     else launch_tile(xa, w, sh, ni, e, ws, true, s);
 }
 void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int ldh, NormOut no, Workspace ws,
                        hipStream_t s) {
     EpiResid e{h, ldh, no, sh.M_tiles};
-    if (sh.M_tiles <= 2) launch_stream<1, 8>(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
+    if (sh.M_tiles <= 2) launch_stream<2, 1, 8, 8, false>(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
+    else if (sh.M_tiles <= 8 && sh.K_tiles <= 128) launch_stream<8, 1, 2, 8, false>(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
     else launch_tile(a, w, sh, NormIn{nullptr, 0, 0.f}, e, ws, true, s);
 }
 void launch_gemm_swiglu(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, u16 *act, Workspace ws, hipStream_t s) {
     EpiSwiGLU e{act, sh.M_tiles};
-    if (sh.M_tiles <= 2) launch_stream<6, 4>(xa, w, sh, ni, e, s);
+    if (sh.M_tiles <= 2) launch_stream<2, 6, 4, 8, true>(xa, w, sh, ni, e, s);
+    else if (sh.M_tiles <= 8) launch_stream<8, 6, 2, 4, true>(xa, w, sh, ni, e, s);
     else launch_tile(xa, w, sh, ni, e, ws, true, s);
 }
 
@@ -79,7 +82,7 @@ constexpr int kLmNG = 6;      // n-tiles per group of the LM head at up to 32 ro
 
 // partials per row that launch_gemm_lmstats writes
 int lm_stats_parts(int n_tiles, int m_tiles) {
-    if (m_tiles <= 2) {
+    if (m_tiles <= 8) {
         const int groups = (n_tiles + kLmNG - 1) / kLmNG;
         return (groups < kStreamWGs ? groups : kStreamWGs) * kLmNG;
     }
@@ -90,13 +93,15 @@ int lm_stats_parts(int n_tiles, int m_tiles) {
 void launch_gemm_lmstats(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, float *stats, Workspace ws,
                          hipStream_t s) {
     const int parts = lm_stats_parts(sh.N_tiles, sh.M_tiles);
-    if (sh.M_tiles <= 2) launch_stream<kLmNG, 4>(xa, w, sh, ni, EpiLMStats<2>(stats, parts), s);
+    if (sh.M_tiles <= 2) launch_stream<2, kLmNG, 4, 8, true>(xa, w, sh, ni, EpiLMStats<2>(stats, parts), s);
+    else if (sh.M_tiles <= 8) launch_stream<8, kLmNG, 2, 4, true>(xa, w, sh, ni, EpiLMStats<16>(stats, parts), s);
     else launch_tile(xa, w, sh, ni, TileLMStats{stats, parts}, ws, false, s);
 }
 void launch_gemm_store(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, float *out, int units, int rpu_pad,
                        int valid, int ld, Workspace ws, hipStream_t s) {
     EpiStore e{out, units, rpu_pad, valid, ld};
-    if (sh.M_tiles <= 2) launch_stream<3, 8>(xa, w, sh, ni, e, s);
+    if (sh.M_tiles <= 2) launch_stream<2, 3, 8, 8, true>(xa, w, sh, ni, e, s);
+    else if (sh.M_tiles <= 8) launch_stream<8, 3, 2, 8, false>(xa, w, sh, ni, e, s);
     else launch_tile(xa, w, sh, ni, e, ws, false, s);
 }
 

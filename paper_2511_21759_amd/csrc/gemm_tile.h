@@ -76,25 +76,34 @@ __global__ __launch_bounds__(64 * NW) void gemm_tile_kernel(TileArgs g, Epi epi)
     }
     const size_t a_step = (size_t)g.MT_total * kTileElems;
 
-    // row scales of the fused RMSNorm: 128 / NW rows per wave
+    // row scales of the fused RMSNorm: 128 / NW rows per wave; a row's partial sums (up to 256) are one
+    // 16-byte load per lane, and the loads of 16 rows are issued back to back
     if (g.ssq) {
-        for (int r = 0; r < 16 * AW; r++) {
-            int row = (mt0 + w * AW) * 16 + r;
-            row = row < g.MT_total * 16 ? row : g.MT_total * 16 - 1;
-            const float *p = g.ssq + (size_t)row * g.n_ssq;
-            float q = 0.f;
-            for (int i0 = 0; i0 < g.n_ssq; i0 += 256) {
-                float v[4];
+        const int si = 4 * lane;
 #pragma unroll
-                for (int u = 0; u < 4; u++) {
-                    int i = i0 + lane + 64 * u;
-                    v[u] = i < g.n_ssq ? p[i] : 0.f;
+        for (int r0 = 0; r0 < 16 * AW; r0 += 16) {
+            f32x4 sv[16];
+            float q[16];
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+                int row = (mt0 + w * AW) * 16 + r0 + r;
+                row = row < g.MT_total * 16 ? row : g.MT_total * 16 - 1;
+                const float *p = g.ssq + (size_t)row * g.n_ssq;
+                q[r] = 0.f;
+                for (int i0 = 256; i0 < g.n_ssq; i0 += 256) {       // rows wider than 4096 only
+                    const int i = i0 + si, ic = i < g.n_ssq - 4 ? i : g.n_ssq - 4;
+                    f32x4 v = *reinterpret_cast<const f32x4 *>(p + ic);
+                    q[r] += i < g.n_ssq ? (v[0] + v[1]) + (v[2] + v[3]) : 0.f;
                 }
-                q += (v[0] + v[1]) + (v[2] + v[3]);
+                sv[r] = *reinterpret_cast<const f32x4 *>(p + (si < g.n_ssq - 4 ? si : g.n_ssq - 4));
             }
 #pragma unroll
-            for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o);
-            if (lane == 0) s_rstd[w * 16 * AW + r] = 1.0f / sqrtf(q * g.inv_d + g.eps);
+            for (int r = 0; r < 16; r++) {
+                float t = q[r] + (si < g.n_ssq ? (sv[r][0] + sv[r][1]) + (sv[r][2] + sv[r][3]) : 0.f);
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) t += __shfl_xor(t, o);
+                if (lane == 0) s_rstd[w * 16 * AW + r0 + r] = 1.0f / sqrtf(t * g.inv_d + g.eps);
+            }
         }
     } else if (lane < 16 * AW) {
         s_rstd[w * 16 * AW + lane] = 1.0f;
@@ -256,7 +265,11 @@ __global__ __launch_bounds__(512) void tile_epilogue_kernel(TileArgs g, Epi epi)
         for (int r = w * 2; r < w * 2 + 2; r++) {
             const float *p = g.ssq + (size_t)(mt * 16 + r) * g.n_ssq;
             float q = 0.f;
-            for (int i = lane; i < g.n_ssq; i += 64) q += p[i];
+            for (int i0 = 0; i0 < g.n_ssq; i0 += 256) {
+                const int i = i0 + 4 * lane, ic = i < g.n_ssq - 4 ? i : g.n_ssq - 4;
+                f32x4 v = *reinterpret_cast<const f32x4 *>(p + ic);
+                q += i < g.n_ssq ? (v[0] + v[1]) + (v[2] + v[3]) : 0.f;
+            }
 #pragma unroll
             for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o);
             if (lane == 0) s_rstd[r] = 1.0f / sqrtf(q * g.inv_d + g.eps);

@@ -86,7 +86,7 @@ __global__ __launch_bounds__(64 * WK) void step_kernel(StepArgs a) {
     GemmArgs gd{a.act, a.wd, F / 32, mt, d / 16, nullptr, 0, 0.f, 0.f};
 
     frag_t w3[PF][3], w1[PF][1];
-    gemm_prefetch_w<3, PF>(gq, wg0, nwg, w3);
+    gemm_prefetch_w<3, PF, WK, true>(gq, wg0, nwg, w3);
 
     // embedding gather (+ input of the first RMSNorm)
     for (int r = wg0; r < mt * 16; r += nwg)
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(64 * WK) void step_kernel(StepArgs a) {
         int wg = opaque(wg0);
         // QKV projection, RoPE, scatter into the attention layouts
         QkvOut qo = a.qo;
-        gemm_wg<MT, 3, PF, true>(gq, EpiQKV{qo, mt}, wg, nwg, 0, w3, smem);
+        gemm_wg<MT, 3, PF, true, EpiQKV, WK, true>(gq, EpiQKV{qo, mt}, wg, nwg, 0, w3, smem);
         grid_sync(a.barrier, target, wg0, nwg, a.status, tr);
         wg = opaque(wg0);
 
@@ -113,12 +113,12 @@ __global__ __launch_bounds__(64 * WK) void step_kernel(StepArgs a) {
         // output projection + residual (+ input of the second RMSNorm)
         gemm_wg<MT, 1, PF, true>(go, EpiResid{a.h, d, NormOut{a.hb, a.ssq, a.g2 + (size_t)l * d, n_ssq}, mt}, wg, nwg, 0, w1,
                                  smem);
-        gemm_prefetch_w<3, PF>(gg, wg, nwg, w3);
+        gemm_prefetch_w<3, PF, WK, true>(gg, wg, nwg, w3);
         grid_sync(a.barrier, target, wg0, nwg, a.status, tr);
         wg = opaque(wg0);
 
         // gate/up projection + SiLU(gate)*up
-        gemm_wg<MT, 3, PF, true>(gg, EpiSwiGLU{a.act, mt}, wg, nwg, 0, w3, smem);
+        gemm_wg<MT, 3, PF, true, EpiSwiGLU, WK, true>(gg, EpiSwiGLU{a.act, mt}, wg, nwg, 0, w3, smem);
         gemm_prefetch_w<1, PF>(gd, wg, nwg, w1);
         grid_sync(a.barrier, target, wg0, nwg, a.status, tr);
         wg = opaque(wg0);
@@ -130,15 +130,15 @@ __global__ __launch_bounds__(64 * WK) void step_kernel(StepArgs a) {
         gq.W += a.qkv_stride; go.W += a.o_stride; gg.W += a.gu_stride; gd.W += a.d_stride;
         if (last) {
             gq = GemmArgs{a.hb, a.wlm, d / 32, mt, a.V / 16, a.ssq, n_ssq, a.eps, 1.0f / (float)d};
-            gemm_prefetch_w<3, PF>(gq, wg < lm_wgs ? wg : lm_wgs - 1, lm_wgs, w3);
+            gemm_prefetch_w<3, PF, WK, true>(gq, wg < lm_wgs ? wg : lm_wgs - 1, lm_wgs, w3);
         } else {
-            gemm_prefetch_w<3, PF>(gq, wg, nwg, w3);
+            gemm_prefetch_w<3, PF, WK, true>(gq, wg, nwg, w3);
         }
         grid_sync(a.barrier, target, wg0, nwg, a.status, tr);
     }
 
     // LM head: softmax statistics per (row, 16 vocabulary columns), then the per-draft finish
-    if (wg0 < lm_wgs) gemm_wg<MT, 3, PF, true>(gq, EpiLMStats<MT / 2>(a.stats, lm_wgs * 3), wg0, lm_wgs, 0, w3, smem);
+    if (wg0 < lm_wgs) gemm_wg<MT, 3, PF, true, EpiLMStats<MT / 2>, WK, true>(gq, EpiLMStats<MT / 2>(a.stats, lm_wgs * 3), wg0, lm_wgs, 0, w3, smem);
     grid_sync(a.barrier, target, wg0, nwg, a.status, tr);
     for (int u = wg0; u < a.rm.units; u += nwg) {
         __syncthreads();
