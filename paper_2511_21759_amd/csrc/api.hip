@@ -147,8 +147,8 @@ struct ProfScope {
 //
 // fused_norm (the step): every RMSNorm is folded into its neighbours - the
 // kernel that produces the residual stream h also writes bf16(h * gain) and
-// per-tile sums of squares, the consuming GEMM turns them into row scales.
-// Otherwise (the prefill) a separate RMSNorm kernel writes the GEMM input.
+// per-tile sums of squares, the consuming GEMM turns them into row scales (both calls run this way).
+// Otherwise a separate RMSNorm kernel writes the GEMM input.
 struct StackIO {
     RowMap rm;
     int pos_off;
@@ -289,8 +289,10 @@ int prefill_impl(odb_model *mh, odb_cache *ch, const int32_t *tokens, int L, int
     if (rc) return rc;
     RowMap rm{c.batch, lp, L};
     c.length = L;
-    launch_embed(m, tokens, rm, (float *)((char *)m.scratch + pl.h), NormOut{nullptr, nullptr, nullptr, 0}, s);
-    StackIO io{rm, 0, true, 0, 0, 0, 1, false};
+    char *base = (char *)m.scratch;
+    launch_embed(m, tokens, rm, (float *)(base + pl.h),
+                 NormOut{(u16 *)(base + pl.xa), (float *)(base + pl.ssq), m.g1, m.cfg.d_model / 16}, s);
+    StackIO io{rm, 0, true, 0, 0, 0, 1, true};
     rc = run_stack(m, c, pl, io, s);
     if (rc) return rc;
     return run_head(m, pl, rm, resp_off, false, nullptr, 64, 0.f, conf, argmax, nullptr, logits, s);

@@ -1,5 +1,5 @@
 // Stand-alone launches of the weight-streaming GEMM (see gemm_core.h).
-#include "gemm_tile.h"
+#include "gemm_big.h"
 
 namespace odb {
 
@@ -58,10 +58,41 @@ static void launch_tile(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi
     }
 }
 
+// 256 rows and more: 256 x 256 blocks through LDS (gemm_big.h)
+template <class Epi>
+static void launch_big(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi e, hipStream_t s) {
+    BigArgs g;
+    g.A = a; g.W = w; g.KT = sh.K_tiles; g.MT_total = sh.M_tiles; g.NT = sh.N_tiles;
+    g.ssq = ni.ssq; g.n_ssq = ni.n_ssq; g.eps = ni.eps; g.inv_d = 1.0f / (float)(sh.K_tiles * 32);
+    g.m_blocks = (sh.M_tiles + 15) / 16;
+    g.n_blocks = (sh.N_tiles + 15) / 16;
+    static bool attr_set = false;           // once per instantiation: the ring needs more than the default 64 KiB
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_big_kernel<Epi>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, kBigSmemBytes);
+        attr_set = true;
+    }
+    dim3 grid(8 * g.m_blocks * ((g.n_blocks + 7) / 8));
+    gemm_big_kernel<Epi><<<grid, 512, kBigSmemBytes, s>>>(g, e);
+}
+// Used from 256 rows on where the 256 x 256 blocks fill the compute units well: with T blocks on 256 units
+// the launch takes ceil(T / 256) block-times, so it pays when the useful share of those block slots (counting
+// a ragged last row block by its real rows) is at least 70 %.  Measured at the 8B shape: 1024 rows QKV 130 us
+// against 166 us for the tile kernel, gate/up equal, LM head 490 against 650; at 640 rows (47 % useful)
+// the tile kernel wins by a third.  The O and down projections (64 blocks at 1024 rows) stay with the tile kernel.
+static bool use_big(GemmShape sh) {
+    if (sh.M_tiles < 16 || sh.N_tiles < 32) return false;
+    const int blocks = ((sh.M_tiles + 15) / 16) * ((sh.N_tiles + 15) / 16);
+    const int rounds = (blocks + kStreamWGs - 1) / kStreamWGs;
+    const double useful = (sh.M_tiles / 16.0) * (sh.N_tiles / 16.0) / ((double)rounds * kStreamWGs);
+    return useful >= 0.7;
+}
+
 void launch_gemm_qkv(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, QkvOut out, Workspace ws, hipStream_t s) {
     EpiQKV e{out, sh.M_tiles};
     if (sh.M_tiles <= 2) launch_stream<2, 3, 8, 8, true>(xa, w, sh, ni, e, s);
     else if (sh.M_tiles <= 8) launch_stream<8, 3, 2, 8, false>(xa, w, sh, ni, e, s);
+    else if (use_big(sh)) launch_big(xa, w, sh, ni, e, s);
     else launch_tile(xa, w, sh, ni, e, ws, true, s);
 }
 void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int ldh, NormOut no, Workspace ws,
@@ -75,6 +106,7 @@ void launch_gemm_swiglu(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, u1
     EpiSwiGLU e{act, sh.M_tiles};
     if (sh.M_tiles <= 2) launch_stream<2, 6, 4, 8, true>(xa, w, sh, ni, e, s);
     else if (sh.M_tiles <= 8) launch_stream<8, 6, 2, 4, true>(xa, w, sh, ni, e, s);
+    else if (use_big(sh)) launch_big(xa, w, sh, ni, e, s);
     else launch_tile(xa, w, sh, ni, e, ws, true, s);
 }
 
@@ -86,6 +118,7 @@ int lm_stats_parts(int n_tiles, int m_tiles) {
         const int groups = (n_tiles + kLmNG - 1) / kLmNG;
         return (groups < kStreamWGs ? groups : kStreamWGs) * kLmNG;
     }
+    if (use_big(GemmShape{m_tiles, n_tiles, 0})) return (n_tiles + 15) / 16;
     const TileCfg c = tile_cfg(m_tiles);
     return (n_tiles + c.nw * c.ngw - 1) / (c.nw * c.ngw);
 }
@@ -95,6 +128,7 @@ void launch_gemm_lmstats(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, f
     const int parts = lm_stats_parts(sh.N_tiles, sh.M_tiles);
     if (sh.M_tiles <= 2) launch_stream<2, kLmNG, 4, 8, true>(xa, w, sh, ni, EpiLMStats<2>(stats, parts), s);
     else if (sh.M_tiles <= 8) launch_stream<8, kLmNG, 2, 4, true>(xa, w, sh, ni, EpiLMStats<16>(stats, parts), s);
+    else if (use_big(sh)) launch_big(xa, w, sh, ni, TileLMStats{stats, parts}, s);
     else launch_tile(xa, w, sh, ni, TileLMStats{stats, parts}, ws, false, s);
 }
 void launch_gemm_store(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, float *out, int units, int rpu_pad,
@@ -102,6 +136,7 @@ void launch_gemm_store(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, flo
     EpiStore e{out, units, rpu_pad, valid, ld};
     if (sh.M_tiles <= 2) launch_stream<2, 3, 8, 8, true>(xa, w, sh, ni, e, s);
     else if (sh.M_tiles <= 8) launch_stream<8, 3, 2, 8, false>(xa, w, sh, ni, e, s);
+    else if (use_big(sh)) launch_big(xa, w, sh, ni, e, s);
     else launch_tile(xa, w, sh, ni, e, ws, false, s);
 }
 

@@ -1,0 +1,254 @@
+// binary16 MFMA GEMM  C[M,N] = A[M,K] * W[N,K]^T  for the compute-bound shapes (256 rows and more:
+// the cache-refresh prefill, the batched long-context step).  Same operand layouts and epilogues
+// as gemm_core.h / gemm_tile.h.
+//
+// A workgroup of eight waves computes a 256 x 256 block of C over all of K.  Per k-tile it needs
+// sixteen 1 KiB tiles of A and sixteen of W; they are copied from global memory straight into LDS
+// (global_load ... lds, no registers in between) into a ring of four stages, three k-tiles ahead of
+// the MFMAs, so one barrier per k-tile is the only synchronisation.  The waves form a 2 x 4 grid,
+// each owning 8 x 4 output tiles: per k-tile a wave reads 12 operand tiles from LDS for 32 MFMAs,
+// one k-tile ahead into a second register set, so LDS traffic and MFMAs overlap within a wave.
+// Operand bytes per flop are half those of the 128-row tile kernel, which is what matters here:
+// a re-read that misses the 4 MiB L2 of an XCD is served at HBM-like bandwidth (about 7 TB/s measured
+// on MI355X, against 22 TB/s for L2 hits), so the ids of the workgroups are also mapped to blocks
+// such that the workgroups resident on one XCD share their weight panels and rows of A.
+#pragma once
+#include <type_traits>
+#include "gemm_tile.h"
+
+namespace odb {
+
+constexpr int kBigStages = 4;
+constexpr int kBigStageBytes = 32 * 1024;                                   // 16 A tiles + 16 W tiles
+constexpr int kBigSmemBytes = kBigStages * kBigStageBytes + 8 * 1024 + 256 * 4;   // ring, per-wave scratch, row scales
+
+struct BigArgs {
+    const u16 *A, *W;
+    int KT, MT_total, NT;
+    int m_blocks, n_blocks;
+    const float *ssq;          // fused RMSNorm of the input rows (see GemmArgs)
+    int n_ssq;
+    float eps, inv_d;
+};
+
+template <class Epi>
+__global__ __launch_bounds__(512) void gemm_big_kernel(BigArgs g, Epi epi) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    typedef frag_t stage_t[32][64];                                          // tiles 0..15: A, 16..31: W
+    stage_t *ring = reinterpret_cast<stage_t *>(smem);
+    f32x4 (*scr)[64] = reinterpret_cast<f32x4 (*)[64]>(smem + kBigStages * kBigStageBytes);   // [8 waves][64]
+    float *s_rstd = reinterpret_cast<float *>(smem + kBigStages * kBigStageBytes + 8 * 1024);
+
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int wm = w >> 2, wn = w & 3;                   // position of the wave in the 2 x 4 grid
+    // Workgroup ids go round-robin over the 8 XCDs.  The ids that land on one XCD walk down the row
+    // blocks of a column of blocks before they move to that XCD's next column, so concurrently
+    // resident workgroups of an XCD share weight panels (and all of them the rows of A) in its L2.
+    const int xcd = blockIdx.x % 8, jx = blockIdx.x / 8;
+    const int nb = (jx / g.m_blocks) * 8 + xcd, mb = jx % g.m_blocks;
+    if (nb >= g.n_blocks) return;
+    const int mt0 = mb * 16, nt0 = nb * 16;
+
+    // this wave copies tiles 4w .. 4w+3 of every stage: waves 0-3 rows of A, waves 4-7 rows of W
+    const u16 *src[4];
+    size_t kstride;
+    if (w < 4) {
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            int mt = mt0 + 4 * w + i;
+            mt = mt < g.MT_total ? mt : g.MT_total - 1;
+            src[i] = g.A + (size_t)mt * kTileElems + lane * 8;
+        }
+        kstride = (size_t)g.MT_total * kTileElems;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            int nt = nt0 + 4 * (w - 4) + i;
+            nt = nt < g.NT ? nt : g.NT - 1;
+            src[i] = g.W + (size_t)nt * g.KT * kTileElems + lane * 8;
+        }
+        kstride = kTileElems;
+    }
+    auto issue = [&](int slot, int k) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+            __builtin_amdgcn_global_load_lds(reinterpret_cast<const void *>(src[i] + (size_t)k * kstride),
+                                             (__attribute__((address_space(3))) void *)(&ring[slot][4 * w + i][0]),
+                                             16, 0, 0);
+    };
+
+    const int nk = g.KT;
+    issue(0, 0);
+    if (nk > 1) issue(1, 1);
+    if (nk > 2) issue(2, 2);
+
+    // Row scales of the fused RMSNorm, 32 rows per wave in two halves.  A row's partial sums (up to 256)
+    // are one 16-byte load per lane, the loads of 16 rows are in flight together (behind the ring's first
+    // stages), and the 64 lane-sums of each row are added through the still unused fourth slot of the
+    // ring: written rotated by the row number, so that the transposed gather is free of bank conflicts.
+    if (g.ssq) {
+        float *tmp = reinterpret_cast<float *>(&ring[3][0][0]) + w * (16 * 64);
+        const int si = 4 * lane, sic = si < g.n_ssq - 4 ? si : g.n_ssq - 4;
+#pragma unroll
+        for (int half = 0; half < 2; half++) {
+            f32x4 sv[16];
+            const float *rp[16];
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+                int row = mt0 * 16 + w * 32 + half * 16 + r;
+                row = row < g.MT_total * 16 ? row : g.MT_total * 16 - 1;
+                rp[r] = g.ssq + (size_t)row * g.n_ssq;
+                sv[r] = *reinterpret_cast<const f32x4 *>(rp[r] + sic);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+                float part = si < g.n_ssq ? (sv[r][0] + sv[r][1]) + (sv[r][2] + sv[r][3]) : 0.f;
+                for (int i0 = 256; i0 < g.n_ssq; i0 += 256) {       // rows wider than 4096 only
+                    const int i = i0 + si, ic = i < g.n_ssq - 4 ? i : g.n_ssq - 4;
+                    f32x4 v = *reinterpret_cast<const f32x4 *>(rp[r] + ic);
+                    part += i < g.n_ssq ? (v[0] + v[1]) + (v[2] + v[3]) : 0.f;
+                }
+                tmp[r * 64 + ((lane + r) & 63)] = part;
+            }
+            const int rr = lane & 15, p0 = (lane >> 4) * 16;
+            float t = 0.f;
+#pragma unroll
+            for (int u = 0; u < 16; u++) t += tmp[rr * 64 + ((p0 + u + rr) & 63)];
+            t += __shfl_xor(t, 16);
+            t += __shfl_xor(t, 32);
+            if (lane < 16) s_rstd[w * 32 + half * 16 + lane] = 1.0f / sqrtf(t * g.inv_d + g.eps);
+        }
+    } else if (lane < 32) {
+        s_rstd[w * 32 + lane] = 1.0f;
+    }
+
+    f32x4 acc[8][4];
+#pragma unroll
+    for (int m = 0; m < 8; m++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) acc[m][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // Software pipeline over the k-tiles.  In iteration k a wave first fetches the operand tiles of stage
+    // k+1 from LDS into the second register set and then issues the MFMAs of stage k, so the LDS reads of
+    // all waves run under the MFMAs instead of in a phase of their own after each barrier.  Stage k+3 is
+    // requested from global memory in iteration k, into the slot whose tiles fed the MFMAs of k-1.
+    static_assert(kBigStages == 4, "slot arithmetic and counted waits below");
+    frag_t a[2][8], b[2][4];
+    auto fetch = [&](auto P, int k) __attribute__((always_inline)) {
+        constexpr int p = decltype(P)::value;
+        const stage_t &st = ring[k % kBigStages];
+#pragma unroll
+        for (int j = 0; j < 4; j++) b[p][j] = st[16 + wn * 4 + j][lane];
+#pragma unroll
+        for (int m = 0; m < 8; m++) a[p][m] = st[wm * 8 + m][lane];
+    };
+    auto step = [&](auto P, int k) __attribute__((always_inline)) {
+        constexpr int p = decltype(P)::value;
+        if (k + 1 < nk) {
+            // stage k+1 has landed once every wave's four loads of it are done (stage k+2's may be in flight)
+            if (k + 2 < nk) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            if (k + 3 < nk) issue((k + 3) % kBigStages, k + 3);
+            fetch(std::integral_constant<int, 1 - p>{}, k + 1);
+        }
+#pragma unroll
+        for (int m = 0; m < 8; m++)
+#pragma unroll
+            for (int j = 0; j < 4; j++) acc[m][j] = mfma16(b[p][j], a[p][m], acc[m][j]);
+    };
+    // stage 0 has landed (everything issued so far has: the row-scale loads came after the ring's)
+    if (g.ssq || nk == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else if (nk > 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    __syncthreads();            // also orders the row-scale scratch before stage 3 reuses its slot
+    fetch(std::integral_constant<int, 0>{}, 0);
+    for (int k = 0; k < nk; k += 2) {
+        step(std::integral_constant<int, 0>{}, k);
+        if (k + 1 < nk) step(std::integral_constant<int, 1>{}, k + 1);
+    }
+    __syncthreads();            // the ring is reused below; also publishes s_rstd
+
+    if constexpr (is_row_stats<Epi>::value) {
+        // softmax statistics per row over this workgroup's 256 columns: lane-local, across the four lane
+        // groups, across the wave's four tiles, then across the four waves of a row half through LDS
+        float *st_m = reinterpret_cast<float *>(smem);               // [4 column waves][256 rows]
+        float *st_s = st_m + 4 * 256;
+        int *st_a = reinterpret_cast<int *>(st_s + 4 * 256);
+        const int mi = lane & 15, gq = lane >> 4;
+#pragma unroll
+        for (int m = 0; m < 8; m++) {
+            const int r = wm * 128 + m * 16 + mi;
+            float rm = -INFINITY, rs = 0.f;
+            int ra = 0x7fffffff;
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const int nt = nt0 + wn * 4 + j;
+                if (nt < g.NT) {
+                    f32x4 c = acc[m][j] * s_rstd[r];
+                    float cm = c[0];
+                    int ca = nt * 16 + 4 * gq;
+#pragma unroll
+                    for (int x = 1; x < 4; x++)
+                        if (c[x] > cm) { cm = c[x]; ca = nt * 16 + 4 * gq + x; }
+                    float cs = 0.f;
+#pragma unroll
+                    for (int x = 0; x < 4; x++) cs += expf(c[x] - cm);
+                    merge_stat(rm, rs, ra, cm, cs, ca);
+                }
+            }
+#pragma unroll
+            for (int o = 16; o <= 32; o <<= 1) {
+                float om = __shfl_xor(rm, o), os = __shfl_xor(rs, o);
+                int oa = __shfl_xor(ra, o);
+                merge_stat(rm, rs, ra, om, os, oa);
+            }
+            if (gq == 0) {
+                st_m[wn * 256 + r] = rm;
+                st_s[wn * 256 + r] = rs;
+                st_a[wn * 256 + r] = ra;
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x < 256) {
+            const int r = threadIdx.x, row = mt0 * 16 + r;
+            float rm = st_m[r], rs = st_s[r];
+            int ra = st_a[r];
+#pragma unroll
+            for (int x = 1; x < 4; x++) merge_stat(rm, rs, ra, st_m[x * 256 + r], st_s[x * 256 + r], st_a[x * 256 + r]);
+            if (row < g.MT_total * 16) {
+                float *p = epi.stats + ((size_t)row * epi.n_part + nb) * 3;
+                p[0] = rm;
+                p[1] = rs;
+                p[2] = __int_as_float(ra);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int m = 0; m < 8; m++)
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const int mt = mt0 + wm * 8 + m, nt = nt0 + wn * 4 + j;
+                if (mt < g.MT_total && nt < g.NT) {
+                    const float *rsd = s_rstd + (wm * 8 + m) * 16;
+                    f32x4 c;
+                    if (!epi.transposed(nt)) {
+                        c = acc[m][j] * rsd[lane & 15];
+                    } else {
+                        // lane (g, ni) gets rows 4g..4g+3 of column ni: through this wave's LDS scratch
+                        const int ni = lane & 15, gq = lane >> 4;
+                        scr[w][lane] = acc[m][j];
+                        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // store before the transposed reads
+                        const float *base = reinterpret_cast<const float *>(&scr[w][0]);
+#pragma unroll
+                        for (int r = 0; r < 4; r++)
+                            c[r] = base[((ni >> 2) * 16 + 4 * gq + r) * 4 + (ni & 3)] * rsd[4 * gq + r];
+                        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // reads before the next tile's store
+                    }
+                    epi(mt, nt, c, lane, 0);
+                }
+            }
+    }
+}
+
+}  // namespace odb
