@@ -11,15 +11,22 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(AttnArgs a, float sc) {
 
 void launch_attention(AttnArgs a, hipStream_t s) {
     const float sc = 1.4426950408889634f / sqrtf((float)a.dh);
-    if (a.fresh > 0) {
+    if (a.fresh > 0 && a.tiles_per_unit >= 3 && a.units * ((a.tiles_per_unit + 3) / 4) * a.H >= 512) {
+        // decode step with long blocks and many drafts or sequences: four row tiles of a draft per workgroup,
+        // so that a K/V tile fetched from L2 serves 64 rows (a quarter of the cache traffic of the case below)
+        dim3 grid(a.units * ((a.tiles_per_unit + 3) / 4), a.H);
+        if (a.dh == 128) attn_kernel<128, 4, 4><<<grid, 256, 0, s>>>(a, sc);
+        else attn_kernel<64, 4, 4><<<grid, 256, 0, s>>>(a, sc);
+    } else if (a.fresh > 0) {
         // decode step: few rows, one 16-row tile per workgroup and eight waves over the keys
         dim3 grid(a.units * a.tiles_per_unit, a.H);
         if (a.dh == 128) attn_kernel<128, 1, 8><<<grid, 512, 0, s>>>(a, sc);
         else attn_kernel<64, 1, 8><<<grid, 512, 0, s>>>(a, sc);
     } else {
-        dim3 grid(a.units * ((a.tiles_per_unit + 1) / 2), a.H);
-        if (a.dh == 128) attn_kernel<128, 2, 4><<<grid, 256, 0, s>>>(a, sc);
-        else attn_kernel<64, 2, 4><<<grid, 256, 0, s>>>(a, sc);
+        constexpr int QT = 4;
+        dim3 grid(a.units * ((a.tiles_per_unit + QT - 1) / QT), a.H);
+        if (a.dh == 128) attn_kernel<128, QT, 4><<<grid, 256, 0, s>>>(a, sc);
+        else attn_kernel<64, QT, 4><<<grid, 256, 0, s>>>(a, sc);
     }
 }
 

@@ -108,13 +108,16 @@ __device__ __forceinline__ void attn_wg(const AttnArgs &a, float sc, int item, i
             tm = fmaxf(tm, __shfl_xor(tm, 32));
             const float mnew = fmaxf(mrun[t], tm);
             const float mref = mnew == -INFINITY ? 0.f : mnew;
-            const float alpha = exp2f(mrun[t] - mref);
+            // once the running maxima have settled (after the first few key tiles) no row of the wave
+            // changes its maximum: then alpha is exactly 1 and the rescaling of O is skipped
+            const bool rescale = __any(mnew != mrun[t]);
+            const float alpha = __builtin_amdgcn_exp2f(mrun[t] - mref);
             float p[2][4], ps = 0.f;
 #pragma unroll
             for (int s = 0; s < 2; s++)
 #pragma unroll
                 for (int rr = 0; rr < 4; rr++) {
-                    p[s][rr] = exp2f(st[s][rr] - mref);
+                    p[s][rr] = __builtin_amdgcn_exp2f(st[s][rr] - mref);
                     ps += p[s][rr];
                 }
             lrun[t] = lrun[t] * alpha + ps;
@@ -124,11 +127,12 @@ __device__ __forceinline__ void attn_wg(const AttnArgs &a, float sc, int item, i
             pf.w[1] = pack2(p[0][2], p[0][3]);
             pf.w[2] = pack2(p[1][0], p[1][1]);
             pf.w[3] = pack2(p[1][2], p[1][3]);
+            if (rescale) {
 #pragma unroll
-            for (int dt = 0; dt < DT16; dt++) {
-                o[t][dt] *= alpha;
-                o[t][dt] = mfma16(vf[dt], pf, o[t][dt]);
+                for (int dt = 0; dt < DT16; dt++) o[t][dt] *= alpha;
             }
+#pragma unroll
+            for (int dt = 0; dt < DT16; dt++) o[t][dt] = mfma16(vf[dt], pf, o[t][dt]);
         }
     };
 

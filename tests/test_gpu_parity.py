@@ -240,6 +240,7 @@ def test_config0_peaked(gf):
     (3, 10, 7, 1, 2, 3),       # single-token block
     (1, 200, 136, 32, 9, 2),   # L = 336 and 288 step rows: the 256-row GEMM blocks, ragged in M, fused norm in the step
     (2, 150, 122, 16, 20, 1),  # batch 2 x L = 272 prefill rows, 2 x 320 step rows
+    (4, 40, 56, 48, 32, 0),    # 128 drafts of three row tiles: the four-tile attention workgroups of the long-block step
 ])
 def test_step_edge_shapes(tiny, Bn, P, R, b, S, blk):
     wl = W.decode_workload(tiny.shape, P, R, b, S, 77 + P, batch=Bn, block_index=blk)
