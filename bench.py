@@ -168,6 +168,9 @@ def main():
     # dominant kernel: the gate/up projection (SwiGLU GEMM), 2*F*d weights per launch.
     # Its launches are bracketed by HIP events on the launch stream in a second,
     # instrumented pass over the same steps (the events would perturb the timed pass).
+    # An event pair also spans the dispatch latency after its start marker (about 3 us here), which
+    # back-to-back launches hide and a profiler's kernel trace does not count: the figure below is
+    # therefore a little pessimistic next to the rocprofv3 average of the same kernel.
     prof = B.odb_profile_kernel(model, run, args.steps) if hasattr(B, "odb_profile_kernel") else None
     compute_bound = name in ("config3", "config4")
     rows_per_launch = rows
