@@ -1,5 +1,5 @@
 // Stand-alone launches of the attention core (see attn_core.h).
-#include "attn_core.h"
+#include "attn_rows.h"
 
 namespace odb {
 
@@ -9,21 +9,49 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(AttnArgs a, float sc) {
     attn_wg<DH, QT, NW>(a, sc, blockIdx.x, blockIdx.y, smem);
 }
 
+// Many rows per (sequence, head): K/V tiles shared through LDS by all rows of a workgroup (attn_rows.h)
+template <int DH, int NW, int QTW, int NS, bool PIPE, bool DUAL>
+static void launch_rows(AttnArgs a, float sc, hipStream_t s) {
+    static bool attr_set = false;           // once per instantiation: the ring may need more than the default LDS limit
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_rows_kernel<DH, NW, QTW, NS, PIPE, DUAL>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, attn_rows_smem_bytes<DH, NS>());
+        attr_set = true;
+    }
+    const int tiles_per_seq = a.units_per_seq * a.tiles_per_unit;
+    const int chunks = (tiles_per_seq + NW * QTW - 1) / (NW * QTW);
+    dim3 grid((a.units / a.units_per_seq) * chunks, a.H);
+    attn_rows_kernel<DH, NW, QTW, NS, PIPE, DUAL><<<grid, 64 * NW, attn_rows_smem_bytes<DH, NS>(), s>>>(a, sc);
+}
+
 void launch_attention(AttnArgs a, hipStream_t s) {
     const float sc = 1.4426950408889634f / sqrtf((float)a.dh);
-    if (a.fresh > 0 && a.tiles_per_unit >= 3 && a.units * ((a.tiles_per_unit + 3) / 4) * a.H >= 512) {
-        // decode step with long blocks and many drafts or sequences: four row tiles of a draft per workgroup,
-        // so that a K/V tile fetched from L2 serves 64 rows (a quarter of the cache traffic of the case below)
-        dim3 grid(a.units * ((a.tiles_per_unit + 3) / 4), a.H);
-        if (a.dh == 128) attn_kernel<128, 4, 4><<<grid, 256, 0, s>>>(a, sc);
-        else attn_kernel<64, 4, 4><<<grid, 256, 0, s>>>(a, sc);
+    const int tiles_per_seq = a.units_per_seq * a.tiles_per_unit;
+    if (tiles_per_seq >= 16 && (a.fresh == 0 || a.tiles_per_unit % 2 == 0)) {
+        // 256 rows per workgroup when that still gives every compute unit a workgroup, else 128
+        const int wgs8 = (a.units / a.units_per_seq) * ((tiles_per_seq + 15) / 16) * a.H;
+        if (a.dh == 128) {
+            if (wgs8 >= 256) launch_rows<128, 8, 2, 8, true, false>(a, sc, s);
+            else launch_rows<128, 4, 2, 4, true, true>(a, sc, s);
+        } else {
+            if (wgs8 >= 256) launch_rows<64, 8, 2, 8, true, true>(a, sc, s);
+            else launch_rows<64, 4, 2, 4, true, true>(a, sc, s);
+        }
+        return;
+    }
+    if (a.fresh > 0 && a.tiles_per_unit >= 2 && a.units * ((a.tiles_per_unit + 1) / 2) * a.H >= 512) {
+        // decode step with blocks of an odd number of row tiles and many drafts or sequences: two row tiles of
+        // a draft per workgroup, so that a K/V tile fetched from L2 serves 32 rows
+        dim3 grid(a.units * ((a.tiles_per_unit + 1) / 2), a.H);
+        if (a.dh == 128) attn_kernel<128, 2, 4><<<grid, 256, 0, s>>>(a, sc);
+        else attn_kernel<64, 2, 4><<<grid, 256, 0, s>>>(a, sc);
     } else if (a.fresh > 0) {
         // decode step: few rows, one 16-row tile per workgroup and eight waves over the keys
         dim3 grid(a.units * a.tiles_per_unit, a.H);
         if (a.dh == 128) attn_kernel<128, 1, 8><<<grid, 512, 0, s>>>(a, sc);
         else attn_kernel<64, 1, 8><<<grid, 512, 0, s>>>(a, sc);
     } else {
-        constexpr int QT = 4;
+        constexpr int QT = 2;
         dim3 grid(a.units * ((a.tiles_per_unit + QT - 1) / QT), a.H);
         if (a.dh == 128) attn_kernel<128, QT, 4><<<grid, 256, 0, s>>>(a, sc);
         else attn_kernel<64, QT, 4><<<grid, 256, 0, s>>>(a, sc);

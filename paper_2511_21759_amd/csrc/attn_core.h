@@ -32,6 +32,104 @@ __device__ inline void store_out_tile(const AttnArgs &a, int mt, int hd, int dt1
     *reinterpret_cast<uint2 *>(dst) = p;
 }
 
+// Scores of one 32-key tile (K fragments kf) against QT row tiles, online-softmax update of the running
+// (max, sum) and the rescaling of O that goes with it; returns the probabilities as operand fragments pf.
+// MASK: some keys of the tile may be invisible - cached: cache positions key0 .. key0+31, those past L or
+// inside the block are masked; otherwise fresh keys of the rows' own draft, those past a.fresh are masked.
+// The running references mrun are in log2 units (raw score * sc, sc = log2(e)/sqrt(dh) > 0).
+constexpr float kAttnSlack = 8.0f;
+template <int DH, int QT, bool MASK>
+__device__ __forceinline__ void attn_scores(const AttnArgs &a, float sc, int key0, bool cached,
+                                            const frag_t (&kf)[2][DH / 32], const frag_t (&q)[QT][DH / 32],
+                                            f32x4 (&o)[QT][DH / 16], float (&mrun)[QT], float (&lrun)[QT],
+                                            frag_t (&pf)[QT], int lane) {
+    constexpr int DT32 = DH / 32, DT16 = DH / 16;
+    const int g = lane >> 4;
+    bool ok[2][4];
+    if (MASK) {
+#pragma unroll
+        for (int s = 0; s < 2; s++)
+#pragma unroll
+            for (int rr = 0; rr < 4; rr++) {
+                int key = key0 + s * 16 + 4 * g + rr;
+                ok[s][rr] = cached ? (key < a.L && !(key >= a.blk_lo && key < a.blk_hi)) : key < a.fresh;
+            }
+    }
+#pragma unroll
+    for (int t = 0; t < QT; t++) {
+        f32x4 st[2];
+#pragma unroll
+        for (int s = 0; s < 2; s++) {
+            st[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int dt = 0; dt < DT32; dt++) st[s] = mfma16(kf[s][dt], q[t][dt], st[s]);
+        }
+        float tm = -INFINITY;
+#pragma unroll
+        for (int s = 0; s < 2; s++)
+#pragma unroll
+            for (int rr = 0; rr < 4; rr++) {
+                if (MASK) st[s][rr] = ok[s][rr] ? st[s][rr] : -INFINITY;
+                tm = fmaxf(tm, st[s][rr]);
+            }
+        // The reference mrun[t] of a row only has to be common to the four lanes that hold the row and to
+        // keep exp2 in range; it need not be the exact running maximum.  It is raised (a cross-lane
+        // maximum, a rescaling of O and of the running sum) only when some score of the wave exceeds its
+        // row's reference by more than 2^kAttnSlack - after the first tiles that is rare, and then the
+        // common path has no cross-lane exchange at all.  Probabilities stay below 2^kAttnSlack (binary16 holds them).
+        if (__any(tm * sc > mrun[t] + kAttnSlack)) {
+            tm = fmaxf(tm, __shfl_xor(tm, 16));
+            tm = fmaxf(tm, __shfl_xor(tm, 32));
+            const float mnew = fmaxf(mrun[t], tm * sc);
+            const float alpha = __builtin_amdgcn_exp2f(mrun[t] - (mnew == -INFINITY ? 0.f : mnew));
+            lrun[t] *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < DT16; dt++) o[t][dt] *= alpha;
+            mrun[t] = mnew;
+        }
+        const float mref = mrun[t] == -INFINITY ? 0.f : mrun[t];
+        float p[2][4], ps = 0.f;
+#pragma unroll
+        for (int s = 0; s < 2; s++)
+#pragma unroll
+            for (int rr = 0; rr < 4; rr++) {
+                p[s][rr] = __builtin_amdgcn_exp2f(__builtin_fmaf(st[s][rr], sc, -mref));
+                ps += p[s][rr];
+            }
+        lrun[t] += ps;
+        pf[t].w[0] = pack2(p[0][0], p[0][1]);
+        pf[t].w[1] = pack2(p[0][2], p[0][3]);
+        pf[t].w[2] = pack2(p[1][0], p[1][1]);
+        pf[t].w[3] = pack2(p[1][2], p[1][3]);
+    }
+}
+
+// O^T += V^T P^T for QT row tiles
+template <int DH, int QT>
+__device__ __forceinline__ void attn_pv(const frag_t (&vf)[DH / 16], const frag_t (&pf)[QT], f32x4 (&o)[QT][DH / 16]) {
+#pragma unroll
+    for (int t = 0; t < QT; t++)
+#pragma unroll
+        for (int dt = 0; dt < DH / 16; dt++) o[t][dt] = mfma16(vf[dt], pf[t], o[t][dt]);
+}
+
+// true if some key of the 32-key tile at key0 is invisible (see attn_scores)
+__device__ __forceinline__ bool attn_tile_masked(const AttnArgs &a, int key0, bool cached) {
+    return cached ? (key0 + 32 > a.L || (key0 < a.blk_hi && key0 + 32 > a.blk_lo)) : key0 + 32 > a.fresh;
+}
+
+// One 32-key tile (K fragments kf, V^T fragments vf) against QT row tiles: scores, online softmax, O update.
+template <int DH, int QT>
+__device__ __forceinline__ void attn_tile_update(const AttnArgs &a, float sc, int key0, bool cached,
+                                                 const frag_t (&kf)[2][DH / 32], const frag_t (&vf)[DH / 16],
+                                                 const frag_t (&q)[QT][DH / 32], f32x4 (&o)[QT][DH / 16],
+                                                 float (&mrun)[QT], float (&lrun)[QT], int lane) {
+    frag_t pf[QT];
+    if (attn_tile_masked(a, key0, cached)) attn_scores<DH, QT, true>(a, sc, key0, cached, kf, q, o, mrun, lrun, pf, lane);
+    else attn_scores<DH, QT, false>(a, sc, key0, cached, kf, q, o, mrun, lrun, pf, lane);
+    attn_pv<DH, QT>(vf, pf, o);
+}
+
 template <int QT, int NW>
 constexpr int attn_smem_bytes() { return NW * 4 * 1024 + 2 * NW * QT * 16 * 4; }
 
@@ -79,61 +177,7 @@ __device__ __forceinline__ void attn_wg(const AttnArgs &a, float sc, int item, i
     };
     auto compute_tile = [&](const TileRef &r, const frag_t (&kf)[2][DT32], const frag_t (&vf)[DT16])
                             __attribute__((always_inline)) {
-        bool ok[2][4];
-#pragma unroll
-        for (int s = 0; s < 2; s++)
-#pragma unroll
-            for (int rr = 0; rr < 4; rr++) {
-                int key = r.key0 + s * 16 + 4 * g + rr;
-                ok[s][rr] = r.cached ? (key < a.L && !(key >= a.blk_lo && key < a.blk_hi)) : key < a.fresh;
-            }
-#pragma unroll
-        for (int t = 0; t < QT; t++) {
-            f32x4 st[2];
-#pragma unroll
-            for (int s = 0; s < 2; s++) {
-                st[s] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int dt = 0; dt < DT32; dt++) st[s] = mfma16(kf[s][dt], q[t][dt], st[s]);
-            }
-            float tm = -INFINITY;
-#pragma unroll
-            for (int s = 0; s < 2; s++)
-#pragma unroll
-                for (int rr = 0; rr < 4; rr++) {
-                    st[s][rr] = ok[s][rr] ? st[s][rr] * sc : -INFINITY;
-                    tm = fmaxf(tm, st[s][rr]);
-                }
-            tm = fmaxf(tm, __shfl_xor(tm, 16));
-            tm = fmaxf(tm, __shfl_xor(tm, 32));
-            const float mnew = fmaxf(mrun[t], tm);
-            const float mref = mnew == -INFINITY ? 0.f : mnew;
-            // once the running maxima have settled (after the first few key tiles) no row of the wave
-            // changes its maximum: then alpha is exactly 1 and the rescaling of O is skipped
-            const bool rescale = __any(mnew != mrun[t]);
-            const float alpha = __builtin_amdgcn_exp2f(mrun[t] - mref);
-            float p[2][4], ps = 0.f;
-#pragma unroll
-            for (int s = 0; s < 2; s++)
-#pragma unroll
-                for (int rr = 0; rr < 4; rr++) {
-                    p[s][rr] = __builtin_amdgcn_exp2f(st[s][rr] - mref);
-                    ps += p[s][rr];
-                }
-            lrun[t] = lrun[t] * alpha + ps;
-            mrun[t] = mnew;
-            frag_t pf;
-            pf.w[0] = pack2(p[0][0], p[0][1]);
-            pf.w[1] = pack2(p[0][2], p[0][3]);
-            pf.w[2] = pack2(p[1][0], p[1][1]);
-            pf.w[3] = pack2(p[1][2], p[1][3]);
-            if (rescale) {
-#pragma unroll
-                for (int dt = 0; dt < DT16; dt++) o[t][dt] *= alpha;
-            }
-#pragma unroll
-            for (int dt = 0; dt < DT16; dt++) o[t][dt] = mfma16(vf[dt], pf, o[t][dt]);
-        }
+        attn_tile_update<DH, QT>(a, sc, r.key0, r.cached, kf, vf, q, o, mrun, lrun, lane);
     };
 
     // This wave's tiles: cached 32-key tiles w, w+NW, ... (those wholly inside the block are dead),

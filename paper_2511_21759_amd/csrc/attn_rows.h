@@ -1,0 +1,171 @@
+// Attention for many query rows per (sequence, head): the prefill and the long-block,
+// many-draft decode step (see attn_core.h for the tile arithmetic and the layouts).
+//
+// A workgroup takes NW * QTW consecutive 16-row tiles of ONE sequence and one head; every wave owns
+// QTW of them from start to finish, so nothing is merged across waves.  All waves walk over the
+// same cached 32-key tiles, which are copied from global memory straight into an LDS ring
+// (global_load ... lds, NS stages, NS - 1 tiles ahead) once per workgroup and read from there by
+// every wave: a K/V tile fetched from L2 serves NW * QTW * 16 rows.  The ring is deep because a
+// workgroup is usually the first on its XCD to touch its K/V: with 16 KiB per tile and a few
+// microseconds of HBM latency, two tiles in flight bound the kernel at 1.7 us per tile (measured).  The fresh keys of a draft
+// (decode step) are private to that draft's rows; each wave reads its own from global memory
+// after the shared loop.  Visibility is as in attn_core.h.
+#pragma once
+#include "attn_core.h"
+
+namespace odb {
+
+template <int DH, int NS>
+constexpr int attn_rows_smem_bytes() { return NS * (2 * (DH / 32) + DH / 16) * 1024; }
+
+// s_waitcnt vmcnt(n) for a run-time n (the instruction takes an immediate)
+__device__ __forceinline__ void wait_vmcnt(int n) {
+    switch (n) {
+#define ODB_VMCNT_CASE(N) case N: asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory"); break;
+        ODB_VMCNT_CASE(1) ODB_VMCNT_CASE(2) ODB_VMCNT_CASE(3) ODB_VMCNT_CASE(4) ODB_VMCNT_CASE(5) ODB_VMCNT_CASE(6)
+        ODB_VMCNT_CASE(7) ODB_VMCNT_CASE(8) ODB_VMCNT_CASE(9) ODB_VMCNT_CASE(10) ODB_VMCNT_CASE(11) ODB_VMCNT_CASE(12)
+        ODB_VMCNT_CASE(13) ODB_VMCNT_CASE(14) ODB_VMCNT_CASE(15) ODB_VMCNT_CASE(16) ODB_VMCNT_CASE(18) ODB_VMCNT_CASE(20)
+        ODB_VMCNT_CASE(24) ODB_VMCNT_CASE(28)
+#undef ODB_VMCNT_CASE
+        default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;      // also every count not listed: waits for more
+    }
+}
+
+// Requires tiles_per_unit % QTW == 0 when there are fresh keys (a wave's tiles then belong to one draft).
+// PIPE: fetch K of tile i+1 from LDS while P*V of tile i is issued.
+// DUAL: a second code path without key masks for tiles whose 32 keys are all visible (fewer VALU operations;
+// with eight waves of dh = 128 the two paths together do not fit the register file without spilling).
+template <int DH, int NW, int QTW, int NS, bool PIPE, bool DUAL>
+__global__ __launch_bounds__(64 * NW) void attn_rows_kernel(AttnArgs a, float sc) {
+    constexpr int DT32 = DH / 32, DT16 = DH / 16;
+    constexpr int FR = 2 * DT32 + DT16;              // 1 KiB fragments per 32-key tile: K then V^T
+    constexpr int PER = (FR + NW - 1) / NW;          // fragments each wave copies per stage
+    static_assert(FR % NW == 0, "every wave copies the same number of fragments");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    typedef frag_t stage_t[FR][64];
+    stage_t *ring = reinterpret_cast<stage_t *>(smem);
+
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, hd = blockIdx.y;
+    const int tiles_per_seq = a.units_per_seq * a.tiles_per_unit;
+    const int chunks = (tiles_per_seq + NW * QTW - 1) / (NW * QTW);
+    const int seq = blockIdx.x / chunks;
+    const int ts0 = (blockIdx.x % chunks) * (NW * QTW) + w * QTW;      // this wave's first tile within the sequence
+    const bool wave_live = ts0 < tiles_per_seq;
+    const int unit = seq * a.units_per_seq + (wave_live ? ts0 : tiles_per_seq - 1) / a.tiles_per_unit;
+
+    frag_t q[QTW][DT32];
+#pragma unroll
+    for (int t = 0; t < QTW; t++) {
+        const int ts = ts0 + t < tiles_per_seq ? ts0 + t : tiles_per_seq - 1;
+        const int mt = seq * tiles_per_seq + ts;
+#pragma unroll
+        for (int dt = 0; dt < DT32; dt++)
+            q[t][dt] = ld_frag(a.q + (((size_t)hd * a.mt_total + mt) * DT32 + dt) * kTileElems + lane * 8);
+    }
+    f32x4 o[QTW][DT16];
+    float mrun[QTW], lrun[QTW];
+#pragma unroll
+    for (int t = 0; t < QTW; t++) {
+        mrun[t] = -INFINITY;
+        lrun[t] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < DT16; dt++) o[t][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // live cached tiles: all 32-key tiles of the sequence but those wholly inside the block
+    const int n32 = (a.L + 31) / 32;
+    const int d_lo = (a.blk_lo + 31) / 32, d_hi = a.blk_hi / 32;
+    const int dead = d_hi > d_lo ? d_hi - d_lo : 0;
+    const int n_live = n32 - dead;
+    auto tile_of = [&](int i) { return dead > 0 && i >= d_lo ? i + dead : i; };
+    const u16 *kc = a.kc + seq * a.kc_seq_stride + hd * a.kc_head_stride + lane * 8;
+    const u16 *vc = a.vc + seq * a.vc_seq_stride + hd * a.vc_head_stride + lane * 8;
+    auto issue = [&](int slot, int i) __attribute__((always_inline)) {
+        const int T = tile_of(i);
+#pragma unroll
+        for (int u = 0; u < PER; u++) {
+            const int f = w + u * NW;
+            const u16 *src = f < 2 * DT32 ? kc + ((size_t)T * 2 * DT32 + f) * kTileElems
+                                          : vc + ((size_t)T * DT16 + (f - 2 * DT32)) * kTileElems;
+            __builtin_amdgcn_global_load_lds(reinterpret_cast<const void *>(src),
+                                             (__attribute__((address_space(3))) void *)(&ring[slot][f][0]), 16, 0, 0);
+        }
+    };
+
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // q has arrived: the counted waits below see only the ring
+    static_assert(PER * (NS - 2) <= 28 && (PER * (NS - 2) <= 16 || PER % 2 == 0), "wait_vmcnt covers these counts");
+    static_assert(NS >= 3, "two tiles are being read while the third is requested");
+    // Copies of tiles 0 .. NS-2 are requested up front; in iteration i tile i+NS-1 follows, into the slot of
+    // tile i-1.  Within an iteration the LDS reads run under the MFMAs: V of tile i is fetched before the
+    // scores are computed, K of tile i+1 while P*V is issued (its registers are free by then).
+    frag_t kf[2][DT32], vf[DT16], pf[QTW];
+    auto read_k = [&](int i) __attribute__((always_inline)) {
+        const stage_t &st = ring[i % NS];
+#pragma unroll
+        for (int s = 0; s < 2; s++)
+#pragma unroll
+            for (int dt = 0; dt < DT32; dt++) kf[s][dt] = st[s * DT32 + dt][lane];
+    };
+    // waits until this wave's copies of tiles 0 .. upto have landed (later requests may still be in flight)
+    auto landed = [&](int upto, int requested) __attribute__((always_inline)) {
+        const int last = requested < n_live - 1 ? requested : n_live - 1;
+        wait_vmcnt(last > upto ? PER * (last - upto) : 0);
+    };
+#pragma unroll
+    for (int j = 0; j < NS - 1; j++)
+        if (j < n_live) issue(j, j);
+    if (PIPE && n_live > 0) {
+        landed(0, NS - 2);
+        __builtin_amdgcn_s_barrier();
+        if (wave_live) read_k(0);
+    }
+    for (int i = 0; i < n_live; i++) {
+        if (!PIPE) landed(i, i + NS - 2);
+        else if (i + 1 < n_live) landed(i + 1, i + NS - 2);
+        __builtin_amdgcn_s_barrier();
+        // tile i (PIPE: i+1) is visible to every wave, and every wave is done with the slot of tile i-1
+        if (i + NS - 1 < n_live) issue((i + NS - 1) % NS, i + NS - 1);
+        if (wave_live) {
+            const stage_t &st = ring[i % NS];
+            if (!PIPE) read_k(i);
+#pragma unroll
+            for (int dt = 0; dt < DT16; dt++) vf[dt] = st[2 * DT32 + dt][lane];
+            const int key0 = tile_of(i) * 32;
+            if (!DUAL || attn_tile_masked(a, key0, true)) attn_scores<DH, QTW, true>(a, sc, key0, true, kf, q, o, mrun, lrun, pf, lane);
+            else attn_scores<DH, QTW, false>(a, sc, key0, true, kf, q, o, mrun, lrun, pf, lane);
+            if (PIPE && i + 1 < n_live) read_k(i + 1);
+            attn_pv<DH, QTW>(vf, pf, o);
+        }
+    }
+    if (!wave_live) return;
+
+    // fresh keys of this wave's draft
+    const int nf32 = a.fresh > 0 ? (a.fresh + 31) / 32 : 0;
+    const u16 *kfr = a.kf + unit * a.kf_unit_stride + hd * a.kf_head_stride + lane * 8;
+    const u16 *vfr = a.vf + unit * a.vf_unit_stride + hd * a.vf_head_stride + lane * 8;
+    for (int T = 0; T < nf32; T++) {
+#pragma unroll
+        for (int s = 0; s < 2; s++)
+#pragma unroll
+            for (int dt = 0; dt < DT32; dt++) kf[s][dt] = ld_frag(kfr + ((size_t)T * 2 * DT32 + s * DT32 + dt) * kTileElems);
+#pragma unroll
+        for (int dt = 0; dt < DT16; dt++) vf[dt] = ld_frag(vfr + ((size_t)T * DT16 + dt) * kTileElems);
+        attn_scores<DH, QTW, true>(a, sc, T * 32, false, kf, q, o, mrun, lrun, pf, lane);
+        attn_pv<DH, QTW>(vf, pf, o);
+    }
+
+#pragma unroll
+    for (int t = 0; t < QTW; t++) {
+        if (ts0 + t < tiles_per_seq) {
+            float l = lrun[t];
+            l += __shfl_xor(l, 16);
+            l += __shfl_xor(l, 32);
+            const float inv = 1.0f / l;
+            const int mt = seq * tiles_per_seq + ts0 + t;
+#pragma unroll
+            for (int dt = 0; dt < DT16; dt++) store_out_tile<DH>(a, mt, hd, dt, lane, o[t][dt] * inv);
+        }
+    }
+}
+
+}  // namespace odb
