@@ -119,3 +119,9 @@ def config3(resp_len: int, seed: int = WEIGHT_SEED + 1) -> np.ndarray:
 def config4(seed: int = WEIGHT_SEED + 1) -> DecodeWorkload:
     """Batch 4, 2048 prompt + 1024 response, block of 64, S=8 (2048 rows)."""
     return decode_workload(MODEL_SHAPES["8b"], 2048, 1024, 64, 8, seed, batch=4)
+
+
+def config4_small(seed: int = WEIGHT_SEED + 4) -> DecodeWorkload:
+    """Config 4's structure (batch 4, block of 64, S=8: 2048 rows) on a 256 + 256 context, second response block:
+    small enough for the CPU oracle at the full 8B width with two layers (parity test, not a bench line)."""
+    return decode_workload(MODEL_SHAPES["8b"], 256, 256, 64, 8, seed, batch=4, block_index=1)

@@ -7,6 +7,7 @@ the HIP library.  Takes the better part of an hour on 8 cores and ~25 GB of RAM
 stored instead of being recomputed inside the GPU tests.
 
     python tests/golden/make_8b_golden.py [n_layers]   (n_layers defaults to 32)
+    python tests/golden/make_8b_golden.py batch4       (config4_small_oracle_2L.npz: batch 4, S=8, b=64, 2 layers)
 """
 import os
 import sys
@@ -58,5 +59,48 @@ def main():
     print("wrote", name, "%.0fs" % (time.time() - t0), flush=True)
 
 
+def main_batch4():
+    """Config 4's structure at the 8B width with 2 layers: sequences 0 and 3 of the batch of four."""
+    shape = dict(W.MODEL_SHAPES["8b"], n_layers=2)
+    cfg = o.Config(**shape)
+    w = o.Weights(cfg, W.WEIGHT_SEED, W.WEIGHT_STD, keep=True)
+    wl = W.config4_small()
+    rng = np.random.default_rng(321)
+    cols = np.sort(rng.choice(cfg.vocab, 128, replace=False))
+    pos = np.sort(rng.choice(wl.tokens.shape[1], 32, replace=False))
+    seqs = [0, 3]
+    out = dict(n_layers=2, tau=wl.tau, block_off=wl.block_off, seqs=np.array(seqs), logit_cols=cols, kv_pos=pos)
+    t0 = time.time()
+    acc = {k: [] for k in ("step_conf", "step_argmax", "step_unmask", "step_logits_sample", "step_top_ids",
+                           "step_top_logits", "step_logit_absmax", "prefill_conf", "prefill_argmax",
+                           "prefill_top_ids", "prefill_top_logits", "prefill_logits_sample", "prefill_logit_absmax",
+                           "k_sample", "v_sample", "k_absmax", "v_absmax")}
+    for bi in seqs:
+        cache, conf_p, am_p, z_p = o.prefill(cfg, w, wl.tokens[bi], wl.resp_off, return_logits=True)
+        conf, am, um, z = o.block_step(cfg, w, cache, wl.drafts[bi], wl.block_off, wl.tau, return_logits=True)
+        print("sequence %d done %.0fs" % (bi, time.time() - t0), flush=True)
+        top = np.argsort(z, axis=-1)[..., -8:]
+        top_p = np.argsort(z_p, axis=-1)[..., -8:]
+        acc["step_conf"].append(conf); acc["step_argmax"].append(am); acc["step_unmask"].append(um)
+        acc["step_logits_sample"].append(z[..., cols].astype(np.float32))
+        acc["step_top_ids"].append(top.astype(np.int32))
+        acc["step_top_logits"].append(np.take_along_axis(z, top, -1).astype(np.float32))
+        acc["step_logit_absmax"].append(np.abs(z).max())
+        acc["prefill_conf"].append(conf_p); acc["prefill_argmax"].append(am_p)
+        acc["prefill_top_ids"].append(top_p.astype(np.int32))
+        acc["prefill_top_logits"].append(np.take_along_axis(z_p, top_p, -1).astype(np.float32))
+        acc["prefill_logits_sample"].append(z_p[..., cols].astype(np.float32))
+        acc["prefill_logit_absmax"].append(np.abs(z_p).max())
+        acc["k_sample"].append(cache.k[:, pos].astype(np.float32)); acc["v_sample"].append(cache.v[:, pos].astype(np.float32))
+        acc["k_absmax"].append(np.abs(cache.k).max(axis=(1, 2, 3))); acc["v_absmax"].append(np.abs(cache.v).max(axis=(1, 2, 3)))
+    out.update({k: np.stack(v) for k, v in acc.items()})
+    name = "config4_small_oracle_2L.npz"
+    np.savez_compressed(os.path.join(os.path.dirname(os.path.abspath(__file__)), name), **out)
+    print("wrote", name, "%.0fs" % (time.time() - t0), flush=True)
+
+
 if __name__ == "__main__":
-    main()
+    if len(sys.argv) > 1 and sys.argv[1] == "batch4":
+        main_batch4()
+    else:
+        main()

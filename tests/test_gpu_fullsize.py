@@ -100,6 +100,47 @@ def test_configs_1_and_2_against_stored_oracle(fname):
         B.odb_model_destroy(model)
 
 
+def test_batch4_long_block_against_stored_oracle():
+    """Config 4's structure (batch 4, S = 8 drafts of a 64-token block: 2048 rows per step) at the full 8B
+    width with two layers, sequences 0 and 3 of the batch against stored oracle outputs: batch indexing, the
+    256 x 256 GEMM blocks with the fused norm, and the shared-K/V attention kernel at head_dim 128."""
+    path = os.path.join(GOLDEN, "config4_small_oracle_2L.npz")
+    if not os.path.exists(path):
+        pytest.skip("config4_small_oracle_2L.npz has not been generated (tests/golden/make_8b_golden.py batch4)")
+    g = np.load(path)
+    shape = dict(W.MODEL_SHAPES["8b"], n_layers=int(g["n_layers"]))
+    wl = W.config4_small()
+    assert wl.block_off == int(g["block_off"])
+    model = B.odb_model_create(shape)
+    try:
+        B.odb_model_init_random(model, W.WEIGHT_SEED, W.WEIGHT_STD)
+        Bn, L = wl.tokens.shape
+        cache = B.odb_cache_create(model, Bn, L)
+        tok = cuda_i32(wl.tokens)
+        zp = B.odb_prefill_logits(model, cache, tok, wl.resp_off, shape["vocab"]).cpu().numpy()
+        conf_p, am_p = (t.cpu().numpy() for t in B.odb_prefill(model, cache, tok, wl.resp_off))
+        d = cuda_i32(wl.drafts)
+        z = B.odb_block_step_logits(model, cache, d, wl.block_off, shape["vocab"]).cpu().numpy()
+        conf, am, um = (t.cpu().numpy() for t in B.odb_block_step(model, cache, d, wl.block_off, float(g["tau"])))
+        B.odb_model_status(model)
+        for i, bi in enumerate(g["seqs"]):
+            view = {k: g[k][i] for k in g.files if g[k].ndim > 0 and g[k].shape[0] == len(g["seqs"]) and k != "seqs"}
+            view["step_logit_cols"] = g["logit_cols"]
+            e, rel, ns, n = check_rows(zp[bi], conf_p[bi], am_p[bi], view, "prefill", "batch4 prefill seq %d" % bi)
+            e2, rel2, ns2, n2 = check_rows(z[bi], conf[bi], am[bi], view, "step", "batch4 step seq %d" % bi)
+            assert np.array_equal(um[bi], view["step_unmask"]), "unmask of sequence %d" % bi
+            print("\nseq %d: prefill logit err rel %.2e (%d/%d rows strict), step rel %.2e (%d/%d)" % (bi, rel, ns, n, rel2, ns2, n2))
+            for layer in range(shape["n_layers"]):
+                for kv, ref, amax in ((0, view["k_sample"][layer], view["k_absmax"][layer]),
+                                      (1, view["v_sample"][layer], view["v_absmax"][layer])):
+                    got = B.odb_cache_read(cache, layer, kv, int(bi), 0, L, 32, 128)[g["kv_pos"]]
+                    err = np.abs(got - ref).max() / amax
+                    assert err <= KV_TOL, "batch4: cache seq %d layer %d kv %d: %.3g" % (bi, layer, kv, err)
+        B.odb_cache_destroy(cache)
+    finally:
+        B.odb_model_destroy(model)
+
+
 def test_full_size_properties_without_an_oracle():
     """Properties that hold at any size (ODB-dLLM Sec. 2.1, Sec. 4.2), on the benchmarked 32-layer model:
     the generator matches sampled slices of the oracle's, a step on the unchanged block reproduces the
