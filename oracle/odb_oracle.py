@@ -9,7 +9,8 @@ What it follows (ODB-dLLM, arXiv 2511.21759):
     outside the current block are cached by a full-sequence forward and reused
     while the block is decoded; the forward is bidirectional (no causal mask).
   * Sec. 4.1 (adaptive length prediction): the refresh computes every response
-    position and yields a decoding attempt (confidence, token) for all of them.
+    position and yields a decoding attempt (confidence, token) for all of them;
+    the attempt is scanned for a confident [EOS] and the response cut there.
   * Sec. 3, Observation 3: masked tokens of the block are decoded in parallel
     and accepted when their confidence exceeds a threshold.
   * Sec. 4.2 (jump-share speculative decoding): speculative copies of the block
@@ -280,6 +281,30 @@ def threshold_unmask(tokens: np.ndarray, conf: np.ndarray, tau: float,
     out[masked & (conf > tau)] = 1
     out[top] = 1
     return out
+
+
+def predict_length(tokens: np.ndarray, conf: np.ndarray, argmax: np.ndarray, resp_off: int,
+                   mask_id: int, eos_id: int, truncate_thr: float) -> int:
+    """Adaptive length prediction after a cache refresh (Sec. 4.1).
+
+    The refresh yields a decoding attempt (conf[i], argmax[i]) for every response
+    position resp_off + i.  The response as the model currently drafts it holds the
+    decoded token where one is decoded and the attempted token where the position is
+    still MASK.  That draft is scanned from the front for [EOS]: an attempted [EOS]
+    counts only if its confidence exceeds the truncate threshold (strictly), a
+    decoded [EOS] counts as it stands.  The sequence is cut right after the earliest
+    such position and its new length is returned; without one the length is unchanged.
+    """
+    tokens = np.asarray(tokens)
+    L = tokens.shape[0]
+    for pos in range(resp_off, L):
+        i = pos - resp_off
+        if tokens[pos] == mask_id:
+            if int(argmax[i]) == eos_id and float(conf[i]) > truncate_thr:
+                return pos + 1
+        elif tokens[pos] == eos_id:
+            return pos + 1
+    return L
 
 
 # --------------------------------------------------------------------------- the two calls

@@ -439,3 +439,73 @@ def test_step_unmask_uses_draft_tokens_and_tau():
     assert u[0][np.argmax(np.where(masked, c[0], -1))] == 1
     c, a, u = o.block_step(MICRO, w, cache, drafts, 16, -1.0)
     assert np.array_equal(u[0], masked.astype(np.uint8))
+
+
+# ------------------------------------------------------------------ adaptive length prediction (Sec. 4.1)
+
+def _alp_case(L=20, resp_off=8, mask_id=99, eos=7):
+    tokens = np.arange(L, dtype=np.int32) % 5 + 10           # no MASK, no EOS anywhere
+    tokens[resp_off:] = mask_id
+    conf = np.full(L - resp_off, 0.5)
+    am = np.full(L - resp_off, 3, np.int32)
+    return tokens, conf, am
+
+
+def test_length_prediction_cases_constructed_by_hand():
+    """Each case is built so that the answer is known by construction (Sec. 4.1: no [EOS] or none above the
+    threshold keeps the length; a confident [EOS] cuts right after itself; the earliest one wins)."""
+    mask_id, eos, ro = 99, 7, 8
+    t, c, a = _alp_case()
+    assert o.predict_length(t, c, a, ro, mask_id, eos, 0.9) == 20             # no [EOS] attempted
+    a[5] = eos
+    assert o.predict_length(t, c, a, ro, mask_id, eos, 0.9) == 20             # attempted, confidence 0.5 <= 0.9
+    c[5] = 0.9
+    assert o.predict_length(t, c, a, ro, mask_id, eos, 0.9) == 20             # "exceeds" is strict
+    c[5] = np.nextafter(0.9, 1.0)
+    assert o.predict_length(t, c, a, ro, mask_id, eos, 0.9) == ro + 5 + 1     # cut right after position 13
+    a[9], c[9] = eos, 0.99
+    assert o.predict_length(t, c, a, ro, mask_id, eos, 0.9) == ro + 5 + 1     # a later one does not matter
+    a[2], c[2] = eos, 0.3
+    assert o.predict_length(t, c, a, ro, mask_id, eos, 0.9) == ro + 5 + 1     # an earlier unconfident one neither
+    c[2] = 0.95
+    assert o.predict_length(t, c, a, ro, mask_id, eos, 0.9) == ro + 2 + 1     # ... until it is confident
+    a[0], c[0] = eos, 1.0
+    assert o.predict_length(t, c, a, ro, mask_id, eos, 0.9) == ro + 1         # first response position
+    t2, c2, a2 = _alp_case()
+    a2[-1], c2[-1] = eos, 0.95
+    assert o.predict_length(t2, c2, a2, ro, mask_id, eos, 0.9) == 20          # last position: nothing to cut
+
+
+def test_length_prediction_decoded_positions():
+    """A decoded position is judged by the token it holds, not by the attempt computed for it."""
+    mask_id, eos, ro = 99, 7, 8
+    t, c, a = _alp_case()
+    t[ro + 4] = 11                                     # decoded, not [EOS]
+    a[4], c[4] = eos, 0.99                             # the attempt at a decoded position is ignored
+    assert o.predict_length(t, c, a, ro, mask_id, eos, 0.9) == 20
+    t[ro + 6] = eos                                    # a decoded [EOS] ends the response as it stands
+    c[6] = 0.0
+    assert o.predict_length(t, c, a, ro, mask_id, eos, 0.9) == ro + 6 + 1
+    t[3] = eos                                         # [EOS] inside the prompt is not part of the response
+    assert o.predict_length(t, c, a, ro, mask_id, eos, 0.9) == ro + 6 + 1
+    a[1], c[1] = eos, 0.91                             # an earlier confident attempt still wins
+    assert o.predict_length(t, c, a, ro, mask_id, eos, 0.9) == ro + 1 + 1
+
+
+def test_length_prediction_against_a_vectorised_restatement_on_random_inputs():
+    """Brute force over random inputs: the loop of the oracle against an independent array formulation."""
+    rng = np.random.default_rng(5)
+    mask_id, eos = 63, 5
+    for trial in range(300):
+        L = int(rng.integers(2, 60))
+        ro = int(rng.integers(0, L))
+        tokens = rng.integers(0, 8, L).astype(np.int32)
+        tokens[ro:][rng.random(L - ro) < 0.6] = mask_id
+        conf = rng.random(L - ro)
+        am = rng.integers(0, 8, L - ro).astype(np.int32)
+        thr = float(rng.choice([0.0, 0.3, 0.8, 1.0]))
+        draft = np.where(tokens[ro:] == mask_id, am, tokens[ro:])
+        sure = np.where(tokens[ro:] == mask_id, conf > thr, True)
+        hits = np.flatnonzero((draft == eos) & sure)
+        want = ro + int(hits[0]) + 1 if hits.size else L
+        assert o.predict_length(tokens, conf, am, ro, mask_id, eos, thr) == want
