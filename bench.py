@@ -1,11 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the block-decode step (and, on request, the cache-refresh prefill).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config1|config2|config3|config4]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config1|config2|config3|config3_chain|config4]
 
 One "step" is one pass of the whole hot path over one batch of synthetic input:
 odb_block_step on the 8B-shaped model against a prefilled cache (config1: S=1,
-config2: S=4, config4: batch 4, S=8) or odb_prefill (config3, L=1024).  Inputs,
+config2: S=4, config4: batch 4, S=8) or odb_prefill (config3, L=1024; config3_chain:
+three refreshes of 1024, 768 and 640 positions, each followed by the adaptive length
+prediction scan, the shrinking lengths standing in for what the scan would cut).  Inputs,
 weights and the cache are resident in HBM before the timed region starts.
 Prints ONE JSON line.  Everything runs on one GPU; --gpus above 1 is refused.
 """
@@ -92,7 +94,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="config1", choices=["config0", "config1", "config2", "config3", "config4"])
+    ap.add_argument("--workload", default="config1", choices=["config0", "config1", "config2", "config3", "config3_chain", "config4"])
     ap.add_argument("--resp", type=int, default=512, help="response length for config3 (512, 256 or 128)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
@@ -120,7 +122,27 @@ def main():
     per_layer_w, total_w = weight_bytes(shape)
     d, f = shape["d_model"], shape["d_ff"]
 
-    if name == "config3":
+    if name == "config3_chain":
+        # Adaptive length prediction (ODB-dLLM Sec. 4.1) shortens the response from refresh to refresh.  With
+        # random weights no [EOS] is ever confident, so the three lengths of config 3 are imposed and the
+        # scan runs for its cost only ([EOS] id 2, threshold 0.9: the paper prints neither).
+        toks = [torch.from_numpy(W.config3(r)).cuda() for r in (512, 256, 128)]
+        caches = [B.odb_cache_create(model, 1, t.shape[1]) for t in toks]
+        outs = [(torch.empty((1, t.shape[1] - 512), dtype=torch.float32, device="cuda"),
+                 torch.empty((1, t.shape[1] - 512), dtype=torch.int32, device="cuda"),
+                 torch.empty((1,), dtype=torch.int32, device="cuda")) for t in toks]
+
+        def run():
+            for t, c, (cf, am, nl) in zip(toks, caches, outs):
+                B.odb_prefill(model, c, t, 512, cf, am)
+                B.odb_predict_length(model, t, cf, am, 512, 2, 0.9, nl)
+        cache = None
+        rows = sum(t.shape[1] for t in toks)
+        flops = sum(step_flops(shape, t.shape[1], t.shape[1]) - 2 * 512 * shape["vocab"] * d for t in toks)
+        alg_bytes = 3 * total_w + rows * kv_bytes_per_pos(shape)
+        wl = None
+        label = "three cache refreshes of 1024, 768 and 640 positions, each with the length-prediction scan, 8B shape"
+    elif name == "config3":
         tokens = torch.from_numpy(W.config3(args.resp)).cuda()
         Bn, L = tokens.shape
         cache = B.odb_cache_create(model, Bn, L)
@@ -172,8 +194,8 @@ def main():
     # back-to-back launches hide and a profiler's kernel trace does not count: the figure below is
     # therefore a little pessimistic next to the rocprofv3 average of the same kernel.
     prof = B.odb_profile_kernel(model, run, args.steps) if hasattr(B, "odb_profile_kernel") else None
-    compute_bound = name in ("config3", "config4")
-    rows_per_launch = rows
+    compute_bound = name in ("config3", "config3_chain", "config4")
+    rows_per_launch = rows / 3.0 if name == "config3_chain" else rows
     gu_bytes = 2 * f * d * 2 + rows_per_launch * d * 2 + rows_per_launch * f * 2
     gu_flops = 2 * rows_per_launch * 2 * f * d
     roofline = None
@@ -215,7 +237,8 @@ def main():
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
-    B.odb_cache_destroy(cache)
+    for c in ([cache] if cache is not None else caches):
+        B.odb_cache_destroy(c)
     B.odb_model_destroy(model)
 
 

@@ -164,6 +164,26 @@ int odb_block_step_logits(odb_model *m, const odb_cache *c,
                           const int32_t *drafts_dev, int block_off, int b, int S,
                           float *logits_dev, void *stream);
 
+/* Adaptive length prediction after a refresh (ODB-dLLM Sec. 4.1).  The refresh's
+ * decoding attempt (the conf / argmax that odb_prefill wrote for response positions
+ * resp_off .. L-1) is scanned per sequence for [EOS]: the response as currently
+ * drafted holds tokens[p] where position p is decoded and argmax where it still holds
+ * the model's MASK id; an attempted [EOS] counts only if its confidence exceeds
+ * truncate_thr (strictly), a decoded one counts as it stands.  new_len_dev[b] = index
+ * of the earliest such position + 1 (the [EOS] stays the last position of the
+ * sequence), or L when there is none.  The paper prints neither the threshold nor the
+ * [EOS] id: both are arguments.
+ *   tokens_dev  device int32 [batch, L]          the tokens the refresh ran on
+ *   conf_dev    device float [batch, L-resp_off] \ outputs of odb_prefill
+ *   argmax_dev  device int32 [batch, L-resp_off] /
+ *   new_len_dev device int32 [batch]             written
+ * Asynchronous on `stream`; all buffers are the caller's.  Errors: ODB_E_INVALID_ARG
+ * for NULL pointers, batch < 1, L < 1, resp_off outside [0, L), eos_id outside
+ * [0, vocab) or equal to the MASK id. */
+int odb_predict_length(const odb_model *m, const int32_t *tokens_dev, const float *conf_dev,
+                       const int32_t *argmax_dev, int batch, int L, int resp_off, int eos_id,
+                       float truncate_thr, int32_t *new_len_dev, void *stream);
+
 /* Copies cached K (kv = 0, post-RoPE, logical channel order) or V (kv = 1) of
  * positions pos0 .. pos0+n-1 of one sequence and layer to host memory as
  * float [n, n_heads, head_dim].  Synchronous (device-wide). */

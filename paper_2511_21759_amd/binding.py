@@ -22,7 +22,7 @@ SYMBOLS = (
     "odb_model_get_tensor", "odb_cache_create", "odb_cache_destroy", "odb_cache_length", "odb_prefill",
     "odb_block_step", "odb_prefill_logits", "odb_block_step_logits", "odb_cache_read", "odb_strerror",
     "odb_last_error", "odb_profile_begin", "odb_profile_end", "odb_set_step_mode", "odb_model_status",
-    "odb_debug_step_trace",
+    "odb_debug_step_trace", "odb_predict_length",
 )
 
 KERNEL_CLASSES = ("gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "rmsnorm",
@@ -75,6 +75,7 @@ def lib() -> ctypes.CDLL:
     L.odb_cache_read.argtypes = [vp, ci, ci, ci, ci, ci, vp]
     L.odb_profile_begin.argtypes = [vp, ci, ci]
     L.odb_profile_end.argtypes = [vp, ctypes.POINTER(ci), ctypes.POINTER(cf)]
+    L.odb_predict_length.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, cf, vp, vp]
     L.odb_set_step_mode.argtypes = [vp, ci]
     L.odb_model_status.argtypes = [vp]
     L.odb_debug_step_trace.argtypes = [vp, vp, ci]
@@ -156,6 +157,21 @@ def odb_prefill(model: int, cache: int, tokens, resp_off: int, conf=None, argmax
     _check(lib().odb_prefill(model, cache, _dev_i32(tokens), L, resp_off, conf.data_ptr(), argmax.data_ptr(),
                              _stream()))
     return conf, argmax
+
+
+def odb_predict_length(model: int, tokens, conf, argmax, resp_off: int, eos_id: int, truncate_thr: float, out=None):
+    """tokens int32 [B, L], conf f32 / argmax int32 [B, L-resp_off] (CUDA tensors) -> new lengths int32 [B]."""
+    import torch
+    B, L = tokens.shape
+    if conf.dtype != torch.float32 or argmax.dtype != torch.int32 or not conf.is_contiguous() or not argmax.is_contiguous():
+        raise TypeError("conf must be contiguous float32 and argmax contiguous int32")
+    if tuple(conf.shape) != (B, L - resp_off) or tuple(argmax.shape) != (B, L - resp_off):
+        raise ValueError("conf / argmax must have shape [B, L - resp_off]")
+    if out is None:
+        out = torch.empty((B,), dtype=torch.int32, device=tokens.device)
+    _check(lib().odb_predict_length(model, _dev_i32(tokens), conf.data_ptr(), argmax.data_ptr(), B, L, resp_off, eos_id,
+                                    truncate_thr, out.data_ptr(), _stream()))
+    return out
 
 
 def odb_block_step(model: int, cache: int, drafts, block_off: int, tau: float, conf=None, argmax=None, unmask=None):

@@ -666,6 +666,21 @@ int odb_profile_end(odb_model *mh, int *n_launches, float *total_ms) {
     return ODB_OK;
 }
 
+int odb_predict_length(const odb_model *mh, const int32_t *tokens, const float *conf, const int32_t *argmax, int batch,
+                       int L, int resp_off, int eos_id, float truncate_thr, int32_t *new_len, void *stream) {
+    if (!mh || !tokens || !conf || !argmax || !new_len) return fail(ODB_E_INVALID_ARG, "predict_length: NULL argument");
+    const Model &m = mh->m;
+    if (batch < 1 || L < 1) return fail(ODB_E_INVALID_ARG, "predict_length: batch=%d, L=%d", batch, L);
+    if (resp_off < 0 || resp_off >= L) return fail(ODB_E_INVALID_ARG, "predict_length: resp_off=%d outside [0, %d)", resp_off, L);
+    if (eos_id < 0 || eos_id >= m.cfg.vocab || eos_id == m.cfg.mask_id)
+        return fail(ODB_E_INVALID_ARG, "predict_length: eos_id=%d (vocab %d, MASK %d)", eos_id, m.cfg.vocab, m.cfg.mask_id);
+    HIP_TRY(hipSetDevice(m.device));
+    launch_predict_length(tokens, conf, argmax, batch, L, resp_off, m.cfg.mask_id, eos_id, truncate_thr, new_len,
+                          (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return ODB_OK;
+}
+
 int odb_cache_read(const odb_cache *ch, int layer, int kv, int batch_index, int pos0, int n, float *host_f32) {
     if (!ch || !host_f32) return fail(ODB_E_INVALID_ARG, "cache_read: NULL argument");
     const Cache &c = ch->c;

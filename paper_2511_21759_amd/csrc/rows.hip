@@ -86,4 +86,36 @@ void launch_lm_finish(const float *stats, int n_part, int rows, int rpu, int rpu
                                                  argmax, unmask);
 }
 
+// Adaptive length prediction (ODB-dLLM Sec. 4.1): one workgroup per sequence scans the response for the
+// earliest position whose drafted token is [EOS] - an attempted one (position still MASK) must exceed the
+// truncate threshold, a decoded one counts as it stands - and writes the length that keeps it as last position.
+__global__ __launch_bounds__(256) void predict_length_kernel(const int32_t *tokens, const float *conf,
+                                                             const int32_t *argmax, int L, int resp_off, int mask_id,
+                                                             int eos_id, float thr, int32_t *new_len) {
+    __shared__ int s_min[4];
+    const int b = blockIdx.x, R = L - resp_off;
+    const int32_t *tok = tokens + (size_t)b * L + resp_off;
+    const float *c = conf + (size_t)b * R;
+    const int32_t *a = argmax + (size_t)b * R;
+    int best = R;                                   // index of the earliest hit seen by this thread
+    for (int i = threadIdx.x; i < R; i += blockDim.x) {
+        const int t = tok[i];
+        const bool hit = t == mask_id ? (a[i] == eos_id && c[i] > thr) : t == eos_id;
+        if (hit) { best = i; break; }               // this thread's indices only grow
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) best = min(best, __shfl_xor(best, o));
+    if ((threadIdx.x & 63) == 0) s_min[threadIdx.x >> 6] = best;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        best = min(min(s_min[0], s_min[1]), min(s_min[2], s_min[3]));
+        new_len[b] = best < R ? resp_off + best + 1 : L;
+    }
+}
+
+void launch_predict_length(const int32_t *tokens, const float *conf, const int32_t *argmax, int batch, int L,
+                           int resp_off, int mask_id, int eos_id, float thr, int32_t *new_len, hipStream_t s) {
+    predict_length_kernel<<<dim3(batch), 256, 0, s>>>(tokens, conf, argmax, L, resp_off, mask_id, eos_id, thr, new_len);
+}
+
 }  // namespace odb

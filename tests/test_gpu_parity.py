@@ -336,3 +336,63 @@ def test_error_paths(tiny):
     with pytest.raises(B.OdbError):
         B.odb_cache_create(tiny.model, 0, 16)
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ adaptive length prediction (Sec. 4.1)
+
+def test_predict_length_bit_exact_on_random_attempts(tiny):
+    """Integer work: the kernel's lengths equal the oracle's on the same (tokens, conf, argmax), bit for bit."""
+    rng = np.random.default_rng(11)
+    mask_id, V = tiny.cfg.mask_id, tiny.cfg.vocab
+    eos = 5
+    cases = [(1, 2, 1), (1, 64, 0), (3, 300, 17), (2, 1024 + 512, 512), (4, 777, 776), (5, 40, 39)]
+    for Bn, L, ro in cases:
+        for density in (0.0, 0.002, 0.05, 0.5):
+            R = L - ro
+            tokens = rng.integers(0, V - 1, (Bn, L)).astype(np.int32)
+            tokens[tokens == eos] = eos + 1
+            resp = tokens[:, ro:]
+            resp[rng.random((Bn, R)) < 0.6] = mask_id
+            resp[(rng.random((Bn, R)) < density / 4) & (resp != mask_id)] = eos        # decoded [EOS]
+            conf = rng.random((Bn, R)).astype(np.float32)
+            am = rng.integers(0, V, (Bn, R)).astype(np.int32)
+            am[rng.random((Bn, R)) < density] = eos
+            thr = float(rng.choice([0.0, 0.5, 0.9]))
+            conf[0, rng.integers(0, R)] = thr                                           # equality is not "exceeds"
+            got = B.odb_predict_length(tiny.model, cuda_i32(tokens), torch.from_numpy(conf).cuda(), cuda_i32(am), ro,
+                                       eos, thr).cpu().numpy()
+            want = [o.predict_length(tokens[b], conf[b], am[b], ro, mask_id, eos, thr) for b in range(Bn)]
+            assert np.array_equal(got, np.array(want, np.int32)), (Bn, L, ro, density, got, want)
+    with pytest.raises(B.OdbError):
+        B.odb_predict_length(tiny.model, cuda_i32(np.zeros((1, 8))), torch.zeros((1, 4)).cuda(),
+                             cuda_i32(np.zeros((1, 4))), 4, mask_id, 0.5)              # [EOS] may not be the MASK id
+    with pytest.raises(B.OdbError):
+        B.odb_predict_length(tiny.model, cuda_i32(np.zeros((1, 8))), torch.zeros((1, 4)).cuda(),
+                             cuda_i32(np.zeros((1, 4))), 4, V, 0.5)
+
+
+def test_refresh_then_length_prediction_matches_the_oracle_chain(tiny):
+    """odb_prefill -> odb_predict_length against oracle prefill -> oracle predict_length.  [EOS] is taken to be
+    the token the refresh attempts at a masked position in the middle of the response, and the threshold is put
+    below that attempt's confidence, away from the confidence of every attempt at the same token (so that
+    rounding cannot move one across it); then the refresh is repeated on the shortened sequence, as the scheme does."""
+    wl = W.decode_workload(tiny.shape, 100, 156, 16, 1, 4242)
+    tokens, ro = wl.tokens, wl.resp_off
+    for _ in range(2):
+        L = tokens.shape[1]
+        cache = tiny.cache(1, L)
+        tg = cuda_i32(tokens)
+        conf, am = B.odb_prefill(tiny.model, cache, tg, ro)
+        _, conf_o, am_o, _ = o.prefill(tiny.cfg, tiny.w, tokens[0], ro, return_logits=True)
+        masked = np.flatnonzero(tokens[0, ro:] == tiny.cfg.mask_id)
+        masked = masked[am_o[masked] != tiny.cfg.mask_id]
+        p_star = int(masked[(6 * masked.size) // 10])
+        eos = int(am_o[p_star])
+        cs = conf_o[masked[am_o[masked] == eos]]
+        thr = next(f * conf_o[p_star] for f in (0.7, 0.6, 0.8, 0.5) if np.abs(np.log(cs / (f * conf_o[p_star]))).min() > 4e-3)
+        got = int(B.odb_predict_length(tiny.model, tg, conf, am, ro, eos, float(thr)).cpu().numpy()[0])
+        want = o.predict_length(tokens[0], conf_o, am_o, ro, tiny.cfg.mask_id, eos, float(thr))
+        same_inputs = o.predict_length(tokens[0], conf.cpu().numpy()[0], am.cpu().numpy()[0], ro, tiny.cfg.mask_id, eos, float(thr))
+        assert got == same_inputs                      # the scan itself: bit-exact on identical inputs
+        assert got == want and ro < got <= ro + p_star + 1      # the whole chain: GPU refresh vs oracle refresh
+        tokens = tokens[:, :got].copy()
