@@ -18,19 +18,6 @@ namespace odb {
 template <int DH, int NS>
 constexpr int attn_rows_smem_bytes() { return NS * (2 * (DH / 32) + DH / 16) * 1024; }
 
-// s_waitcnt vmcnt(n) for a run-time n (the instruction takes an immediate)
-__device__ __forceinline__ void wait_vmcnt(int n) {
-    switch (n) {
-#define ODB_VMCNT_CASE(N) case N: asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory"); break;
-        ODB_VMCNT_CASE(1) ODB_VMCNT_CASE(2) ODB_VMCNT_CASE(3) ODB_VMCNT_CASE(4) ODB_VMCNT_CASE(5) ODB_VMCNT_CASE(6)
-        ODB_VMCNT_CASE(7) ODB_VMCNT_CASE(8) ODB_VMCNT_CASE(9) ODB_VMCNT_CASE(10) ODB_VMCNT_CASE(11) ODB_VMCNT_CASE(12)
-        ODB_VMCNT_CASE(13) ODB_VMCNT_CASE(14) ODB_VMCNT_CASE(15) ODB_VMCNT_CASE(16) ODB_VMCNT_CASE(18) ODB_VMCNT_CASE(20)
-        ODB_VMCNT_CASE(24) ODB_VMCNT_CASE(28)
-#undef ODB_VMCNT_CASE
-        default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;      // also every count not listed: waits for more
-    }
-}
-
 // Requires tiles_per_unit % QTW == 0 when there are fresh keys (a wave's tiles then belong to one draft).
 // PIPE: fetch K of tile i+1 from LDS while P*V of tile i is issued.
 // DUAL: a second code path without key masks for tiles whose 32 keys are all visible (fewer VALU operations;

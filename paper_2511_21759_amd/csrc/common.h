@@ -61,4 +61,17 @@ __device__ inline f32x4 mfma16(const frag_t &x, const frag_t &y, f32x4 acc) {
         __builtin_bit_cast(f16x8, x), __builtin_bit_cast(f16x8, y), acc, 0, 0, 0);
 }
 
+// s_waitcnt vmcnt(n) for a run-time n (the instruction takes an immediate)
+__device__ __forceinline__ void wait_vmcnt(int n) {
+    switch (n) {
+#define ODB_VMCNT_CASE(N) case N: asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory"); break;
+        ODB_VMCNT_CASE(1) ODB_VMCNT_CASE(2) ODB_VMCNT_CASE(3) ODB_VMCNT_CASE(4) ODB_VMCNT_CASE(5) ODB_VMCNT_CASE(6)
+        ODB_VMCNT_CASE(7) ODB_VMCNT_CASE(8) ODB_VMCNT_CASE(9) ODB_VMCNT_CASE(10) ODB_VMCNT_CASE(11) ODB_VMCNT_CASE(12)
+        ODB_VMCNT_CASE(13) ODB_VMCNT_CASE(14) ODB_VMCNT_CASE(15) ODB_VMCNT_CASE(16) ODB_VMCNT_CASE(18) ODB_VMCNT_CASE(20)
+        ODB_VMCNT_CASE(24) ODB_VMCNT_CASE(28)
+#undef ODB_VMCNT_CASE
+        default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;      // also every count not listed: waits for more
+    }
+}
+
 }  // namespace odb

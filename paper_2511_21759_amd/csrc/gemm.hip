@@ -58,34 +58,54 @@ static void launch_tile(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi
     }
 }
 
-// 256 rows and more: 256 x 256 blocks through LDS (gemm_big.h)
-template <class Epi>
-static void launch_big(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi e, hipStream_t s) {
+// 256 rows and more: 256-row blocks through LDS (gemm_big.h), 64 * WN columns wide
+template <int WN, class Epi>
+static void launch_big_wn(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi e, hipStream_t s) {
     BigArgs g;
     g.A = a; g.W = w; g.KT = sh.K_tiles; g.MT_total = sh.M_tiles; g.NT = sh.N_tiles;
     g.ssq = ni.ssq; g.n_ssq = ni.n_ssq; g.eps = ni.eps; g.inv_d = 1.0f / (float)(sh.K_tiles * 32);
     g.m_blocks = (sh.M_tiles + 15) / 16;
-    g.n_blocks = (sh.N_tiles + 15) / 16;
+    g.n_blocks = (sh.N_tiles + 4 * WN - 1) / (4 * WN);
     static bool attr_set = false;           // once per instantiation: the ring needs more than the default 64 KiB
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_big_kernel<Epi>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, kBigSmemBytes);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_big_kernel<WN, Epi>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, big_smem_bytes(WN));
         attr_set = true;
     }
     dim3 grid(8 * g.m_blocks * ((g.n_blocks + 7) / 8));
-    gemm_big_kernel<Epi><<<grid, 512, kBigSmemBytes, s>>>(g, e);
+    gemm_big_kernel<WN, Epi><<<grid, 512, big_smem_bytes(WN), s>>>(g, e);
 }
-// Used from 256 rows on where the 256 x 256 blocks fill the compute units well: with T blocks on 256 units
-// the launch takes ceil(T / 256) block-times, so it pays when the useful share of those block slots (counting
-// a ragged last row block by its real rows) is at least 70 %.  Measured at the 8B shape: 1024 rows QKV 130 us
-// against 166 us for the tile kernel, gate/up equal, LM head 490 against 650; at 640 rows (47 % useful)
-// the tile kernel wins by a third.  The O and down projections (64 blocks at 1024 rows) stay with the tile kernel.
-static bool use_big(GemmShape sh) {
-    if (sh.M_tiles < 16 || sh.N_tiles < 32) return false;
-    const int blocks = ((sh.M_tiles + 15) / 16) * ((sh.N_tiles + 15) / 16);
-    const int rounds = (blocks + kStreamWGs - 1) / kStreamWGs;
-    const double useful = (sh.M_tiles / 16.0) * (sh.N_tiles / 16.0) / ((double)rounds * kStreamWGs);
-    return useful >= 0.7;
+
+// Block width for the 256-row kernel, or 0 when the tile kernel should run instead.  With T blocks on 256
+// compute units a launch takes ceil(T / 256) block-times, and a block-time hardly depends on the block's
+// width (measured on one GPU, 1024 rows: 256 and 192 columns within 3 %, 128 columns 30 % slower - the
+// k-step is bound by its barrier and operand delivery, not by its MFMAs).  So the widest block is taken whose
+// block slots are at least 70 % useful (a ragged last row block counts by its real rows); a narrower one
+// only if it needs fewer rounds.  Below 70 % for every width the 128-row tile kernel wins (measured at 640
+// rows).  The O and down projections (N = 4096) stay with the tile kernel.
+static int big_width(GemmShape sh) {
+    if (sh.M_tiles < 16 || sh.N_tiles < 32) return 0;
+    const double rel[5] = {0, 0, 1.3, 1.0, 1.0};
+    int best = 0;
+    double best_cost = 0;
+    for (int wn = 4; wn >= 2; wn--) {
+        const int blocks = ((sh.M_tiles + 15) / 16) * ((sh.N_tiles + 4 * wn - 1) / (4 * wn));
+        const int rounds = (blocks + kStreamWGs - 1) / kStreamWGs;
+        const double useful = (sh.M_tiles / 16.0) * (sh.N_tiles / (4.0 * wn)) / ((double)rounds * kStreamWGs);
+        const double cost = rounds * rel[wn];
+        if (useful >= 0.7 && (best == 0 || cost < best_cost - 1e-9)) { best = wn; best_cost = cost; }
+    }
+    return best;
+}
+static bool use_big(GemmShape sh) { return big_width(sh) != 0; }
+
+template <class Epi>
+static void launch_big(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi e, hipStream_t s) {
+    switch (big_width(sh)) {
+        case 2: launch_big_wn<2>(a, w, sh, ni, e, s); break;
+        case 3: launch_big_wn<3>(a, w, sh, ni, e, s); break;
+        default: launch_big_wn<4>(a, w, sh, ni, e, s); break;
+    }
 }
 
 void launch_gemm_qkv(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, QkvOut out, Workspace ws, hipStream_t s) {
@@ -118,7 +138,7 @@ int lm_stats_parts(int n_tiles, int m_tiles) {
         const int groups = (n_tiles + kLmNG - 1) / kLmNG;
         return (groups < kStreamWGs ? groups : kStreamWGs) * kLmNG;
     }
-    if (use_big(GemmShape{m_tiles, n_tiles, 0})) return (n_tiles + 15) / 16;
+    if (const int wn = big_width(GemmShape{m_tiles, n_tiles, 0})) return (n_tiles + 4 * wn - 1) / (4 * wn);
     const TileCfg c = tile_cfg(m_tiles);
     return (n_tiles + c.nw * c.ngw - 1) / (c.nw * c.ngw);
 }

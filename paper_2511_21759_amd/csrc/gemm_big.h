@@ -2,11 +2,12 @@
 // the cache-refresh prefill, the batched long-context step).  Same operand layouts and epilogues
 // as gemm_core.h / gemm_tile.h.
 //
-// A workgroup of eight waves computes a 256 x 256 block of C over all of K.  Per k-tile it needs
-// sixteen 1 KiB tiles of A and sixteen of W; they are copied from global memory straight into LDS
+// A workgroup of eight waves computes a 256 x (64 WN) block of C over all of K, WN = 4, 3 or 2 (256, 192 or
+// 128 columns: the narrower blocks exist for shapes whose count of 256-wide blocks fills the compute units
+// badly).  Per k-tile it needs sixteen 1 KiB tiles of A and 4 WN of W; they are copied from global memory straight into LDS
 // (global_load ... lds, no registers in between) into a ring of four stages, three k-tiles ahead of
 // the MFMAs, so one barrier per k-tile is the only synchronisation.  The waves form a 2 x 4 grid,
-// each owning 8 x 4 output tiles: per k-tile a wave reads 12 operand tiles from LDS for 32 MFMAs,
+// each owning 8 x WN output tiles: per k-tile a wave reads 8 + WN operand tiles from LDS for 8 WN MFMAs,
 // one k-tile ahead into a second register set, so LDS traffic and MFMAs overlap within a wave.
 // Operand bytes per flop are half those of the 128-row tile kernel, which is what matters here:
 // a re-read that misses the 4 MiB L2 of an XCD is served at HBM-like bandwidth (about 7 TB/s measured
@@ -18,9 +19,11 @@
 
 namespace odb {
 
-constexpr int kBigStages = 4;
-constexpr int kBigStageBytes = 32 * 1024;                                   // 16 A tiles + 16 W tiles
-constexpr int kBigSmemBytes = kBigStages * kBigStageBytes + 8 * 1024 + 256 * 4;   // ring, per-wave scratch, row scales
+// ring stages for a block 64 * WN columns wide (16 + 4 WN KiB of a 32 KiB slot per stage).  Four for every
+// width: three and five measured within 3 % of it on the same GPU (differences between GPUs of the pool are larger).
+constexpr int big_stages(int) { return 4; }
+constexpr int big_stage_bytes(int) { return 32 * 1024; }       // every width uses 32 KiB slots (narrower slots measured slower)
+constexpr int big_smem_bytes(int wn) { return big_stages(wn) * big_stage_bytes(wn) + 8 * 1024 + 256 * 4; }   // ring, per-wave scratch, row scales
 
 struct BigArgs {
     const u16 *A, *W;
@@ -31,13 +34,15 @@ struct BigArgs {
     float eps, inv_d;
 };
 
-template <class Epi>
+template <int WN, class Epi>
 __global__ __launch_bounds__(512) void gemm_big_kernel(BigArgs g, Epi epi) {
+    static_assert(WN >= 2 && WN <= 4, "columns per wave, in 16-column tiles");
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    typedef frag_t stage_t[32][64];                                          // tiles 0..15: A, 16..31: W
+    constexpr int NS = big_stages(WN);
+    typedef frag_t stage_t[32][64];                                          // tiles 0..15: A, 16..16+4*WN-1: W
     stage_t *ring = reinterpret_cast<stage_t *>(smem);
-    f32x4 (*scr)[64] = reinterpret_cast<f32x4 (*)[64]>(smem + kBigStages * kBigStageBytes);   // [8 waves][64]
-    float *s_rstd = reinterpret_cast<float *>(smem + kBigStages * kBigStageBytes + 8 * 1024);
+    f32x4 (*scr)[64] = reinterpret_cast<f32x4 (*)[64]>(smem + NS * big_stage_bytes(WN));   // [8 waves][64]
+    float *s_rstd = reinterpret_cast<float *>(smem + NS * big_stage_bytes(WN) + 8 * 1024);
 
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int wm = w >> 2, wn = w & 3;                   // position of the wave in the 2 x 4 grid
@@ -47,11 +52,12 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(BigArgs g, Epi epi) {
     const int xcd = blockIdx.x % 8, jx = blockIdx.x / 8;
     const int nb = (jx / g.m_blocks) * 8 + xcd, mb = jx % g.m_blocks;
     if (nb >= g.n_blocks) return;
-    const int mt0 = mb * 16, nt0 = nb * 16;
+    const int mt0 = mb * 16, nt0 = nb * 4 * WN;
 
-    // this wave copies tiles 4w .. 4w+3 of every stage: waves 0-3 rows of A, waves 4-7 rows of W
+    // waves 0-3 copy four tiles of A each into every stage, waves 4-7 WN tiles of W each
     const u16 *src[4];
     size_t kstride;
+    const int per = w < 4 ? 4 : WN, slot0 = w < 4 ? 4 * w : 16 + (w - 4) * WN;
     if (w < 4) {
 #pragma unroll
         for (int i = 0; i < 4; i++) {
@@ -63,7 +69,7 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(BigArgs g, Epi epi) {
     } else {
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            int nt = nt0 + 4 * (w - 4) + i;
+            int nt = nt0 + WN * (w - 4) + (i < WN ? i : WN - 1);
             nt = nt < g.NT ? nt : g.NT - 1;
             src[i] = g.W + (size_t)nt * g.KT * kTileElems + lane * 8;
         }
@@ -72,22 +78,26 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(BigArgs g, Epi epi) {
     auto issue = [&](int slot, int k) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < 4; i++)
-            __builtin_amdgcn_global_load_lds(reinterpret_cast<const void *>(src[i] + (size_t)k * kstride),
-                                             (__attribute__((address_space(3))) void *)(&ring[slot][4 * w + i][0]),
-                                             16, 0, 0);
+            if (i < per)
+                __builtin_amdgcn_global_load_lds(reinterpret_cast<const void *>(src[i] + (size_t)k * kstride),
+                                                 (__attribute__((address_space(3))) void *)(&ring[slot][slot0 + i][0]),
+                                                 16, 0, 0);
     };
 
     const int nk = g.KT;
-    issue(0, 0);
-    if (nk > 1) issue(1, 1);
-    if (nk > 2) issue(2, 2);
+#pragma unroll
+    for (int j = 0; j < NS - 1; j++)
+        if (j < nk) issue(j, j);
 
     // Row scales of the fused RMSNorm, 32 rows per wave in two halves.  A row's partial sums (up to 256)
     // are one 16-byte load per lane, the loads of 16 rows are in flight together (behind the ring's first
-    // stages), and the 64 lane-sums of each row are added through the still unused fourth slot of the
+    // stages), and the 64 lane-sums of each row are added through the still unused last slot of the
     // ring: written rotated by the row number, so that the transposed gather is free of bank conflicts.
     if (g.ssq) {
-        float *tmp = reinterpret_cast<float *>(&ring[3][0][0]) + w * (16 * 64);
+        // (32 KiB from the start of the last slot: for the narrower blocks this runs on into the per-wave
+        // scratch behind the ring, which is not in use yet, and ends before the row scales)
+        static_assert(big_stage_bytes(WN) + 8 * 1024 >= 8 * 16 * 64 * 4, "room for the row-scale scratch");
+        float *tmp = reinterpret_cast<float *>(&ring[NS - 1][0][0]) + w * (16 * 64);
         const int si = 4 * lane, sic = si < g.n_ssq - 4 ? si : g.n_ssq - 4;
 #pragma unroll
         for (int half = 0; half < 2; half++) {
@@ -122,45 +132,43 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(BigArgs g, Epi epi) {
         s_rstd[w * 32 + lane] = 1.0f;
     }
 
-    f32x4 acc[8][4];
+    f32x4 acc[8][WN];
 #pragma unroll
     for (int m = 0; m < 8; m++)
 #pragma unroll
-        for (int j = 0; j < 4; j++) acc[m][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < WN; j++) acc[m][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // Software pipeline over the k-tiles.  In iteration k a wave first fetches the operand tiles of stage
     // k+1 from LDS into the second register set and then issues the MFMAs of stage k, so the LDS reads of
-    // all waves run under the MFMAs instead of in a phase of their own after each barrier.  Stage k+3 is
-    // requested from global memory in iteration k, into the slot whose tiles fed the MFMAs of k-1.
-    static_assert(kBigStages == 4, "slot arithmetic and counted waits below");
-    frag_t a[2][8], b[2][4];
+    // all waves run under the MFMAs instead of in a phase of their own after each barrier.  Stage k+NS-1
+    // is requested from global memory in iteration k, into the slot whose tiles fed the MFMAs of k-1.
+    static_assert(NS >= 3 && (NS - 2) * 4 <= 16, "slot arithmetic and counted waits below");
+    frag_t a[2][8], b[2][WN];
     auto fetch = [&](auto P, int k) __attribute__((always_inline)) {
         constexpr int p = decltype(P)::value;
-        const stage_t &st = ring[k % kBigStages];
+        const stage_t &st = ring[k % NS];
 #pragma unroll
-        for (int j = 0; j < 4; j++) b[p][j] = st[16 + wn * 4 + j][lane];
+        for (int j = 0; j < WN; j++) b[p][j] = st[16 + wn * WN + j][lane];
 #pragma unroll
         for (int m = 0; m < 8; m++) a[p][m] = st[wm * 8 + m][lane];
     };
     auto step = [&](auto P, int k) __attribute__((always_inline)) {
         constexpr int p = decltype(P)::value;
         if (k + 1 < nk) {
-            // stage k+1 has landed once every wave's four loads of it are done (stage k+2's may be in flight)
-            if (k + 2 < nk) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            // stage k+1 has landed once every wave's copies of it are done (those of stages k+2 .. k+NS-2 may be in flight)
+            const int last = k + NS - 2 < nk - 1 ? k + NS - 2 : nk - 1;
+            wait_vmcnt(per * (last - (k + 1)));
             __builtin_amdgcn_s_barrier();
-            if (k + 3 < nk) issue((k + 3) % kBigStages, k + 3);
+            if (k + NS - 1 < nk) issue((k + NS - 1) % NS, k + NS - 1);
             fetch(std::integral_constant<int, 1 - p>{}, k + 1);
         }
 #pragma unroll
         for (int m = 0; m < 8; m++)
 #pragma unroll
-            for (int j = 0; j < 4; j++) acc[m][j] = mfma16(b[p][j], a[p][m], acc[m][j]);
+            for (int j = 0; j < WN; j++) acc[m][j] = mfma16(b[p][j], a[p][m], acc[m][j]);
     };
     // stage 0 has landed (everything issued so far has: the row-scale loads came after the ring's)
-    if (g.ssq || nk == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    else if (nk > 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    wait_vmcnt(g.ssq ? 0 : per * ((nk < NS - 1 ? nk : NS - 1) - 1));
     __syncthreads();            // also orders the row-scale scratch before stage 3 reuses its slot
     fetch(std::integral_constant<int, 0>{}, 0);
     for (int k = 0; k < nk; k += 2) {
@@ -170,7 +178,7 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(BigArgs g, Epi epi) {
     __syncthreads();            // the ring is reused below; also publishes s_rstd
 
     if constexpr (is_row_stats<Epi>::value) {
-        // softmax statistics per row over this workgroup's 256 columns: lane-local, across the four lane
+        // softmax statistics per row over this workgroup's columns: lane-local, across the four lane
         // groups, across the wave's four tiles, then across the four waves of a row half through LDS
         float *st_m = reinterpret_cast<float *>(smem);               // [4 column waves][256 rows]
         float *st_s = st_m + 4 * 256;
@@ -182,8 +190,8 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(BigArgs g, Epi epi) {
             float rm = -INFINITY, rs = 0.f;
             int ra = 0x7fffffff;
 #pragma unroll
-            for (int j = 0; j < 4; j++) {
-                const int nt = nt0 + wn * 4 + j;
+            for (int j = 0; j < WN; j++) {
+                const int nt = nt0 + wn * WN + j;
                 if (nt < g.NT) {
                     f32x4 c = acc[m][j] * s_rstd[r];
                     float cm = c[0];
@@ -227,8 +235,8 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(BigArgs g, Epi epi) {
 #pragma unroll
         for (int m = 0; m < 8; m++)
 #pragma unroll
-            for (int j = 0; j < 4; j++) {
-                const int mt = mt0 + wm * 8 + m, nt = nt0 + wn * 4 + j;
+            for (int j = 0; j < WN; j++) {
+                const int mt = mt0 + wm * 8 + m, nt = nt0 + wn * WN + j;
                 if (mt < g.MT_total && nt < g.NT) {
                     const float *rsd = s_rstd + (wm * 8 + m) * 16;
                     f32x4 c;
