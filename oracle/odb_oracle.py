@@ -15,7 +15,9 @@ What it follows (ODB-dLLM, arXiv 2511.21759):
     and accepted when their confidence exceeds a threshold.
   * Sec. 4.2 (jump-share speculative decoding): speculative copies of the block
     (drafts) see the cached context and themselves, never each other, and keep
-    the position ids of the block they shadow (Fig. 8 caption).
+    the position ids of the block they shadow (Fig. 8 caption).  Sec. 4.2.1
+    (accept-jump): which draft's result a step adopts and how the next drafts
+    are formed from its two most confident unaccepted positions.
 
 Arithmetic: float64 throughout, on weights whose values are exactly
 representable in bfloat16 (they are stored as bf16 bit patterns).  The model
@@ -305,6 +307,66 @@ def predict_length(tokens: np.ndarray, conf: np.ndarray, argmax: np.ndarray, res
         elif tokens[pos] == eos_id:
             return pos + 1
     return L
+
+
+def speculative_candidates(block: np.ndarray, conf: np.ndarray, argmax: np.ndarray, mask_id: int,
+                           k: int = 2) -> Tuple[np.ndarray, np.ndarray]:
+    """The k most confident positions of a block that are still MASK (Sec. 4.2: the top-k tokens among
+    those that fell below the acceptance threshold) and the tokens attempted there; lower index first on
+    equal confidence; position -1 (token 0) where fewer than k remain."""
+    pos = np.full(k, -1, np.int32)
+    tok = np.zeros(k, np.int32)
+    masked = [i for i in range(len(block)) if block[i] == mask_id]
+    masked.sort(key=lambda i: (-float(conf[i]), i))
+    for j, i in enumerate(masked[:k]):
+        pos[j], tok[j] = i, int(argmax[i])
+    return pos, tok
+
+
+def accept_jump_drafts(block: np.ndarray, cand_pos: np.ndarray, cand_tok: np.ndarray) -> np.ndarray:
+    """block_0 and the three speculative blocks of the accept-jump stage (Sec. 4.2.1): the block as it is,
+    with candidate B unmasked, with candidate D unmasked, with both.  A missing candidate (-1) adds nothing."""
+    drafts = np.stack([np.asarray(block, np.int32)] * 4)
+    for s, which in ((1, (0,)), (2, (1,)), (3, (0, 1))):
+        for c in which:
+            if cand_pos[c] >= 0:
+                drafts[s, cand_pos[c]] = cand_tok[c]
+    return drafts
+
+
+def accept_jump(drafts: np.ndarray, conf: np.ndarray, argmax: np.ndarray, unmask: np.ndarray,
+                cand_pos: np.ndarray, cand_tok: np.ndarray, mask_id: int):
+    """One controller step of the accept-jump strategy (Sec. 4.2.1) on the outputs of a 4-draft block step.
+
+    drafts/conf/argmax/unmask are [4, b]: block_0 (the block as it stood), block_1 (candidate B unmasked
+    beforehand), block_2 (D), block_3 (B and D).  A candidate counts as verified in a draft when that
+    draft's step unmasks its position with the very token that was speculated.
+      * B and D both verified in block_0          -> jump to block_3;
+      * only B verified in block_0                -> go to block_1; if D is verified there jump to block_3,
+                                                     otherwise adopt block_1;  (symmetrically for only D, block_2)
+      * neither                                   -> block_0.
+    Adopting a draft means taking its tokens plus every position its own step unmasked (with that step's
+    greedy token).  From the adopted draft's outputs the two most confident still-masked positions become
+    the next candidates and the next four drafts are built.
+
+    Returns (chosen, new_block[b], new_cand_pos[2], new_cand_tok[2], new_drafts[4, b]).
+    """
+    def verified(s, c):
+        p = int(cand_pos[c])
+        return p >= 0 and drafts[s, p] == mask_id and bool(unmask[s, p]) and int(argmax[s, p]) == int(cand_tok[c])
+
+    b0, d0 = verified(0, 0), verified(0, 1)
+    if b0 and d0:
+        chosen = 3
+    elif b0:
+        chosen = 3 if verified(1, 1) else 1
+    elif d0:
+        chosen = 3 if verified(2, 0) else 2
+    else:
+        chosen = 0
+    new_block = np.where(np.asarray(unmask[chosen], bool), argmax[chosen], drafts[chosen]).astype(np.int32)
+    pos, tok = speculative_candidates(new_block, conf[chosen], argmax[chosen], mask_id)
+    return chosen, new_block, pos, tok, accept_jump_drafts(new_block, pos, tok)
 
 
 # --------------------------------------------------------------------------- the two calls

@@ -509,3 +509,115 @@ def test_length_prediction_against_a_vectorised_restatement_on_random_inputs():
         hits = np.flatnonzero((draft == eos) & sure)
         want = ro + int(hits[0]) + 1 if hits.size else L
         assert o.predict_length(tokens, conf, am, ro, mask_id, eos, thr) == want
+
+
+# ------------------------------------------------------------------ accept-jump controller (Sec. 4.2.1)
+
+M_ = 99          # MASK id of the hand-built cases
+
+
+def _aj_inputs(block, cand_pos, cand_tok):
+    """Four drafts of `block` plus blank step outputs (nothing unmasked, confidence 0.1, attempt 50)."""
+    drafts = o.accept_jump_drafts(np.array(block, np.int32), np.array(cand_pos), np.array(cand_tok))
+    b = drafts.shape[1]
+    return drafts, np.full((4, b), 0.1), np.full((4, b), 50, np.int32), np.zeros((4, b), np.uint8)
+
+
+def test_accept_jump_drafts_and_candidates_by_hand():
+    block = [1, M_, M_, 4, M_, M_]
+    d = o.accept_jump_drafts(np.array(block, np.int32), np.array([2, 5]), np.array([70, 80]))
+    assert d.tolist() == [[1, M_, M_, 4, M_, M_], [1, M_, 70, 4, M_, M_], [1, M_, M_, 4, M_, 80], [1, M_, 70, 4, M_, 80]]
+    d = o.accept_jump_drafts(np.array(block, np.int32), np.array([2, -1]), np.array([70, 0]))
+    assert d[1].tolist() == d[3].tolist() == [1, M_, 70, 4, M_, M_] and d[2].tolist() == block
+    conf = np.array([0.99, 0.3, 0.8, 0.99, 0.8, 0.5])
+    am = np.array([10, 11, 12, 13, 14, 15], np.int32)
+    pos, tok = o.speculative_candidates(np.array(block), conf, am, M_)
+    assert pos.tolist() == [2, 4] and tok.tolist() == [12, 14]          # tie at 0.8: lower index first; decoded positions never
+    pos, tok = o.speculative_candidates(np.array([1, 2, M_, 4]), conf[:4], am[:4], M_)
+    assert pos.tolist() == [2, -1] and tok.tolist() == [12, 0]          # one MASK left
+    pos, tok = o.speculative_candidates(np.array([1, 2, 3, 4]), conf[:4], am[:4], M_)
+    assert pos.tolist() == [-1, -1]
+
+
+def test_accept_jump_branches_by_hand():
+    """Every branch of the rule, on inputs where the adopted draft is known by construction."""
+    block, cp, ct = [1, M_, M_, 4, M_, M_], [2, 5], [70, 80]
+
+    def run(setup):
+        drafts, conf, am, um = _aj_inputs(block, cp, ct)
+        setup(conf, am, um)
+        return o.accept_jump(drafts, conf, am, um, np.array(cp), np.array(ct), M_)
+
+    def accept(um, am, s, p, t):
+        um[s, p], am[s, p] = 1, t
+
+    # neither candidate is unmasked by block_0: block_0's own result (it unmasks position 1 here)
+    ch, nb, *_ = run(lambda c, a, u: accept(u, a, 0, 1, 33))
+    assert ch == 0 and nb.tolist() == [1, 33, M_, 4, M_, M_]
+    # both verified in block_0: jump to block_3, whose step unmasks position 4
+    def both(c, a, u):
+        accept(u, a, 0, 2, 70); accept(u, a, 0, 5, 80); accept(u, a, 3, 4, 44); accept(u, a, 0, 1, 33)
+    ch, nb, *_ = run(both)
+    assert ch == 3 and nb.tolist() == [1, M_, 70, 4, 44, 80]            # block_0's extra position 1 is not carried over
+    # only B verified, D fails in block_1: adopt block_1
+    def only_b(c, a, u):
+        accept(u, a, 0, 2, 70); accept(u, a, 1, 1, 21)
+    ch, nb, *_ = run(only_b)
+    assert ch == 1 and nb.tolist() == [1, 21, 70, 4, M_, M_]
+    # only B verified in block_0, D verified in block_1: jump to block_3
+    def b_then_d(c, a, u):
+        accept(u, a, 0, 2, 70); accept(u, a, 1, 5, 80); accept(u, a, 3, 1, 23)
+    ch, nb, *_ = run(b_then_d)
+    assert ch == 3 and nb.tolist() == [1, 23, 70, 4, M_, 80]
+    # only D verified in block_0, B fails in block_2 / succeeds in block_2
+    ch, nb, *_ = run(lambda c, a, u: accept(u, a, 0, 5, 80))
+    assert ch == 2 and nb.tolist() == [1, M_, M_, 4, M_, 80]
+    def d_then_b(c, a, u):
+        accept(u, a, 0, 5, 80); accept(u, a, 2, 2, 70)
+    assert run(d_then_b)[0] == 3
+    # a position unmasked with ANOTHER token than the speculated one does not verify the candidate
+    ch, nb, *_ = run(lambda c, a, u: accept(u, a, 0, 2, 71))
+    assert ch == 0 and nb.tolist() == [1, M_, 71, 4, M_, M_]
+    # no candidates at all (first step of a block): block_0
+    drafts, conf, am, um = _aj_inputs(block, [-1, -1], [0, 0])
+    um[0, 1], am[0, 1] = 1, 9
+    ch, nb, pos, tok, nd = o.accept_jump(drafts, conf, am, um, np.array([-1, -1]), np.array([0, 0]), M_)
+    assert ch == 0 and nb.tolist() == [1, 9, M_, 4, M_, M_]
+
+
+def test_accept_jump_next_drafts_and_invariants_on_random_inputs():
+    """Properties that any input must satisfy, and an independent restatement of the branch rule."""
+    rng = np.random.default_rng(9)
+    for trial in range(400):
+        b = int(rng.integers(2, 20))
+        block = rng.integers(0, 8, b).astype(np.int32)
+        block[rng.random(b) < 0.6] = M_
+        masked = np.flatnonzero(block == M_)
+        cp = np.full(2, -1, np.int32)
+        ct = rng.integers(0, 8, 2).astype(np.int32)
+        k = min(2, masked.size, int(rng.integers(0, 3)))
+        cp[:k] = rng.permutation(masked)[:k]
+        drafts = o.accept_jump_drafts(block, cp, ct)
+        conf = rng.random((4, b))
+        am = rng.integers(0, 8, (4, b)).astype(np.int32)
+        for c in range(2):                                   # make verification events common
+            if cp[c] >= 0:
+                am[:, cp[c]] = np.where(rng.random(4) < 0.7, ct[c], am[:, cp[c]])
+        um = ((rng.random((4, b)) < 0.4) & (drafts == M_)).astype(np.uint8)
+        ch, nb, pos, tok, nd = o.accept_jump(drafts, conf, am, um, cp, ct, M_)
+        ok = lambda s, c: cp[c] >= 0 and drafts[s, cp[c]] == M_ and um[s, cp[c]] == 1 and am[s, cp[c]] == ct[c]
+        want = {(True, True): 3, (False, False): 0}.get((ok(0, 0), ok(0, 1)))
+        if want is None:
+            want = (3 if ok(1, 1) else 1) if ok(0, 0) else (3 if ok(2, 0) else 2)
+        assert ch == want
+        src = drafts[ch]
+        assert np.array_equal(nb[um[ch] == 0], src[um[ch] == 0]) and np.array_equal(nb[um[ch] == 1], am[ch][um[ch] == 1])
+        assert np.array_equal(nd[0], nb)
+        still = np.flatnonzero(nb == M_)
+        assert all(p == -1 or nb[p] == M_ for p in pos) and (pos >= 0).sum() == min(2, still.size)
+        if (pos >= 0).all():
+            assert pos[0] != pos[1] and conf[ch][pos[0]] >= conf[ch][pos[1]]
+            assert all(conf[ch][q] <= conf[ch][pos[1]] for q in still if q not in pos)
+        for s, which in ((1, [0]), (2, [1]), (3, [0, 1])):
+            diff = np.flatnonzero(nd[s] != nb)
+            assert set(diff) <= {int(pos[c]) for c in which if pos[c] >= 0}
