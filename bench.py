@@ -1,7 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the block-decode step (and, on request, the cache-refresh prefill).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config1|config2|config3|config3_chain|config4]
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+                    [--workload config1|config2|config2_jump|config3|config3_chain|config4]
 
 One "step" is one pass of the whole hot path over one batch of synthetic input:
 odb_block_step on the 8B-shaped model against a prefilled cache (config1: S=1,
@@ -94,7 +95,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="config1", choices=["config0", "config1", "config2", "config3", "config3_chain", "config4"])
+    ap.add_argument("--workload", default="config1", choices=["config0", "config1", "config2", "config2_jump", "config3", "config3_chain", "config4"])
     ap.add_argument("--resp", type=int, default=512, help="response length for config3 (512, 256 or 128)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
@@ -155,7 +156,8 @@ def main():
         wl = None
         label = "cache-refresh prefill, 8B shape, 512 prompt + %d MASK, batch 1" % args.resp
     else:
-        wl = {"config0": W.config0, "config1": W.config1, "config2": W.config2, "config4": W.config4}[name]()
+        wl = {"config0": W.config0, "config1": W.config1, "config2": W.config2, "config2_jump": W.config2,
+              "config4": W.config4}[name]()
         Bn, L = wl.tokens.shape
         S, b = wl.drafts.shape[1:]
         cache = B.odb_cache_create(model, Bn, L)
@@ -166,6 +168,19 @@ def main():
         am = torch.empty((Bn, S, b), dtype=torch.int32, device="cuda")
         um = torch.empty((Bn, S, b), dtype=torch.uint8, device="cuda")
         run = lambda: B.odb_block_step(model, cache, drafts, wl.block_off, wl.tau, conf, am, um)
+        if name == "config2_jump":
+            # config 2's four drafts followed by the accept-jump controller (ODB-dLLM Sec. 4.2.1), which adopts a
+            # draft and builds the next four on the device; the candidates are the two positions that drafts 1
+            # and 2 of the workload unmask.  Timed with fixed inputs: one iteration of the loop.
+            d0 = wl.drafts[0]
+            cpos = [int(np.flatnonzero(d0[s] != d0[0])[0]) if (d0[s] != d0[0]).any() else -1 for s in (1, 2)]
+            cand_pos = torch.tensor([cpos], dtype=torch.int32, device="cuda")
+            cand_tok = torch.tensor([[int(d0[1][cpos[0]]) if cpos[0] >= 0 else 0,
+                                      int(d0[2][cpos[1]]) if cpos[1] >= 0 else 0]], dtype=torch.int32, device="cuda")
+
+            def run():
+                B.odb_block_step(model, cache, drafts, wl.block_off, wl.tau, conf, am, um)
+                B.odb_accept_jump(model, drafts, conf, am, um, cand_pos, cand_tok)
         rows = Bn * S * b
         flops = step_flops(shape, rows, L)
         alg_bytes = total_w + Bn * (L - b) * kv_bytes_per_pos(shape)

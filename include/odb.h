@@ -184,6 +184,33 @@ int odb_predict_length(const odb_model *m, const int32_t *tokens_dev, const floa
                        const int32_t *argmax_dev, int batch, int L, int resp_off, int eos_id,
                        float truncate_thr, int32_t *new_len_dev, void *stream);
 
+/* Accept-jump controller (ODB-dLLM Sec. 4.2.1): decides which of the four drafts of
+ * the last block step is adopted and builds the drafts of the next one, on the device.
+ * The step ran on drafts[.,0] = block_0 (the block as it stood), [.,1] = block_0 with
+ * candidate B unmasked beforehand, [.,2] = with candidate D, [.,3] = with both
+ * (cand_pos / cand_tok: position inside the block and speculated token of B and D;
+ * position -1 = no such candidate, as in the first step of a block).  A candidate is
+ * verified in a draft when that draft's step unmasks its position with exactly the
+ * speculated token.  Both verified in block_0: block_3 is adopted.  Only one: the draft
+ * that had it unmasked beforehand is taken, and block_3 instead if the other candidate is
+ * verified there.  Neither: block_0.  Adopting a draft = its tokens plus every position
+ * its own step unmasked (with that step's greedy token); that is new_drafts[.,0].  The
+ * next candidates are the two most confident positions of the adopted draft that are
+ * still MASK afterwards (lower index first on equal confidence; -1 / token 0 if fewer
+ * remain), their tokens that draft's greedy tokens, and new_drafts[.,1..3] unmask them.
+ *   drafts_dev, argmax_dev  device int32 [batch, 4, b]     inputs / outputs of odb_block_step
+ *   conf_dev device float [batch, 4, b], unmask_dev device uint8 [batch, 4, b]
+ *   cand_pos_dev, cand_tok_dev       device int32 [batch, 2]
+ *   chosen_dev device int32 [batch] (0..3), new_drafts_dev device int32 [batch, 4, b],
+ *   new_cand_pos_dev, new_cand_tok_dev device int32 [batch, 2]             written
+ * Output buffers must not overlap input buffers.  Asynchronous on `stream`; all buffers
+ * are the caller's.  Errors: ODB_E_INVALID_ARG for NULL pointers, batch < 1, b < 1. */
+int odb_accept_jump(const odb_model *m, const int32_t *drafts_dev, const float *conf_dev,
+                    const int32_t *argmax_dev, const uint8_t *unmask_dev,
+                    const int32_t *cand_pos_dev, const int32_t *cand_tok_dev, int batch, int b,
+                    int32_t *chosen_dev, int32_t *new_drafts_dev, int32_t *new_cand_pos_dev,
+                    int32_t *new_cand_tok_dev, void *stream);
+
 /* Copies cached K (kv = 0, post-RoPE, logical channel order) or V (kv = 1) of
  * positions pos0 .. pos0+n-1 of one sequence and layer to host memory as
  * float [n, n_heads, head_dim].  Synchronous (device-wide). */

@@ -22,7 +22,7 @@ SYMBOLS = (
     "odb_model_get_tensor", "odb_cache_create", "odb_cache_destroy", "odb_cache_length", "odb_prefill",
     "odb_block_step", "odb_prefill_logits", "odb_block_step_logits", "odb_cache_read", "odb_strerror",
     "odb_last_error", "odb_profile_begin", "odb_profile_end", "odb_set_step_mode", "odb_model_status",
-    "odb_debug_step_trace", "odb_predict_length",
+    "odb_debug_step_trace", "odb_predict_length", "odb_accept_jump",
 )
 
 KERNEL_CLASSES = ("gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "rmsnorm",
@@ -76,6 +76,7 @@ def lib() -> ctypes.CDLL:
     L.odb_profile_begin.argtypes = [vp, ci, ci]
     L.odb_profile_end.argtypes = [vp, ctypes.POINTER(ci), ctypes.POINTER(cf)]
     L.odb_predict_length.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, cf, vp, vp]
+    L.odb_accept_jump.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, vp, vp, vp, vp, vp]
     L.odb_set_step_mode.argtypes = [vp, ci]
     L.odb_model_status.argtypes = [vp]
     L.odb_debug_step_trace.argtypes = [vp, vp, ci]
@@ -172,6 +173,28 @@ def odb_predict_length(model: int, tokens, conf, argmax, resp_off: int, eos_id: 
     _check(lib().odb_predict_length(model, _dev_i32(tokens), conf.data_ptr(), argmax.data_ptr(), B, L, resp_off, eos_id,
                                     truncate_thr, out.data_ptr(), _stream()))
     return out
+
+
+def odb_accept_jump(model: int, drafts, conf, argmax, unmask, cand_pos, cand_tok):
+    """drafts/argmax int32, conf f32, unmask uint8: CUDA tensors [B, 4, b]; cand_pos/cand_tok int32 [B, 2]
+    -> (chosen int32 [B], new_drafts int32 [B, 4, b], new_cand_pos int32 [B, 2], new_cand_tok int32 [B, 2])."""
+    import torch
+    B, S, b = drafts.shape
+    if S != 4:
+        raise ValueError("the accept-jump stage runs on four drafts")
+    want = {"drafts": (drafts, torch.int32, (B, 4, b)), "conf": (conf, torch.float32, (B, 4, b)),
+            "argmax": (argmax, torch.int32, (B, 4, b)), "unmask": (unmask, torch.uint8, (B, 4, b)),
+            "cand_pos": (cand_pos, torch.int32, (B, 2)), "cand_tok": (cand_tok, torch.int32, (B, 2))}
+    for name, (t, dt, shp) in want.items():
+        if t.dtype != dt or tuple(t.shape) != shp or not t.is_contiguous() or not t.is_cuda:
+            raise TypeError("%s must be a contiguous CUDA tensor of dtype %s and shape %s" % (name, dt, shp))
+    chosen = torch.empty((B,), dtype=torch.int32, device=drafts.device)
+    new_drafts = torch.empty_like(drafts)
+    new_pos, new_tok = torch.empty_like(cand_pos), torch.empty_like(cand_tok)
+    _check(lib().odb_accept_jump(model, drafts.data_ptr(), conf.data_ptr(), argmax.data_ptr(), unmask.data_ptr(),
+                                 cand_pos.data_ptr(), cand_tok.data_ptr(), B, b, chosen.data_ptr(), new_drafts.data_ptr(),
+                                 new_pos.data_ptr(), new_tok.data_ptr(), _stream()))
+    return chosen, new_drafts, new_pos, new_tok
 
 
 def odb_block_step(model: int, cache: int, drafts, block_off: int, tau: float, conf=None, argmax=None, unmask=None):

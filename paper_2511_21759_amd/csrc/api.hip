@@ -666,6 +666,21 @@ int odb_profile_end(odb_model *mh, int *n_launches, float *total_ms) {
     return ODB_OK;
 }
 
+int odb_accept_jump(const odb_model *mh, const int32_t *drafts, const float *conf, const int32_t *argmax,
+                    const uint8_t *unmask, const int32_t *cand_pos, const int32_t *cand_tok, int batch, int b,
+                    int32_t *chosen, int32_t *new_drafts, int32_t *new_cand_pos, int32_t *new_cand_tok, void *stream) {
+    if (!mh || !drafts || !conf || !argmax || !unmask || !cand_pos || !cand_tok || !chosen || !new_drafts || !new_cand_pos ||
+        !new_cand_tok)
+        return fail(ODB_E_INVALID_ARG, "accept_jump: NULL argument");
+    if (batch < 1 || b < 1) return fail(ODB_E_INVALID_ARG, "accept_jump: batch=%d, b=%d", batch, b);
+    const Model &m = mh->m;
+    HIP_TRY(hipSetDevice(m.device));
+    launch_accept_jump(drafts, conf, argmax, unmask, cand_pos, cand_tok, batch, b, m.cfg.mask_id, chosen, new_drafts,
+                       new_cand_pos, new_cand_tok, (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return ODB_OK;
+}
+
 int odb_predict_length(const odb_model *mh, const int32_t *tokens, const float *conf, const int32_t *argmax, int batch,
                        int L, int resp_off, int eos_id, float truncate_thr, int32_t *new_len, void *stream) {
     if (!mh || !tokens || !conf || !argmax || !new_len) return fail(ODB_E_INVALID_ARG, "predict_length: NULL argument");

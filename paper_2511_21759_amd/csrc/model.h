@@ -80,6 +80,9 @@ void launch_embed(const Model &m, const int32_t *tokens, RowMap rm, float *h, No
 void launch_rmsnorm(const float *h, const float *gain, float eps, int d, RowMap rm, int skip, bool compact,
                     int dst_mt_total, u16 *xa, hipStream_t s);
 // stats rows come in units of rpu_pad rows of which the first rpu are real; the `rows` outputs are compact
+void launch_accept_jump(const int32_t *drafts, const float *conf, const int32_t *argmax, const uint8_t *unmask,
+                        const int32_t *cand_pos, const int32_t *cand_tok, int batch, int b, int mask_id, int32_t *chosen,
+                        int32_t *new_drafts, int32_t *new_cand_pos, int32_t *new_cand_tok, hipStream_t s);
 void launch_predict_length(const int32_t *tokens, const float *conf, const int32_t *argmax, int batch, int L,
                            int resp_off, int mask_id, int eos_id, float thr, int32_t *new_len, hipStream_t s);
 void launch_lm_finish(const float *stats, int n_part, int rows, int rpu, int rpu_pad, const int32_t *tokens,

@@ -113,6 +113,79 @@ __global__ __launch_bounds__(256) void predict_length_kernel(const int32_t *toke
     }
 }
 
+// Accept-jump controller (ODB-dLLM Sec. 4.2.1), one wave per sequence.  Inputs are the four drafts of a
+// block step (block_0; B unmasked; D unmasked; both) and that step's outputs.  A candidate is verified in a
+// draft when the draft's step unmasks its position with the speculated token.  Both verified in block_0 ->
+// block_3; only one -> the draft that had it unmasked beforehand, and on to block_3 if the other one is
+// verified there; neither -> block_0.  The adopted draft plus its step's unmaskings is the new block; its
+// two most confident still-masked positions (lower index first on ties) become the next candidates.
+struct Cand { float c; int i; };
+__device__ inline bool cand_better(Cand a, Cand b) { return a.c > b.c || (a.c == b.c && a.i < b.i); }
+__device__ inline void cand_push(Cand &x0, Cand &x1, Cand y) {         // keeps the two best, x0 the better
+    if (cand_better(y, x0)) { x1 = x0; x0 = y; }
+    else if (cand_better(y, x1)) x1 = y;
+}
+
+__global__ __launch_bounds__(64) void accept_jump_kernel(const int32_t *drafts, const float *conf, const int32_t *argmax,
+                                                         const uint8_t *unmask, const int32_t *cand_pos,
+                                                         const int32_t *cand_tok, int b, int mask_id, int32_t *chosen_out,
+                                                         int32_t *new_drafts, int32_t *new_cand_pos, int32_t *new_cand_tok) {
+    const int seq = blockIdx.x, lane = threadIdx.x;
+    const size_t base = (size_t)seq * 4 * b;
+    const int32_t *dr = drafts + base, *am = argmax + base;
+    const float *cf = conf + base;
+    const uint8_t *um = unmask + base;
+    const int p0 = cand_pos[seq * 2], p1 = cand_pos[seq * 2 + 1], t0 = cand_tok[seq * 2], t1 = cand_tok[seq * 2 + 1];
+    auto verified = [&](int s, int p, int t) {
+        return p >= 0 && p < b && dr[s * b + p] == mask_id && um[s * b + p] != 0 && am[s * b + p] == t;
+    };
+    const bool b0 = verified(0, p0, t0), d0 = verified(0, p1, t1);
+    int ch;
+    if (b0 && d0) ch = 3;
+    else if (b0) ch = verified(1, p1, t1) ? 3 : 1;
+    else if (d0) ch = verified(2, p0, t0) ? 3 : 2;
+    else ch = 0;
+
+    // the new block, and this lane's two best still-masked positions
+    const Cand none{-INFINITY, 0x7fffffff};
+    Cand x0 = none, x1 = none;
+    int32_t *nd = new_drafts + base;
+    for (int i = lane; i < b; i += 64) {
+        const int t = um[ch * b + i] ? am[ch * b + i] : dr[ch * b + i];
+        nd[i] = t;
+        if (t == mask_id) cand_push(x0, x1, Cand{cf[ch * b + i], i});
+    }
+    // the two best of the wave: butterfly over the lanes, every lane ends with the same pair
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        Cand y0{__shfl_xor(x0.c, o), __shfl_xor(x0.i, o)}, y1{__shfl_xor(x1.c, o), __shfl_xor(x1.i, o)};
+        cand_push(x0, x1, y0);
+        cand_push(x0, x1, y1);
+    }
+    const int q0 = x0.i != 0x7fffffff ? x0.i : -1, q1 = x1.i != 0x7fffffff ? x1.i : -1;
+    const int u0 = q0 >= 0 ? am[ch * b + q0] : 0, u1 = q1 >= 0 ? am[ch * b + q1] : 0;
+    if (lane == 0) {
+        chosen_out[seq] = ch;
+        new_cand_pos[seq * 2] = q0; new_cand_pos[seq * 2 + 1] = q1;
+        new_cand_tok[seq * 2] = u0; new_cand_tok[seq * 2 + 1] = u1;
+    }
+    // block_1 .. block_3 of the next step (each lane rewrites the positions it wrote above, so no lane reads
+    // another lane's stores)
+    for (int i = lane; i < b; i += 64) {
+        const int t = nd[i];
+        nd[b + i] = i == q0 ? u0 : t;
+        nd[2 * b + i] = i == q1 ? u1 : t;
+        nd[3 * b + i] = i == q0 ? u0 : (i == q1 ? u1 : t);
+    }
+}
+
+void launch_accept_jump(const int32_t *drafts, const float *conf, const int32_t *argmax, const uint8_t *unmask,
+                        const int32_t *cand_pos, const int32_t *cand_tok, int batch, int b, int mask_id, int32_t *chosen,
+                        int32_t *new_drafts, int32_t *new_cand_pos, int32_t *new_cand_tok, hipStream_t s) {
+    accept_jump_kernel<<<dim3(batch), 64, 0, s>>>(drafts, conf, argmax, unmask, cand_pos, cand_tok, b, mask_id, chosen,
+                                                  new_drafts, new_cand_pos, new_cand_tok);
+}
+
 void launch_predict_length(const int32_t *tokens, const float *conf, const int32_t *argmax, int batch, int L,
                            int resp_off, int mask_id, int eos_id, float thr, int32_t *new_len, hipStream_t s) {
     predict_length_kernel<<<dim3(batch), 256, 0, s>>>(tokens, conf, argmax, L, resp_off, mask_id, eos_id, thr, new_len);

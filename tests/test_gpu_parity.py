@@ -396,3 +396,81 @@ def test_refresh_then_length_prediction_matches_the_oracle_chain(tiny):
         assert got == same_inputs                      # the scan itself: bit-exact on identical inputs
         assert got == want and ro < got <= ro + p_star + 1      # the whole chain: GPU refresh vs oracle refresh
         tokens = tokens[:, :got].copy()
+
+
+# ------------------------------------------------------------------ accept-jump controller (Sec. 4.2.1)
+
+def _oracle_accept_jump_batch(drafts, conf, am, um, cp, ct, mask_id):
+    outs = [o.accept_jump(drafts[i], conf[i], am[i], um[i], cp[i], ct[i], mask_id) for i in range(drafts.shape[0])]
+    return (np.array([x[0] for x in outs], np.int32), np.stack([x[4] for x in outs]),
+            np.stack([x[2] for x in outs]), np.stack([x[3] for x in outs]))
+
+
+def _gpu_accept_jump(model, drafts, conf, am, um, cp, ct):
+    res = B.odb_accept_jump(model, cuda_i32(drafts), torch.from_numpy(np.ascontiguousarray(conf, np.float32)).cuda(),
+                            cuda_i32(am), torch.from_numpy(np.ascontiguousarray(um, np.uint8)).cuda(), cuda_i32(cp),
+                            cuda_i32(ct))
+    return tuple(t.cpu().numpy() for t in res)
+
+
+def test_accept_jump_bit_exact_on_random_step_outputs(tiny):
+    """Integer and index work: chosen draft, next drafts and next candidates equal the oracle's exactly."""
+    rng = np.random.default_rng(21)
+    mask_id, V = tiny.cfg.mask_id, tiny.cfg.vocab
+    for Bn, b in [(1, 1), (1, 2), (3, 16), (2, 32), (4, 64), (2, 100), (1, 257)]:
+        for trial in range(6):
+            block = rng.integers(0, V - 1, (Bn, b)).astype(np.int32)
+            block[rng.random((Bn, b)) < [0.0, 0.1, 0.5, 0.7, 0.9, 1.0][trial]] = mask_id
+            cp = np.full((Bn, 2), -1, np.int32)
+            ct = rng.integers(0, V - 1, (Bn, 2)).astype(np.int32)
+            drafts = np.empty((Bn, 4, b), np.int32)
+            for i in range(Bn):
+                masked = np.flatnonzero(block[i] == mask_id)
+                k = min(2, masked.size, int(rng.integers(0, 3)))
+                cp[i, :k] = rng.permutation(masked)[:k]
+                drafts[i] = o.accept_jump_drafts(block[i], cp[i], ct[i])
+            conf = rng.random((Bn, 4, b)).astype(np.float32)
+            conf[rng.random((Bn, 4, b)) < 0.3] = np.float32(0.5)          # ties in the candidate ranking
+            am = rng.integers(0, V - 1, (Bn, 4, b)).astype(np.int32)
+            for i in range(Bn):
+                for c in range(2):
+                    if cp[i, c] >= 0:
+                        am[i, :, cp[i, c]] = np.where(rng.random(4) < 0.7, ct[i, c], am[i, :, cp[i, c]])
+            um = ((rng.random((Bn, 4, b)) < 0.4) & (drafts == mask_id)).astype(np.uint8)
+            got = _gpu_accept_jump(tiny.model, drafts, conf, am, um, cp, ct)
+            want = _oracle_accept_jump_batch(drafts, conf, am, um, cp, ct, mask_id)
+            for g_, w_, name in zip(got, want, ("chosen", "new_drafts", "new_cand_pos", "new_cand_tok")):
+                assert np.array_equal(g_, w_), (Bn, b, trial, name)
+    assert set(np.unique(got[0])) <= {0, 1, 2, 3}
+
+
+def test_accept_jump_decoding_loop_on_the_peaked_model():
+    """A block decoded by repeated [4-draft step -> accept-jump] on the GPU.  In every iteration the controller
+    is compared bit-exactly with the oracle's on the same step outputs, and the step outputs themselves with
+    the oracle's step on the same drafts (decisions within the usual error band); the loop must terminate
+    with the block fully decoded, unmasking at least one position per iteration (forced progress)."""
+    p = Pair(W.MODEL_SHAPES["tiny"], gf=64.0)
+    try:
+        wl = W.decode_workload(p.shape, 96, 64, 32, 1, W.WEIGHT_SEED + 9, p_unmasked=0.2)
+        cache, oc = run_prefill_case(p, wl.tokens, wl.resp_off, "jump prefill")
+        mask_id = p.cfg.mask_id
+        block = wl.drafts[0, 0]
+        cp, ct = np.full((1, 2), -1, np.int32), np.zeros((1, 2), np.int32)
+        drafts = o.accept_jump_drafts(block, cp[0], ct[0])[None]
+        chosen_seen, steps = set(), 0
+        while (drafts[0, 0] == mask_id).any():
+            n_masked = int((drafts[0, 0] == mask_id).sum())
+            conf, am, um, _ = run_step_case(p, cache, oc, drafts, wl.block_off, 0.9, "jump step %d" % steps)
+            got = _gpu_accept_jump(p.model, drafts, conf, am, um, cp, ct)
+            want = _oracle_accept_jump_batch(drafts, conf, am, um, cp, ct, mask_id)
+            for g_, w_ in zip(got, want):
+                assert np.array_equal(g_, w_)
+            chosen, drafts, cp, ct = got
+            chosen_seen.add(int(chosen[0]))
+            assert int((drafts[0, 0] == mask_id).sum()) < n_masked
+            steps += 1
+            assert steps <= 32
+        print("\naccept-jump loop: %d steps for %d masked positions, drafts adopted %s" % (
+            steps, int((block == mask_id).sum()), sorted(chosen_seen)))
+    finally:
+        p.close()
