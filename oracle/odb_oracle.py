@@ -17,7 +17,10 @@ What it follows (ODB-dLLM, arXiv 2511.21759):
     (drafts) see the cached context and themselves, never each other, and keep
     the position ids of the block they shadow (Fig. 8 caption).  Sec. 4.2.1
     (accept-jump): which draft's result a step adopts and how the next drafts
-    are formed from its two most confident unaccepted positions.
+    are formed from its two most confident unaccepted positions.  Sec. 4.2.2
+    (decoded-share): decoded positions of the block are computed once, in
+    block_0, and their K/V shared by the speculative blocks, which shrink to
+    the still-masked positions.
 
 Arithmetic: float64 throughout, on weights whose values are exactly
 representable in bfloat16 (they are stored as bf16 bit patterns).  The model
@@ -475,3 +478,76 @@ def block_step(cfg: Config, w: Weights, cache: Cache, drafts: np.ndarray,
             logits.append(z)
     out = (conf, amax, unmask)
     return out + (np.stack(logits),) if return_logits else out
+
+
+def block_step_shared(cfg: Config, w: Weights, cache: Cache, drafts: np.ndarray,
+                      block_off: int, tau: float, pos0: int = 0,
+                      return_logits: bool = False):
+    """Decode step in the decoded-share stage (Sec. 4.2.2, Fig. 8 caption).
+
+    drafts[S, b]: block_0 = drafts[0] is forwarded in full, exactly as in block_step.  The positions
+    that block_0 has already decoded (tokens other than MASK) are identical in every draft; they are
+    computed only in block_0, and their fresh K/V of every layer are shared: a speculative block
+    s >= 1 consists of the still-masked positions of block_0 only (with their position ids kept),
+    and at every layer its rows attend to the cached K/V outside the block, to block_0's fresh K/V
+    of the decoded positions, and to their own fresh K/V.  Speculative blocks do not see each other
+    nor block_0's rows at masked positions.
+
+    Returns conf[S,b], argmax[S,b], unmask[S,b] as block_step does; for s >= 1 the entries at decoded
+    positions are not computed and read conf 0, argmax = the token held there, unmask 0.
+    With return_logits: also a list of S arrays, [b, V] for block_0 and [m, V] for the others
+    (rows in increasing position order).
+    """
+    drafts = np.asarray(drafts, np.int64)
+    S, b = drafts.shape
+    L = cache.length
+    assert 0 <= block_off and block_off + b <= L
+    masked = drafts[0] == cfg.mask_id
+    P, D = np.flatnonzero(masked), np.flatnonzero(~masked)
+    assert np.array_equal(drafts[:, D], np.broadcast_to(drafts[0, D], (S, D.size))), "decoded positions differ"
+    conf = np.zeros((S, b))
+    amax = drafts.astype(np.int32).copy()
+    unmask = np.zeros((S, b), np.uint8)
+    logits = []
+
+    # block_0: the whole block; its fresh K/V of every layer are kept
+    pos = pos0 + block_off + np.arange(b)
+    h = w.embed_rows(drafts[0])
+    k0, v0 = [], []
+    for layer in range(cfg.n_layers):
+        ck, cv = cache.k[layer], cache.v[layer]
+
+        def kv(kn, vn, ck=ck, cv=cv):
+            return [(slice(0, b), np.concatenate([ck[:block_off], kn, ck[block_off + b:]]),
+                     np.concatenate([cv[:block_off], vn, cv[block_off + b:]]))]
+
+        h, k, v = _layer(cfg, w, layer, h, pos, kv)
+        k0.append(k)
+        v0.append(v)
+    z = _head(cfg, w, h)
+    conf[0], amax[0] = confidence_argmax(z)
+    unmask[0] = threshold_unmask(drafts[0], conf[0], tau, cfg.mask_id)
+    logits.append(z)
+
+    # speculative blocks: the masked positions only, decoded K/V borrowed from block_0
+    for s in range(1, S):
+        if P.size == 0:
+            logits.append(np.zeros((0, cfg.vocab)))
+            continue
+        h = w.embed_rows(drafts[s, P])
+        for layer in range(cfg.n_layers):
+            ck, cv = cache.k[layer], cache.v[layer]
+
+            def kv(kn, vn, ck=ck, cv=cv, layer=layer):
+                return [(slice(0, P.size),
+                         np.concatenate([ck[:block_off], k0[layer][D], kn, ck[block_off + b:]]),
+                         np.concatenate([cv[:block_off], v0[layer][D], vn, cv[block_off + b:]]))]
+
+            h, _, _ = _layer(cfg, w, layer, h, pos[P], kv)
+        z = _head(cfg, w, h)
+        c, a = confidence_argmax(z)
+        conf[s, P], amax[s, P] = c, a
+        unmask[s, P] = threshold_unmask(drafts[s, P], c, tau, cfg.mask_id)
+        logits.append(z)
+    out = (conf, amax, unmask)
+    return out + (logits,) if return_logits else out

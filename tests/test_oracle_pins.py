@@ -621,3 +621,95 @@ def test_accept_jump_next_drafts_and_invariants_on_random_inputs():
         for s, which in ((1, [0]), (2, [1]), (3, [0, 1])):
             diff = np.flatnonzero(nd[s] != nb)
             assert set(diff) <= {int(pos[c]) for c in which if pos[c] >= 0}
+
+
+# ------------------------------------------------------------------ decoded-share stage (Sec. 4.2.2)
+
+def _shared_case(seed=3, b=8, S=4, n_decoded=3):
+    cfg = o.Config(n_layers=2, d_model=32, n_heads=2, head_dim=16, d_ff=48, vocab=40, mask_id=39)
+    w = o.Weights(cfg, 77, 0.3)
+    rng = np.random.default_rng(seed)
+    L, off = 20, 6
+    tokens = rng.integers(0, 38, L)
+    tokens[off:] = cfg.mask_id
+    dec = rng.permutation(b)[:n_decoded]
+    tokens[off + dec] = rng.integers(0, 38, n_decoded)
+    cache, _, _ = o.prefill(cfg, w, tokens)
+    drafts = np.stack([tokens[off:off + b]] * S)
+    masked = np.flatnonzero(drafts[0] == cfg.mask_id)
+    for s in range(1, S):
+        if masked.size:
+            drafts[s, masked[(s - 1) % masked.size]] = int(rng.integers(0, 38))
+    return cfg, w, cache, drafts, off
+
+
+def test_shared_step_with_nothing_decoded_is_the_plain_step():
+    """No decoded position: every speculative block is the whole block, nothing is borrowed (exact)."""
+    cfg, w, cache, drafts, off = _shared_case(n_decoded=0)
+    a = o.block_step(cfg, w, cache, drafts, off, 0.05)
+    b_ = o.block_step_shared(cfg, w, cache, drafts, off, 0.05)
+    for x, y in zip(a, b_):
+        assert np.array_equal(x, y)
+
+
+def test_shared_step_block0_and_copies_of_block0():
+    """block_0 of the shared step is the plain step's block_0 (exact); a speculative block that holds
+    block_0's own tokens reproduces block_0's outputs at the masked positions (by induction over the layers
+    its rows see exactly the keys block_0's rows see), up to rounding order."""
+    cfg, w, cache, drafts, off = _shared_case()
+    drafts[2] = drafts[0]
+    plain = o.block_step(cfg, w, cache, drafts[:1], off, 0.05)
+    conf, am, um, z = o.block_step_shared(cfg, w, cache, drafts, off, 0.05, return_logits=True)
+    assert np.array_equal(conf[0], plain[0][0]) and np.array_equal(am[0], plain[1][0]) and np.array_equal(um[0], plain[2][0])
+    P = np.flatnonzero(drafts[0] == cfg.mask_id)
+    assert np.allclose(z[2], z[0][P], rtol=0, atol=1e-12)
+    assert np.allclose(conf[2, P], conf[0, P], rtol=1e-12) and np.array_equal(am[2, P], am[0, P])
+    D = np.flatnonzero(drafts[0] != cfg.mask_id)
+    assert np.all(conf[1:, D] == 0) and np.array_equal(am[1:, D], drafts[1:, D]) and not um[1:, D].any()
+
+
+def test_shared_step_visibility():
+    """Speculative blocks do not see each other; they do see block_0's decoded tokens through the borrowed K/V
+    and do not see block_0's masked rows; decoded-position K/V really are block_0's (the result changes if
+    they are recomputed inside the speculative block, which is what the plain step does)."""
+    cfg, w, cache, drafts, off = _shared_case(S=4)
+    base = o.block_step_shared(cfg, w, cache, drafts, off, 0.05, return_logits=True)[3]
+    # another speculative block changes: block 1 unaffected
+    d2 = drafts.copy()
+    P = np.flatnonzero(drafts[0] == cfg.mask_id)
+    d2[3, P[0]] = (d2[3, P[0]] + 1) % 38
+    alt = o.block_step_shared(cfg, w, cache, d2, off, 0.05, return_logits=True)[3]
+    assert np.array_equal(alt[1], base[1]) and np.array_equal(alt[2], base[2]) and not np.array_equal(alt[3], base[3])
+    # the shared result is NOT the plain multi-draft step when a speculative token differs from block_0
+    # (there the decoded positions' K/V would be recomputed with the speculative token in view) ...
+    plain = o.block_step(cfg, w, cache, drafts, off, 0.05, return_logits=True)[3]
+    assert np.abs(plain[1][P] - base[1]).max() > 1e-9
+    # ... and equals a hand-assembled forward in which those K/V are taken from block_0 (one layer, by hand)
+    cfg1 = o.Config(n_layers=1, d_model=32, n_heads=2, head_dim=16, d_ff=48, vocab=40, mask_id=39)
+    w1 = o.Weights(cfg1, 77, 0.3)
+    c1 = o.Cache(cache.k[:1], cache.v[:1])
+    z1 = o.block_step_shared(cfg1, w1, c1, drafts, off, 0.05, return_logits=True)[3][1]
+    D = np.flatnonzero(drafts[0] != cfg.mask_id)
+    b = drafts.shape[1]
+    pos = off + np.arange(b)
+    def qkv(tok, pp):
+        h = w1.embed_rows(tok)
+        a = o.rmsnorm(h, w1.f64(o.T_G1, 0), cfg1.rms_eps)
+        q = o.rope((a @ w1.f64(o.T_WQ, 0).T).reshape(-1, 2, 16), pp, cfg1.rope_base)
+        k = o.rope((a @ w1.f64(o.T_WK, 0).T).reshape(-1, 2, 16), pp, cfg1.rope_base)
+        return h, q, k, (a @ w1.f64(o.T_WV, 0).T).reshape(-1, 2, 16)
+    _, _, k0, v0 = qkv(drafts[0], pos)
+    h, q, k, v = qkv(drafts[1, P], pos[P])
+    kk = np.concatenate([c1.k[0][:off], k0[D], k, c1.k[0][off + b:]])
+    vv = np.concatenate([c1.v[0][:off], v0[D], v, c1.v[0][off + b:]])
+    h = h + o.attention(q, kk, vv).reshape(-1, 32) @ w1.f64(o.T_WO, 0).T
+    m = o.rmsnorm(h, w1.f64(o.T_G2, 0), cfg1.rms_eps)
+    h = h + (o.silu(m @ w1.f64(o.T_WG, 0).T) * (m @ w1.f64(o.T_WU, 0).T)) @ w1.f64(o.T_WD, 0).T
+    zz = o.rmsnorm(h, w1.f64(o.T_GF, 0), cfg1.rms_eps) @ w1.f64(o.T_LM, 0).T
+    assert np.allclose(zz, z1, rtol=0, atol=1e-11)
+
+
+def test_shared_step_fully_decoded_block():
+    cfg, w, cache, drafts, off = _shared_case(n_decoded=8)
+    conf, am, um = o.block_step_shared(cfg, w, cache, drafts[:1].repeat(3, 0), off, 0.05)
+    assert not um.any() and np.all(conf[1:] == 0) and conf[0].min() > 0
