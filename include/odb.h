@@ -184,6 +184,37 @@ int odb_predict_length(const odb_model *m, const int32_t *tokens_dev, const floa
                        const int32_t *argmax_dev, int batch, int L, int resp_off, int eos_id,
                        float truncate_thr, int32_t *new_len_dev, void *stream);
 
+/* Decode step in the decoded-share stage (ODB-dLLM Sec. 4.2.2, Fig. 8 caption).
+ * drafts_dev [batch, S, b] as for odb_block_step, with S >= 2 and b <= 64; the drafts of a
+ * sequence must agree with its block_0 (draft 0) wherever block_0 holds a decoded token.
+ * block_0 is forwarded in full, exactly as odb_block_step does it.  A speculative block
+ * s >= 1 is reduced to the positions that block_0 still has MASKed (position ids kept); at
+ * every layer its rows attend to the cached K/V outside the block, to block_0's fresh K/V
+ * of the decoded positions, and to their own fresh K/V - not to other speculative blocks,
+ * not to block_0's rows at masked positions.  So the decoded tokens are computed once per
+ * step and the step has b + (S-1) * n_masked rows per sequence instead of S * b.
+ *   n_masked    host value: upper bound of the MASK positions in block_0 of any sequence
+ *               (sets the row count; a block with more raises an error that
+ *               odb_model_status reports as ODB_E_INVALID_ARG, its outputs are then invalid)
+ *   conf_dev, argmax_dev, unmask_dev [batch, S, b] as for odb_block_step; for s >= 1 the
+ *               entries at decoded positions are not computed and read conf 0,
+ *               argmax = the token held there, unmask 0
+ * Asynchronous on `stream`; does not modify the cache.  Errors as odb_block_step, plus
+ * ODB_E_INVALID_ARG for b > 64, S outside [2, 64], n_masked outside [0, b]. */
+int odb_block_step_shared(odb_model *m, const odb_cache *c, const int32_t *drafts_dev,
+                          int block_off, int b, int S, int n_masked, float tau,
+                          float *conf_dev, int32_t *argmax_dev, uint8_t *unmask_dev, void *stream);
+
+/* Test aid: rows of a decoded-share step (block_0 of every sequence, padded to 16, then
+ * the speculative blocks, each padded to 16), or a negative error code. */
+int odb_block_step_shared_rows(int batch, int b, int S, int n_masked);
+/* Test aid: the logits of every row of the decoded-share step, float [rows, vocab], and for
+ * every row its index into [batch, S, b] (-1 for padding rows), int32 [rows]; both device
+ * buffers of the caller. */
+int odb_block_step_shared_logits(odb_model *m, const odb_cache *c, const int32_t *drafts_dev,
+                                 int block_off, int b, int S, int n_masked, float *logits_dev,
+                                 int32_t *rowout_dev, void *stream);
+
 /* Accept-jump controller (ODB-dLLM Sec. 4.2.1): decides which of the four drafts of
  * the last block step is adopted and builds the drafts of the next one, on the device.
  * The step ran on drafts[.,0] = block_0 (the block as it stood), [.,1] = block_0 with

@@ -22,7 +22,8 @@ SYMBOLS = (
     "odb_model_get_tensor", "odb_cache_create", "odb_cache_destroy", "odb_cache_length", "odb_prefill",
     "odb_block_step", "odb_prefill_logits", "odb_block_step_logits", "odb_cache_read", "odb_strerror",
     "odb_last_error", "odb_profile_begin", "odb_profile_end", "odb_set_step_mode", "odb_model_status",
-    "odb_debug_step_trace", "odb_predict_length", "odb_accept_jump",
+    "odb_debug_step_trace", "odb_predict_length", "odb_accept_jump", "odb_block_step_shared",
+    "odb_block_step_shared_rows", "odb_block_step_shared_logits",
 )
 
 KERNEL_CLASSES = ("gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "rmsnorm",
@@ -77,6 +78,9 @@ def lib() -> ctypes.CDLL:
     L.odb_profile_end.argtypes = [vp, ctypes.POINTER(ci), ctypes.POINTER(cf)]
     L.odb_predict_length.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, cf, vp, vp]
     L.odb_accept_jump.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, vp, vp, vp, vp, vp]
+    L.odb_block_step_shared.argtypes = [vp, vp, vp, ci, ci, ci, ci, cf, vp, vp, vp, vp]
+    L.odb_block_step_shared_rows.argtypes = [ci, ci, ci, ci]
+    L.odb_block_step_shared_logits.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp, vp]
     L.odb_set_step_mode.argtypes = [vp, ci]
     L.odb_model_status.argtypes = [vp]
     L.odb_debug_step_trace.argtypes = [vp, vp, ci]
@@ -173,6 +177,35 @@ def odb_predict_length(model: int, tokens, conf, argmax, resp_off: int, eos_id: 
     _check(lib().odb_predict_length(model, _dev_i32(tokens), conf.data_ptr(), argmax.data_ptr(), B, L, resp_off, eos_id,
                                     truncate_thr, out.data_ptr(), _stream()))
     return out
+
+
+def odb_block_step_shared(model: int, cache: int, drafts, block_off: int, n_masked: int, tau: float,
+                          conf=None, argmax=None, unmask=None):
+    """drafts: int32 CUDA tensor [B, S, b] -> (conf f32, argmax int32, unmask uint8), each [B, S, b]."""
+    import torch
+    B, S, b = drafts.shape
+    if conf is None:
+        conf = torch.empty((B, S, b), dtype=torch.float32, device=drafts.device)
+    if argmax is None:
+        argmax = torch.empty((B, S, b), dtype=torch.int32, device=drafts.device)
+    if unmask is None:
+        unmask = torch.empty((B, S, b), dtype=torch.uint8, device=drafts.device)
+    _check(lib().odb_block_step_shared(model, cache, _dev_i32(drafts), block_off, b, S, n_masked, tau, conf.data_ptr(),
+                                       argmax.data_ptr(), unmask.data_ptr(), _stream()))
+    return conf, argmax, unmask
+
+
+def odb_block_step_shared_logits(model: int, cache: int, drafts, block_off: int, n_masked: int, vocab: int):
+    """-> (logits f32 [rows, vocab], rowout int32 [rows]: index into [B, S, b] of every row, -1 for padding)."""
+    import torch
+    B, S, b = drafts.shape
+    rows = lib().odb_block_step_shared_rows(B, b, S, n_masked)
+    _check(min(rows, 0))
+    logits = torch.empty((rows, vocab), dtype=torch.float32, device=drafts.device)
+    rowout = torch.empty((rows,), dtype=torch.int32, device=drafts.device)
+    _check(lib().odb_block_step_shared_logits(model, cache, _dev_i32(drafts), block_off, b, S, n_masked,
+                                              logits.data_ptr(), rowout.data_ptr(), _stream()))
+    return logits, rowout
 
 
 def odb_accept_jump(model: int, drafts, conf, argmax, unmask, cand_pos, cand_tok):

@@ -53,10 +53,10 @@ constexpr size_t kPartialBytes = 32u << 20;   // K-split partial sums of the til
 
 // byte offsets of the per-call buffers inside the model's scratch allocation
 struct Plan {
-    size_t h, xa, q, kf, vf, ao, act, ssq, stats, part, total;
+    size_t h, xa, q, kf, vf, ao, act, ssq, stats, part, extra, total;
 };
 
-Plan make_plan(const odb_config &c, int rows_pad, int fresh_rows, int lm_rows_pad, bool need_stats) {
+Plan make_plan(const odb_config &c, int rows_pad, int fresh_rows, int lm_rows_pad, bool need_stats, size_t extra_bytes = 0) {
     Plan p;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
@@ -71,6 +71,7 @@ Plan make_plan(const odb_config &c, int rows_pad, int fresh_rows, int lm_rows_pa
     p.ssq = take((size_t)rows_pad * (d / 16) * 4);
     p.stats = take(need_stats ? (size_t)lm_rows_pad * 256 * 6 * 3 * 4 : 0);      // room for any launch variant
     p.part = take(kPartialBytes);
+    p.extra = take(extra_bytes);
     p.total = off;
     return p;
 }
@@ -155,6 +156,7 @@ struct StackIO {
     bool to_cache;      // prefill: K/V are written into the cache
     int blk_lo, blk_hi, fresh, units_per_seq;
     bool fused_norm;
+    const SharedMap *shared;    // decoded-share step: ragged units (see model.h), else nullptr
 };
 
 int run_stack(Model &m, const Cache &c, const Plan &pl, const StackIO &io, hipStream_t s) {
@@ -164,7 +166,11 @@ int run_stack(Model &m, const Cache &c, const Plan &pl, const StackIO &io, hipSt
     u16 *xa = (u16 *)(base + pl.xa), *q = (u16 *)(base + pl.q), *kf = (u16 *)(base + pl.kf),
         *vf = (u16 *)(base + pl.vf), *ao = (u16 *)(base + pl.ao), *act = (u16 *)(base + pl.act);
     const int d = cfg.d_model, H = cfg.n_heads, dh = cfg.head_dim, F = cfg.d_ff;
-    const int rows_pad = io.rm.units * io.rm.rpu_pad, mt = rows_pad / 16, tpu = io.rm.rpu_pad / 16;
+    const SharedMap *sm = io.shared;
+    const int rows_pad = sm ? sm->rows() : io.rm.units * io.rm.rpu_pad, mt = rows_pad / 16, tpu = io.rm.rpu_pad / 16;
+    // decoded-share step: fresh K/V of the batch block_0 units (bp32 rows each) first, then of the speculative units (mp32 rows each)
+    const int mp32 = sm ? ru(sm->mp, 32) : 0;
+    const size_t spec_off = sm ? (size_t)sm->batch * H * ru(sm->bp, 32) * dh : 0;
     const size_t seq_elems = (size_t)H * c.lmax32 * dh;
     const int fresh32 = ru(io.rm.rpu_pad, 32);
     const int n_ssq = d / 16;
@@ -177,7 +183,7 @@ int run_stack(Model &m, const Cache &c, const Plan &pl, const StackIO &io, hipSt
             ProfScope ps(m, ODB_K_RMSNORM, s);
             launch_rmsnorm(h, w.g1, cfg.rms_eps, d, io.rm, 0, false, mt, xa, s);
         }
-        QkvOut qo;
+        QkvOut qo{};
         qo.q = q;
         qo.rope = c.rope;
         qo.tiles_per_unit = tpu; qo.pos_off = io.pos_off; qo.H = H; qo.dh = dh; qo.d = d;
@@ -189,12 +195,19 @@ int run_stack(Model &m, const Cache &c, const Plan &pl, const StackIO &io, hipSt
             qo.k = kf; qo.k_head_stride = (size_t)fresh32 * dh; qo.k_unit_stride = (size_t)H * fresh32 * dh;
             qo.v = vf; qo.v_head_stride = (size_t)fresh32 * dh; qo.v_unit_stride = (size_t)H * fresh32 * dh;
         }
+        if (sm) {
+            qo.rowpos = sm->rowpos;
+            qo.split_tile = sm->batch * sm->bp / 16;
+            qo.tiles_per_unit_b = sm->mp / 16;
+            qo.k_b = kf + spec_off; qo.k_b_head_stride = (size_t)mp32 * dh; qo.k_b_unit_stride = (size_t)H * mp32 * dh;
+            qo.v_b = vf + spec_off; qo.v_b_head_stride = (size_t)mp32 * dh; qo.v_b_unit_stride = (size_t)H * mp32 * dh;
+        }
         {
             ProfScope ps(m, ODB_K_GEMM_QKV, s);
             launch_gemm_qkv(xa, w.qkv, GemmShape{mt, 3 * d / 16, d / 32}, ni, qo, ws, s);
         }
 
-        AttnArgs a;
+        AttnArgs a{};
         a.q = q; a.kc = kc; a.vc = vc;
         a.kc_seq_stride = seq_elems; a.kc_head_stride = (size_t)c.lmax32 * dh;
         a.vc_seq_stride = seq_elems; a.vc_head_stride = (size_t)c.lmax32 * dh;
@@ -205,6 +218,12 @@ int run_stack(Model &m, const Cache &c, const Plan &pl, const StackIO &io, hipSt
         a.H = H; a.dh = dh; a.mt_total = mt; a.tiles_per_unit = tpu; a.units = io.rm.units;
         a.units_per_seq = io.units_per_seq; a.L = c.length; a.blk_lo = io.blk_lo; a.blk_hi = io.blk_hi;
         a.fresh = io.fresh;
+        if (sm) {
+            a.split_tile = qo.split_tile; a.tiles_per_unit_b = qo.tiles_per_unit_b; a.units_per_seq_b = sm->S - 1;
+            a.kf_b = qo.k_b; a.kf_b_unit_stride = qo.k_b_unit_stride; a.kf_b_head_stride = qo.k_b_head_stride;
+            a.vf_b = qo.v_b; a.vf_b_unit_stride = qo.v_b_unit_stride; a.vf_b_head_stride = qo.v_b_head_stride;
+            a.mcount = sm->mcount; a.dmask = sm->dmask;
+        }
         {
             ProfScope ps(m, ODB_K_ATTENTION, s);
             launch_attention(a, s);
@@ -587,6 +606,92 @@ int odb_block_step_logits(odb_model *m, const odb_cache *c, const int32_t *draft
     return step_impl(m, c, drafts_dev, block_off, b, S, 0.f, nullptr, nullptr, nullptr, logits_dev, stream);
 }
 
+// Decode step in the decoded-share stage (ODB-dLLM Sec. 4.2.2): block_0 in full, the speculative blocks reduced to
+// the positions that block_0 still has masked, block_0's fresh K/V of the decoded positions shared with them.
+static int step_shared_impl(odb_model *mh, const odb_cache *ch, const int32_t *drafts, int block_off, int b, int S,
+                            int n_masked, float tau, float *conf, int32_t *argmax, uint8_t *unmask, float *logits,
+                            int32_t *rowout, void *stream) {
+    if (!mh || !ch || !drafts) return fail(ODB_E_INVALID_ARG, "block_step_shared: NULL handle or drafts");
+    Model &m = mh->m;
+    const Cache &c = ch->c;
+    if (c.m != &m) return fail(ODB_E_INVALID_ARG, "block_step_shared: cache belongs to another model");
+    if (c.length < 1) return fail(ODB_E_INVALID_ARG, "block_step_shared: cache has not been prefilled");
+    if (b < 1 || b > 64) return fail(ODB_E_INVALID_ARG, "block_step_shared: b=%d outside [1, 64]", b);
+    if (S < 2 || S > 64) return fail(ODB_E_INVALID_ARG, "block_step_shared: S=%d outside [2, 64]", S);
+    if (n_masked < 0 || n_masked > b) return fail(ODB_E_INVALID_ARG, "block_step_shared: n_masked=%d outside [0, %d]", n_masked, b);
+    if (block_off < 0 || block_off + b > c.length)
+        return fail(ODB_E_INVALID_ARG, "block_step_shared: block [%d, %d) outside the cached length %d", block_off,
+                    block_off + b, c.length);
+    if (!logits && (!conf || !argmax || !unmask)) return fail(ODB_E_INVALID_ARG, "block_step_shared: NULL output");
+    if (logits && !rowout) return fail(ODB_E_INVALID_ARG, "block_step_shared: NULL row map");
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(hipSetDevice(m.device));
+    const odb_config &cfg = m.cfg;
+    SharedMap sm;
+    sm.batch = c.batch; sm.S = S; sm.b = b; sm.bp = ru(b, 16); sm.mp = ru(n_masked > 0 ? n_masked : 1, 16);
+    const int rows_pad = sm.rows();
+    const int fresh_rows = c.batch * ru(sm.bp, 32) + c.batch * (S - 1) * ru(sm.mp, 32);
+    const size_t tables = align_up((size_t)rows_pad * 4, 256) * 3 + align_up((size_t)c.batch * 4, 256) +
+                          align_up((size_t)c.batch * 8, 256);
+    Plan pl = make_plan(cfg, rows_pad, fresh_rows, rows_pad, logits == nullptr, tables);
+    int rc = ensure_scratch(m, pl.total, s);
+    if (rc) return rc;
+    char *base = (char *)m.scratch, *t = base + pl.extra;
+    sm.rowtok = (int32_t *)t; t += align_up((size_t)rows_pad * 4, 256);
+    sm.rowpos = (int32_t *)t; t += align_up((size_t)rows_pad * 4, 256);
+    sm.rowout = (int32_t *)t; t += align_up((size_t)rows_pad * 4, 256);
+    sm.mcount = (int32_t *)t; t += align_up((size_t)c.batch * 4, 256);
+    sm.dmask = (unsigned long long *)t;
+    launch_shared_setup(drafts, sm, block_off, cfg.mask_id, n_masked, conf, argmax, unmask, m.counters, s);
+    // rows are embedded through the token-per-row table: every row is its own unit of one
+    launch_embed(m, sm.rowtok, RowMap{rows_pad, 1, 1}, (float *)(base + pl.h),
+                 NormOut{(u16 *)(base + pl.xa), (float *)(base + pl.ssq), m.g1, cfg.d_model / 16}, s);
+    // slots of padded keys must hold finite values: they meet zero probabilities in the P*V product
+    launch_fill_f32((float *)(base + pl.vf), 0.f, (size_t)fresh_rows * cfg.d_model / 2, s);
+    RowMap rm{c.batch, sm.bp, b};
+    StackIO io{rm, block_off, false, block_off, block_off + b, b, 1, true, &sm};
+    rc = run_stack(m, c, pl, io, s);
+    if (rc) return rc;
+    // final norm (fused) + LM head on all rows, then the per-unit finish
+    u16 *xa = (u16 *)(base + pl.xa);
+    const Workspace ws{(float *)(base + pl.part), kPartialBytes};
+    const NormIn ni{(float *)(base + pl.ssq), cfg.d_model / 16, cfg.rms_eps};
+    const GemmShape sh{rows_pad / 16, cfg.vocab / 16, cfg.d_model / 32};
+    if (logits) {
+        launch_gemm_store(xa, m.w[PK_LM], sh, ni, logits, 1, rows_pad, rows_pad, cfg.vocab, ws, s);
+        HIP_TRY(hipMemcpyAsync(rowout, sm.rowout, (size_t)rows_pad * 4, hipMemcpyDeviceToDevice, s));
+    } else {
+        float *stats = (float *)(base + pl.stats);
+        {
+            ProfScope ps(m, ODB_K_GEMM_LM_HEAD, s);
+            launch_gemm_lmstats(xa, m.w[PK_LM], sh, ni, stats, ws, s);
+        }
+        launch_lm_finish_shared(stats, lm_stats_parts(cfg.vocab / 16, rows_pad / 16), sm, cfg.mask_id, tau, conf, argmax,
+                                unmask, s);
+    }
+    HIP_TRY(hipGetLastError());
+    return ODB_OK;
+}
+
+int odb_block_step_shared(odb_model *m, const odb_cache *c, const int32_t *drafts_dev, int block_off, int b, int S,
+                          int n_masked, float tau, float *conf_dev, int32_t *argmax_dev, uint8_t *unmask_dev,
+                          void *stream) {
+    return step_shared_impl(m, c, drafts_dev, block_off, b, S, n_masked, tau, conf_dev, argmax_dev, unmask_dev, nullptr,
+                            nullptr, stream);
+}
+
+int odb_block_step_shared_rows(int batch, int b, int S, int n_masked) {
+    if (batch < 1 || b < 1 || S < 2 || n_masked < 0 || n_masked > b) return fail(ODB_E_INVALID_ARG, "block_step_shared_rows");
+    return batch * ru(b, 16) + batch * (S - 1) * ru(n_masked > 0 ? n_masked : 1, 16);
+}
+
+int odb_block_step_shared_logits(odb_model *m, const odb_cache *c, const int32_t *drafts_dev, int block_off, int b,
+                                 int S, int n_masked, float *logits_dev, int32_t *rowout_dev, void *stream) {
+    if (!logits_dev) return fail(ODB_E_INVALID_ARG, "block_step_shared_logits: logits is NULL");
+    return step_shared_impl(m, c, drafts_dev, block_off, b, S, n_masked, 0.f, nullptr, nullptr, nullptr, logits_dev,
+                            rowout_dev, stream);
+}
+
 int odb_set_step_mode(odb_model *mh, int mode) {
     if (!mh) return fail(ODB_E_INVALID_ARG, "set_step_mode: model is NULL");
     if (mode != ODB_STEP_FUSED && mode != ODB_STEP_KERNELS) return fail(ODB_E_INVALID_ARG, "set_step_mode: mode %d", mode);
@@ -611,10 +716,11 @@ int odb_model_status(odb_model *mh) {
     unsigned host = 0;
     HIP_TRY(hipMemcpy(&host, m.counters, sizeof(host), hipMemcpyDeviceToHost));
     if (host != 0) {
-        // a barrier gave up: bring flags, epoch and status back to a clean state
+        // bring flags, epoch and status back to a clean state
         HIP_TRY(hipMemset(m.counters, 0, kCounters * sizeof(unsigned)));
         m.barrier_epoch = 0;
-        return fail(ODB_E_HIP, "a fused step kernel timed out at a grid barrier");
+        if (host & ~2u) return fail(ODB_E_HIP, "a fused step kernel timed out at a grid barrier");
+        return fail(ODB_E_INVALID_ARG, "block_step_shared: a block held more MASK positions than n_masked");
     }
     return ODB_OK;
 }

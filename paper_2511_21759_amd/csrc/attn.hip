@@ -3,10 +3,10 @@
 
 namespace odb {
 
-template <int DH, int QT, int NW>
+template <int DH, int QT, int NW, bool SHARED = false>
 __global__ __launch_bounds__(64 * NW) void attn_kernel(AttnArgs a, float sc) {
     __shared__ __attribute__((aligned(16))) char smem[attn_smem_bytes<QT, NW>()];
-    attn_wg<DH, QT, NW>(a, sc, blockIdx.x, blockIdx.y, smem);
+    attn_wg<DH, QT, NW, SHARED>(a, sc, blockIdx.x, blockIdx.y, smem);
 }
 
 // Many rows per (sequence, head): K/V tiles shared through LDS by all rows of a workgroup (attn_rows.h)
@@ -26,6 +26,13 @@ static void launch_rows(AttnArgs a, float sc, hipStream_t s) {
 
 void launch_attention(AttnArgs a, hipStream_t s) {
     const float sc = 1.4426950408889634f / sqrtf((float)a.dh);
+    if (a.split_tile > 0) {
+        // decoded-share step: one row tile per workgroup, block_0 tiles first, then the speculative units'
+        dim3 grid(a.mt_total, a.H);
+        if (a.dh == 128) attn_kernel<128, 1, 8, true><<<grid, 512, 0, s>>>(a, sc);
+        else attn_kernel<64, 1, 8, true><<<grid, 512, 0, s>>>(a, sc);
+        return;
+    }
     const int tiles_per_seq = a.units_per_seq * a.tiles_per_unit;
     if (tiles_per_seq >= 16 && (a.fresh == 0 || a.tiles_per_unit % 2 == 0)) {
         // 256 rows per workgroup when that still gives every compute unit a workgroup, else 128

@@ -34,12 +34,15 @@ __device__ inline void store_out_tile(const AttnArgs &a, int mt, int hd, int dt1
 
 // Scores of one 32-key tile (K fragments kf) against QT row tiles, online-softmax update of the running
 // (max, sum) and the rescaling of O that goes with it; returns the probabilities as operand fragments pf.
-// MASK: some keys of the tile may be invisible - cached: cache positions key0 .. key0+31, those past L or
-// inside the block are masked; otherwise fresh keys of the rows' own draft, those past a.fresh are masked.
+// MASK: some keys of the tile may be invisible.  mode kKeysCached: cache positions key0 .. key0+31, those past
+// L or inside the block are masked; kKeysFresh: fresh keys of the rows' own unit, those from fresh_n on are
+// masked; kKeysShared: fresh keys of block_0 of the sequence, visible where bit key of `visible` is set.
 // The running references mrun are in log2 units (raw score * sc, sc = log2(e)/sqrt(dh) > 0).
 constexpr float kAttnSlack = 8.0f;
+constexpr int kKeysCached = 0, kKeysFresh = 1, kKeysShared = 2;
 template <int DH, int QT, bool MASK>
-__device__ __forceinline__ void attn_scores(const AttnArgs &a, float sc, int key0, bool cached,
+__device__ __forceinline__ void attn_scores(const AttnArgs &a, float sc, int key0, int mode, int fresh_n,
+                                            unsigned long long visible,
                                             const frag_t (&kf)[2][DH / 32], const frag_t (&q)[QT][DH / 32],
                                             f32x4 (&o)[QT][DH / 16], float (&mrun)[QT], float (&lrun)[QT],
                                             frag_t (&pf)[QT], int lane) {
@@ -52,7 +55,9 @@ __device__ __forceinline__ void attn_scores(const AttnArgs &a, float sc, int key
 #pragma unroll
             for (int rr = 0; rr < 4; rr++) {
                 int key = key0 + s * 16 + 4 * g + rr;
-                ok[s][rr] = cached ? (key < a.L && !(key >= a.blk_lo && key < a.blk_hi)) : key < a.fresh;
+                ok[s][rr] = mode == kKeysCached ? (key < a.L && !(key >= a.blk_lo && key < a.blk_hi))
+                          : mode == kKeysFresh ? key < fresh_n
+                                               : (key < 64 && ((visible >> key) & 1ull) != 0);
             }
     }
 #pragma unroll
@@ -113,20 +118,24 @@ __device__ __forceinline__ void attn_pv(const frag_t (&vf)[DH / 16], const frag_
         for (int dt = 0; dt < DH / 16; dt++) o[t][dt] = mfma16(vf[dt], pf[t], o[t][dt]);
 }
 
-// true if some key of the 32-key tile at key0 is invisible (see attn_scores)
-__device__ __forceinline__ bool attn_tile_masked(const AttnArgs &a, int key0, bool cached) {
-    return cached ? (key0 + 32 > a.L || (key0 < a.blk_hi && key0 + 32 > a.blk_lo)) : key0 + 32 > a.fresh;
+// true if some key of the 32-key tile at key0 may be invisible (see attn_scores)
+__device__ __forceinline__ bool attn_tile_masked(const AttnArgs &a, int key0, int mode, int fresh_n) {
+    return mode == kKeysCached ? (key0 + 32 > a.L || (key0 < a.blk_hi && key0 + 32 > a.blk_lo))
+         : mode == kKeysFresh ? key0 + 32 > fresh_n : true;
 }
 
 // One 32-key tile (K fragments kf, V^T fragments vf) against QT row tiles: scores, online softmax, O update.
 template <int DH, int QT>
-__device__ __forceinline__ void attn_tile_update(const AttnArgs &a, float sc, int key0, bool cached,
+__device__ __forceinline__ void attn_tile_update(const AttnArgs &a, float sc, int key0, int mode, int fresh_n,
+                                                 unsigned long long visible,
                                                  const frag_t (&kf)[2][DH / 32], const frag_t (&vf)[DH / 16],
                                                  const frag_t (&q)[QT][DH / 32], f32x4 (&o)[QT][DH / 16],
                                                  float (&mrun)[QT], float (&lrun)[QT], int lane) {
     frag_t pf[QT];
-    if (attn_tile_masked(a, key0, cached)) attn_scores<DH, QT, true>(a, sc, key0, cached, kf, q, o, mrun, lrun, pf, lane);
-    else attn_scores<DH, QT, false>(a, sc, key0, cached, kf, q, o, mrun, lrun, pf, lane);
+    if (attn_tile_masked(a, key0, mode, fresh_n))
+        attn_scores<DH, QT, true>(a, sc, key0, mode, fresh_n, visible, kf, q, o, mrun, lrun, pf, lane);
+    else
+        attn_scores<DH, QT, false>(a, sc, key0, mode, fresh_n, visible, kf, q, o, mrun, lrun, pf, lane);
     attn_pv<DH, QT>(vf, pf, o);
 }
 
@@ -134,14 +143,21 @@ template <int QT, int NW>
 constexpr int attn_smem_bytes() { return NW * 4 * 1024 + 2 * NW * QT * 16 * 4; }
 
 // One work item: QT row tiles (chunk `item` of the units' tiles) of head hd.  sc = log2(e)/sqrt(dh).
-template <int DH, int QT, int NW>
+// SHARED (decoded-share step, QT = 1): item is the m-tile; tiles from a.split_tile on belong to speculative
+// units, which see the cache, their own fresh keys and block_0's fresh keys at the decoded positions.
+template <int DH, int QT, int NW, bool SHARED = false>
 __device__ __forceinline__ void attn_wg(const AttnArgs &a, float sc, int item, int hd, char *smem) {
     constexpr int DT32 = DH / 32, DT16 = DH / 16;
     constexpr int DC = DT16 < 4 ? DT16 : 4;          // channel tiles merged per pass through LDS
+    static_assert(!SHARED || QT == 1, "the decoded-share step works on single row tiles");
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, mi = lane & 15, g = lane >> 4;
-    const int chunks = (a.tiles_per_unit + QT - 1) / QT;
-    const int unit = item / chunks, tu0 = (item % chunks) * QT;
-    const int seq = unit / a.units_per_seq;
+    const bool spec = SHARED && item >= a.split_tile;                     // a speculative unit's tile
+    const int tpu = spec ? a.tiles_per_unit_b : a.tiles_per_unit;
+    const int chunks = (tpu + QT - 1) / QT;
+    const int item_u = spec ? item - a.split_tile : item;
+    const int unit = item_u / chunks, tu0 = (item_u % chunks) * QT;
+    const int seq = unit / (spec ? a.units_per_seq_b : a.units_per_seq);
+    const int mt_base = (spec ? a.split_tile : 0) + unit * tpu;           // first m-tile of the unit
     f32x4 (*s_o)[DC][64] = reinterpret_cast<f32x4 (*)[DC][64]>(smem);
     float (*s_m)[QT][16] = reinterpret_cast<float (*)[QT][16]>(smem + NW * 4 * 1024);
     float (*s_l)[QT][16] = s_m + NW;
@@ -149,8 +165,8 @@ __device__ __forceinline__ void attn_wg(const AttnArgs &a, float sc, int item, i
     frag_t q[QT][DT32];
 #pragma unroll
     for (int t = 0; t < QT; t++) {
-        int tu = tu0 + t < a.tiles_per_unit ? tu0 + t : a.tiles_per_unit - 1;
-        int mt = unit * a.tiles_per_unit + tu;
+        int tu = tu0 + t < tpu ? tu0 + t : tpu - 1;
+        int mt = mt_base + tu;
 #pragma unroll
         for (int dt = 0; dt < DT32; dt++)
             q[t][dt] = ld_frag(a.q + (((size_t)hd * a.mt_total + mt) * DT32 + dt) * kTileElems + lane * 8);
@@ -165,7 +181,10 @@ __device__ __forceinline__ void attn_wg(const AttnArgs &a, float sc, int item, i
         for (int dt = 0; dt < DT16; dt++) o[t][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    struct TileRef { const u16 *kp, *vp; int key0; bool cached, live; };
+    // own fresh keys that count, and (speculative units) which of block_0's fresh keys are visible
+    const int fresh_n = spec ? a.mcount[seq] : a.fresh;
+    const unsigned long long visible = spec ? a.dmask[seq] : 0ull;
+    struct TileRef { const u16 *kp, *vp; int key0, mode; bool live; };
     auto load_tile = [&](const TileRef &r, frag_t (&kf)[2][DT32], frag_t (&vf)[DT16]) __attribute__((always_inline)) {
 #pragma unroll
         for (int s = 0; s < 2; s++)
@@ -177,37 +196,47 @@ __device__ __forceinline__ void attn_wg(const AttnArgs &a, float sc, int item, i
     };
     auto compute_tile = [&](const TileRef &r, const frag_t (&kf)[2][DT32], const frag_t (&vf)[DT16])
                             __attribute__((always_inline)) {
-        attn_tile_update<DH, QT>(a, sc, r.key0, r.cached, kf, vf, q, o, mrun, lrun, lane);
+        attn_tile_update<DH, QT>(a, sc, r.key0, r.mode, fresh_n, visible, kf, vf, q, o, mrun, lrun, lane);
     };
 
-    // This wave's tiles: cached 32-key tiles w, w+NW, ... (those wholly inside the block are dead),
-    // then the fresh tiles that continue the same rotation.  The loads of tile i+1 are issued
-    // before tile i is computed.
+    // This wave's tiles: the 32-key tiles of the cache (those wholly inside the block are dead), then the
+    // unit's own fresh tiles, then (speculative units of the decoded-share step) block_0's fresh tiles, dealt
+    // to the waves round-robin as one sequence.  The loads of tile i+1 are issued before tile i is computed.
     const int n32 = (a.L + 31) / 32;
     const u16 *kc = a.kc + seq * a.kc_seq_stride + hd * a.kc_head_stride;
     const u16 *vc = a.vc + seq * a.vc_seq_stride + hd * a.vc_head_stride;
-    const u16 *kfr = a.kf + unit * a.kf_unit_stride + hd * a.kf_head_stride;
-    const u16 *vfr = a.vf + unit * a.vf_unit_stride + hd * a.vf_head_stride;
-    const int nc = w < n32 ? (n32 - w + NW - 1) / NW : 0;
-    const int nf32 = a.fresh > 0 ? (a.fresh + 31) / 32 : 0;
-    const int f0 = (w + NW - n32 % NW) % NW;
-    const int nfw = f0 < nf32 ? (nf32 - f0 + NW - 1) / NW : 0;
-    const int total = nc + nfw;
+    const u16 *kfr = spec ? a.kf_b + unit * a.kf_b_unit_stride + hd * a.kf_b_head_stride
+                          : a.kf + unit * a.kf_unit_stride + hd * a.kf_head_stride;
+    const u16 *vfr = spec ? a.vf_b + unit * a.vf_b_unit_stride + hd * a.vf_b_head_stride
+                          : a.vf + unit * a.vf_unit_stride + hd * a.vf_head_stride;
+    const u16 *ksh = a.kf + seq * a.kf_unit_stride + hd * a.kf_head_stride;      // block_0 of this sequence (spec only)
+    const u16 *vsh = a.vf + seq * a.vf_unit_stride + hd * a.vf_head_stride;
+    const int nf32 = fresh_n > 0 ? (fresh_n + 31) / 32 : 0;
+    const int ns32 = spec ? (a.fresh + 31) / 32 : 0;
+    const int n_all = n32 + nf32 + ns32;
+    const int total = w < n_all ? (n_all - w + NW - 1) / NW : 0;
     auto get = [&](int i) __attribute__((always_inline)) {
         TileRef r;
-        if (i < nc) {
-            const int T = w + i * NW;
-            r.kp = kc + (size_t)T * 2 * DT32 * kTileElems;
-            r.vp = vc + (size_t)T * DT16 * kTileElems;
-            r.key0 = T * 32;
-            r.cached = true;
-            r.live = !(T * 32 >= a.blk_lo && T * 32 + 32 <= a.blk_hi);
-        } else {
-            const int T = f0 + (i - nc) * NW;
+        const int gi = w + i * NW;
+        if (gi < n32) {
+            r.kp = kc + (size_t)gi * 2 * DT32 * kTileElems;
+            r.vp = vc + (size_t)gi * DT16 * kTileElems;
+            r.key0 = gi * 32;
+            r.mode = kKeysCached;
+            r.live = !(gi * 32 >= a.blk_lo && gi * 32 + 32 <= a.blk_hi);
+        } else if (gi < n32 + nf32) {
+            const int T = gi - n32;
             r.kp = kfr + (size_t)T * 2 * DT32 * kTileElems;
             r.vp = vfr + (size_t)T * DT16 * kTileElems;
             r.key0 = T * 32;
-            r.cached = false;
+            r.mode = kKeysFresh;
+            r.live = true;
+        } else {
+            const int T = gi - n32 - nf32;
+            r.kp = ksh + (size_t)T * 2 * DT32 * kTileElems;
+            r.vp = vsh + (size_t)T * DT16 * kTileElems;
+            r.key0 = T * 32;
+            r.mode = kKeysShared;
             r.live = true;
         }
         return r;
@@ -263,13 +292,13 @@ __device__ __forceinline__ void attn_wg(const AttnArgs &a, float sc, int item, i
             if (x == w) fown = f;
         }
         const int tu = tu0 + t;
-        const int mt = unit * a.tiles_per_unit + tu;
+        const int mt = mt_base + tu;
 #pragma unroll
         for (int d0 = 0; d0 < DT16; d0 += DC) {
 #pragma unroll
             for (int dt = 0; dt < DC; dt++) s_o[w][dt][lane] = o[t][d0 + dt] * fown;
             __syncthreads();
-            if (tu < a.tiles_per_unit) {
+            if (tu < tpu) {
                 for (int dt = w; dt < DC; dt += NW) {
                     f32x4 v = s_o[0][dt][lane];
 #pragma unroll

@@ -118,8 +118,10 @@ __global__ __launch_bounds__(64 * NW) void attn_rows_kernel(AttnArgs a, float sc
 #pragma unroll
             for (int dt = 0; dt < DT16; dt++) vf[dt] = st[2 * DT32 + dt][lane];
             const int key0 = tile_of(i) * 32;
-            if (!DUAL || attn_tile_masked(a, key0, true)) attn_scores<DH, QTW, true>(a, sc, key0, true, kf, q, o, mrun, lrun, pf, lane);
-            else attn_scores<DH, QTW, false>(a, sc, key0, true, kf, q, o, mrun, lrun, pf, lane);
+            if (!DUAL || attn_tile_masked(a, key0, kKeysCached, 0))
+                attn_scores<DH, QTW, true>(a, sc, key0, kKeysCached, 0, 0ull, kf, q, o, mrun, lrun, pf, lane);
+            else
+                attn_scores<DH, QTW, false>(a, sc, key0, kKeysCached, 0, 0ull, kf, q, o, mrun, lrun, pf, lane);
             if (PIPE && i + 1 < n_live) read_k(i + 1);
             attn_pv<DH, QTW>(vf, pf, o);
         }
@@ -137,7 +139,7 @@ __global__ __launch_bounds__(64 * NW) void attn_rows_kernel(AttnArgs a, float sc
             for (int dt = 0; dt < DT32; dt++) kf[s][dt] = ld_frag(kfr + ((size_t)T * 2 * DT32 + s * DT32 + dt) * kTileElems);
 #pragma unroll
         for (int dt = 0; dt < DT16; dt++) vf[dt] = ld_frag(vfr + ((size_t)T * DT16 + dt) * kTileElems);
-        attn_scores<DH, QTW, true>(a, sc, T * 32, false, kf, q, o, mrun, lrun, pf, lane);
+        attn_scores<DH, QTW, true>(a, sc, T * 32, kKeysFresh, a.fresh, 0ull, kf, q, o, mrun, lrun, pf, lane);
         attn_pv<DH, QTW>(vf, pf, o);
     }
 

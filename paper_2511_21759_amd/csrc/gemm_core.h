@@ -254,16 +254,22 @@ struct EpiQKV {
     __device__ void finish(int, int, int, int) const {}
     __device__ void operator()(int mt, int nt, f32x4 c, int lane, int) const {
         const int mi = lane & 15, g = lane >> 4;
-        const int unit = mt / o.tiles_per_unit, tu = mt % o.tiles_per_unit;
+        // unit and tile inside the unit; in the decoded-share step the speculative units have their own size and K/V area
+        const bool spec = o.split_tile > 0 && mt >= o.split_tile;
+        const int unit = spec ? (mt - o.split_tile) / o.tiles_per_unit_b : mt / o.tiles_per_unit;
+        const int tu = spec ? (mt - o.split_tile) % o.tiles_per_unit_b : mt % o.tiles_per_unit;
+        u16 *kdst = spec ? o.k_b + unit * o.k_b_unit_stride : o.k + unit * o.k_unit_stride;
+        u16 *vdst = spec ? o.v_b + unit * o.v_b_unit_stride : o.v + unit * o.v_unit_stride;
+        const size_t khs = spec ? o.k_b_head_stride : o.k_head_stride, vhs = spec ? o.v_b_head_stride : o.v_head_stride;
         const int n = nt * 16, sec = n / o.d, rr = n % o.d;
         const int hd = rr / o.dh, p0 = rr % o.dh;            // p0 is a multiple of 16
         if (sec < 2) {
             // physical channel 2j is logical j, 2j+1 is j + dh/2: each adjacent pair is a RoPE pair
-            const int pos = o.pos_off + tu * 16 + mi;
+            const int pos = o.rowpos ? o.rowpos[mt * 16 + mi] : o.pos_off + tu * 16 + mi;
             const float2 *tab = reinterpret_cast<const float2 *>(o.rope) + (size_t)pos * (o.dh / 2);
             u16 *dst = sec == 0
                 ? o.q + (((size_t)hd * mt_total + mt) * (o.dh / 32) + p0 / 32) * kTileElems
-                : o.k + unit * o.k_unit_stride + hd * o.k_head_stride + ((size_t)tu * (o.dh / 32) + p0 / 32) * kTileElems;
+                : kdst + hd * khs + ((size_t)tu * (o.dh / 32) + p0 / 32) * kTileElems;
             const int j = (p0 + 4 * g) >> 1;
             float2 cs0 = tab[j], cs1 = tab[j + 1];
             float y0 = c[0] * cs0.x - c[1] * cs0.y;
@@ -274,8 +280,7 @@ struct EpiQKV {
             st_bf16x4(dst + ((kk >> 3) * 16 + mi) * 8 + (kk & 7), y0, y1, y2, y3);
         } else {
             // V^T tile: row = channel, the 32 keys of a tile sit in k-slot 8*g + 4*half + r
-            u16 *dst = o.v + unit * o.v_unit_stride + hd * o.v_head_stride +
-                       ((size_t)(tu >> 1) * (o.dh / 16) + p0 / 16) * kTileElems + lane * 8 + 4 * (tu & 1);
+            u16 *dst = vdst + hd * vhs + ((size_t)(tu >> 1) * (o.dh / 16) + p0 / 16) * kTileElems + lane * 8 + 4 * (tu & 1);
             st_bf16x4(dst, c[0], c[1], c[2], c[3]);
         }
     }

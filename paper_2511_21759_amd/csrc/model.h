@@ -87,6 +87,22 @@ void launch_predict_length(const int32_t *tokens, const float *conf, const int32
                            int resp_off, int mask_id, int eos_id, float thr, int32_t *new_len, hipStream_t s);
 void launch_lm_finish(const float *stats, int n_part, int rows, int rpu, int rpu_pad, const int32_t *tokens,
                       int mask_id, float tau, float *conf, int32_t *argmax, uint8_t *unmask, hipStream_t s);
+// Decoded-share step: row bookkeeping built on the device from the drafts.  Rows: block_0 of every sequence
+// first (batch units of bp rows), then the speculative units (batch * (S-1) of mp rows), which hold the
+// positions that are MASK in block_0, in increasing order.
+struct SharedMap {
+    int batch, S, b, bp, mp;           // bp, mp: rows per unit, multiples of 16
+    int32_t *rowtok, *rowpos, *rowout; // per row: token, absolute position, index into [batch, S, b] (-1: padding)
+    int32_t *mcount;                   // [batch] masked positions of block_0
+    unsigned long long *dmask;         // [batch] bit i set: position i of the block is decoded
+    int rows() const { return batch * bp + batch * (S - 1) * mp; }
+};
+// fills the tables, presets the outputs of the positions that are not computed (conf 0, argmax = token,
+// unmask 0) and raises status bit 2 if a block has more than m_cap masked positions
+void launch_shared_setup(const int32_t *drafts, SharedMap sm, int block_off, int mask_id, int m_cap, float *conf,
+                         int32_t *argmax, uint8_t *unmask, unsigned int *status, hipStream_t s);
+void launch_lm_finish_shared(const float *stats, int n_part, SharedMap sm, int mask_id, float tau, float *conf,
+                             int32_t *argmax, uint8_t *unmask, hipStream_t s);
 
 // ---- gemm.hip ---------------------------------------------------------------
 struct GemmShape { int M_tiles, N_tiles, K_tiles; };
@@ -96,6 +112,12 @@ struct QkvOut {
     u16 *v; size_t v_unit_stride, v_head_stride;   // tiles [pos/32][dh/16], keys permuted inside
     const float *rope;         // (cos,sin) table
     int tiles_per_unit, pos_off, H, dh, d;
+    // Decoded-share step (rowpos != nullptr): row r sits at absolute position rowpos[r]; m-tiles from
+    // split_tile on belong to the speculative units (tiles_per_unit_b each), whose fresh K/V go to k_b / v_b.
+    const int32_t *rowpos;
+    int split_tile, tiles_per_unit_b;
+    u16 *k_b; size_t k_b_unit_stride, k_b_head_stride;
+    u16 *v_b; size_t v_b_unit_stride, v_b_head_stride;
 };
 // fp32 workspace for K-split partial sums (multi-draft step)
 struct Workspace { float *partial; size_t partial_bytes; };
@@ -123,6 +145,15 @@ struct AttnArgs {
     int L;                     // cached length
     int blk_lo, blk_hi;        // cached keys in [blk_lo, blk_hi) are ignored
     int fresh;                 // number of fresh keys per unit (0 in the prefill)
+    // Decoded-share step (split_tile > 0): m-tiles below split_tile are block_0 units (one per sequence, the
+    // fields above), the others speculative units (units_per_seq_b per sequence, tiles_per_unit_b tiles each)
+    // whose own fresh K/V are in kf_b / vf_b (mcount[seq] valid keys) and which also see block_0's fresh K/V
+    // of their sequence at the positions set in dmask[seq] (the decoded ones).
+    int split_tile, tiles_per_unit_b, units_per_seq_b;
+    const u16 *kf_b, *vf_b;
+    size_t kf_b_unit_stride, kf_b_head_stride, vf_b_unit_stride, vf_b_head_stride;
+    const int32_t *mcount;
+    const unsigned long long *dmask;
 };
 void launch_attention(AttnArgs a, hipStream_t s);
 

@@ -113,6 +113,100 @@ __global__ __launch_bounds__(256) void predict_length_kernel(const int32_t *toke
     }
 }
 
+// ---- decoded-share step (ODB-dLLM Sec. 4.2.2): row bookkeeping and the finish ----------------------
+// One wave per sequence builds the tables of SharedMap from the drafts (see model.h) and presets the
+// outputs of the positions of the speculative blocks that are not computed.
+__global__ __launch_bounds__(64) void shared_setup_kernel(const int32_t *drafts, SharedMap sm, int block_off, int mask_id,
+                                                          int m_cap, float *conf, int32_t *argmax, uint8_t *unmask,
+                                                          unsigned int *status) {
+    const int seq = blockIdx.x, lane = threadIdx.x, b = sm.b, S = sm.S;
+    const int32_t *d0 = drafts + (size_t)seq * S * b;
+    // b <= 64: lane i looks at position i of block_0
+    const bool in = lane < b, masked = in && d0[lane] == mask_id;
+    const unsigned long long mm = __ballot(masked), dm = __ballot(in && !masked);
+    const int m = __popcll(mm);
+    if (lane == 0) {
+        sm.mcount[seq] = m < m_cap ? m : m_cap;
+        sm.dmask[seq] = dm;
+        if (m > m_cap) atomicOr(status, 2u);
+    }
+    // block_0: bp rows, row i = position i
+    const int rowA = seq * sm.bp;
+    for (int i = lane; i < sm.bp; i += 64) {
+        sm.rowtok[rowA + i] = i < b ? d0[i] : 0;
+        sm.rowpos[rowA + i] = block_off + (i < b ? i : 0);
+        sm.rowout[rowA + i] = i < b ? (seq * S + 0) * b + i : -1;
+    }
+    // speculative blocks: mp <= 64 rows each, row j = j-th masked position (padding rows sit at the block's
+    // first position with token 0 and have no output); lane j owns row j
+    unsigned long long t = mm;
+    for (int k = 0; k < lane; k++) t &= t - 1;                       // drop the `lane` lowest set bits
+    const int mpos = t ? __ffsll(t) - 1 : -1;                        // position of the lane-th masked one, if any
+    const bool row_real = mpos >= 0 && lane < m_cap && lane < sm.mp;
+    for (int s = 1; s < S; s++) {
+        const int rowB = sm.batch * sm.bp + (seq * (S - 1) + (s - 1)) * sm.mp;
+        const int32_t *ds = d0 + (size_t)s * b;
+        if (lane < sm.mp) {
+            sm.rowtok[rowB + lane] = row_real ? ds[mpos] : 0;
+            sm.rowpos[rowB + lane] = block_off + (row_real ? mpos : 0);
+            sm.rowout[rowB + lane] = row_real ? (seq * S + s) * b + mpos : -1;
+        }
+        if (in && !masked) {                      // not computed: reads as "nothing to decide here"
+            const size_t o = (size_t)(seq * S + s) * b + lane;
+            if (conf) conf[o] = 0.f;
+            if (argmax) argmax[o] = ds[lane];
+            if (unmask) unmask[o] = 0;
+        }
+    }
+}
+
+void launch_shared_setup(const int32_t *drafts, SharedMap sm, int block_off, int mask_id, int m_cap, float *conf,
+                         int32_t *argmax, uint8_t *unmask, unsigned int *status, hipStream_t s) {
+    shared_setup_kernel<<<dim3(sm.batch), 64, 0, s>>>(drafts, sm, block_off, mask_id, m_cap, conf, argmax, unmask, status);
+}
+
+// One workgroup per unit (block_0 of a sequence, or one of its speculative blocks): confidence and greedy token
+// of every real row, then the acceptance rule over the unit's rows that still hold MASK; results are scattered
+// to their positions in the [batch, S, b] outputs.
+__global__ __launch_bounds__(512) void lm_finish_shared_kernel(const float *stats, int n_part, SharedMap sm, int mask_id,
+                                                               float tau, float *conf, int32_t *argmax, uint8_t *unmask) {
+    __shared__ float s_conf[64];
+    const int u = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const bool spec = u >= sm.batch;
+    const int seq = spec ? (u - sm.batch) / (sm.S - 1) : u;
+    const int row0 = spec ? sm.batch * sm.bp + (u - sm.batch) * sm.mp : u * sm.bp;
+    const int nrows = spec ? sm.mcount[seq] : sm.b;
+    for (int i = wave; i < nrows; i += nw) {
+        const Stat acc = merge_row_partials(stats + (size_t)(row0 + i) * n_part * 3, n_part, lane);
+        if (lane == 0) {
+            const float c = 1.0f / acc.s;
+            const int o = sm.rowout[row0 + i];
+            conf[o] = c;
+            argmax[o] = acc.a;
+            s_conf[i] = c;
+        }
+    }
+    __syncthreads();
+    if (wave == 0) {
+        float best = -1.f;
+        int best_i = 0x7fffffff;
+        const bool masked = lane < nrows && sm.rowtok[row0 + lane] == mask_id;
+        if (masked) { best = s_conf[lane]; best_i = lane; }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            float ob = __shfl_xor(best, o);
+            int oi = __shfl_xor(best_i, o);
+            if (ob > best || (ob == best && oi < best_i)) { best = ob; best_i = oi; }
+        }
+        if (lane < nrows) unmask[sm.rowout[row0 + lane]] = (masked && (s_conf[lane] > tau || lane == best_i)) ? 1 : 0;
+    }
+}
+
+void launch_lm_finish_shared(const float *stats, int n_part, SharedMap sm, int mask_id, float tau, float *conf,
+                             int32_t *argmax, uint8_t *unmask, hipStream_t s) {
+    lm_finish_shared_kernel<<<dim3(sm.batch * sm.S), 512, 0, s>>>(stats, n_part, sm, mask_id, tau, conf, argmax, unmask);
+}
+
 // Accept-jump controller (ODB-dLLM Sec. 4.2.1), one wave per sequence.  Inputs are the four drafts of a
 // block step (block_0; B unmasked; D unmasked; both) and that step's outputs.  A candidate is verified in a
 // draft when the draft's step unmasks its position with the speculated token.  Both verified in block_0 ->

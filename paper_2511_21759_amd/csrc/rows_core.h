@@ -66,6 +66,28 @@ __device__ inline Stat merge(Stat x, Stat y) {
     return o;
 }
 
+// the whole wave merges the n_part partials of one row (p = first partial of the row); every lane gets the result
+__device__ __forceinline__ Stat merge_row_partials(const float *p, int n_part, int lane) {
+    Stat acc = {-INFINITY, 0.f, 0x7fffffff};
+    for (int q0 = 0; q0 < n_part; q0 += 64 * 8) {            // eight independent partials per lane and pass
+        Stat t[8];
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            int q = q0 + lane + 64 * j;
+            if (q < n_part) t[j] = Stat{p[q * 3], p[q * 3 + 1], __float_as_int(p[q * 3 + 2])};
+            else t[j] = Stat{-INFINITY, 0.f, 0x7fffffff};
+        }
+#pragma unroll
+        for (int j = 0; j < 8; j++) acc = merge(acc, t[j]);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        Stat t = {__shfl_xor(acc.m, o), __shfl_xor(acc.s, o), __shfl_xor(acc.a, o)};
+        acc = merge(acc, t);
+    }
+    return acc;
+}
+
 // One workgroup finishes unit u: merges the partial statistics of its rpu rows, then applies the
 // acceptance rule (ODB-dLLM Sec. 3, Observation 3, plus the forced most-confident pick).
 __device__ __forceinline__ void lm_finish_wg(int u, const float *stats, int n_part, int rows, int rpu, int rpu_pad,
@@ -77,23 +99,7 @@ __device__ __forceinline__ void lm_finish_wg(int u, const float *stats, int n_pa
         int row = u * rpu + i;                                  // compact output row
         if (row >= rows) break;
         const float *p = stats + ((size_t)u * rpu_pad + i) * n_part * 3;
-        Stat acc = {-INFINITY, 0.f, 0x7fffffff};
-        for (int q0 = 0; q0 < n_part; q0 += 64 * 8) {            // eight independent partials per lane and pass
-            Stat t[8];
-#pragma unroll
-            for (int j = 0; j < 8; j++) {
-                int q = q0 + lane + 64 * j;
-                if (q < n_part) t[j] = Stat{p[q * 3], p[q * 3 + 1], __float_as_int(p[q * 3 + 2])};
-                else t[j] = Stat{-INFINITY, 0.f, 0x7fffffff};
-            }
-#pragma unroll
-            for (int j = 0; j < 8; j++) acc = merge(acc, t[j]);
-        }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            Stat t = {__shfl_xor(acc.m, o), __shfl_xor(acc.s, o), __shfl_xor(acc.a, o)};
-            acc = merge(acc, t);
-        }
+        const Stat acc = merge_row_partials(p, n_part, lane);
         if (lane == 0) {
             float c = 1.0f / acc.s;
             if (conf) conf[row] = c;

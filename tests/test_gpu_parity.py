@@ -474,3 +474,86 @@ def test_accept_jump_decoding_loop_on_the_peaked_model():
             steps, int((block == mask_id).sum()), sorted(chosen_seen)))
     finally:
         p.close()
+
+
+# ------------------------------------------------------------------ decoded-share step (Sec. 4.2.2)
+
+def _shared_workload(shape, P_len, R_len, b, S, seed, batch, frac_decoded, block_index=0):
+    """Tokens with a partly decoded block and S drafts that differ from block_0 only at masked positions."""
+    rng = np.random.default_rng(seed)
+    wl = W.decode_workload(shape, P_len, R_len, b, 1, seed, batch=batch, block_index=block_index)
+    tokens, off = wl.tokens.copy(), wl.block_off
+    V, mask_id = shape["vocab"], shape["mask_id"]
+    drafts = np.empty((batch, S, b), np.int32)
+    for bi in range(batch):
+        blk = np.full(b, mask_id, np.int32)
+        dec = rng.random(b) < frac_decoded
+        blk[dec] = rng.integers(0, V - 1, int(dec.sum()))
+        tokens[bi, off:off + b] = blk
+        drafts[bi] = blk
+        masked = np.flatnonzero(blk == mask_id)
+        for s in range(1, S):
+            k = min(masked.size, 1 + (s - 1) % 3)
+            if k:
+                drafts[bi, s, rng.permutation(masked)[:k]] = rng.integers(0, V - 1, k)
+    return tokens, drafts, off, wl.resp_off
+
+
+@pytest.mark.parametrize("Bn,P,R,b,S,frac,slack", [
+    (1, 64, 64, 32, 4, 0.5, 0),      # half the block decoded
+    (1, 40, 24, 20, 3, 0.3, 2),      # ragged block, bound above the real count
+    (2, 96, 128, 64, 8, 0.75, 0),    # the paper's eight blocks, 64 positions, batch 2
+    (1, 64, 32, 32, 2, 0.0, 0),      # nothing decoded: the plain step
+    (2, 33, 31, 16, 5, 1.0, 0),      # everything decoded: the speculative blocks are empty
+    (1, 128, 64, 48, 8, 0.9, 3),     # few masked positions left
+])
+def test_decoded_share_step_against_the_oracle(tiny, Bn, P, R, b, S, frac, slack):
+    tokens, drafts, off, ro = _shared_workload(tiny.shape, P, R, b, S, 1000 + b + S, Bn, frac)
+    cache, oc = run_prefill_case(tiny, tokens, ro, "shared prefill")
+    mask_id, V = tiny.cfg.mask_id, tiny.cfg.vocab
+    n_masked = min(b, int((drafts[:, 0] == mask_id).sum(-1).max()) + slack)
+    dg = cuda_i32(drafts)
+    logits, rowout = B.odb_block_step_shared_logits(tiny.model, cache, dg, off, n_masked, V)
+    conf, am, um = B.odb_block_step_shared(tiny.model, cache, dg, off, n_masked, 0.9)
+    torch.cuda.synchronize()
+    B.odb_model_status(tiny.model)
+    logits, rowout = logits.cpu().numpy(), rowout.cpu().numpy()
+    conf, am, um = conf.cpu().numpy(), am.cpu().numpy(), um.cpu().numpy()
+    seen = np.zeros((Bn, S, b), bool)
+    for bi in range(Bn):
+        c_o, a_o, u_o, z_o = o.block_step_shared(tiny.cfg, tiny.w, oc[bi], drafts[bi], off, 0.9, return_logits=True)
+        pos_masked = np.flatnonzero(drafts[bi, 0] == mask_id)
+        for s in range(S):
+            where = np.arange(b) if s == 0 else pos_masked          # positions of the rows of this block
+            if where.size == 0:
+                continue
+            rows = np.array([int(np.flatnonzero(rowout == (bi * S + s) * b + p)[0]) for p in where])
+            z_g = logits[rows]
+            assert rel_err(z_g, z_o[s]) <= LOGIT_TOL, "shared step logits seq %d block %d: %g" % (bi, s, rel_err(z_g, z_o[s]))
+            err = np.abs(z_g - z_o[s]).max()
+            check_decisions(conf[bi, s, where], am[bi, s, where], c_o[s, where], a_o[s, where], z_o[s], err, "shared step")
+            check_unmask(um[bi, s, where][None], drafts[bi, s, where][None], c_o[s, where][None], 0.9, mask_id, err, "shared step")
+            seen[bi, s, where] = True
+        # positions of the speculative blocks that are not computed
+        rest = ~seen[bi]
+        assert np.all(conf[bi][rest] == 0) and np.array_equal(am[bi][rest], drafts[bi][rest]) and not um[bi][rest].any()
+    assert (rowout >= 0).sum() == seen.sum()
+    # block_0 is bit-identical to the plain step's block_0 only up to the GEMM variant (other row counts): compare loosely
+    c1, a1, u1 = (t.cpu().numpy() for t in B.odb_block_step(tiny.model, cache, cuda_i32(drafts[:, :1]), off, 0.9))
+    assert np.allclose(np.log(c1[:, 0]), np.log(conf[:, 0]), atol=5e-3)
+
+
+def test_decoded_share_step_errors(tiny):
+    tokens, drafts, off, ro = _shared_workload(tiny.shape, 32, 32, 16, 3, 5, 1, 0.5)
+    cache = tiny.cache(1, tokens.shape[1])
+    B.odb_prefill(tiny.model, cache, cuda_i32(tokens), ro)
+    m = int((drafts[0, 0] == tiny.cfg.mask_id).sum())
+    with pytest.raises(B.OdbError):
+        B.odb_block_step_shared(tiny.model, cache, cuda_i32(drafts), off, 17, 0.9)           # n_masked > b
+    with pytest.raises(B.OdbError):
+        B.odb_block_step_shared(tiny.model, cache, cuda_i32(drafts[:, :1]), off, m, 0.9)     # S < 2
+    if m > 1:
+        B.odb_block_step_shared(tiny.model, cache, cuda_i32(drafts), off, m - 1, 0.9)        # bound too small: reported by status
+        with pytest.raises(B.OdbError):
+            B.odb_model_status(tiny.model)
+        B.odb_model_status(tiny.model)                                                        # cleared
