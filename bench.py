@@ -95,7 +95,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="config1", choices=["config0", "config1", "config2", "config2_jump", "config3", "config3_chain", "config4"])
+    ap.add_argument("--workload", default="config1", choices=["config0", "config1", "config2", "config2_jump", "config2_shared", "config3", "config3_chain",
+                             "config4"])
     ap.add_argument("--resp", type=int, default=512, help="response length for config3 (512, 256 or 128)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
@@ -157,7 +158,7 @@ def main():
         label = "cache-refresh prefill, 8B shape, 512 prompt + %d MASK, batch 1" % args.resp
     else:
         wl = {"config0": W.config0, "config1": W.config1, "config2": W.config2, "config2_jump": W.config2,
-              "config4": W.config4}[name]()
+              "config2_shared": W.config2_shared, "config4": W.config4}[name]()
         Bn, L = wl.tokens.shape
         S, b = wl.drafts.shape[1:]
         cache = B.odb_cache_create(model, Bn, L)
@@ -182,6 +183,23 @@ def main():
                 B.odb_block_step(model, cache, drafts, wl.block_off, wl.tau, conf, am, um)
                 B.odb_accept_jump(model, drafts, conf, am, um, cand_pos, cand_tok)
         rows = Bn * S * b
+        extra = {}
+        if name == "config2_shared":
+            # decoded-share stage (ODB-dLLM Sec. 4.2.2): eight blocks, the speculative ones reduced to the still
+            # masked positions; the plain eight-draft step on the same drafts is timed beside it
+            n_masked = int((wl.drafts[:, 0] == shape["mask_id"]).sum(-1).max())
+            plain = run
+            for _ in range(3):
+                plain()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(10):
+                plain()
+            torch.cuda.synchronize()
+            extra = {"plain_8_draft_step_ms": (time.perf_counter() - t0) * 100.0, "n_masked": n_masked,
+                     "rows_plain": rows}
+            run = lambda: B.odb_block_step_shared(model, cache, drafts, wl.block_off, n_masked, wl.tau, conf, am, um)
+            rows = Bn * (b + (S - 1) * n_masked)
         flops = step_flops(shape, rows, L)
         alg_bytes = total_w + Bn * (L - b) * kv_bytes_per_pos(shape)
         label = "block-decode step, %s shape, cache L=%d, block b=%d, S=%d drafts, batch %d" % (
@@ -233,8 +251,8 @@ def main():
         "value": rows / (ms * 1e-3), "unit": "rows/s" if wl is not None else "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "ms_per_step_gpu_events": ms_gpu,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
-        "config": {"workload": "%s: %s" % (name, label), "rows_per_step": rows,
-                   "steps_per_s": 1e3 / ms},
+        "config": dict({"workload": "%s: %s" % (name, label), "rows_per_step": rows,
+                        "steps_per_s": 1e3 / ms}, **(extra if wl is not None else {})),
         "step_hbm": {"algorithmic_bytes": alg_bytes, "achieved_GBps": alg_bytes / (ms * 1e-3) / 1e9,
                      "frac_of_8TBps": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "step_mfma": {"flops": flops, "achieved_TFLOPps": flops / (ms * 1e-3) / 1e12,

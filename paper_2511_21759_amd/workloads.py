@@ -125,3 +125,9 @@ def config4_small(seed: int = WEIGHT_SEED + 4) -> DecodeWorkload:
     """Config 4's structure (batch 4, block of 64, S=8: 2048 rows) on a 256 + 256 context, second response block:
     small enough for the CPU oracle at the full 8B width with two layers (parity test, not a bench line)."""
     return decode_workload(MODEL_SHAPES["8b"], 256, 256, 64, 8, seed, batch=4, block_index=1)
+
+
+def config2_shared(seed: int = WEIGHT_SEED + 1) -> DecodeWorkload:
+    """Decoded-share stage (ODB-dLLM Sec. 4.2.2): config 1's cache, a block of 32 three quarters decoded, block_0
+    plus seven speculative blocks (third, top three, fourth, top four candidates on top of B, D, B+D)."""
+    return decode_workload(MODEL_SHAPES["8b"], 256, 256, 32, 8, seed, p_unmasked=0.75)

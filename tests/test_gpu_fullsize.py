@@ -141,6 +141,55 @@ def test_batch4_long_block_against_stored_oracle():
         B.odb_model_destroy(model)
 
 
+def test_decoded_share_step_properties_at_full_width():
+    """The decoded-share step (ODB-dLLM Sec. 4.2.2) at the 8B width with two layers, head_dim 128, checked by the
+    properties that pin its oracle: with nothing decoded it is the plain step; block_0 is the plain step's
+    block_0; a speculative block that repeats block_0's tokens reproduces block_0 at the masked positions;
+    speculative blocks do not see each other."""
+    shape = dict(W.MODEL_SHAPES["8b"], n_layers=2)
+    wl = W.config2()
+    mask_id = shape["mask_id"]
+    model = B.odb_model_create(shape)
+    try:
+        B.odb_model_init_random(model, W.WEIGHT_SEED, W.WEIGHT_STD)
+        L = wl.tokens.shape[1]
+        cache = B.odb_cache_create(model, 1, L)
+        B.odb_prefill(model, cache, cuda_i32(wl.tokens), wl.resp_off)
+        blk = wl.drafts[0, 0]
+        masked = np.flatnonzero(blk == mask_id)
+        assert 4 <= masked.size < 32
+        rng = np.random.default_rng(17)
+        drafts = np.stack([blk] * 8)[None].copy()                      # [1, 8, 32]
+        for s in (1, 2, 3, 5, 6, 7):                                    # blocks 4 stays a copy of block_0
+            drafts[0, s, masked[s % masked.size]] = int(rng.integers(0, 1000))
+        d = cuda_i32(drafts)
+        conf, am, um = (t.cpu().numpy()[0] for t in B.odb_block_step_shared(model, cache, d, wl.block_off, int(masked.size), wl.tau))
+        B.odb_model_status(model)
+        c0, a0, u0 = (t.cpu().numpy()[0, 0] for t in B.odb_block_step(model, cache, cuda_i32(drafts[:, :1]), wl.block_off, wl.tau))
+        assert np.allclose(np.log(conf[0]), np.log(c0), atol=2e-2) and (am[0] == a0).mean() >= 0.9
+        assert np.allclose(np.log(conf[4, masked]), np.log(conf[0, masked]), atol=2e-2)
+        assert (am[4, masked] == am[0, masked]).mean() >= 0.8 and um[4].sum() == 1 and um[0].sum() == 1
+        dec = np.flatnonzero(blk != mask_id)
+        assert np.all(conf[1:][:, dec] == 0) and np.array_equal(am[1:][:, dec], drafts[0][1:][:, dec]) and not um[1:][:, dec].any()
+        # another speculative block changes: the others are bit-identical (same rows, same kernels)
+        d2 = drafts.copy()
+        d2[0, 7, masked[0]] = 77
+        conf2 = B.odb_block_step_shared(model, cache, cuda_i32(d2), wl.block_off, int(masked.size), wl.tau)[0].cpu().numpy()[0]
+        assert np.array_equal(conf2[:7], conf[:7]) and not np.array_equal(conf2[7], conf[7])
+        # nothing decoded: every block is computed in full, as in the plain step
+        allm = np.full((1, 4, 32), mask_id, np.int32)
+        allm[0, 1, 3], allm[0, 2, 9], allm[0, 3, 30] = 5, 6, 7
+        tok2 = wl.tokens.copy()
+        tok2[0, wl.block_off:wl.block_off + 32] = mask_id
+        B.odb_prefill(model, cache, cuda_i32(tok2), wl.resp_off)
+        cs, as_, us = (t.cpu().numpy()[0] for t in B.odb_block_step_shared(model, cache, cuda_i32(allm), wl.block_off, 32, wl.tau))
+        cp, ap, up = (t.cpu().numpy()[0] for t in B.odb_block_step(model, cache, cuda_i32(allm), wl.block_off, wl.tau))
+        assert np.allclose(np.log(cs[0]), np.log(cp[0]), atol=2e-2) and (as_[0] == ap[0]).mean() >= 0.9
+        B.odb_cache_destroy(cache)
+    finally:
+        B.odb_model_destroy(model)
+
+
 def test_full_size_properties_without_an_oracle():
     """Properties that hold at any size (ODB-dLLM Sec. 2.1, Sec. 4.2), on the benchmarked 32-layer model:
     the generator matches sampled slices of the oracle's, a step on the unchanged block reproduces the
