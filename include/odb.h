@@ -192,7 +192,8 @@ int odb_predict_length(const odb_model *m, const int32_t *tokens_dev, const floa
  * every layer its rows attend to the cached K/V outside the block, to block_0's fresh K/V
  * of the decoded positions, and to their own fresh K/V - not to other speculative blocks,
  * not to block_0's rows at masked positions.  So the decoded tokens are computed once per
- * step and the step has b + (S-1) * n_masked rows per sequence instead of S * b.
+ * step and the step has b + (S-1) * n_masked rows per sequence (each of the two parts
+ * padded to a multiple of 16) instead of S * b.
  *   n_masked    host value: upper bound of the MASK positions in block_0 of any sequence
  *               (sets the row count; a block with more raises an error that
  *               odb_model_status reports as ODB_E_INVALID_ARG, its outputs are then invalid)
@@ -206,7 +207,8 @@ int odb_block_step_shared(odb_model *m, const odb_cache *c, const int32_t *draft
                           float *conf_dev, int32_t *argmax_dev, uint8_t *unmask_dev, void *stream);
 
 /* Test aid: rows of a decoded-share step (block_0 of every sequence, padded to 16, then
- * the speculative blocks, each padded to 16), or a negative error code. */
+ * per sequence its speculative blocks one after the other, together padded to 16), or a
+ * negative error code. */
 int odb_block_step_shared_rows(int batch, int b, int S, int n_masked);
 /* Test aid: the logits of every row of the decoded-share step, float [rows, vocab], and for
  * every row its index into [batch, S, b] (-1 for padding rows), int32 [rows]; both device

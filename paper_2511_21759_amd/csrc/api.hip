@@ -168,7 +168,7 @@ int run_stack(Model &m, const Cache &c, const Plan &pl, const StackIO &io, hipSt
     const int d = cfg.d_model, H = cfg.n_heads, dh = cfg.head_dim, F = cfg.d_ff;
     const SharedMap *sm = io.shared;
     const int rows_pad = sm ? sm->rows() : io.rm.units * io.rm.rpu_pad, mt = rows_pad / 16, tpu = io.rm.rpu_pad / 16;
-    // decoded-share step: fresh K/V of the batch block_0 units (bp32 rows each) first, then of the speculative units (mp32 rows each)
+    // decoded-share step: fresh K/V of the batch block_0 units (bp32 rows each) first, then of the pooled speculative units (mp32 rows each)
     const int mp32 = sm ? ru(sm->mp, 32) : 0;
     const size_t spec_off = sm ? (size_t)sm->batch * H * ru(sm->bp, 32) * dh : 0;
     const size_t seq_elems = (size_t)H * c.lmax32 * dh;
@@ -219,7 +219,7 @@ int run_stack(Model &m, const Cache &c, const Plan &pl, const StackIO &io, hipSt
         a.units_per_seq = io.units_per_seq; a.L = c.length; a.blk_lo = io.blk_lo; a.blk_hi = io.blk_hi;
         a.fresh = io.fresh;
         if (sm) {
-            a.split_tile = qo.split_tile; a.tiles_per_unit_b = qo.tiles_per_unit_b; a.units_per_seq_b = sm->S - 1;
+            a.split_tile = qo.split_tile; a.tiles_per_unit_b = qo.tiles_per_unit_b; a.spec_blocks = sm->S - 1;
             a.kf_b = qo.k_b; a.kf_b_unit_stride = qo.k_b_unit_stride; a.kf_b_head_stride = qo.k_b_head_stride;
             a.vf_b = qo.v_b; a.vf_b_unit_stride = qo.v_b_unit_stride; a.vf_b_head_stride = qo.v_b_head_stride;
             a.mcount = sm->mcount; a.dmask = sm->dmask;
@@ -628,9 +628,9 @@ static int step_shared_impl(odb_model *mh, const odb_cache *ch, const int32_t *d
     HIP_TRY(hipSetDevice(m.device));
     const odb_config &cfg = m.cfg;
     SharedMap sm;
-    sm.batch = c.batch; sm.S = S; sm.b = b; sm.bp = ru(b, 16); sm.mp = ru(n_masked > 0 ? n_masked : 1, 16);
+    sm.batch = c.batch; sm.S = S; sm.b = b; sm.bp = ru(b, 16); sm.mp = ru(n_masked > 0 ? (S - 1) * n_masked : 1, 16);
     const int rows_pad = sm.rows();
-    const int fresh_rows = c.batch * ru(sm.bp, 32) + c.batch * (S - 1) * ru(sm.mp, 32);
+    const int fresh_rows = c.batch * (ru(sm.bp, 32) + ru(sm.mp, 32));
     const size_t tables = align_up((size_t)rows_pad * 4, 256) * 3 + align_up((size_t)c.batch * 4, 256) +
                           align_up((size_t)c.batch * 8, 256);
     Plan pl = make_plan(cfg, rows_pad, fresh_rows, rows_pad, logits == nullptr, tables);
@@ -682,7 +682,7 @@ int odb_block_step_shared(odb_model *m, const odb_cache *c, const int32_t *draft
 
 int odb_block_step_shared_rows(int batch, int b, int S, int n_masked) {
     if (batch < 1 || b < 1 || S < 2 || n_masked < 0 || n_masked > b) return fail(ODB_E_INVALID_ARG, "block_step_shared_rows");
-    return batch * ru(b, 16) + batch * (S - 1) * ru(n_masked > 0 ? n_masked : 1, 16);
+    return batch * (ru(b, 16) + ru(n_masked > 0 ? (S - 1) * n_masked : 1, 16));
 }
 
 int odb_block_step_shared_logits(odb_model *m, const odb_cache *c, const int32_t *drafts_dev, int block_off, int b,

@@ -34,15 +34,22 @@ __device__ inline void store_out_tile(const AttnArgs &a, int mt, int hd, int dt1
 
 // Scores of one 32-key tile (K fragments kf) against QT row tiles, online-softmax update of the running
 // (max, sum) and the rescaling of O that goes with it; returns the probabilities as operand fragments pf.
-// MASK: some keys of the tile may be invisible.  mode kKeysCached: cache positions key0 .. key0+31, those past
-// L or inside the block are masked; kKeysFresh: fresh keys of the rows' own unit, those from fresh_n on are
-// masked; kKeysShared: fresh keys of block_0 of the sequence, visible where bit key of `visible` is set.
+// MASK: some keys of the tile may be invisible, as KeyVis says.  kKeysCached: cache positions key0 .. key0+31,
+// those past L or inside the block are masked; kKeysFresh: fresh keys of the rows' own unit, those from fresh_n
+// on are masked; kKeysShared: fresh keys of block_0 of the sequence, visible where bit key of `visible` is set;
+// kKeysPooled: the fresh keys of all speculative blocks of the sequence, m per block one after the other - a
+// row sees those of its own block only (block of row r of the pooled unit = r / m), the block-diagonal mask of
+// the decoded-share stage.
 // The running references mrun are in log2 units (raw score * sc, sc = log2(e)/sqrt(dh) > 0).
 constexpr float kAttnSlack = 8.0f;
-constexpr int kKeysCached = 0, kKeysFresh = 1, kKeysShared = 2;
+constexpr int kKeysCached = 0, kKeysFresh = 1, kKeysShared = 2, kKeysPooled = 3;
+struct KeyVis {
+    int mode, fresh_n;               // fresh_n: number of valid fresh keys (kKeysFresh, kKeysPooled)
+    unsigned long long visible;      // kKeysShared
+    int m, row0;                     // kKeysPooled: keys per block, first row of the tile inside the pooled unit
+};
 template <int DH, int QT, bool MASK>
-__device__ __forceinline__ void attn_scores(const AttnArgs &a, float sc, int key0, int mode, int fresh_n,
-                                            unsigned long long visible,
+__device__ __forceinline__ void attn_scores(const AttnArgs &a, float sc, int key0, const KeyVis &kv,
                                             const frag_t (&kf)[2][DH / 32], const frag_t (&q)[QT][DH / 32],
                                             f32x4 (&o)[QT][DH / 16], float (&mrun)[QT], float (&lrun)[QT],
                                             frag_t (&pf)[QT], int lane) {
@@ -50,14 +57,16 @@ __device__ __forceinline__ void attn_scores(const AttnArgs &a, float sc, int key
     const int g = lane >> 4;
     bool ok[2][4];
     if (MASK) {
+        const int my_block = kv.mode == kKeysPooled ? (kv.row0 + (lane & 15)) / kv.m : 0;     // QT == 1 in this mode
 #pragma unroll
         for (int s = 0; s < 2; s++)
 #pragma unroll
             for (int rr = 0; rr < 4; rr++) {
                 int key = key0 + s * 16 + 4 * g + rr;
-                ok[s][rr] = mode == kKeysCached ? (key < a.L && !(key >= a.blk_lo && key < a.blk_hi))
-                          : mode == kKeysFresh ? key < fresh_n
-                                               : (key < 64 && ((visible >> key) & 1ull) != 0);
+                ok[s][rr] = kv.mode == kKeysCached ? (key < a.L && !(key >= a.blk_lo && key < a.blk_hi))
+                          : kv.mode == kKeysFresh  ? key < kv.fresh_n
+                          : kv.mode == kKeysShared ? (key < 64 && ((kv.visible >> key) & 1ull) != 0)
+                                                   : (key < kv.fresh_n && key / kv.m == my_block);
             }
     }
 #pragma unroll
@@ -119,23 +128,20 @@ __device__ __forceinline__ void attn_pv(const frag_t (&vf)[DH / 16], const frag_
 }
 
 // true if some key of the 32-key tile at key0 may be invisible (see attn_scores)
-__device__ __forceinline__ bool attn_tile_masked(const AttnArgs &a, int key0, int mode, int fresh_n) {
-    return mode == kKeysCached ? (key0 + 32 > a.L || (key0 < a.blk_hi && key0 + 32 > a.blk_lo))
-         : mode == kKeysFresh ? key0 + 32 > fresh_n : true;
+__device__ __forceinline__ bool attn_tile_masked(const AttnArgs &a, int key0, const KeyVis &kv) {
+    return kv.mode == kKeysCached ? (key0 + 32 > a.L || (key0 < a.blk_hi && key0 + 32 > a.blk_lo))
+         : kv.mode == kKeysFresh ? key0 + 32 > kv.fresh_n : true;
 }
 
 // One 32-key tile (K fragments kf, V^T fragments vf) against QT row tiles: scores, online softmax, O update.
 template <int DH, int QT>
-__device__ __forceinline__ void attn_tile_update(const AttnArgs &a, float sc, int key0, int mode, int fresh_n,
-                                                 unsigned long long visible,
+__device__ __forceinline__ void attn_tile_update(const AttnArgs &a, float sc, int key0, const KeyVis &kv,
                                                  const frag_t (&kf)[2][DH / 32], const frag_t (&vf)[DH / 16],
                                                  const frag_t (&q)[QT][DH / 32], f32x4 (&o)[QT][DH / 16],
                                                  float (&mrun)[QT], float (&lrun)[QT], int lane) {
     frag_t pf[QT];
-    if (attn_tile_masked(a, key0, mode, fresh_n))
-        attn_scores<DH, QT, true>(a, sc, key0, mode, fresh_n, visible, kf, q, o, mrun, lrun, pf, lane);
-    else
-        attn_scores<DH, QT, false>(a, sc, key0, mode, fresh_n, visible, kf, q, o, mrun, lrun, pf, lane);
+    if (attn_tile_masked(a, key0, kv)) attn_scores<DH, QT, true>(a, sc, key0, kv, kf, q, o, mrun, lrun, pf, lane);
+    else attn_scores<DH, QT, false>(a, sc, key0, kv, kf, q, o, mrun, lrun, pf, lane);
     attn_pv<DH, QT>(vf, pf, o);
 }
 
@@ -143,8 +149,9 @@ template <int QT, int NW>
 constexpr int attn_smem_bytes() { return NW * 4 * 1024 + 2 * NW * QT * 16 * 4; }
 
 // One work item: QT row tiles (chunk `item` of the units' tiles) of head hd.  sc = log2(e)/sqrt(dh).
-// SHARED (decoded-share step, QT = 1): item is the m-tile; tiles from a.split_tile on belong to speculative
-// units, which see the cache, their own fresh keys and block_0's fresh keys at the decoded positions.
+// SHARED (decoded-share step, QT = 1): item is the m-tile; tiles from a.split_tile on belong to the pooled
+// speculative unit of a sequence (the rows of its speculative blocks one after the other), whose rows see the
+// cache, the pooled fresh keys of their own block and block_0's fresh keys at the decoded positions.
 template <int DH, int QT, int NW, bool SHARED = false>
 __device__ __forceinline__ void attn_wg(const AttnArgs &a, float sc, int item, int hd, char *smem) {
     constexpr int DT32 = DH / 32, DT16 = DH / 16;
@@ -156,7 +163,7 @@ __device__ __forceinline__ void attn_wg(const AttnArgs &a, float sc, int item, i
     const int chunks = (tpu + QT - 1) / QT;
     const int item_u = spec ? item - a.split_tile : item;
     const int unit = item_u / chunks, tu0 = (item_u % chunks) * QT;
-    const int seq = unit / (spec ? a.units_per_seq_b : a.units_per_seq);
+    const int seq = spec ? unit : unit / a.units_per_seq;              // one pooled speculative unit per sequence
     const int mt_base = (spec ? a.split_tile : 0) + unit * tpu;           // first m-tile of the unit
     f32x4 (*s_o)[DC][64] = reinterpret_cast<f32x4 (*)[DC][64]>(smem);
     float (*s_m)[QT][16] = reinterpret_cast<float (*)[QT][16]>(smem + NW * 4 * 1024);
@@ -181,9 +188,12 @@ __device__ __forceinline__ void attn_wg(const AttnArgs &a, float sc, int item, i
         for (int dt = 0; dt < DT16; dt++) o[t][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    // own fresh keys that count, and (speculative units) which of block_0's fresh keys are visible
-    const int fresh_n = spec ? a.mcount[seq] : a.fresh;
-    const unsigned long long visible = spec ? a.dmask[seq] : 0ull;
+    // visibility of the unit's own fresh keys and (speculative unit) of block_0's
+    const int m_seq = spec ? (a.mcount[seq] > 0 ? a.mcount[seq] : 1) : 1;
+    const int fresh_n = spec ? a.spec_blocks * a.mcount[seq] : a.fresh;
+    const KeyVis vis_cached{kKeysCached, 0, 0ull, 1, 0};
+    const KeyVis vis_own{spec ? kKeysPooled : kKeysFresh, fresh_n, 0ull, m_seq, tu0 * 16};
+    const KeyVis vis_shared{kKeysShared, 0, spec ? a.dmask[seq] : 0ull, 1, 0};
     struct TileRef { const u16 *kp, *vp; int key0, mode; bool live; };
     auto load_tile = [&](const TileRef &r, frag_t (&kf)[2][DT32], frag_t (&vf)[DT16]) __attribute__((always_inline)) {
 #pragma unroll
@@ -196,7 +206,8 @@ __device__ __forceinline__ void attn_wg(const AttnArgs &a, float sc, int item, i
     };
     auto compute_tile = [&](const TileRef &r, const frag_t (&kf)[2][DT32], const frag_t (&vf)[DT16])
                             __attribute__((always_inline)) {
-        attn_tile_update<DH, QT>(a, sc, r.key0, r.mode, fresh_n, visible, kf, vf, q, o, mrun, lrun, lane);
+        attn_tile_update<DH, QT>(a, sc, r.key0, r.mode == kKeysCached ? vis_cached : (r.mode == kKeysShared ? vis_shared : vis_own),
+                                 kf, vf, q, o, mrun, lrun, lane);
     };
 
     // This wave's tiles: the 32-key tiles of the cache (those wholly inside the block are dead), then the
@@ -229,7 +240,7 @@ __device__ __forceinline__ void attn_wg(const AttnArgs &a, float sc, int item, i
             r.kp = kfr + (size_t)T * 2 * DT32 * kTileElems;
             r.vp = vfr + (size_t)T * DT16 * kTileElems;
             r.key0 = T * 32;
-            r.mode = kKeysFresh;
+            r.mode = kKeysFresh;          // (pooled for a speculative unit: see vis_own)
             r.live = true;
         } else {
             const int T = gi - n32 - nf32;

@@ -88,14 +88,15 @@ void launch_predict_length(const int32_t *tokens, const float *conf, const int32
 void launch_lm_finish(const float *stats, int n_part, int rows, int rpu, int rpu_pad, const int32_t *tokens,
                       int mask_id, float tau, float *conf, int32_t *argmax, uint8_t *unmask, hipStream_t s);
 // Decoded-share step: row bookkeeping built on the device from the drafts.  Rows: block_0 of every sequence
-// first (batch units of bp rows), then the speculative units (batch * (S-1) of mp rows), which hold the
-// positions that are MASK in block_0, in increasing order.
+// first (batch units of bp rows), then one pooled speculative unit per sequence (mp rows): its S-1 speculative
+// blocks one after the other, each the positions that are MASK in block_0, in increasing order (mcount[seq]
+// rows per block, so the pooled unit is dense and only its end is padding).
 struct SharedMap {
     int batch, S, b, bp, mp;           // bp, mp: rows per unit, multiples of 16
     int32_t *rowtok, *rowpos, *rowout; // per row: token, absolute position, index into [batch, S, b] (-1: padding)
     int32_t *mcount;                   // [batch] masked positions of block_0
     unsigned long long *dmask;         // [batch] bit i set: position i of the block is decoded
-    int rows() const { return batch * bp + batch * (S - 1) * mp; }
+    int rows() const { return batch * (bp + mp); }
 };
 // fills the tables, presets the outputs of the positions that are not computed (conf 0, argmax = token,
 // unmask 0) and raises status bit 2 if a block has more than m_cap masked positions
@@ -146,10 +147,11 @@ struct AttnArgs {
     int blk_lo, blk_hi;        // cached keys in [blk_lo, blk_hi) are ignored
     int fresh;                 // number of fresh keys per unit (0 in the prefill)
     // Decoded-share step (split_tile > 0): m-tiles below split_tile are block_0 units (one per sequence, the
-    // fields above), the others speculative units (units_per_seq_b per sequence, tiles_per_unit_b tiles each)
-    // whose own fresh K/V are in kf_b / vf_b (mcount[seq] valid keys) and which also see block_0's fresh K/V
-    // of their sequence at the positions set in dmask[seq] (the decoded ones).
-    int split_tile, tiles_per_unit_b, units_per_seq_b;
+    // fields above), the others the pooled speculative units (one per sequence, tiles_per_unit_b tiles: the
+    // rows of its spec_blocks speculative blocks, mcount[seq] each, one after the other).  Their fresh K/V are in
+    // kf_b / vf_b; a row sees the pooled keys of its own block and block_0's fresh K/V of its sequence at the
+    // positions set in dmask[seq] (the decoded ones).
+    int split_tile, tiles_per_unit_b, spec_blocks;
     const u16 *kf_b, *vf_b;
     size_t kf_b_unit_stride, kf_b_head_stride, vf_b_unit_stride, vf_b_head_stride;
     const int32_t *mcount;

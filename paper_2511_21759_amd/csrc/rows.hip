@@ -137,27 +137,32 @@ __global__ __launch_bounds__(64) void shared_setup_kernel(const int32_t *drafts,
         sm.rowpos[rowA + i] = block_off + (i < b ? i : 0);
         sm.rowout[rowA + i] = i < b ? (seq * S + 0) * b + i : -1;
     }
-    // speculative blocks: mp <= 64 rows each, row j = j-th masked position (padding rows sit at the block's
-    // first position with token 0 and have no output); lane j owns row j
-    unsigned long long t = mm;
-    for (int k = 0; k < lane; k++) t &= t - 1;                       // drop the `lane` lowest set bits
-    const int mpos = t ? __ffsll(t) - 1 : -1;                        // position of the lane-th masked one, if any
-    const bool row_real = mpos >= 0 && lane < m_cap && lane < sm.mp;
-    for (int s = 1; s < S; s++) {
-        const int rowB = sm.batch * sm.bp + (seq * (S - 1) + (s - 1)) * sm.mp;
-        const int32_t *ds = d0 + (size_t)s * b;
-        if (lane < sm.mp) {
-            sm.rowtok[rowB + lane] = row_real ? ds[mpos] : 0;
-            sm.rowpos[rowB + lane] = block_off + (row_real ? mpos : 0);
-            sm.rowout[rowB + lane] = row_real ? (seq * S + s) * b + mpos : -1;
+    // pooled speculative unit: row j = block 1 + j / mc, its (j % mc)-th masked position; rows past the last
+    // block are padding (token 0 at the block's first position, no output)
+    const int mc = m < m_cap ? m : m_cap;
+    const int rowB = sm.batch * sm.bp + seq * sm.mp;
+    for (int j = lane; j < sm.mp; j += 64) {
+        const int s = mc > 0 ? 1 + j / mc : S, r = mc > 0 ? j % mc : 0;
+        int tok = 0, pos = 0, out = -1;
+        if (s < S) {
+            unsigned long long t = mm;
+            for (int k = 0; k < r; k++) t &= t - 1;                  // drop the r lowest set bits
+            pos = __ffsll(t) - 1;                                    // the r-th masked position (r < mc <= m)
+            tok = d0[(size_t)s * b + pos];
+            out = (seq * S + s) * b + pos;
         }
-        if (in && !masked) {                      // not computed: reads as "nothing to decide here"
+        sm.rowtok[rowB + j] = tok;
+        sm.rowpos[rowB + j] = block_off + pos;
+        sm.rowout[rowB + j] = out;
+    }
+    // decoded positions of the speculative blocks are not computed: they read as "nothing to decide here"
+    if (in && !masked)
+        for (int s = 1; s < S; s++) {
             const size_t o = (size_t)(seq * S + s) * b + lane;
             if (conf) conf[o] = 0.f;
-            if (argmax) argmax[o] = ds[lane];
+            if (argmax) argmax[o] = d0[(size_t)s * b + lane];
             if (unmask) unmask[o] = 0;
         }
-    }
 }
 
 void launch_shared_setup(const int32_t *drafts, SharedMap sm, int block_off, int mask_id, int m_cap, float *conf,
@@ -173,9 +178,9 @@ __global__ __launch_bounds__(512) void lm_finish_shared_kernel(const float *stat
     __shared__ float s_conf[64];
     const int u = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     const bool spec = u >= sm.batch;
-    const int seq = spec ? (u - sm.batch) / (sm.S - 1) : u;
-    const int row0 = spec ? sm.batch * sm.bp + (u - sm.batch) * sm.mp : u * sm.bp;
+    const int seq = spec ? (u - sm.batch) / (sm.S - 1) : u, blk = spec ? (u - sm.batch) % (sm.S - 1) : 0;
     const int nrows = spec ? sm.mcount[seq] : sm.b;
+    const int row0 = spec ? sm.batch * sm.bp + seq * sm.mp + blk * nrows : u * sm.bp;
     for (int i = wave; i < nrows; i += nw) {
         const Stat acc = merge_row_partials(stats + (size_t)(row0 + i) * n_part * 3, n_part, lane);
         if (lane == 0) {
