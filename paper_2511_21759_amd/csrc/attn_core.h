@@ -43,13 +43,17 @@ __device__ inline void store_out_tile(const AttnArgs &a, int mt, int hd, int dt1
 // The running references mrun are in log2 units (raw score * sc, sc = log2(e)/sqrt(dh) > 0).
 constexpr float kAttnSlack = 8.0f;
 constexpr int kKeysCached = 0, kKeysFresh = 1, kKeysShared = 2, kKeysPooled = 3;
+// What attn_scores needs to know about key visibility (all wave-uniform):
+//   mode; fresh_n: number of valid fresh keys (kKeysFresh, kKeysPooled); visible: kKeysShared;
+//   m, row0 (kKeysPooled): keys per block, first row of the tile inside the pooled unit.
+// POOL: the kKeysShared / kKeysPooled modes can occur (decoded-share step only; compiled out otherwise).
 struct KeyVis {
-    int mode, fresh_n;               // fresh_n: number of valid fresh keys (kKeysFresh, kKeysPooled)
-    unsigned long long visible;      // kKeysShared
-    int m, row0;                     // kKeysPooled: keys per block, first row of the tile inside the pooled unit
+    int fresh_n;
+    unsigned long long visible;
+    int m, row0;
 };
-template <int DH, int QT, bool MASK>
-__device__ __forceinline__ void attn_scores(const AttnArgs &a, float sc, int key0, const KeyVis &kv,
+template <int DH, int QT, bool MASK, bool POOL = false>
+__device__ __forceinline__ void attn_scores(const AttnArgs &a, float sc, int key0, int mode, const KeyVis &kv,
                                             const frag_t (&kf)[2][DH / 32], const frag_t (&q)[QT][DH / 32],
                                             f32x4 (&o)[QT][DH / 16], float (&mrun)[QT], float (&lrun)[QT],
                                             frag_t (&pf)[QT], int lane) {
@@ -57,17 +61,33 @@ __device__ __forceinline__ void attn_scores(const AttnArgs &a, float sc, int key
     const int g = lane >> 4;
     bool ok[2][4];
     if (MASK) {
-        const int my_block = kv.mode == kKeysPooled ? (kv.row0 + (lane & 15)) / kv.m : 0;     // QT == 1 in this mode
+        if (POOL && mode == kKeysPooled) {
+            // a row sees the keys [blk * m, blk * m + m) of its own block, blk = row / m (QT == 1 in this mode)
+            const int lo = (kv.row0 + (lane & 15)) / kv.m * kv.m, hi = lo + kv.m < kv.fresh_n ? lo + kv.m : kv.fresh_n;
 #pragma unroll
-        for (int s = 0; s < 2; s++)
+            for (int s = 0; s < 2; s++)
 #pragma unroll
-            for (int rr = 0; rr < 4; rr++) {
-                int key = key0 + s * 16 + 4 * g + rr;
-                ok[s][rr] = kv.mode == kKeysCached ? (key < a.L && !(key >= a.blk_lo && key < a.blk_hi))
-                          : kv.mode == kKeysFresh  ? key < kv.fresh_n
-                          : kv.mode == kKeysShared ? (key < 64 && ((kv.visible >> key) & 1ull) != 0)
-                                                   : (key < kv.fresh_n && key / kv.m == my_block);
-            }
+                for (int rr = 0; rr < 4; rr++) {
+                    int key = key0 + s * 16 + 4 * g + rr;
+                    ok[s][rr] = key >= lo && key < hi;
+                }
+        } else if (POOL && mode == kKeysShared) {
+#pragma unroll
+            for (int s = 0; s < 2; s++)
+#pragma unroll
+                for (int rr = 0; rr < 4; rr++) {
+                    int key = key0 + s * 16 + 4 * g + rr;
+                    ok[s][rr] = key < 64 && ((kv.visible >> key) & 1ull) != 0;
+                }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 2; s++)
+#pragma unroll
+                for (int rr = 0; rr < 4; rr++) {
+                    int key = key0 + s * 16 + 4 * g + rr;
+                    ok[s][rr] = mode == kKeysCached ? (key < a.L && !(key >= a.blk_lo && key < a.blk_hi)) : key < kv.fresh_n;
+                }
+        }
     }
 #pragma unroll
     for (int t = 0; t < QT; t++) {
@@ -128,20 +148,20 @@ __device__ __forceinline__ void attn_pv(const frag_t (&vf)[DH / 16], const frag_
 }
 
 // true if some key of the 32-key tile at key0 may be invisible (see attn_scores)
-__device__ __forceinline__ bool attn_tile_masked(const AttnArgs &a, int key0, const KeyVis &kv) {
-    return kv.mode == kKeysCached ? (key0 + 32 > a.L || (key0 < a.blk_hi && key0 + 32 > a.blk_lo))
-         : kv.mode == kKeysFresh ? key0 + 32 > kv.fresh_n : true;
+__device__ __forceinline__ bool attn_tile_masked(const AttnArgs &a, int key0, int mode, int fresh_n) {
+    return mode == kKeysCached ? (key0 + 32 > a.L || (key0 < a.blk_hi && key0 + 32 > a.blk_lo))
+         : mode == kKeysFresh ? key0 + 32 > fresh_n : true;
 }
 
 // One 32-key tile (K fragments kf, V^T fragments vf) against QT row tiles: scores, online softmax, O update.
-template <int DH, int QT>
-__device__ __forceinline__ void attn_tile_update(const AttnArgs &a, float sc, int key0, const KeyVis &kv,
+template <int DH, int QT, bool POOL = false>
+__device__ __forceinline__ void attn_tile_update(const AttnArgs &a, float sc, int key0, int mode, const KeyVis &kv,
                                                  const frag_t (&kf)[2][DH / 32], const frag_t (&vf)[DH / 16],
                                                  const frag_t (&q)[QT][DH / 32], f32x4 (&o)[QT][DH / 16],
                                                  float (&mrun)[QT], float (&lrun)[QT], int lane) {
     frag_t pf[QT];
-    if (attn_tile_masked(a, key0, kv)) attn_scores<DH, QT, true>(a, sc, key0, kv, kf, q, o, mrun, lrun, pf, lane);
-    else attn_scores<DH, QT, false>(a, sc, key0, kv, kf, q, o, mrun, lrun, pf, lane);
+    if (attn_tile_masked(a, key0, mode, kv.fresh_n)) attn_scores<DH, QT, true, POOL>(a, sc, key0, mode, kv, kf, q, o, mrun, lrun, pf, lane);
+    else attn_scores<DH, QT, false, POOL>(a, sc, key0, mode, kv, kf, q, o, mrun, lrun, pf, lane);
     attn_pv<DH, QT>(vf, pf, o);
 }
 
@@ -191,9 +211,7 @@ __device__ __forceinline__ void attn_wg(const AttnArgs &a, float sc, int item, i
     // visibility of the unit's own fresh keys and (speculative unit) of block_0's
     const int m_seq = spec ? (a.mcount[seq] > 0 ? a.mcount[seq] : 1) : 1;
     const int fresh_n = spec ? a.spec_blocks * a.mcount[seq] : a.fresh;
-    const KeyVis vis_cached{kKeysCached, 0, 0ull, 1, 0};
-    const KeyVis vis_own{spec ? kKeysPooled : kKeysFresh, fresh_n, 0ull, m_seq, tu0 * 16};
-    const KeyVis vis_shared{kKeysShared, 0, spec ? a.dmask[seq] : 0ull, 1, 0};
+    const KeyVis kv{fresh_n, spec ? a.dmask[seq] : 0ull, m_seq, tu0 * 16};
     struct TileRef { const u16 *kp, *vp; int key0, mode; bool live; };
     auto load_tile = [&](const TileRef &r, frag_t (&kf)[2][DT32], frag_t (&vf)[DT16]) __attribute__((always_inline)) {
 #pragma unroll
@@ -206,8 +224,7 @@ __device__ __forceinline__ void attn_wg(const AttnArgs &a, float sc, int item, i
     };
     auto compute_tile = [&](const TileRef &r, const frag_t (&kf)[2][DT32], const frag_t (&vf)[DT16])
                             __attribute__((always_inline)) {
-        attn_tile_update<DH, QT>(a, sc, r.key0, r.mode == kKeysCached ? vis_cached : (r.mode == kKeysShared ? vis_shared : vis_own),
-                                 kf, vf, q, o, mrun, lrun, lane);
+        attn_tile_update<DH, QT, SHARED>(a, sc, r.key0, r.mode, kv, kf, vf, q, o, mrun, lrun, lane);
     };
 
     // This wave's tiles: the 32-key tiles of the cache (those wholly inside the block are dead), then the
@@ -240,7 +257,7 @@ __device__ __forceinline__ void attn_wg(const AttnArgs &a, float sc, int item, i
             r.kp = kfr + (size_t)T * 2 * DT32 * kTileElems;
             r.vp = vfr + (size_t)T * DT16 * kTileElems;
             r.key0 = T * 32;
-            r.mode = kKeysFresh;          // (pooled for a speculative unit: see vis_own)
+            r.mode = spec ? kKeysPooled : kKeysFresh;
             r.live = true;
         } else {
             const int T = gi - n32 - nf32;

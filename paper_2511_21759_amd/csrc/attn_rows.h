@@ -86,7 +86,7 @@ __global__ __launch_bounds__(64 * NW) void attn_rows_kernel(AttnArgs a, float sc
     // tile i-1.  Within an iteration the LDS reads run under the MFMAs: V of tile i is fetched before the
     // scores are computed, K of tile i+1 while P*V is issued (its registers are free by then).
     frag_t kf[2][DT32], vf[DT16], pf[QTW];
-    const KeyVis vis_cached{kKeysCached, 0, 0ull, 1, 0}, vis_fresh{kKeysFresh, a.fresh, 0ull, 1, 0};
+    const KeyVis kv{a.fresh, 0ull, 1, 0};
     auto read_k = [&](int i) __attribute__((always_inline)) {
         const stage_t &st = ring[i % NS];
 #pragma unroll
@@ -119,8 +119,8 @@ __global__ __launch_bounds__(64 * NW) void attn_rows_kernel(AttnArgs a, float sc
 #pragma unroll
             for (int dt = 0; dt < DT16; dt++) vf[dt] = st[2 * DT32 + dt][lane];
             const int key0 = tile_of(i) * 32;
-            if (!DUAL || attn_tile_masked(a, key0, vis_cached)) attn_scores<DH, QTW, true>(a, sc, key0, vis_cached, kf, q, o, mrun, lrun, pf, lane);
-            else attn_scores<DH, QTW, false>(a, sc, key0, vis_cached, kf, q, o, mrun, lrun, pf, lane);
+            if (!DUAL || attn_tile_masked(a, key0, kKeysCached, 0)) attn_scores<DH, QTW, true>(a, sc, key0, kKeysCached, kv, kf, q, o, mrun, lrun, pf, lane);
+            else attn_scores<DH, QTW, false>(a, sc, key0, kKeysCached, kv, kf, q, o, mrun, lrun, pf, lane);
             if (PIPE && i + 1 < n_live) read_k(i + 1);
             attn_pv<DH, QTW>(vf, pf, o);
         }
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(64 * NW) void attn_rows_kernel(AttnArgs a, float sc
             for (int dt = 0; dt < DT32; dt++) kf[s][dt] = ld_frag(kfr + ((size_t)T * 2 * DT32 + s * DT32 + dt) * kTileElems);
 #pragma unroll
         for (int dt = 0; dt < DT16; dt++) vf[dt] = ld_frag(vfr + ((size_t)T * DT16 + dt) * kTileElems);
-        attn_scores<DH, QTW, true>(a, sc, T * 32, vis_fresh, kf, q, o, mrun, lrun, pf, lane);
+        attn_scores<DH, QTW, true>(a, sc, T * 32, kKeysFresh, kv, kf, q, o, mrun, lrun, pf, lane);
         attn_pv<DH, QTW>(vf, pf, o);
     }
 

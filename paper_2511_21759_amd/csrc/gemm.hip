@@ -111,7 +111,7 @@ static void launch_big(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi 
 void launch_gemm_qkv(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, QkvOut out, Workspace ws, hipStream_t s) {
     EpiQKV e{out, sh.M_tiles};
     if (sh.M_tiles <= 2) launch_stream<2, 3, 8, 8, true>(xa, w, sh, ni, e, s);
-    else if (sh.M_tiles <= 8) launch_stream<8, 3, 2, 8, false>(xa, w, sh, ni, e, s);
+    else if (sh.M_tiles <= 8) launch_stream<8, 3, 4, 4, false>(xa, w, sh, ni, e, s);     // four waves: 24 accumulator tiles + the ring need the 512-register budget
     else if (use_big(sh)) launch_big(xa, w, sh, ni, e, s);
     else launch_tile(xa, w, sh, ni, e, ws, true, s);
 }

@@ -247,6 +247,11 @@ __device__ inline void st_bf16x4(u16 *p, float a, float b, float c, float d) {
     *reinterpret_cast<uint2 *>(p) = v;
 }
 
+// (by-value pick: `c ? x : y` on two struct members is an lvalue conditional, which the compiler turns into a
+// select of addresses and then parks the members on the stack)
+template <class T>
+__device__ __forceinline__ T pick(bool c, T a, T b) { return c ? a : b; }
+
 struct EpiQKV {
     QkvOut o;
     int mt_total;
@@ -256,11 +261,11 @@ struct EpiQKV {
         const int mi = lane & 15, g = lane >> 4;
         // unit and tile inside the unit; in the decoded-share step the speculative units have their own size and K/V area
         const bool spec = o.split_tile > 0 && mt >= o.split_tile;
-        const int unit = spec ? (mt - o.split_tile) / o.tiles_per_unit_b : mt / o.tiles_per_unit;
-        const int tu = spec ? (mt - o.split_tile) % o.tiles_per_unit_b : mt % o.tiles_per_unit;
-        u16 *kdst = spec ? o.k_b + unit * o.k_b_unit_stride : o.k + unit * o.k_unit_stride;
-        u16 *vdst = spec ? o.v_b + unit * o.v_b_unit_stride : o.v + unit * o.v_unit_stride;
-        const size_t khs = spec ? o.k_b_head_stride : o.k_head_stride, vhs = spec ? o.v_b_head_stride : o.v_head_stride;
+        const int tpu = pick(spec, o.tiles_per_unit_b, o.tiles_per_unit), mtu = pick(spec, mt - o.split_tile, mt);
+        const int unit = mtu / tpu, tu = mtu % tpu;
+        u16 *kdst = pick(spec, o.k_b, o.k) + unit * pick(spec, o.k_b_unit_stride, o.k_unit_stride);
+        u16 *vdst = pick(spec, o.v_b, o.v) + unit * pick(spec, o.v_b_unit_stride, o.v_unit_stride);
+        const size_t khs = pick(spec, o.k_b_head_stride, o.k_head_stride), vhs = pick(spec, o.v_b_head_stride, o.v_head_stride);
         const int n = nt * 16, sec = n / o.d, rr = n % o.d;
         const int hd = rr / o.dh, p0 = rr % o.dh;            // p0 is a multiple of 16
         if (sec < 2) {
