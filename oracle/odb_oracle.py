@@ -8,6 +8,8 @@ What it follows (ODB-dLLM, arXiv 2511.21759):
   * Sec. 2.1 (block-wise generation with a dual cache): K/V of every token
     outside the current block are cached by a full-sequence forward and reused
     while the block is decoded; the forward is bidirectional (no causal mask).
+    Once a block is filled the cache is refreshed for the next one: generate()
+    is that loop, with Sec. 4.1 and Sec. 4.2 as options.
   * Sec. 4.1 (adaptive length prediction): the refresh computes every response
     position and yields a decoding attempt (confidence, token) for all of them;
     the attempt is scanned for a confident [EOS] and the response cut there.
@@ -551,3 +553,106 @@ def block_step_shared(cfg: Config, w: Weights, cache: Cache, drafts: np.ndarray,
         logits.append(z)
     out = (conf, amax, unmask)
     return out + (logits,) if return_logits else out
+
+
+# --------------------------------------------------------------------------- the generation loop
+
+@dataclasses.dataclass(frozen=True)
+class GenParams:
+    """Knobs of the generation loop.  None of their values is printed in the paper."""
+    block_len: int                      # positions per block (32 in the paper's runs)
+    n_drafts: int = 1                   # 1: threshold decoding only; 4: accept-jump (Sec. 4.2.1)
+    tau: float = 0.9                    # acceptance threshold
+    eos_id: Optional[int] = None        # None: no length prediction
+    truncate_thr: float = 0.9           # Sec. 4.1
+    share_from: Optional[int] = None    # decoded positions of the block from which steps run in the
+                                        # decoded-share stage (Sec. 4.2.2); None: never
+
+
+def truncate_cache(cache: Cache, new_len: int) -> Cache:
+    """The cache of a sequence cut to new_len positions: the dropped positions' K/V are no longer keys."""
+    return Cache(cache.k[:, :new_len], cache.v[:, :new_len])
+
+
+def generate(cfg: Config, w: Weights, prompt: np.ndarray, resp_len: int, p: GenParams):
+    """Block-wise generation of one response (Sec. 2.1, with Sec. 4.1 and Sec. 4.2 switched on by p).
+
+    The response starts as resp_len MASK tokens behind the prompt and is decoded block by block, front
+    to back.  Each block cycle opens with a refresh: a forward over the whole sequence that rebuilds
+    the cache and attempts every response position.  Then, in this order:
+      * length prediction (Sec. 4.1) scans the attempt and may cut the sequence; the cut takes effect
+        at once - dropped positions leave the token sequence and stop being keys of this cycle's steps
+        (the K/V of the kept positions stay as the refresh computed them);
+      * the refresh's attempt at the positions of the current block is put through the acceptance
+        rule, so the refresh is also the block's first decoding iteration (unmasking decisions of a
+        refresh are restricted to the current block);
+      * decode steps against the cache follow until the block holds no MASK.  With n_drafts = 1 a step
+        forwards the block alone; with n_drafts = 4 it forwards the four accept-jump drafts and the
+        controller adopts one (the first candidates are the two most confident positions the refresh
+        left masked).  Once share_from positions of the block are decoded the step runs in the
+        decoded-share stage, with the same four drafts.
+    The block's tokens are written back and the next block cycle begins; generation ends when the
+    block start reaches the (possibly shortened) end of the sequence.
+
+    Returns (tokens[final_len], stats, events).  stats: n_refresh, n_step, n_step_shared (of n_step),
+    refresh_positions (sum of the refreshed lengths), step_rows (rows forwarded by the steps).
+    events: one dict per forward, in order - kind ('refresh' | 'step' | 'shared'), L (length after the
+    event), block_off, block_len, chosen, cand_pos, cand_tok, tokens (copy of the sequence after it).
+    """
+    mask_id, b = cfg.mask_id, p.block_len
+    assert p.n_drafts in (1, 4) and b >= 1 and resp_len >= 1
+    prompt = np.asarray(prompt, np.int32)
+    P = prompt.shape[0]
+    tokens = np.concatenate([prompt, np.full(resp_len, mask_id, np.int32)])
+    L, off = tokens.shape[0], P
+    stats = dict(n_refresh=0, n_step=0, n_step_shared=0, refresh_positions=0, step_rows=0)
+    events = []
+
+    def record(kind, bb, chosen, cp, ct):
+        events.append(dict(kind=kind, L=L, block_off=off, block_len=bb, chosen=int(chosen),
+                           cand_pos=np.array(cp, np.int32), cand_tok=np.array(ct, np.int32), tokens=tokens.copy()))
+
+    while off < L:
+        cache, conf, am = prefill(cfg, w, tokens, resp_off=P)
+        stats["n_refresh"] += 1
+        stats["refresh_positions"] += L
+        if p.eos_id is not None:
+            new_len = predict_length(tokens, conf, am, P, mask_id, p.eos_id, p.truncate_thr)
+            if new_len < L:
+                L = new_len
+                tokens, cache = tokens[:L], truncate_cache(cache, L)
+        if off >= L:                                    # the cut fell into what is already decoded
+            record("refresh", 0, 0, (-1, -1), (0, 0))
+            break
+        bb = min(b, L - off)
+        block = tokens[off:off + bb].copy()
+        c_blk, a_blk = conf[off - P:off - P + bb], am[off - P:off - P + bb]
+        um = threshold_unmask(block, c_blk, p.tau, mask_id)
+        block = np.where(um.astype(bool), a_blk, block).astype(np.int32)
+        cp, ct = speculative_candidates(block, c_blk, a_blk, mask_id)
+        tokens[off:off + bb] = block
+        record("refresh", bb, 0, cp, ct)
+        while (block == mask_id).any():
+            if p.n_drafts == 1:
+                conf_s, am_s, um_s = block_step(cfg, w, cache, block[None], off, p.tau)
+                block = np.where(um_s[0].astype(bool), am_s[0], block).astype(np.int32)
+                cp, ct = speculative_candidates(block, conf_s[0], am_s[0], mask_id)
+                chosen, kind, rows = 0, "step", bb
+            else:
+                drafts = accept_jump_drafts(block, cp, ct)
+                n_masked = int((block == mask_id).sum())
+                if p.share_from is not None and bb - n_masked >= p.share_from:
+                    conf_s, am_s, um_s = block_step_shared(cfg, w, cache, drafts, off, p.tau)
+                    kind, rows = "shared", bb + 3 * n_masked
+                    stats["n_step_shared"] += 1
+                else:
+                    conf_s, am_s, um_s = block_step(cfg, w, cache, drafts, off, p.tau)
+                    kind, rows = "step", 4 * bb
+                chosen, block, cp, ct, _ = accept_jump(drafts, conf_s, am_s, um_s, cp, ct, mask_id)
+            stats["n_step"] += 1
+            stats["step_rows"] += rows
+            tokens[off:off + bb] = block
+            record(kind, bb, chosen, cp, ct)
+        off += bb
+    stats["final_len"] = L
+    return tokens, stats, events

@@ -713,3 +713,150 @@ def test_shared_step_fully_decoded_block():
     cfg, w, cache, drafts, off = _shared_case(n_decoded=8)
     conf, am, um = o.block_step_shared(cfg, w, cache, drafts[:1].repeat(3, 0), off, 0.05)
     assert not um.any() and np.all(conf[1:] == 0) and conf[0].min() > 0
+
+
+# ------------------------------------------------------------------ the generation loop (Sec. 2.1 + 4.1 + 4.2)
+
+def _gen_setup(seed=11, P=12, gain=6.0):
+    rng = np.random.default_rng(seed)
+    w = o.Weights(MICRO, seed, 0.25)
+    w.set_values(o.T_GF, 0, np.full(MICRO.d_model, gain))
+    return w, rng.integers(0, MICRO.vocab - 1, P).astype(np.int32)
+
+
+def _n_masked(ev, P):
+    return int((ev["tokens"][P:] == MICRO.mask_id).sum())
+
+
+def test_generate_threshold_never_reached_decodes_one_position_per_forward():
+    """tau above 1: only forced progress acts, so every forward (refresh or step) fills exactly one position,
+    the most confident masked one of the current block, and R forwards fill R positions."""
+    w, prompt = _gen_setup()
+    P, R, b = len(prompt), 20, 8                                     # ragged last block of 4
+    tokens, stats, events = o.generate(MICRO, w, prompt, R, o.GenParams(block_len=b, tau=2.0))
+    assert stats["n_refresh"] == 3 and stats["n_refresh"] + stats["n_step"] == R == len(events)
+    assert stats["refresh_positions"] == 3 * (P + R) and stats["step_rows"] == 7 * 8 + 7 * 8 + 3 * 4
+    assert not (tokens == MICRO.mask_id).any() and np.array_equal(tokens[:P], prompt)
+    prev = np.concatenate([prompt, np.full(R, MICRO.mask_id, np.int32)])
+    for n, ev in enumerate(events):
+        diff = np.flatnonzero(ev["tokens"] != prev)
+        assert diff.size == 1 and ev["block_off"] <= diff[0] < ev["block_off"] + ev["block_len"]
+        assert prev[diff[0]] == MICRO.mask_id and ev["kind"] == ("refresh" if n in (0, 8, 16) else "step")
+        prev = ev["tokens"]
+
+
+def test_generate_threshold_always_reached_needs_refreshes_only():
+    """tau below 0: the refresh's attempt fills its whole block, no step ever runs, and block k holds the greedy
+    tokens of a full forward over the sequence as it stood when block k's cycle began."""
+    w, prompt = _gen_setup(seed=12)
+    P, R, b = len(prompt), 24, 8
+    tokens, stats, events = o.generate(MICRO, w, prompt, R, o.GenParams(block_len=b, tau=-1.0))
+    assert stats["n_step"] == 0 and stats["n_refresh"] == 3 and [e["kind"] for e in events] == ["refresh"] * 3
+    seq = np.concatenate([prompt, np.full(R, MICRO.mask_id, np.int32)])
+    for k in range(3):
+        _, _, am = o.prefill(MICRO, w, seq, resp_off=P)
+        seq[P + k * b:P + (k + 1) * b] = am[k * b:(k + 1) * b]
+        assert np.array_equal(events[k]["tokens"], seq)
+    assert np.array_equal(tokens, seq)
+
+
+def test_generate_steps_use_the_cache_of_the_cycles_refresh():
+    """The first block cycle redone from the primitives: acceptance on the refresh's attempt, then steps against
+    that same (ageing) cache, each on the block as the previous forward left it."""
+    w, prompt = _gen_setup(seed=13)
+    P, R, b, tau = len(prompt), 16, 8, 0.8
+    _, _, events = o.generate(MICRO, w, prompt, R, o.GenParams(block_len=b, tau=tau))
+    seq = np.concatenate([prompt, np.full(R, MICRO.mask_id, np.int32)])
+    cache, conf, am = o.prefill(MICRO, w, seq, resp_off=P)
+    blk = seq[P:P + b].copy()
+    take = conf[:b] > tau
+    take[np.argmax(conf[:b])] = True
+    blk[take] = am[:b][take]
+    assert np.array_equal(events[0]["tokens"][P:P + b], blk) and (events[0]["tokens"][P + b:] == MICRO.mask_id).all()
+    # the candidates a refresh hands to the first step: the two most confident positions it left masked
+    left = sorted(np.flatnonzero(blk == MICRO.mask_id), key=lambda i: -conf[i])[:2]
+    assert list(events[0]["cand_pos"][:len(left)]) == left and list(events[0]["cand_tok"][:len(left)]) == [am[i] for i in left]
+    _, _, ev4 = o.generate(MICRO, w, prompt, R, o.GenParams(block_len=b, n_drafts=4, tau=tau))
+    assert np.array_equal(ev4[0]["tokens"], events[0]["tokens"]) and np.array_equal(ev4[0]["cand_pos"], events[0]["cand_pos"])
+    d4 = np.stack([blk] * 4)
+    d4[1, left[0]] = d4[3, left[0]] = am[left[0]]
+    d4[2, left[1]] = d4[3, left[1]] = am[left[1]]
+    c4, a4, u4 = o.block_step(MICRO, w, cache, d4, P, tau)
+    s_ = ev4[1]["chosen"]
+    assert s_ == 1, "the case is chosen so that the first step adopts a speculative block"
+    assert np.array_equal(ev4[1]["tokens"][P:P + b], np.where(u4[s_] == 1, a4[s_], d4[s_]))
+    n = 1
+    while (blk == MICRO.mask_id).any():
+        c, a, u = o.block_step(MICRO, w, cache, blk[None], P, tau)
+        blk = np.where(u[0] == 1, a[0], blk)
+        assert events[n]["kind"] == "step" and np.array_equal(events[n]["tokens"][P:P + b], blk)
+        n += 1
+    assert n > 1, "the case must exercise at least one step"
+    assert events[n]["kind"] == "refresh" and events[n]["block_off"] == P + b
+
+
+def test_generate_length_prediction_cuts_at_the_attempted_eos():
+    """Sec. 4.1 inside the loop: the first refresh's attempt decides the first cut; the cut block is ragged; an
+    [EOS] decoded inside a finished block ends generation at the next refresh."""
+    w, prompt = _gen_setup(seed=14)
+    P, R, b = len(prompt), 24, 8
+    seq = np.concatenate([prompt, np.full(R, MICRO.mask_id, np.int32)])
+    _, conf, am = o.prefill(MICRO, w, seq, resp_off=P)
+    q = 8 + int(np.argmax(conf[8:20]))                                # a confident attempt in blocks 1-2
+    eos, thr = int(am[q]), float(conf[q]) * 0.999
+    first = min(i for i in range(R) if am[i] == eos and conf[i] > thr)
+    tokens, stats, events = o.generate(MICRO, w, prompt, R, o.GenParams(block_len=b, tau=0.6, eos_id=eos, truncate_thr=thr))
+    assert events[0]["L"] == P + first + 1 and len(events[0]["tokens"]) == P + first + 1
+    lens = [e["L"] for e in events]
+    assert all(x >= y for x, y in zip(lens, lens[1:])) and stats["final_len"] == lens[-1] == len(tokens)
+    assert not (tokens == MICRO.mask_id).any()
+    # a refresh runs at the length the previous event left behind
+    assert stats["refresh_positions"] == (P + R) + sum(events[i - 1]["L"] for i in range(1, len(events))
+                                                       if events[i]["kind"] == "refresh")
+    # never exceeded threshold: only a decoded [EOS] cuts.  Take the token block 0 really decodes first.
+    full, _, ev_full = o.generate(MICRO, w, prompt, R, o.GenParams(block_len=b, tau=0.6))
+    eos2 = int(full[P + 3])
+    j = int(np.flatnonzero(full[P:P + b] == eos2)[0])
+    tokens2, stats2, ev2 = o.generate(MICRO, w, prompt, R, o.GenParams(block_len=b, tau=0.6, eos_id=eos2, truncate_thr=2.0))
+    assert stats2["n_refresh"] == 2 and stats2["final_len"] == P + j + 1 and np.array_equal(tokens2, full[:P + j + 1])
+    assert ev2[-1]["kind"] == "refresh" and ev2[-1]["block_len"] == 0
+
+
+def test_generate_accept_jump_invariants_and_stage_switch():
+    """Four drafts: every forward fills at least one position of the block, drafts other than block_0 do get
+    adopted on peaked weights, a switch point beyond the block length never engages the decoded-share stage,
+    and a switch point of 0 runs every step in it (rows: b + 3 * masked instead of 4 * b)."""
+    seen = set()
+    for seed in (21, 22, 23):
+        w, prompt = _gen_setup(seed=seed, gain=8.0)
+        P, R, b = len(prompt), 16, 8
+        base = o.GenParams(block_len=b, n_drafts=4, tau=0.7)
+        tokens, stats, events = o.generate(MICRO, w, prompt, R, base)
+        assert not (tokens == MICRO.mask_id).any()
+        prev = R
+        for ev in events:
+            assert _n_masked(ev, P) < prev
+            prev = _n_masked(ev, P)
+            seen.add(ev["chosen"])
+        assert stats["n_step_shared"] == 0 and stats["step_rows"] == 4 * b * stats["n_step"]
+        t2, s2, e2 = o.generate(MICRO, w, prompt, R, dataclasses_replace(base, share_from=b + 1))
+        assert np.array_equal(t2, tokens) and s2 == stats
+        t3, s3, e3 = o.generate(MICRO, w, prompt, R, dataclasses_replace(base, share_from=0))
+        assert s3["n_step_shared"] == s3["n_step"] and not (t3 == MICRO.mask_id).any()
+        rows, before = 0, None
+        for ev in e3:
+            if ev["kind"] == "shared":
+                rows += b + 3 * before
+            before = int((ev["tokens"][ev["block_off"]:ev["block_off"] + ev["block_len"]] == MICRO.mask_id).sum())
+        assert rows == s3["step_rows"]
+        _, _, e4 = o.generate(MICRO, w, prompt, R, dataclasses_replace(base, share_from=5))
+        for prev_ev, ev in zip(e4, e4[1:]):
+            if ev["kind"] != "refresh":
+                blk = prev_ev["tokens"][ev["block_off"]:ev["block_off"] + ev["block_len"]]
+                assert (ev["kind"] == "shared") == (int((blk != MICRO.mask_id).sum()) >= 5)
+    assert seen - {0}, "no speculative draft was ever adopted: the case does not exercise the controller"
+
+
+def dataclasses_replace(p, **kw):
+    import dataclasses
+    return dataclasses.replace(p, **kw)
