@@ -109,6 +109,12 @@ int odb_cache_create(odb_model *m, int batch, int max_len, odb_cache **out);
 void odb_cache_destroy(odb_cache *c);
 /* Current sequence length set by the last odb_prefill (0 before). */
 int odb_cache_length(const odb_cache *c);
+/* Cuts the cached sequences to new_len positions (ODB-dLLM Sec. 4.1: the response is
+ * truncated at the predicted end): positions new_len .. length-1 stop being keys of later
+ * decode steps; the K/V of the kept positions stay as the last odb_prefill wrote them.
+ * Host-side bookkeeping only; takes effect for calls issued afterwards.  Errors:
+ * ODB_E_INVALID_ARG for a NULL cache or new_len outside [1, current length]. */
+int odb_cache_truncate(odb_cache *c, int new_len);
 
 /* Cache refresh (Sec. 2.1; Sec. 4.1).  tokens: dev int32 [batch, L], ids in
  * [0, vocab).  Runs the bidirectional forward over all L positions of every
@@ -243,6 +249,74 @@ int odb_accept_jump(const odb_model *m, const int32_t *drafts_dev, const float *
                     const int32_t *cand_pos_dev, const int32_t *cand_tok_dev, int batch, int b,
                     int32_t *chosen_dev, int32_t *new_drafts_dev, int32_t *new_cand_pos_dev,
                     int32_t *new_cand_tok_dev, void *stream);
+
+/* Block-wise generation of one response (ODB-dLLM Sec. 2.1, with the adaptive length
+ * prediction of Sec. 4.1 and the jump-share decoding of Sec. 4.2 switched on by the
+ * parameters).  The host loop is the library's; every decision is taken by kernels and the
+ * host reads back eight words per forward.
+ *
+ * The response starts as resp_len MASK tokens behind the prompt and is decoded block by
+ * block, front to back.  A block cycle opens with a refresh (odb_prefill over the whole
+ * sequence: the cache is rebuilt and every response position attempted).  Then
+ *   1. if eos_id >= 0, the attempt is scanned as odb_predict_length does and the sequence
+ *      is cut at once: dropped positions leave the token sequence and, as for
+ *      odb_cache_truncate, stop being keys of this cycle's steps;
+ *   2. the attempt at the current block goes through the acceptance rule of odb_block_step
+ *      (MASK positions whose confidence exceeds tau, and always the most confident one), so
+ *      the refresh is also the block's first decoding iteration;
+ *   3. decode steps follow until the block holds no MASK.  n_drafts = 1: odb_block_step on
+ *      the block alone.  n_drafts = 4: the four accept-jump drafts and odb_accept_jump (the
+ *      first candidates are the two most confident positions the refresh left MASKed); once
+ *      share_from positions of the block are decoded the step is odb_block_step_shared
+ *      on the same four drafts.
+ * Generation ends when the next block would start at or behind the end of the sequence.
+ * None of the parameter values is printed in the paper.
+ *
+ *   tokens_dev  device int32 [prompt_len + resp_len]; the caller fills the prompt, the call
+ *               writes the MASKs and then the decoded tokens; positions behind the final
+ *               length are left as they were when they were cut
+ *   c           a cache for batch 1 with max_len >= prompt_len + resp_len; left holding the
+ *               last refresh, cut to the final length
+ *   stats       host, written (counts, lengths, host wall-clock of the two phases)
+ *   events      host array of max_events records or NULL: one record per forward, in order
+ *   event_tokens_dev  device int32 [max_events, prompt_len + resp_len] or NULL: the token
+ *               sequence after every forward (test aid; costs one device copy per forward)
+ * Synchronous: returns after the last forward has finished; the stream is synchronised
+ * once per forward.  Working buffers come from the model's allocator and are released
+ * before returning.  Errors: ODB_E_INVALID_ARG for NULL handles / tokens / params / stats,
+ * prompt_len < 1, resp_len < 1, a cache of batch != 1 or too short, block_len outside
+ * [1, 256] (or > 64 with share_from >= 0), n_drafts other than 1 and 4, eos_id >= vocab or
+ * equal to the MASK id; more than max_events forwards stop being recorded (stats.n_events
+ * still counts them).  On an error of an inner call its code is returned and tokens_dev is
+ * left partly decoded. */
+enum { ODB_EV_REFRESH = 0, ODB_EV_STEP = 1, ODB_EV_STEP_SHARED = 2 };
+typedef struct {
+    int block_len;        /* positions per block (32 in the paper's runs) */
+    int n_drafts;         /* 1: threshold decoding; 4: accept-jump (Sec. 4.2.1) */
+    float tau;            /* acceptance threshold */
+    int eos_id;           /* < 0: no length prediction */
+    float truncate_thr;   /* Sec. 4.1 */
+    int share_from;       /* decoded positions of the block from which steps run in the
+                             decoded-share stage (Sec. 4.2.2); < 0: never */
+} odb_generate_params;
+typedef struct {
+    int kind;             /* ODB_EV_* */
+    int length;           /* sequence length after the event */
+    int block_off, block_len;   /* block_len 0: the cut fell into what was already decoded */
+    int chosen;           /* adopted draft (0 for a refresh and for n_drafts = 1) */
+    int n_masked;         /* MASK positions left in the block */
+    int cand_pos[2], cand_tok[2];   /* the candidates handed to the next step */
+} odb_generate_event;
+typedef struct {
+    int n_refresh, n_step, n_step_shared, final_len, n_events;
+    long long refresh_positions;    /* sum of the refreshed lengths */
+    long long step_rows;            /* rows forwarded by the steps (padding not counted) */
+    double refresh_ms, step_ms, total_ms;   /* host wall-clock, each phase up to its read-back */
+} odb_generate_stats;
+int odb_generate(odb_model *m, odb_cache *c, int32_t *tokens_dev, int prompt_len, int resp_len,
+                 const odb_generate_params *params, odb_generate_stats *stats,
+                 odb_generate_event *events, int32_t *event_tokens_dev, int max_events,
+                 void *stream);
 
 /* Copies cached K (kv = 0, post-RoPE, logical channel order) or V (kv = 1) of
  * positions pos0 .. pos0+n-1 of one sequence and layer to host memory as

@@ -23,7 +23,7 @@ SYMBOLS = (
     "odb_block_step", "odb_prefill_logits", "odb_block_step_logits", "odb_cache_read", "odb_strerror",
     "odb_last_error", "odb_profile_begin", "odb_profile_end", "odb_set_step_mode", "odb_model_status",
     "odb_debug_step_trace", "odb_predict_length", "odb_accept_jump", "odb_block_step_shared",
-    "odb_block_step_shared_rows", "odb_block_step_shared_logits",
+    "odb_block_step_shared_rows", "odb_block_step_shared_logits", "odb_cache_truncate", "odb_generate",
 )
 
 KERNEL_CLASSES = ("gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "rmsnorm",
@@ -42,6 +42,26 @@ class odb_config(ctypes.Structure):
                 ("head_dim", ctypes.c_int), ("d_ff", ctypes.c_int), ("vocab", ctypes.c_int),
                 ("rope_base", ctypes.c_float), ("rms_eps", ctypes.c_float), ("mask_id", ctypes.c_int)]
 
+
+class odb_generate_params(ctypes.Structure):
+    _fields_ = [("block_len", ctypes.c_int), ("n_drafts", ctypes.c_int), ("tau", ctypes.c_float),
+                ("eos_id", ctypes.c_int), ("truncate_thr", ctypes.c_float), ("share_from", ctypes.c_int)]
+
+
+class odb_generate_event(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int), ("length", ctypes.c_int), ("block_off", ctypes.c_int),
+                ("block_len", ctypes.c_int), ("chosen", ctypes.c_int), ("n_masked", ctypes.c_int),
+                ("cand_pos", ctypes.c_int * 2), ("cand_tok", ctypes.c_int * 2)]
+
+
+class odb_generate_stats(ctypes.Structure):
+    _fields_ = [("n_refresh", ctypes.c_int), ("n_step", ctypes.c_int), ("n_step_shared", ctypes.c_int),
+                ("final_len", ctypes.c_int), ("n_events", ctypes.c_int), ("refresh_positions", ctypes.c_longlong),
+                ("step_rows", ctypes.c_longlong), ("refresh_ms", ctypes.c_double), ("step_ms", ctypes.c_double),
+                ("total_ms", ctypes.c_double)]
+
+
+EVENT_KINDS = ("refresh", "step", "shared")
 
 _lib = None
 
@@ -77,6 +97,8 @@ def lib() -> ctypes.CDLL:
     L.odb_profile_begin.argtypes = [vp, ci, ci]
     L.odb_profile_end.argtypes = [vp, ctypes.POINTER(ci), ctypes.POINTER(cf)]
     L.odb_predict_length.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, cf, vp, vp]
+    L.odb_cache_truncate.argtypes = [vp, ci]
+    L.odb_generate.argtypes = [vp, vp, vp, ci, ci, vp, vp, vp, vp, ci, vp]
     L.odb_accept_jump.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, vp, vp, vp, vp, vp]
     L.odb_block_step_shared.argtypes = [vp, vp, vp, ci, ci, ci, ci, cf, vp, vp, vp, vp]
     L.odb_block_step_shared_rows.argtypes = [ci, ci, ci, ci]
@@ -206,6 +228,34 @@ def odb_block_step_shared_logits(model: int, cache: int, drafts, block_off: int,
     _check(lib().odb_block_step_shared_logits(model, cache, _dev_i32(drafts), block_off, b, S, n_masked,
                                               logits.data_ptr(), rowout.data_ptr(), _stream()))
     return logits, rowout
+
+
+def odb_cache_truncate(cache: int, new_len: int) -> None:
+    _check(lib().odb_cache_truncate(cache, new_len))
+
+
+def odb_generate(model: int, cache: int, tokens, prompt_len: int, block_len: int, n_drafts: int = 1, tau: float = 0.9,
+                 eos_id: int = -1, truncate_thr: float = 0.9, share_from: int = -1, max_events: int = 0,
+                 event_tokens: bool = False):
+    """tokens: int32 CUDA tensor [prompt_len + resp_len] whose first prompt_len entries hold the prompt; decoded
+    in place.  -> (stats dict, events list of dicts, event_tokens int32 CUDA tensor [n, L0] or None)."""
+    import torch
+    if tokens.dtype != torch.int32 or tokens.dim() != 1 or not tokens.is_contiguous() or not tokens.is_cuda:
+        raise TypeError("tokens must be a contiguous 1-D int32 CUDA tensor")
+    L0 = tokens.shape[0]
+    gp = odb_generate_params(block_len, n_drafts, tau, eos_id, truncate_thr, share_from)
+    st = odb_generate_stats()
+    ev = (odb_generate_event * max_events)() if max_events > 0 else None
+    snap = torch.empty((max_events, L0), dtype=torch.int32, device=tokens.device) if event_tokens and max_events > 0 else None
+    _check(lib().odb_generate(model, cache, tokens.data_ptr(), prompt_len, L0 - prompt_len, ctypes.byref(gp),
+                              ctypes.byref(st), ctypes.cast(ev, ctypes.c_void_p) if ev is not None else None,
+                              snap.data_ptr() if snap is not None else None, max_events, _stream()))
+    stats = {name: getattr(st, name) for name, _ in odb_generate_stats._fields_}
+    n = min(st.n_events, max_events)
+    events = [dict(kind=EVENT_KINDS[e.kind], L=e.length, block_off=e.block_off, block_len=e.block_len, chosen=e.chosen,
+                   n_masked=e.n_masked, cand_pos=np.array(list(e.cand_pos), np.int32),
+                   cand_tok=np.array(list(e.cand_tok), np.int32)) for e in (ev[i] for i in range(n))]
+    return stats, events, (snap[:n] if snap is not None else None)
 
 
 def odb_accept_jump(model: int, drafts, conf, argmax, unmask, cand_pos, cand_tok):

@@ -4,6 +4,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <chrono>
 #include <new>
 
 #include "model.h"
@@ -584,6 +585,14 @@ void odb_cache_destroy(odb_cache *ch) {
 
 int odb_cache_length(const odb_cache *ch) { return ch ? ch->c.length : 0; }
 
+int odb_cache_truncate(odb_cache *ch, int new_len) {
+    if (!ch) return fail(ODB_E_INVALID_ARG, "cache_truncate: cache is NULL");
+    if (new_len < 1 || new_len > ch->c.length)
+        return fail(ODB_E_INVALID_ARG, "cache_truncate: new_len=%d outside [1, %d]", new_len, ch->c.length);
+    ch->c.length = new_len;
+    return ODB_OK;
+}
+
 int odb_prefill(odb_model *m, odb_cache *c, const int32_t *tokens_dev, int L, int resp_off, float *conf_dev,
                 int32_t *argmax_dev, void *stream) {
     return prefill_impl(m, c, tokens_dev, L, resp_off, conf_dev, argmax_dev, nullptr, stream);
@@ -800,6 +809,136 @@ int odb_predict_length(const odb_model *mh, const int32_t *tokens, const float *
                           (hipStream_t)stream);
     HIP_TRY(hipGetLastError());
     return ODB_OK;
+}
+
+// The generation loop (ODB-dLLM Sec. 2.1 + 4.1 + 4.2): see odb.h for the order of events.  Every decision is
+// a kernel's; the host reads eight words back per forward to learn the length, the block's MASK count (loop
+// exit, row bound of the decoded-share step) and what to record.
+int odb_generate(odb_model *mh, odb_cache *ch, int32_t *tokens, int prompt_len, int resp_len,
+                 const odb_generate_params *gp, odb_generate_stats *st, odb_generate_event *events,
+                 int32_t *event_tokens, int max_events, void *stream) {
+    if (!mh || !ch || !tokens || !gp || !st) return fail(ODB_E_INVALID_ARG, "generate: NULL argument");
+    Model &m = mh->m;
+    Cache &c = ch->c;
+    const int P = prompt_len, R = resp_len, b = gp->block_len, mask_id = m.cfg.mask_id;
+    if (c.m != &m) return fail(ODB_E_INVALID_ARG, "generate: cache belongs to another model");
+    if (P < 1 || R < 1) return fail(ODB_E_INVALID_ARG, "generate: prompt_len=%d, resp_len=%d", P, R);
+    if (c.batch != 1 || c.max_len < P + R)
+        return fail(ODB_E_INVALID_ARG, "generate: needs a cache of batch 1 and max_len >= %d (has batch %d, max_len %d)",
+                    P + R, c.batch, c.max_len);
+    if (gp->n_drafts != 1 && gp->n_drafts != 4) return fail(ODB_E_INVALID_ARG, "generate: n_drafts=%d", gp->n_drafts);
+    const bool share = gp->n_drafts == 4 && gp->share_from >= 0;
+    if (b < 1 || b > 256 || (share && b > 64)) return fail(ODB_E_INVALID_ARG, "generate: block_len=%d", b);
+    if (gp->eos_id >= m.cfg.vocab || gp->eos_id == mask_id) return fail(ODB_E_INVALID_ARG, "generate: eos_id=%d", gp->eos_id);
+    if (max_events < 0 || ((events || event_tokens) && max_events < 1))
+        return fail(ODB_E_INVALID_ARG, "generate: max_events=%d", max_events);
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(hipSetDevice(m.device));
+    memset(st, 0, sizeof(*st));
+
+    // working buffers: the refresh's attempt, two sets of drafts and candidates (the controller reads one and
+    // writes the other), one step's outputs, the words for the host
+    const size_t nb = (size_t)4 * b;
+    const size_t bytes = align_up((size_t)R * 4, 256) * 2 + align_up(nb * 4, 256) * 4 + align_up(nb, 256) + 256 * 4;
+    char *buf = (char *)dev_alloc(m, bytes);
+    int32_t *host_ctl = nullptr;
+    if (!buf) return fail(ODB_E_NOMEM, "generate: cannot allocate %zu bytes", bytes);
+    if (hipHostMalloc((void **)&host_ctl, 64, hipHostMallocDefault) != hipSuccess) {
+        dev_free(m, buf);
+        return fail(ODB_E_NOMEM, "generate: cannot allocate pinned host memory");
+    }
+    char *t = buf;
+    auto take = [&](size_t n) { char *r = t; t += align_up(n, 256); return r; };
+    float *att_conf = (float *)take((size_t)R * 4);
+    int32_t *att_am = (int32_t *)take((size_t)R * 4);
+    int32_t *drafts[2] = {(int32_t *)take(nb * 4), (int32_t *)take(nb * 4)};
+    float *conf = (float *)take(nb * 4);
+    int32_t *am = (int32_t *)take(nb * 4);
+    uint8_t *um = (uint8_t *)take(nb);
+    int32_t *cand[2] = {(int32_t *)take(16), (int32_t *)take(16)};
+    int32_t *chosen = (int32_t *)take(4), *ctl = (int32_t *)take(32);
+
+    using clk = std::chrono::steady_clock;
+    auto ms_since = [](clk::time_point a) { return std::chrono::duration<double, std::milli>(clk::now() - a).count(); };
+    int rc = ODB_OK, L = P + R, off = P, cur = 0;
+    const int L0 = P + R;
+    const auto t_all = clk::now();
+    auto read_back = [&](int kind) -> int {      // ctl -> host, one record; the only synchronisation of a forward
+        if (event_tokens && st->n_events < max_events)
+            HIP_TRY(hipMemcpyAsync(event_tokens + (size_t)st->n_events * L0, tokens, (size_t)L0 * 4, hipMemcpyDeviceToDevice, s));
+        HIP_TRY(hipMemcpyAsync(host_ctl, ctl, 32, hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        if (events && st->n_events < max_events) {
+            odb_generate_event &e = events[st->n_events];
+            e.kind = kind; e.length = host_ctl[0]; e.block_off = off; e.block_len = host_ctl[7]; e.chosen = host_ctl[2];
+            e.n_masked = host_ctl[1];
+            e.cand_pos[0] = host_ctl[3]; e.cand_pos[1] = host_ctl[4]; e.cand_tok[0] = host_ctl[5]; e.cand_tok[1] = host_ctl[6];
+        }
+        st->n_events++;
+        return ODB_OK;
+    };
+    launch_fill_i32(tokens + P, mask_id, (size_t)R, s);
+    while (rc == ODB_OK && off < L) {
+        // ---- refresh, length prediction, adoption of the attempt at the block
+        auto t0 = clk::now();
+        rc = prefill_impl(mh, ch, tokens, L, P, att_conf, att_am, nullptr, stream);
+        if (rc) break;
+        st->n_refresh++;
+        st->refresh_positions += L;
+        if (gp->eos_id >= 0)
+            launch_predict_length(tokens, att_conf, att_am, 1, L, P, mask_id, gp->eos_id, gp->truncate_thr, ctl + 8, s);
+        launch_gen_adopt(tokens, off, b, gp->eos_id >= 0 ? ctl + 8 : nullptr, L, att_conf + (off - P), att_am + (off - P),
+                         nullptr, mask_id, gp->tau, gp->n_drafts == 4 ? drafts[cur] : nullptr, cand[cur], ctl, s);
+        if ((rc = read_back(ODB_EV_REFRESH))) break;
+        st->refresh_ms += ms_since(t0);
+        L = host_ctl[0];
+        c.length = L;
+        const int bb = host_ctl[7];
+        int n_masked = host_ctl[1];
+        if (bb <= 0) break;
+        // ---- decode steps against this cycle's cache
+        while (n_masked > 0) {
+            t0 = clk::now();
+            int kind = ODB_EV_STEP;
+            if (gp->n_drafts == 1) {
+                rc = step_impl(mh, ch, tokens + off, off, bb, 1, gp->tau, conf, am, um, nullptr, stream);
+                if (rc) break;
+                launch_gen_adopt(tokens, off, bb, nullptr, L, conf, am, um, mask_id, gp->tau, nullptr, cand[cur], ctl, s);
+                st->step_rows += bb;
+            } else {
+                if (share && bb - n_masked >= gp->share_from) {
+                    kind = ODB_EV_STEP_SHARED;
+                    rc = step_shared_impl(mh, ch, drafts[cur], off, bb, 4, n_masked, gp->tau, conf, am, um, nullptr, nullptr, stream);
+                    st->step_rows += bb + 3 * n_masked;
+                    st->n_step_shared++;
+                } else {
+                    rc = step_impl(mh, ch, drafts[cur], off, bb, 4, gp->tau, conf, am, um, nullptr, stream);
+                    st->step_rows += 4 * bb;
+                }
+                if (rc) break;
+                launch_accept_jump(drafts[cur], conf, am, um, cand[cur], cand[cur] + 2, 1, bb, mask_id, chosen, drafts[cur ^ 1],
+                                   cand[cur ^ 1], cand[cur ^ 1] + 2, s);
+                cur ^= 1;
+                launch_gen_commit(tokens, off, bb, L, drafts[cur], chosen, cand[cur], mask_id, ctl, s);
+            }
+            st->n_step++;
+            if ((rc = read_back(kind))) break;
+            st->step_ms += ms_since(t0);
+            if (host_ctl[1] >= n_masked) {           // forced progress makes this impossible; never spin on it
+                rc = fail(ODB_E_HIP, "generate: a step left %d of %d positions masked", host_ctl[1], n_masked);
+                break;
+            }
+            n_masked = host_ctl[1];
+        }
+        off += bb;
+    }
+    hipError_t e = hipStreamSynchronize(s);
+    st->final_len = L;
+    st->total_ms = ms_since(t_all);
+    (void)hipHostFree(host_ctl);
+    dev_free(m, buf);
+    if (rc == ODB_OK && e != hipSuccess) rc = fail(ODB_E_HIP, "generate: %s", hipGetErrorString(e));
+    return rc;
 }
 
 int odb_cache_read(const odb_cache *ch, int layer, int kv, int batch_index, int pos0, int n, float *host_f32) {

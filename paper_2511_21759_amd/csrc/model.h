@@ -59,6 +59,7 @@ void launch_init_random(const Model &m, uint64_t seed, double std, hipStream_t s
 void launch_tensor_copy(const Model &m, int tensor_id, int layer, u16 *staging, bool to_model, hipStream_t s);
 void launch_gain_copy(float *gain, u16 *staging, int n, bool to_model, hipStream_t s);
 void launch_fill_f32(float *p, float v, size_t n, hipStream_t s);
+void launch_fill_i32(int32_t *p, int32_t v, size_t n, hipStream_t s);
 void launch_rope_table(float *table, int n_pos, int dh, double base, hipStream_t s);
 void launch_cache_read(const Cache &c, int layer, int kv, int batch_index, int pos0, int n, float *out, hipStream_t s);
 
@@ -83,6 +84,13 @@ void launch_rmsnorm(const float *h, const float *gain, float eps, int d, RowMap 
 void launch_accept_jump(const int32_t *drafts, const float *conf, const int32_t *argmax, const uint8_t *unmask,
                         const int32_t *cand_pos, const int32_t *cand_tok, int batch, int b, int mask_id, int32_t *chosen,
                         int32_t *new_drafts, int32_t *new_cand_pos, int32_t *new_cand_tok, hipStream_t s);
+// generation loop bookkeeping (see rows.hip): adoption of a forward's attempt at the current block, and the
+// write-back after the accept-jump controller; both pack ctl[0..8) for the host.  cand = {pos B, pos D, token B, token D}
+void launch_gen_adopt(int32_t *tokens, int off, int b, const int32_t *len_ptr, int len, const float *conf,
+                      const int32_t *argmax, const uint8_t *unmask, int mask_id, float tau, int32_t *drafts,
+                      int32_t *cand, int32_t *ctl, hipStream_t s);
+void launch_gen_commit(int32_t *tokens, int off, int bb, int len, const int32_t *new_drafts, const int32_t *chosen,
+                       const int32_t *cand, int mask_id, int32_t *ctl, hipStream_t s);
 void launch_predict_length(const int32_t *tokens, const float *conf, const int32_t *argmax, int batch, int L,
                            int resp_off, int mask_id, int eos_id, float thr, int32_t *new_len, hipStream_t s);
 void launch_lm_finish(const float *stats, int n_part, int rows, int rpu, int rpu_pad, const int32_t *tokens,

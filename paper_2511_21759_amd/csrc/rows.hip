@@ -278,6 +278,101 @@ __global__ __launch_bounds__(64) void accept_jump_kernel(const int32_t *drafts, 
     }
 }
 
+// ---- generation loop bookkeeping (ODB-dLLM Sec. 2.1 / 4.1 / 4.2.1), one wave ------------------------
+// ctl words written for the host: [0] sequence length, [1] MASK positions left in the block, [2] adopted
+// draft, [3..4] candidate positions, [5..6] candidate tokens, [7] length of the block.
+//
+// Adoption of one forward's attempt at the current block.  The block is tokens[off .. off+bb) with
+// bb = min(b, len - off), len read from len_ptr (the length prediction's output) when given.  Position i
+// takes argmax[i] if unmask[i] (a step's own decision) or, without an unmask array (a refresh), if it holds
+// MASK and its confidence exceeds tau or is the largest among the block's MASK positions (lower index on
+// ties).  The two most confident positions still MASK afterwards become the candidates, and with drafts
+// given the block and its three speculative variants (candidate B, D, both) are written there.
+__global__ __launch_bounds__(64) void gen_adopt_kernel(int32_t *tokens, int off, int b, const int32_t *len_ptr, int len,
+                                                       const float *conf, const int32_t *argmax, const uint8_t *unmask,
+                                                       int mask_id, float tau, int32_t *drafts, int32_t *cand,
+                                                       int32_t *ctl) {
+    const int lane = threadIdx.x;
+    if (len_ptr) len = *len_ptr;
+    const int bb = min(b, len - off);
+    if (bb <= 0) {
+        if (lane == 0) { ctl[0] = len; ctl[1] = 0; ctl[2] = 0; ctl[3] = ctl[4] = -1; ctl[5] = ctl[6] = 0; ctl[7] = 0; }
+        return;
+    }
+    int32_t *blk = tokens + off;
+    const Cand none{-INFINITY, 0x7fffffff};
+    int forced = -1;
+    if (!unmask) {
+        Cand f = none, f1 = none;
+        for (int i = lane; i < bb; i += 64)
+            if (blk[i] == mask_id) cand_push(f, f1, Cand{conf[i], i});
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) cand_push(f, f1, Cand{__shfl_xor(f.c, o), __shfl_xor(f.i, o)});
+        forced = f.i;
+    }
+    Cand x0 = none, x1 = none;
+    int left = 0;
+    for (int i = lane; i < bb; i += 64) {
+        const int t0 = blk[i];
+        const bool take = unmask ? unmask[i] != 0 : (t0 == mask_id && (conf[i] > tau || i == forced));
+        const int t = take ? argmax[i] : t0;
+        blk[i] = t;
+        if (t == mask_id) { cand_push(x0, x1, Cand{conf[i], i}); left++; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        Cand y0{__shfl_xor(x0.c, o), __shfl_xor(x0.i, o)}, y1{__shfl_xor(x1.c, o), __shfl_xor(x1.i, o)};
+        cand_push(x0, x1, y0);
+        cand_push(x0, x1, y1);
+        left += __shfl_xor(left, o);
+    }
+    const int q0 = x0.i != 0x7fffffff ? x0.i : -1, q1 = x1.i != 0x7fffffff ? x1.i : -1;
+    const int u0 = q0 >= 0 ? argmax[q0] : 0, u1 = q1 >= 0 ? argmax[q1] : 0;
+    if (lane == 0) {
+        ctl[0] = len; ctl[1] = left; ctl[2] = 0; ctl[3] = q0; ctl[4] = q1; ctl[5] = u0; ctl[6] = u1; ctl[7] = bb;
+        if (cand) { cand[0] = q0; cand[1] = q1; cand[2] = u0; cand[3] = u1; }
+    }
+    if (drafts)     // each lane re-reads only the positions it wrote itself
+        for (int i = lane; i < bb; i += 64) {
+            const int t = blk[i];
+            drafts[i] = t;
+            drafts[bb + i] = i == q0 ? u0 : t;
+            drafts[2 * bb + i] = i == q1 ? u1 : t;
+            drafts[3 * bb + i] = i == q0 ? u0 : (i == q1 ? u1 : t);
+        }
+}
+
+// After the accept-jump controller: the adopted block (new_drafts[0]) goes back into the sequence and the
+// controller's decision is packed for the host.
+__global__ __launch_bounds__(64) void gen_commit_kernel(int32_t *tokens, int off, int bb, int len, const int32_t *new_drafts,
+                                                        const int32_t *chosen, const int32_t *cand, int mask_id,
+                                                        int32_t *ctl) {
+    const int lane = threadIdx.x;
+    int left = 0;
+    for (int i = lane; i < bb; i += 64) {
+        const int t = new_drafts[i];
+        tokens[off + i] = t;
+        left += t == mask_id;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) left += __shfl_xor(left, o);
+    if (lane == 0) {
+        ctl[0] = len; ctl[1] = left; ctl[2] = chosen[0];
+        ctl[3] = cand[0]; ctl[4] = cand[1]; ctl[5] = cand[2]; ctl[6] = cand[3]; ctl[7] = bb;
+    }
+}
+
+void launch_gen_adopt(int32_t *tokens, int off, int b, const int32_t *len_ptr, int len, const float *conf,
+                      const int32_t *argmax, const uint8_t *unmask, int mask_id, float tau, int32_t *drafts,
+                      int32_t *cand, int32_t *ctl, hipStream_t s) {
+    gen_adopt_kernel<<<1, 64, 0, s>>>(tokens, off, b, len_ptr, len, conf, argmax, unmask, mask_id, tau, drafts, cand, ctl);
+}
+
+void launch_gen_commit(int32_t *tokens, int off, int bb, int len, const int32_t *new_drafts, const int32_t *chosen,
+                       const int32_t *cand, int mask_id, int32_t *ctl, hipStream_t s) {
+    gen_commit_kernel<<<1, 64, 0, s>>>(tokens, off, bb, len, new_drafts, chosen, cand, mask_id, ctl);
+}
+
 void launch_accept_jump(const int32_t *drafts, const float *conf, const int32_t *argmax, const uint8_t *unmask,
                         const int32_t *cand_pos, const int32_t *cand_tok, int batch, int b, int mask_id, int32_t *chosen,
                         int32_t *new_drafts, int32_t *new_cand_pos, int32_t *new_cand_tok, hipStream_t s) {

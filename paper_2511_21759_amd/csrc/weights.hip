@@ -107,6 +107,16 @@ void launch_fill_f32(float *p, float v, size_t n, hipStream_t s) {
     fill_f32_kernel<<<dim3((unsigned)((n + 255) / 256)), 256, 0, s>>>(p, v, n);
 }
 
+__global__ void fill_i32_kernel(int32_t *p, int32_t v, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+void launch_fill_i32(int32_t *p, int32_t v, size_t n, hipStream_t s) {
+    if (n == 0) return;
+    fill_i32_kernel<<<dim3((unsigned)((n + 255) / 256)), 256, 0, s>>>(p, v, n);
+}
+
 static int kind_k(const odb_config &c, int pk) { return pk == PK_D ? c.d_ff : c.d_model; }
 
 void launch_init_random(const Model &m, uint64_t seed, double std, hipStream_t s) {
