@@ -274,3 +274,75 @@ def test_truncated_cache_equals_the_oracle_on_the_kept_keys():
         assert e_cut <= LOGIT_TOL and np.abs(z - z_full).max() > 10 * np.abs(z - z_o).max()
     finally:
         p.close()
+
+
+def test_generate_at_full_width_equals_the_composed_calls():
+    """8B width (d = 4096, F = 12288, V = 126464; 2 layers), where the oracle is too slow to replay a run: every
+    forward of odb_generate must equal, bit for bit, what the separately tested entry points give on the state
+    before it (odb_prefill / odb_block_step / odb_block_step_shared / odb_accept_jump, and the acceptance rule and
+    candidate choice restated on the host from the library's own confidences)."""
+    shape = dict(W.MODEL_SHAPES["8b"], n_layers=2)
+    model = B.odb_model_create(shape)
+    try:
+        B.odb_model_init_random(model, W.WEIGHT_SEED, W.WEIGHT_STD)
+        B.odb_model_set_tensor(model, B.T_GF, 0, np.full(shape["d_model"], 0x4100, np.uint16))      # gain 8
+        mask, P, R, b, tau, SHARE = shape["mask_id"], 100, 150, 32, 0.9, 16
+        rng = np.random.default_rng(77)
+        prompt = rng.integers(0, shape["vocab"] - 1, P).astype(np.int32)
+        cache = B.odb_cache_create(model, 1, P + R)
+        tokens = cuda_i32(np.concatenate([prompt, np.zeros(R, np.int32)]))
+        # an [EOS] the first refresh attempts with confidence, two thirds into the response
+        c0, a0 = B.odb_prefill(model, cache, cuda_i32(np.concatenate([prompt, np.full(R, mask, np.int32)])[None]), P)
+        c0, a0 = c0.cpu().numpy()[0], a0.cpu().numpy()[0]
+        late = [i for i in range(90, 130) if a0[i] not in a0[:90]]           # attempted nowhere earlier
+        q = max(late, key=lambda i: c0[i])
+        eos, thr = int(a0[q]), float(c0[q]) * 0.9
+        stats, events, snaps = B.odb_generate(model, cache, tokens, P, block_len=b, n_drafts=4, tau=tau, eos_id=eos,
+                                              truncate_thr=thr, share_from=SHARE, max_events=400, event_tokens=True)
+        snaps = snaps.cpu().numpy()
+        assert stats["n_events"] == len(events) and stats["final_len"] < P + R
+        final = tokens.cpu().numpy()[:stats["final_len"]]
+        assert not (final == mask).any() and np.array_equal(final[:P], prompt)
+        pre = np.concatenate([prompt, np.full(R, mask, np.int32)])
+        L, cp, ct, kinds = P + R, None, None, set()
+        for n, (e, post) in enumerate(zip(events, snaps)):
+            off, bb, tag = e["block_off"], e["block_len"], "event %d (%s)" % (n, e["kind"])
+            kinds.add(e["kind"])
+            if e["kind"] == "refresh":
+                seq = cuda_i32(pre[None, :L])
+                conf_t, am_t = B.odb_prefill(model, cache, seq, P)
+                new_len = int(B.odb_predict_length(model, seq, conf_t, am_t, P, eos, thr).cpu().numpy()[0])
+                conf, am = conf_t.cpu().numpy()[0], am_t.cpu().numpy()[0]
+                assert e["L"] == new_len, tag
+                L = new_len
+                B.odb_cache_truncate(cache, L)
+                assert bb == max(0, min(b, L - off)), tag
+                if bb == 0:
+                    continue
+                blk, c_b, a_b = pre[off:off + bb], conf[off - P:off - P + bb], am[off - P:off - P + bb]
+                new = np.where(o.threshold_unmask(blk, c_b, np.float32(tau), mask) == 1, a_b, blk).astype(np.int32)
+                pos, tok = o.speculative_candidates(new, c_b, a_b, mask)
+                chosen = 0
+            else:
+                blk = pre[off:off + bb]
+                share = int((blk != mask).sum()) >= SHARE
+                assert e["kind"] == ("shared" if share else "step"), tag
+                drafts = cuda_i32(o.accept_jump_drafts(blk, cp, ct)[None])
+                if share:
+                    out = B.odb_block_step_shared(model, cache, drafts, off, int((blk == mask).sum()), tau)
+                else:
+                    out = B.odb_block_step(model, cache, drafts, off, tau)
+                ch, nd, npos, ntok = B.odb_accept_jump(model, drafts, *out, cuda_i32(cp[None]), cuda_i32(ct[None]))
+                chosen, new = int(ch.cpu().numpy()[0]), nd.cpu().numpy()[0, 0]
+                pos, tok = npos.cpu().numpy()[0], ntok.cpu().numpy()[0]
+            assert e["chosen"] == chosen and np.array_equal(post[off:off + bb], new), tag
+            assert np.array_equal(e["cand_pos"], pos) and np.array_equal(e["cand_tok"], tok), tag
+            assert np.array_equal(post[:off], pre[:off]) and np.array_equal(post[off + bb:L], pre[off + bb:L]), tag
+            pre, cp, ct = post.copy(), e["cand_pos"], e["cand_tok"]
+        print("\nfull-width generate: %d refreshes + %d steps (%d shared), final length %d of %d, adopted %s" % (
+            stats["n_refresh"], stats["n_step"], stats["n_step_shared"], stats["final_len"], P + R,
+            sorted(set(e["chosen"] for e in events))))
+        assert kinds == {"refresh", "step", "shared"}, "the case must run all three kinds of forward (ran %s)" % kinds
+        B.odb_cache_destroy(cache)
+    finally:
+        B.odb_model_destroy(model)
