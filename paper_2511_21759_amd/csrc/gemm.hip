@@ -59,7 +59,7 @@ static void launch_tile(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi
 }
 
 // 256 rows and more: 256-row blocks through LDS (gemm_big.h), 64 * WN columns wide
-template <int WN, class Epi>
+template <int WN, class Epi, int NWV = 8>
 static void launch_big_wn(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi e, hipStream_t s) {
     BigArgs g;
     g.A = a; g.W = w; g.KT = sh.K_tiles; g.MT_total = sh.M_tiles; g.NT = sh.N_tiles;
@@ -68,24 +68,25 @@ static void launch_big_wn(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, E
     g.n_blocks = (sh.N_tiles + 4 * WN - 1) / (4 * WN);
     static bool attr_set = false;           // once per instantiation: the ring needs more than the default 64 KiB
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_big_kernel<WN, Epi>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_big_kernel<WN, Epi, NWV>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, big_smem_bytes(WN));
         attr_set = true;
     }
     dim3 grid(8 * g.m_blocks * ((g.n_blocks + 7) / 8));
-    gemm_big_kernel<WN, Epi><<<grid, 512, big_smem_bytes(WN), s>>>(g, e);
+    gemm_big_kernel<WN, Epi, NWV><<<grid, 64 * NWV, big_smem_bytes(WN), s>>>(g, e);
 }
 
 // Block width for the 256-row kernel, or 0 when the tile kernel should run instead.  With T blocks on 256
-// compute units a launch takes ceil(T / 256) block-times, and a block-time hardly depends on the block's
-// width (measured on one GPU, 1024 rows: 256 and 192 columns within 3 %, 128 columns 30 % slower - the
-// k-step is bound by its barrier and operand delivery, not by its MFMAs).  So the widest block is taken whose
-// block slots are at least 70 % useful (a ragged last row block counts by its real rows); a narrower one
-// only if it needs fewer rounds.  Below 70 % for every width the 128-row tile kernel wins (measured at 640
-// rows).  The O and down projections (N = 4096) stay with the tile kernel.
+// compute units a launch takes ceil(T / 256) block-times, and a block-time shrinks more slowly than the
+// block: measured on one GPU at 1024 and 2048 rows, a 192-column block takes 0.87 and a 128-column block
+// 0.68 of the time of a 256-column one (the k-step is bound by its barrier and operand delivery as much as
+// by its MFMAs).  The width with the smallest rounds x block-time wins among those whose block slots are at
+// least 70 % useful (a ragged last row block counts by its real rows); below 70 % for every width the
+// 128-row tile kernel wins (measured at 640 rows).  The O and down projections (N = 4096) stay with the
+// tile kernel.
 static int big_width(GemmShape sh) {
     if (sh.M_tiles < 16 || sh.N_tiles < 32) return 0;
-    const double rel[5] = {0, 0, 1.3, 1.0, 1.0};
+    const double rel[5] = {0, 0, 0.68, 0.87, 1.0};
     int best = 0;
     double best_cost = 0;
     for (int wn = 4; wn >= 2; wn--) {
