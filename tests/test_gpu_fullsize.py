@@ -225,6 +225,12 @@ def test_full_size_properties_without_an_oracle():
         c3, a3, u3 = B.odb_block_step(model, cache, dr, wl.block_off, wl.tau)
         assert torch.equal(c3, conf) and torch.equal(a3, am) and torch.equal(u3, um)
         assert um.sum().item() == 4 and (um.sum(-1) == 1).all()
+        # two and three drafts run through other GEMM variants (64 rows: the 33..64-row kernels); drafts are
+        # independent, so their results must agree with the four-draft call up to summation order
+        for S in (2, 3):
+            cS, aS, uS = B.odb_block_step(model, cache, dr[:, :S].contiguous(), wl.block_off, wl.tau)
+            assert torch.allclose(torch.log(cS), torch.log(conf[:, :S]), atol=0.05), S
+            assert (aS == am[:, :S]).float().mean() > 0.9 and (uS.sum(-1) == 1).all(), S
         B.odb_cache_destroy(cache)
     finally:
         B.odb_model_destroy(model)

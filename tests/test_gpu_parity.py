@@ -241,6 +241,8 @@ def test_config0_peaked(gf):
     (1, 200, 136, 32, 9, 2),   # L = 336 and 288 step rows: the 256-row GEMM blocks, ragged in M, fused norm in the step
     (2, 150, 122, 16, 20, 1),  # batch 2 x L = 272 prefill rows, 2 x 320 step rows
     (4, 40, 56, 48, 32, 0),    # 128 drafts of three row tiles: the four-tile attention workgroups of the long-block step
+    (1, 64, 64, 32, 2, 0),     # 64 step rows: the 33..64-row GEMM variants at their upper edge
+    (2, 50, 40, 16, 2, 1),     # 64 step rows from two sequences
 ])
 def test_step_edge_shapes(tiny, Bn, P, R, b, S, blk):
     wl = W.decode_workload(tiny.shape, P, R, b, S, 77 + P, batch=Bn, block_index=blk)
