@@ -856,7 +856,7 @@ int odb_generate(odb_model *mh, odb_cache *ch, int32_t *tokens, int prompt_len, 
     int32_t *am = (int32_t *)take(nb * 4);
     uint8_t *um = (uint8_t *)take(nb);
     int32_t *cand[2] = {(int32_t *)take(16), (int32_t *)take(16)};
-    int32_t *chosen = (int32_t *)take(4), *ctl = (int32_t *)take(32);
+    int32_t *chosen = (int32_t *)take(4), *ctl = (int32_t *)take(64);     // ctl[0..8) for the host, ctl[8] the predicted length
 
     using clk = std::chrono::steady_clock;
     auto ms_since = [](clk::time_point a) { return std::chrono::duration<double, std::milli>(clk::now() - a).count(); };
