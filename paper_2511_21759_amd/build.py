@@ -16,7 +16,10 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libodb.so")
 SOURCES = ["api.hip", "weights.hip", "rows.hip", "gemm.hip", "attn.hip", "step.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # MFMA results may stay in ordinary vector registers: without this the four-wave kernels (accumulators
+         # beyond 256 registers) get their accumulators copied between the two register files around every MFMA
+         "-mllvm", "-amdgpu-mfma-vgpr-form"]
 
 
 def _hipcc() -> str:
