@@ -207,6 +207,8 @@ CASES = [
     (3, 48, 128, dict(block_len=32, n_drafts=4, tau=0.9, share_from=16), (40, 100)),
     (4, 30, 50, dict(block_len=20, n_drafts=4, tau=0.8, share_from=0), None),
     (5, 40, 70, dict(block_len=48, n_drafts=1, tau=0.7), (20, 60)),
+    (6, 32, 128, dict(block_len=64, n_drafts=4, tau=0.9, share_from=32), None),      # the largest block the shared step takes
+    (7, 20, 130, dict(block_len=128, n_drafts=4, tau=0.85), None),                    # blocks longer than a wave, a two-position tail
 ]
 
 
