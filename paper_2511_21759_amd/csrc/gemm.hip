@@ -113,6 +113,7 @@ void launch_gemm_qkv(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, QkvOu
     EpiQKV e{out, sh.M_tiles};
     if (sh.M_tiles <= 2) launch_stream<2, 3, 8, 8, true>(xa, w, sh, ni, e, s);
     else if (sh.M_tiles <= 4) launch_stream<4, 3, 4, 8, true>(xa, w, sh, ni, e, s);          // 33..64 rows: still eight waves
+    else if (sh.M_tiles <= 6) launch_stream<6, 3, 2, 8, true>(xa, w, sh, ni, e, s);          // 65..96 rows
     else if (sh.M_tiles <= 8) launch_stream<8, 3, 4, 4, false>(xa, w, sh, ni, e, s);     // four waves: 24 accumulator tiles + the ring need the 512-register budget
     else if (use_big(sh)) launch_big(xa, w, sh, ni, e, s);
     else launch_tile(xa, w, sh, ni, e, ws, true, s);
@@ -122,6 +123,7 @@ void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int l
     EpiResid e{h, ldh, no, sh.M_tiles};
     if (sh.M_tiles <= 2) launch_stream<2, 1, 8, 8, false>(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
     else if (sh.M_tiles <= 4) launch_stream<4, 1, 8, 8, false>(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
+    else if (sh.M_tiles <= 6 && sh.K_tiles <= 128) launch_stream<6, 1, 4, 8, false>(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
     else if (sh.M_tiles <= 8 && sh.K_tiles <= 128) launch_stream<8, 1, 2, 8, false>(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
     else launch_tile(a, w, sh, NormIn{nullptr, 0, 0.f}, e, ws, true, s);
 }
@@ -129,6 +131,7 @@ void launch_gemm_swiglu(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, u1
     EpiSwiGLU e{act, sh.M_tiles};
     if (sh.M_tiles <= 2) launch_stream<2, 6, 4, 8, true>(xa, w, sh, ni, e, s);
     else if (sh.M_tiles <= 4) launch_stream<4, 6, 2, 8, true>(xa, w, sh, ni, e, s);
+    else if (sh.M_tiles <= 6) launch_stream<6, 6, 1, 8, true>(xa, w, sh, ni, e, s);
     else if (sh.M_tiles <= 8) launch_stream<8, 6, 2, 4, true>(xa, w, sh, ni, e, s);
     else if (use_big(sh)) launch_big(xa, w, sh, ni, e, s);
     else launch_tile(xa, w, sh, ni, e, ws, true, s);
@@ -152,6 +155,7 @@ void launch_gemm_lmstats(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, f
     const int parts = lm_stats_parts(sh.N_tiles, sh.M_tiles);
     if (sh.M_tiles <= 2) launch_stream<2, kLmNG, 4, 8, true>(xa, w, sh, ni, EpiLMStats<2>(stats, parts), s);
     else if (sh.M_tiles <= 4) launch_stream<4, kLmNG, 2, 8, true>(xa, w, sh, ni, EpiLMStats<4>(stats, parts), s);
+    else if (sh.M_tiles <= 6) launch_stream<6, kLmNG, 1, 8, true>(xa, w, sh, ni, EpiLMStats<6>(stats, parts), s);
     else if (sh.M_tiles <= 8) launch_stream<8, kLmNG, 2, 4, true>(xa, w, sh, ni, EpiLMStats<16>(stats, parts), s);
     else if (use_big(sh)) launch_big(xa, w, sh, ni, TileLMStats{stats, parts}, s);
     else launch_tile(xa, w, sh, ni, TileLMStats{stats, parts}, ws, false, s);

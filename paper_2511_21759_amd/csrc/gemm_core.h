@@ -41,7 +41,7 @@ struct GemmArgs {
 };
 
 // m-tiles per reduction pass: at most six 1 KiB tiles per wave go through LDS at a time
-constexpr int gemm_mc(int mt, int ng) { return ng >= 6 ? 1 : (ng >= 3 ? 2 : (mt < 4 ? mt : 4)); }
+constexpr int gemm_mc(int mt, int ng) { return ng >= 6 ? 1 : (ng >= 3 ? 2 : (mt < 4 ? mt : (mt % 4 == 0 ? 4 : 3))); }
 
 constexpr int kGemmSmemBytes = WK * 6 * 1024 + 8 * 16 * 4;    // LDS one workgroup needs (red + row scales)
 
@@ -149,17 +149,20 @@ __device__ __forceinline__ void gemm_wg(const GemmArgs &g, Epi epi, int wg, int 
         // 64 lane-partials per row -> one sum per row: transposed through LDS (row stride 65 floats keeps
         // the gather conflict-free), then lane l adds RPW of the partials of row l % RPW and the 64 / RPW
         // lanes of a row finish with shuffles.  A wave only touches its own part of the buffer.
-        static_assert(RPW <= 64 && (RPW & (RPW - 1)) == 0, "rows per wave");
-        float *tmp = reinterpret_cast<float *>(smem) + wk * (RPW * 65);
+        // (RP: RPW rounded up to a power of two - six row tiles over eight waves give twelve rows per wave;
+        // the lanes of the rows beyond RPW add stale scratch and are dropped)
+        constexpr int RP = RPW <= 1 ? 1 : RPW <= 2 ? 2 : RPW <= 4 ? 4 : RPW <= 8 ? 8 : RPW <= 16 ? 16 : RPW <= 32 ? 32 : 64;
+        static_assert(RPW <= 64 && WKT * RP * 65 * 4 <= WK * 6 * 1024, "rows per wave");
+        float *tmp = reinterpret_cast<float *>(smem) + wk * (RP * 65);
 #pragma unroll
         for (int j = 0; j < RPW; j++)
             tmp[j * 65 + lane] = q[j] + (si < g.n_ssq ? (sv[j][0] + sv[j][1]) + (sv[j][2] + sv[j][3]) : 0.f);
-        const int row = lane % RPW, part = lane / RPW;
+        const int row = lane % RP, part = lane / RP;
         float t = 0.f;
 #pragma unroll
-        for (int i = 0; i < RPW; i++) t += tmp[row * 65 + part * RPW + i];
+        for (int i = 0; i < RP; i++) t += tmp[row * 65 + part * RP + i];
 #pragma unroll
-        for (int o = RPW; o < 64; o <<= 1) t += __shfl_xor(t, o);
+        for (int o = RP; o < 64; o <<= 1) t += __shfl_xor(t, o);
         if (lane < RPW) s_rstd[wk + lane * WKT] = 1.0f / sqrtf(t * g.inv_d + g.eps);
         __syncthreads();                        // the buffer is reused by the K reduction below
     } else if (lane < RPW) {
