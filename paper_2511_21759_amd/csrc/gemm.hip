@@ -121,10 +121,9 @@ void launch_gemm_qkv(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, QkvOu
 void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int ldh, NormOut no, Workspace ws,
                        hipStream_t s) {
     EpiResid e{h, ldh, no, sh.M_tiles};
+    // more than 32 rows: the tile kernel, whose K split over workgroups also splits the activation reads (a
+    // workgroup of the streaming kernel reads all of A for its 16 columns: measured 3-4 % of the step slower)
     if (sh.M_tiles <= 2) launch_stream<2, 1, 8, 8, false>(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
-    else if (sh.M_tiles <= 4) launch_stream<4, 1, 8, 8, false>(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
-    else if (sh.M_tiles <= 6 && sh.K_tiles <= 128) launch_stream<6, 1, 4, 8, false>(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
-    else if (sh.M_tiles <= 8 && sh.K_tiles <= 128) launch_stream<8, 1, 2, 8, false>(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
     else launch_tile(a, w, sh, NormIn{nullptr, 0, 0.f}, e, ws, true, s);
 }
 void launch_gemm_swiglu(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, u16 *act, Workspace ws, hipStream_t s) {
