@@ -41,7 +41,11 @@ struct GemmArgs {
 };
 
 // m-tiles per reduction pass: at most six 1 KiB tiles per wave go through LDS at a time
-constexpr int gemm_mc(int mt, int ng) { return ng >= 6 ? 1 : (ng >= 3 ? 2 : (mt < 4 ? mt : (mt % 4 == 0 ? 4 : 3))); }
+// (with four waves twice as many: the buffer holds WK * 6 tiles)
+constexpr int gemm_mc(int mt, int ng, int wkt = WK) {
+    return wkt == 4 && mt == 8 ? (ng >= 6 ? 2 : (ng >= 3 ? 4 : 8))
+                               : (ng >= 6 ? 1 : (ng >= 3 ? 2 : (mt < 4 ? mt : (mt % 4 == 0 ? 4 : 3))));
+}
 
 constexpr int kGemmSmemBytes = WK * 6 * 1024 + 8 * 16 * 4;    // LDS one workgroup needs (red + row scales)
 
@@ -77,9 +81,9 @@ __device__ __forceinline__ void gemm_prefetch_w(const GemmArgs &g, int wg, int n
 template <int MT, int NG, int PF, bool HAVE_W, class Epi, int WKT = WK, bool IL = false>
 __device__ __forceinline__ void gemm_wg(const GemmArgs &g, Epi epi, int wg, int nwg, int mt0,
                                         frag_t (&wb)[PF][NG], char *smem) {
-    constexpr int MC = gemm_mc(MT, NG);                     // m-tiles reduced per pass through LDS (<= 48 KiB)
+    constexpr int MC = gemm_mc(MT, NG, WKT);                // m-tiles reduced per pass through LDS (<= 48 KiB)
     constexpr int SPW = (MC * NG + WKT - 1) / WKT;          // reduced tiles a wave serves per m-chunk
-    static_assert(MT % MC == 0 && MC * NG <= 6 && MT <= 8 && WKT <= WK, "m chunking");
+    static_assert(MT % MC == 0 && MC * NG * WKT <= 6 * WK && MT <= 8 && WKT <= WK, "m chunking");
     f32x4 (*red)[MC * NG][64] = reinterpret_cast<f32x4 (*)[MC * NG][64]>(smem);
     float *s_rstd = reinterpret_cast<float *>(smem + WK * 6 * 1024);
 
