@@ -292,7 +292,10 @@ def main():
             ach = gu_bytes / avg_s / 1e9
             roofline = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(name)}
+        # an event pair with nothing between its events, recorded behind every timed launch: the kernel's own
+        # duration (what a kernel trace reports) lies between avg_us - empty_pair_us and avg_us
         roofline.update({"kernel": prof["kernel"], "launches": prof["launches"], "avg_us": prof["avg_ms"] * 1e3,
+                         "empty_pair_us": prof["avg_empty_pair_ms"] * 1e3,
                          "algorithmic_per_launch": gu_flops if compute_bound else gu_bytes})
 
     out = {

@@ -329,14 +329,19 @@ int odb_cache_read(const odb_cache *c, int layer, int kv, int batch_index,
  * by a pair of HIP events recorded on the launch stream (at most max_launches
  * pairs; further launches are not timed).  odb_profile_end synchronises the
  * device, returns the number of timed launches and the sum of their durations
- * in milliseconds, and releases the events.  The events serialise nothing but
- * do cost a few microseconds each: do not time whole steps while enabled. */
+ * in milliseconds, and releases the events.  A pair also spans the latency
+ * from its first event to the start of the kernel, which a kernel trace does
+ * not count: behind every pair a third event is recorded, and empty_pairs_ms
+ * (may be NULL) receives the sum of the intervals between second and third
+ * events - what a pair measures with nothing in between.  The events serialise
+ * nothing but do cost a few microseconds each: do not time whole steps while
+ * enabled. */
 enum {
     ODB_K_GEMM_QKV = 0, ODB_K_ATTENTION, ODB_K_GEMM_O, ODB_K_GEMM_GATE_UP,
     ODB_K_GEMM_DOWN, ODB_K_GEMM_LM_HEAD, ODB_K_RMSNORM, ODB_K_STEP_FUSED, ODB_K_COUNT
 };
 int odb_profile_begin(odb_model *m, int kernel_class, int max_launches);
-int odb_profile_end(odb_model *m, int *n_launches, float *total_ms);
+int odb_profile_end(odb_model *m, int *n_launches, float *total_ms, float *empty_pairs_ms);
 
 const char *odb_strerror(int code);
 const char *odb_last_error(void);

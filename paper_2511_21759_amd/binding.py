@@ -95,7 +95,7 @@ def lib() -> ctypes.CDLL:
     L.odb_block_step_logits.argtypes = [vp, vp, vp, ci, ci, ci, vp, vp]
     L.odb_cache_read.argtypes = [vp, ci, ci, ci, ci, ci, vp]
     L.odb_profile_begin.argtypes = [vp, ci, ci]
-    L.odb_profile_end.argtypes = [vp, ctypes.POINTER(ci), ctypes.POINTER(cf)]
+    L.odb_profile_end.argtypes = [vp, ctypes.POINTER(ci), ctypes.POINTER(cf), ctypes.POINTER(cf)]
     L.odb_predict_length.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, cf, vp, vp]
     L.odb_cache_truncate.argtypes = [vp, ci]
     L.odb_generate.argtypes = [vp, vp, vp, ci, ci, vp, vp, vp, vp, ci, vp]
@@ -336,10 +336,11 @@ def odb_profile_begin(model: int, kernel_class: int, max_launches: int) -> None:
     _check(lib().odb_profile_begin(model, kernel_class, max_launches))
 
 
-def odb_profile_end(model: int) -> Tuple[int, float]:
-    n, ms = ctypes.c_int(), ctypes.c_float()
-    _check(lib().odb_profile_end(model, ctypes.byref(n), ctypes.byref(ms)))
-    return n.value, ms.value
+def odb_profile_end(model: int) -> Tuple[int, float, float]:
+    """-> (timed launches, sum of their event-pair durations in ms, sum of the empty pairs recorded behind them)."""
+    n, ms, empty = ctypes.c_int(), ctypes.c_float(), ctypes.c_float()
+    _check(lib().odb_profile_end(model, ctypes.byref(n), ctypes.byref(ms), ctypes.byref(empty)))
+    return n.value, ms.value, empty.value
 
 
 def odb_profile_kernel(model: int, run, steps: int, kernel_class: int = 3, max_launches: int = 1 << 16) -> Dict:
@@ -349,8 +350,9 @@ def odb_profile_kernel(model: int, run, steps: int, kernel_class: int = 3, max_l
         for _ in range(steps):
             run()
     finally:
-        n, ms = odb_profile_end(model)
-    return {"kernel": KERNEL_CLASSES[kernel_class], "launches": n, "avg_ms": ms / max(n, 1)}
+        n, ms, empty = odb_profile_end(model)
+    return {"kernel": KERNEL_CLASSES[kernel_class], "launches": n, "avg_ms": ms / max(n, 1),
+            "avg_empty_pair_ms": empty / max(n, 1)}
 
 
 def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:

@@ -136,11 +136,14 @@ struct ProfScope {
     ProfScope(Model &m_, int cls, hipStream_t s_) : m(m_), s(s_), slot(-1) {
         if (m.prof_class == cls && m.prof_used < m.prof_cap) {
             slot = m.prof_used++;
-            (void)hipEventRecord(m.prof_ev[2 * slot], s);
+            (void)hipEventRecord(m.prof_ev[3 * slot], s);
         }
     }
     ~ProfScope() {
-        if (slot >= 0) (void)hipEventRecord(m.prof_ev[2 * slot + 1], s);
+        if (slot >= 0) {
+            (void)hipEventRecord(m.prof_ev[3 * slot + 1], s);
+            (void)hipEventRecord(m.prof_ev[3 * slot + 2], s);     // an empty pair: what a pair costs by itself
+        }
     }
 };
 
@@ -476,7 +479,7 @@ void odb_model_destroy(odb_model *mh) {
     dev_free(m, m.scratch);
     dev_free(m, m.staging);
     if (m.prof_ev) {
-        for (int i = 0; i < 2 * m.prof_cap; i++) (void)hipEventDestroy(m.prof_ev[i]);
+        for (int i = 0; i < 3 * m.prof_cap; i++) (void)hipEventDestroy(m.prof_ev[i]);
         delete[] m.prof_ev;
     }
     delete mh;
@@ -741,9 +744,9 @@ int odb_profile_begin(odb_model *mh, int kernel_class, int max_launches) {
     if (max_launches < 1 || max_launches > (1 << 20)) return fail(ODB_E_INVALID_ARG, "profile_begin: max_launches");
     if (m.prof_ev) return fail(ODB_E_INVALID_ARG, "profile_begin: already profiling");
     HIP_TRY(hipSetDevice(m.device));
-    m.prof_ev = new (std::nothrow) hipEvent_t[2 * (size_t)max_launches];
+    m.prof_ev = new (std::nothrow) hipEvent_t[3 * (size_t)max_launches];
     if (!m.prof_ev) return fail(ODB_E_NOMEM, "profile_begin: host allocation");
-    for (int i = 0; i < 2 * max_launches; i++) {
+    for (int i = 0; i < 3 * max_launches; i++) {
         hipError_t e = hipEventCreate(&m.prof_ev[i]);
         if (e != hipSuccess) {
             for (int j = 0; j < i; j++) (void)hipEventDestroy(m.prof_ev[j]);
@@ -758,23 +761,26 @@ int odb_profile_begin(odb_model *mh, int kernel_class, int max_launches) {
     return ODB_OK;
 }
 
-int odb_profile_end(odb_model *mh, int *n_launches, float *total_ms) {
+int odb_profile_end(odb_model *mh, int *n_launches, float *total_ms, float *empty_pairs_ms) {
     if (!mh || !n_launches || !total_ms) return fail(ODB_E_INVALID_ARG, "profile_end: NULL argument");
     Model &m = mh->m;
     if (!m.prof_ev) return fail(ODB_E_INVALID_ARG, "profile_end: not profiling");
     HIP_TRY(hipSetDevice(m.device));
     hipError_t e = hipDeviceSynchronize();
-    float total = 0.f;
+    float total = 0.f, empty = 0.f;
     for (int i = 0; i < m.prof_used && e == hipSuccess; i++) {
         float ms = 0.f;
-        e = hipEventElapsedTime(&ms, m.prof_ev[2 * i], m.prof_ev[2 * i + 1]);
+        e = hipEventElapsedTime(&ms, m.prof_ev[3 * i], m.prof_ev[3 * i + 1]);
         total += ms;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, m.prof_ev[3 * i + 1], m.prof_ev[3 * i + 2]);
+        empty += ms;
     }
-    for (int i = 0; i < 2 * m.prof_cap; i++) (void)hipEventDestroy(m.prof_ev[i]);
+    for (int i = 0; i < 3 * m.prof_cap; i++) (void)hipEventDestroy(m.prof_ev[i]);
     delete[] m.prof_ev;
     m.prof_ev = nullptr;
     *n_launches = m.prof_used;
     *total_ms = total;
+    if (empty_pairs_ms) *empty_pairs_ms = empty;
     m.prof_class = -1;
     m.prof_cap = m.prof_used = 0;
     if (e != hipSuccess) return fail(ODB_E_HIP, "profile_end: %s", hipGetErrorString(e));

@@ -42,7 +42,7 @@ struct Model {
     size_t staging_bytes;
     // optional per-kernel-class timing (odb_profile_begin / odb_profile_end)
     int prof_class, prof_cap, prof_used;
-    hipEvent_t *prof_ev;       // 2 * prof_cap events
+    hipEvent_t *prof_ev;       // 3 * prof_cap events: before, after, and once more after (an empty pair)
 };
 
 struct Cache {
