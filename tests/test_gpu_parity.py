@@ -243,6 +243,8 @@ def test_config0_peaked(gf):
     (4, 40, 56, 48, 32, 0),    # 128 drafts of three row tiles: the four-tile attention workgroups of the long-block step
     (1, 64, 64, 32, 2, 0),     # 64 step rows: the 33..64-row GEMM variants at their upper edge
     (2, 50, 40, 16, 2, 1),     # 64 step rows from two sequences
+    (1, 48, 48, 16, 5, 1),     # 80 step rows: five row tiles in the six-tile kernels
+    (1, 30, 34, 16, 7, 0),     # 112 step rows: seven row tiles in the eight-tile kernels
 ])
 def test_step_edge_shapes(tiny, Bn, P, R, b, S, blk):
     wl = W.decode_workload(tiny.shape, P, R, b, S, 77 + P, batch=Bn, block_index=blk)
