@@ -12,8 +12,10 @@ __global__ __launch_bounds__(64 * WKT) void gemm_stream_kernel(GemmArgs g, Epi e
 
 constexpr int kStreamWGs = 256;      // one workgroup per compute unit
 
-// Up to 32 rows: the persistent streaming kernel with NG n-tiles per group and a PF-deep ring.
-// More rows: the tile kernel (gemm_tile.h), K-split over workgroups when there are too few n-blocks.
+// The persistent streaming kernel for up to 128 rows: MT row tiles per wave (2, 4, 6 or 8: 32-row steps),
+// NG n-tiles per group, a PF-deep ring, WKT waves (four when the accumulators need the 512-register budget).
+// The per-projection choices below are the fastest measured on MI355X; K_tiles that the ring depth does not
+// divide fall back to a ring of one.
 template <int MT, int NG, int PF, int WKT, bool IL, class Epi>
 static void launch_stream(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi e, hipStream_t s) {
     GemmArgs g;
@@ -121,9 +123,9 @@ void launch_gemm_qkv(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, QkvOu
 void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int ldh, NormOut no, Workspace ws,
                        hipStream_t s) {
     EpiResid e{h, ldh, no, sh.M_tiles};
-    // more than 32 rows: the tile kernel, whose K split over workgroups also splits the activation reads (a
-    // workgroup of the streaming kernel reads all of A for its 16 columns: measured 3-4 % of the step slower)
-    // from 2048 rows the 256 x 128 blocks fill the chip (8 x 32 blocks for N = 4096): 17 % faster than the tile kernel there
+    // More than 32 rows: the tile kernel, whose K split over workgroups also splits the activation reads (a
+    // workgroup of the streaming kernel reads all of A for its 16 columns: measured 3-4 % of the step slower).
+    // From 2048 rows the 256 x 128 blocks of the 256-row kernel fill the chip (8 x 32 blocks for N = 4096).
     if (sh.M_tiles <= 2) launch_stream<2, 1, 8, 8, false>(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
     else if (use_big(sh)) launch_big(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
     else launch_tile(a, w, sh, NormIn{nullptr, 0, 0.f}, e, ws, true, s);
