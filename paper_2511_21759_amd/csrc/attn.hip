@@ -46,9 +46,10 @@ void launch_attention(AttnArgs a, hipStream_t s) {
         }
         return;
     }
-    if (a.fresh > 0 && a.tiles_per_unit >= 2 && a.units * ((a.tiles_per_unit + 1) / 2) * a.H >= 512) {
-        // decode step with blocks of an odd number of row tiles and many drafts or sequences: two row tiles of
-        // a draft per workgroup, so that a K/V tile fetched from L2 serves 32 rows
+    if (a.fresh > 0 && a.tiles_per_unit >= 2 && a.units * ((a.tiles_per_unit + 1) / 2) * a.H >= 128) {
+        // decode step with at least 128 such workgroups (four drafts of 32 rows at 32 heads; fewer measured
+        // slower than one row tile per workgroup): two row tiles of a draft per workgroup, so that a K/V tile
+        // fetched from L2 serves 32 rows
         dim3 grid(a.units * ((a.tiles_per_unit + 1) / 2), a.H);
         if (a.dh == 128) attn_kernel<128, 2, 4><<<grid, 256, 0, s>>>(a, sc);
         else attn_kernel<64, 2, 4><<<grid, 256, 0, s>>>(a, sc);
