@@ -7,16 +7,20 @@
  *   - odb_block_step: the forward of S mutually invisible drafts of one
  *     response block against the cached K/V of every position outside the
  *     block, followed by the confidence-threshold acceptance
- *     (Sec. 3 Observation 3; Sec. 4.2 and Fig. 8 for the drafts).
+ *     (Sec. 3 Observation 3; Sec. 4.2 and Fig. 8 for the drafts);
+ * and, built on those two, the paper's controllers: odb_predict_length (Sec. 4.1),
+ * odb_accept_jump (Sec. 4.2.1), odb_block_step_shared (Sec. 4.2.2) and the whole
+ * block-wise loop, odb_generate (Sec. 2.1).
  *
  * Conventions
  *   - "dev" pointers are device (HBM) addresses on the current HIP device,
  *     "host" pointers are ordinary host memory.  The caller owns every buffer
  *     it passes; the library owns models, caches and its internal scratch.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *     odb_prefill / odb_block_step are asynchronous on it: outputs are valid
- *     once the caller has synchronised the stream.  Calls that use the same
- *     model must be issued on one stream at a time (they share scratch).
+ *     Calls with a stream argument are asynchronous on it unless they say
+ *     otherwise (odb_generate is synchronous): outputs are valid once the caller
+ *     has synchronised the stream.  Calls that use the same model must be issued
+ *     on one stream at a time (they share scratch).
  *   - Every function returns ODB_OK (0) or a negative ODB_E_* code; a message
  *     for the last failure on the calling thread is kept in odb_last_error().
  *     Arguments are validated on the host before any kernel is launched, so an
