@@ -8,6 +8,7 @@ stored instead of being recomputed inside the GPU tests.
 
     python tests/golden/make_8b_golden.py [n_layers]   (n_layers defaults to 32)
     python tests/golden/make_8b_golden.py batch4       (config4_small_oracle_2L.npz: batch 4, S=8, b=64, 2 layers)
+    python tests/golden/make_8b_golden.py prefill      (config3_oracle_2L.npz: the 1024- and 640-position refreshes, 2 layers)
 """
 import os
 import sys
@@ -99,8 +100,38 @@ def main_batch4():
     print("wrote", name, "%.0fs" % (time.time() - t0), flush=True)
 
 
+def main_prefill():
+    """Config 3 (cache-refresh prefill, 512 prompt + 512 / 128 MASK positions) at the 8B width with 2 layers."""
+    shape = dict(W.MODEL_SHAPES["8b"], n_layers=2)
+    cfg = o.Config(**shape)
+    w = o.Weights(cfg, W.WEIGHT_SEED, W.WEIGHT_STD, keep=True)
+    rng = np.random.default_rng(654)
+    cols = np.sort(rng.choice(cfg.vocab, 128, replace=False))
+    out = dict(n_layers=2, logit_cols=cols, resp_lens=np.array([512, 128]))
+    t0 = time.time()
+    for resp in (512, 128):
+        tokens = W.config3(resp)[0]
+        pos = np.sort(rng.choice(tokens.shape[0], 32, replace=False))
+        cache, conf, am, z = o.prefill(cfg, w, tokens, 512, return_logits=True)
+        top = np.argsort(z, axis=-1)[..., -8:]
+        tag = "r%d_" % resp
+        out.update({tag + "kv_pos": pos, tag + "prefill_conf": conf, tag + "prefill_argmax": am,
+                    tag + "prefill_logits_sample": z[..., cols].astype(np.float32),
+                    tag + "prefill_top_ids": top.astype(np.int32),
+                    tag + "prefill_top_logits": np.take_along_axis(z, top, -1).astype(np.float32),
+                    tag + "prefill_logit_absmax": np.abs(z).max(),
+                    tag + "k_sample": cache.k[:, pos].astype(np.float32), tag + "v_sample": cache.v[:, pos].astype(np.float32),
+                    tag + "k_absmax": np.abs(cache.k).max(axis=(1, 2, 3)), tag + "v_absmax": np.abs(cache.v).max(axis=(1, 2, 3))})
+        print("response %d done %.0fs" % (resp, time.time() - t0), flush=True)
+    name = "config3_oracle_2L.npz"
+    np.savez_compressed(os.path.join(os.path.dirname(os.path.abspath(__file__)), name), **out)
+    print("wrote", name, "%.0fs" % (time.time() - t0), flush=True)
+
+
 if __name__ == "__main__":
-    if len(sys.argv) > 1 and sys.argv[1] == "batch4":
+    if len(sys.argv) > 1 and sys.argv[1] == "prefill":
+        main_prefill()
+    elif len(sys.argv) > 1 and sys.argv[1] == "batch4":
         main_batch4()
     else:
         main()

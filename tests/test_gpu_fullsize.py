@@ -141,6 +141,41 @@ def test_batch4_long_block_against_stored_oracle():
         B.odb_model_destroy(model)
 
 
+@pytest.mark.parametrize("resp", [512, 128])
+def test_config3_prefill_against_stored_oracle(resp):
+    """Config 3's refreshes (512 prompt + 512 / 128 MASK positions: 1024 and 640 rows, the shapes bench.py times)
+    at the full 8B width with two layers against stored oracle outputs: the 256-row GEMM blocks in their 192-column
+    form at 1024 rows, the 128-row tile kernel at 640 rows, the K/V-sharing attention kernel over a thousand keys."""
+    path = os.path.join(GOLDEN, "config3_oracle_2L.npz")
+    if not os.path.exists(path):
+        pytest.skip("config3_oracle_2L.npz has not been generated (tests/golden/make_8b_golden.py prefill)")
+    g = np.load(path)
+    tag = "r%d_" % resp
+    view = {k[len(tag):]: g[k] for k in g.files if k.startswith(tag)}
+    view["step_logit_cols"] = g["logit_cols"]
+    shape = dict(W.MODEL_SHAPES["8b"], n_layers=int(g["n_layers"]))
+    tokens = W.config3(resp)
+    model = B.odb_model_create(shape)
+    try:
+        B.odb_model_init_random(model, W.WEIGHT_SEED, W.WEIGHT_STD)
+        L = tokens.shape[1]
+        cache = B.odb_cache_create(model, 1, L)
+        tok = cuda_i32(tokens)
+        z = B.odb_prefill_logits(model, cache, tok, 512, shape["vocab"]).cpu().numpy()[0]
+        conf, am = (t.cpu().numpy()[0] for t in B.odb_prefill(model, cache, tok, 512))
+        e, rel, ns, n = check_rows(z, conf, am, view, "prefill", "config3 prefill, %d response positions" % resp)
+        print("\nconfig3 resp %d: logit err rel %.2e (%d/%d rows strict)" % (resp, rel, ns, n))
+        for layer in range(shape["n_layers"]):
+            for kv, ref, amax in ((0, view["k_sample"][layer], view["k_absmax"][layer]),
+                                  (1, view["v_sample"][layer], view["v_absmax"][layer])):
+                got = B.odb_cache_read(cache, layer, kv, 0, 0, L, 32, 128)[view["kv_pos"]]
+                err = np.abs(got - ref).max() / amax
+                assert err <= KV_TOL, "config3: cache layer %d kv %d: %.3g" % (layer, kv, err)
+        B.odb_cache_destroy(cache)
+    finally:
+        B.odb_model_destroy(model)
+
+
 def test_decoded_share_step_properties_at_full_width():
     """The decoded-share step (ODB-dLLM Sec. 4.2.2) at the 8B width with two layers, head_dim 128, checked by the
     properties that pin its oracle: with nothing decoded it is the plain step; block_0 is the plain step's
