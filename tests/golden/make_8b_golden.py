@@ -9,6 +9,7 @@ stored instead of being recomputed inside the GPU tests.
     python tests/golden/make_8b_golden.py [n_layers]   (n_layers defaults to 32)
     python tests/golden/make_8b_golden.py batch4       (config4_small_oracle_2L.npz: batch 4, S=8, b=64, 2 layers)
     python tests/golden/make_8b_golden.py prefill      (config3_oracle_2L.npz: the 1024- and 640-position refreshes, 2 layers)
+    python tests/golden/make_8b_golden.py shared       (config2_shared_oracle_2L.npz: the eight-block decoded-share step, 2 layers)
 """
 import os
 import sys
@@ -128,8 +129,48 @@ def main_prefill():
     print("wrote", name, "%.0fs" % (time.time() - t0), flush=True)
 
 
+def main_shared():
+    """The decoded-share step of bench.py's config2_shared workload (eight blocks, a quarter of block_0 still MASK)
+    at the 8B width with 2 layers.  Per computed row (block, position): confidence, argmax, unmask, the eight
+    largest logits and 128 sampled columns; rows that are not computed keep NaN / -1."""
+    shape = dict(W.MODEL_SHAPES["8b"], n_layers=2)
+    cfg = o.Config(**shape)
+    w = o.Weights(cfg, W.WEIGHT_SEED, W.WEIGHT_STD, keep=True)
+    wl = W.config2_shared()
+    rng = np.random.default_rng(987)
+    cols = np.sort(rng.choice(cfg.vocab, 128, replace=False))
+    t0 = time.time()
+    cache, _, _ = o.prefill(cfg, w, wl.tokens[0], wl.resp_off)
+    drafts = wl.drafts[0]
+    S, b = drafts.shape
+    conf, am, um, zs = o.block_step_shared(cfg, w, cache, drafts, wl.block_off, wl.tau, return_logits=True)
+    masked = np.flatnonzero(drafts[0] == cfg.mask_id)
+    top_ids = np.full((S, b, 8), -1, np.int32)
+    top_logits = np.full((S, b, 8), np.nan, np.float32)
+    sample = np.full((S, b, 128), np.nan, np.float32)
+    absmax = 0.0
+    for s in range(S):
+        rows = np.arange(b) if s == 0 else masked
+        z = zs[s]
+        if z.shape[0] == 0:
+            continue
+        top = np.argsort(z, axis=-1)[:, -8:]
+        top_ids[s, rows] = top
+        top_logits[s, rows] = np.take_along_axis(z, top, -1)
+        sample[s, rows] = z[:, cols]
+        absmax = max(absmax, float(np.abs(z).max()))
+    name = "config2_shared_oracle_2L.npz"
+    np.savez_compressed(os.path.join(os.path.dirname(os.path.abspath(__file__)), name), n_layers=2, tau=wl.tau,
+                        block_off=wl.block_off, logit_cols=cols, step_conf=conf, step_argmax=am, step_unmask=um,
+                        step_top_ids=top_ids, step_top_logits=top_logits, step_logits_sample=sample,
+                        step_logit_absmax=absmax, n_masked=masked.size)
+    print("wrote", name, "%.0fs" % (time.time() - t0), flush=True)
+
+
 if __name__ == "__main__":
-    if len(sys.argv) > 1 and sys.argv[1] == "prefill":
+    if len(sys.argv) > 1 and sys.argv[1] == "shared":
+        main_shared()
+    elif len(sys.argv) > 1 and sys.argv[1] == "prefill":
         main_prefill()
     elif len(sys.argv) > 1 and sys.argv[1] == "batch4":
         main_batch4()

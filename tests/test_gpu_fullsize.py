@@ -176,6 +176,63 @@ def test_config3_prefill_against_stored_oracle(resp):
         B.odb_model_destroy(model)
 
 
+def test_decoded_share_step_against_stored_oracle():
+    """The eight-block decoded-share step that bench.py times (config2_shared: a quarter of block_0 still MASK) at
+    the full 8B width with two layers against stored oracle outputs, row by row."""
+    path = os.path.join(GOLDEN, "config2_shared_oracle_2L.npz")
+    if not os.path.exists(path):
+        pytest.skip("config2_shared_oracle_2L.npz has not been generated (tests/golden/make_8b_golden.py shared)")
+    g = np.load(path)
+    shape = dict(W.MODEL_SHAPES["8b"], n_layers=int(g["n_layers"]))
+    wl = W.config2_shared()
+    assert wl.block_off == int(g["block_off"])
+    n_masked = int(g["n_masked"])
+    model = B.odb_model_create(shape)
+    try:
+        B.odb_model_init_random(model, W.WEIGHT_SEED, W.WEIGHT_STD)
+        cache = B.odb_cache_create(model, 1, wl.tokens.shape[1])
+        B.odb_prefill(model, cache, cuda_i32(wl.tokens), wl.resp_off)
+        d = cuda_i32(wl.drafts)
+        S, b = wl.drafts.shape[1:]
+        z, rowout = B.odb_block_step_shared_logits(model, cache, d, wl.block_off, n_masked, shape["vocab"])
+        z, rowout = z.cpu().numpy(), rowout.cpu().numpy()
+        conf, am, um = (t.cpu().numpy()[0] for t in B.odb_block_step_shared(model, cache, d, wl.block_off, n_masked,
+                                                                             float(g["tau"])))
+        B.odb_model_status(model)
+        computed = ~np.isnan(g["step_top_logits"][..., 0])                     # [S, b]
+        assert sorted(rowout[rowout >= 0].tolist()) == np.flatnonzero(computed.reshape(-1)).tolist()
+        # logits of the computed rows, gathered into [S, b, V] order through the row map
+        e = 0.0
+        zfull = {}
+        for r, o_ in enumerate(rowout):
+            if o_ < 0:
+                continue
+            s_, i_ = divmod(int(o_), b)
+            zfull[(s_, i_)] = z[r]
+            e = max(e, float(np.abs(z[r][g["logit_cols"]] - g["step_logits_sample"][s_, i_]).max()),
+                    float(np.abs(z[r][g["step_top_ids"][s_, i_]] - g["step_top_logits"][s_, i_]).max()))
+        rel = e / float(g["step_logit_absmax"])
+        assert rel <= LOGIT_TOL, "decoded-share logits rel err %.3g" % rel
+        band = 2.5 * e + 1e-5
+        n_strict = 0
+        for (s_, i_), zr in zfull.items():
+            assert abs(np.log(conf[s_, i_]) - np.log(g["step_conf"][s_, i_])) <= band, (s_, i_)
+            top = g["step_top_logits"][s_, i_].astype(np.float64)
+            if top[-1] - top[-2] > band:
+                assert am[s_, i_] == g["step_argmax"][s_, i_], (s_, i_)
+                n_strict += 1
+            else:
+                assert am[s_, i_] in (g["step_argmax"][s_, i_], g["step_top_ids"][s_, i_][-2]), (s_, i_)
+        # positions that are not computed read as the call documents; random weights: only forced picks
+        nc = ~computed
+        assert np.all(conf[nc] == 0) and np.array_equal(am[nc], wl.drafts[0][nc]) and not um[nc].any()
+        assert np.array_equal(um, g["step_unmask"]), "unmask (one forced pick per block, far from any tie)"
+        print("\ndecoded-share step: %d rows, logit err rel %.2e, %d rows strict" % (len(zfull), rel, n_strict))
+        B.odb_cache_destroy(cache)
+    finally:
+        B.odb_model_destroy(model)
+
+
 def test_decoded_share_step_properties_at_full_width():
     """The decoded-share step (ODB-dLLM Sec. 4.2.2) at the 8B width with two layers, head_dim 128, checked by the
     properties that pin its oracle: with nothing decoded it is the plain step; block_0 is the plain step's
