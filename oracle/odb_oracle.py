@@ -23,6 +23,10 @@ What it follows (ODB-dLLM, arXiv 2511.21759):
     (decoded-share): decoded positions of the block are computed once, in
     block_0, and their K/V shared by the speculative blocks, which shrink to
     the still-masked positions.
+    That stage's eight blocks (four extra candidate sets) are
+    SPEC_SETS; the paper gives the jump rule for two candidates only, and
+    speculative_jump() carries it over to eight blocks (for four blocks it is
+    the rule of Sec. 4.2.1, which a test checks against accept_jump()).
 
 Arithmetic: float64 throughout, on weights whose values are exactly
 representable in bfloat16 (they are stored as bf16 bit patterns).  The model
@@ -374,6 +378,61 @@ def accept_jump(drafts: np.ndarray, conf: np.ndarray, argmax: np.ndarray, unmask
     return chosen, new_block, pos, tok, accept_jump_drafts(new_block, pos, tok)
 
 
+# Candidate sets of the eight blocks of the decoded-share stage (Sec. 4.2.2), by rank of the candidate among the
+# most confident positions below the threshold: block_0, B, D, B+D (Sec. 4.2.1), then the four extra ones - the
+# third, the top three, the fourth, the top four.
+SPEC_SETS = ((), (0,), (1,), (0, 1), (2,), (0, 1, 2), (3,), (0, 1, 2, 3))
+
+
+def speculative_drafts(block: np.ndarray, cand_pos: np.ndarray, cand_tok: np.ndarray, n: int) -> np.ndarray:
+    """block_0 and the n - 1 speculative blocks (n = 4: Sec. 4.2.1; n = 8: Sec. 4.2.2): the block with the
+    candidates of SPEC_SETS[s] unmasked beforehand.  A missing candidate (-1) adds nothing."""
+    drafts = np.stack([np.asarray(block, np.int32)] * n)
+    for s in range(n):
+        for c in SPEC_SETS[s]:
+            if c < len(cand_pos) and cand_pos[c] >= 0:
+                drafts[s, cand_pos[c]] = cand_tok[c]
+    return drafts
+
+
+def speculative_jump(drafts: np.ndarray, conf: np.ndarray, argmax: np.ndarray, unmask: np.ndarray,
+                     cand_pos: np.ndarray, cand_tok: np.ndarray, mask_id: int, n_next: int):
+    """The jump rule of Sec. 4.2.1 carried over to the S = 4 or 8 blocks of SPEC_SETS (the paper states it for B
+    and D only; for two candidates this function is that rule).
+
+    Start at block_0.  At the current block, whose candidate set is X, the verified set is X plus every other
+    candidate that this block's own step unmasks with the speculated token.  If some block's set lies strictly
+    between: X < set <= verified, jump to the one with the most candidates (lowest block number among equals)
+    and look again from there; otherwise adopt the current block - its tokens plus every position its own step
+    unmasked.  The n_next // 2 most confident still-masked positions of the adopted block are the next
+    candidates and the next n_next blocks are built from them.
+
+    Returns (chosen, new_block[b], new_cand_pos[k], new_cand_tok[k], new_drafts[n_next, b]), k = n_next // 2.
+    """
+    S = drafts.shape[0]
+    n_cand = S // 2
+
+    def verified(s, c):
+        p = int(cand_pos[c])
+        return p >= 0 and drafts[s, p] == mask_id and bool(unmask[s, p]) and int(argmax[s, p]) == int(cand_tok[c])
+
+    cur = 0
+    while True:
+        X = set(SPEC_SETS[cur])
+        V = X | {c for c in range(n_cand) if c not in X and verified(cur, c)}
+        best = None
+        for s in range(S):
+            T = set(SPEC_SETS[s])
+            if X < T <= V and (best is None or len(T) > len(SPEC_SETS[best])):
+                best = s
+        if best is None:
+            break
+        cur = best
+    new_block = np.where(np.asarray(unmask[cur], bool), argmax[cur], drafts[cur]).astype(np.int32)
+    pos, tok = speculative_candidates(new_block, conf[cur], argmax[cur], mask_id, k=n_next // 2)
+    return cur, new_block, pos, tok, speculative_drafts(new_block, pos, tok, n_next)
+
+
 # --------------------------------------------------------------------------- the two calls
 
 @dataclasses.dataclass
@@ -561,12 +620,13 @@ def block_step_shared(cfg: Config, w: Weights, cache: Cache, drafts: np.ndarray,
 class GenParams:
     """Knobs of the generation loop.  None of their values is printed in the paper."""
     block_len: int                      # positions per block (32 in the paper's runs)
-    n_drafts: int = 1                   # 1: threshold decoding only; 4: accept-jump (Sec. 4.2.1)
+    n_drafts: int = 1                   # 1: threshold decoding only; 4: accept-jump (Sec. 4.2.1); 8: accept-jump,
+                                        # then eight blocks with four extra candidates in the decoded-share stage
     tau: float = 0.9                    # acceptance threshold
     eos_id: Optional[int] = None        # None: no length prediction
     truncate_thr: float = 0.9           # Sec. 4.1
     share_from: Optional[int] = None    # decoded positions of the block from which steps run in the
-                                        # decoded-share stage (Sec. 4.2.2); None: never
+                                        # decoded-share stage (Sec. 4.2.2); None: never (n_drafts = 8 needs it)
 
 
 def truncate_cache(cache: Cache, new_len: int) -> Cache:
@@ -590,7 +650,9 @@ def generate(cfg: Config, w: Weights, prompt: np.ndarray, resp_len: int, p: GenP
         forwards the block alone; with n_drafts = 4 it forwards the four accept-jump drafts and the
         controller adopts one (the first candidates are the two most confident positions the refresh
         left masked).  Once share_from positions of the block are decoded the step runs in the
-        decoded-share stage, with the same four drafts.
+        decoded-share stage, with the same four drafts; with n_drafts = 8 that stage forwards eight
+        blocks (the four most confident positions left masked are the candidates, SPEC_SETS) and the
+        jump rule runs over all of them (speculative_jump), the steps before it stay four-draft ones.
     The block's tokens are written back and the next block cycle begins; generation ends when the
     block start reaches the (possibly shortened) end of the sequence.
 
@@ -600,7 +662,9 @@ def generate(cfg: Config, w: Weights, prompt: np.ndarray, resp_len: int, p: GenP
     event), block_off, block_len, chosen, cand_pos, cand_tok, tokens (copy of the sequence after it).
     """
     mask_id, b = cfg.mask_id, p.block_len
-    assert p.n_drafts in (1, 4) and b >= 1 and resp_len >= 1
+    assert p.n_drafts in (1, 4, 8) and b >= 1 and resp_len >= 1
+    assert p.n_drafts != 8 or p.share_from is not None
+    n_cand = p.n_drafts // 2 if p.n_drafts > 1 else 2
     prompt = np.asarray(prompt, np.int32)
     P = prompt.shape[0]
     tokens = np.concatenate([prompt, np.full(resp_len, mask_id, np.int32)])
@@ -622,14 +686,14 @@ def generate(cfg: Config, w: Weights, prompt: np.ndarray, resp_len: int, p: GenP
                 L = new_len
                 tokens, cache = tokens[:L], truncate_cache(cache, L)
         if off >= L:                                    # the cut fell into what is already decoded
-            record("refresh", 0, 0, (-1, -1), (0, 0))
+            record("refresh", 0, 0, (-1,) * n_cand, (0,) * n_cand)
             break
         bb = min(b, L - off)
         block = tokens[off:off + bb].copy()
         c_blk, a_blk = conf[off - P:off - P + bb], am[off - P:off - P + bb]
         um = threshold_unmask(block, c_blk, p.tau, mask_id)
         block = np.where(um.astype(bool), a_blk, block).astype(np.int32)
-        cp, ct = speculative_candidates(block, c_blk, a_blk, mask_id)
+        cp, ct = speculative_candidates(block, c_blk, a_blk, mask_id, k=n_cand)
         tokens[off:off + bb] = block
         record("refresh", bb, 0, cp, ct)
         while (block == mask_id).any():
@@ -639,18 +703,26 @@ def generate(cfg: Config, w: Weights, prompt: np.ndarray, resp_len: int, p: GenP
                 cp, ct = speculative_candidates(block, conf_s[0], am_s[0], mask_id)
                 chosen, kind, rows = 0, "step", bb
             else:
-                drafts = accept_jump_drafts(block, cp, ct)
                 n_masked = int((block == mask_id).sum())
                 if p.share_from is not None and bb - n_masked >= p.share_from:
+                    drafts = speculative_drafts(block, cp, ct, p.n_drafts)
                     conf_s, am_s, um_s = block_step_shared(cfg, w, cache, drafts, off, p.tau)
-                    kind, rows = "shared", bb + 3 * n_masked
+                    kind, rows = "shared", bb + (p.n_drafts - 1) * n_masked
                     stats["n_step_shared"] += 1
                 else:
+                    drafts = speculative_drafts(block, cp, ct, 4)
                     conf_s, am_s, um_s = block_step(cfg, w, cache, drafts, off, p.tau)
                     kind, rows = "step", 4 * bb
-                chosen, block, cp, ct, _ = accept_jump(drafts, conf_s, am_s, um_s, cp, ct, mask_id)
+                if p.n_drafts == 4:
+                    chosen, block, cp, ct, _ = accept_jump(drafts, conf_s, am_s, um_s, cp, ct, mask_id)
+                else:
+                    chosen, block, cp, ct, _ = speculative_jump(drafts, conf_s, am_s, um_s, cp, ct, mask_id, 8)
             stats["n_step"] += 1
             stats["step_rows"] += rows
+            if int((block == mask_id).sum()) >= int((tokens[off:off + bb] == mask_id).sum()):
+                # forced progress always unmasks a position, but nothing stops an untrained model from
+                # attempting the MASK token itself there; the paper's models never do, so this is an error
+                raise RuntimeError("a step left the block's MASK count unchanged (the greedy token is MASK)")
             tokens[off:off + bb] = block
             record(kind, bb, chosen, cp, ct)
         off += bb

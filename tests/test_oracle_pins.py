@@ -585,6 +585,127 @@ def test_accept_jump_branches_by_hand():
     assert ch == 0 and nb.tolist() == [1, 9, M_, 4, M_, M_]
 
 
+def _random_step_outputs(rng, S, b=None):
+    """A block, k <= S // 2 ranked candidates among its MASK positions, the S blocks built from them and random
+    step outputs in which candidates are often unmasked with the speculated token."""
+    b = b or int(rng.integers(2, 20))
+    n_cand = S // 2
+    block = rng.integers(0, 8, b).astype(np.int32)
+    block[rng.random(b) < 0.6] = M_
+    masked = np.flatnonzero(block == M_)
+    cp = np.full(n_cand, -1, np.int32)
+    ct = rng.integers(0, 8, n_cand).astype(np.int32)
+    k = min(n_cand, masked.size, int(rng.integers(0, n_cand + 1)))
+    cp[:k] = rng.permutation(masked)[:k]
+    drafts = o.speculative_drafts(block, cp, ct, S)
+    conf = rng.random((S, b))
+    am = rng.integers(0, 8, (S, b)).astype(np.int32)
+    for c in range(n_cand):
+        if cp[c] >= 0:
+            am[:, cp[c]] = np.where(rng.random(S) < 0.75, ct[c], am[:, cp[c]])
+    um = ((rng.random((S, b)) < 0.5) & (drafts == M_)).astype(np.uint8)
+    return block, cp, ct, drafts, conf, am, um
+
+
+def test_speculative_drafts_by_hand_and_equal_to_the_four_of_accept_jump():
+    block = np.array([1, M_, M_, 4, M_, M_, M_], np.int32)
+    d = o.speculative_drafts(block, np.array([2, 5, 1, 6]), np.array([70, 80, 60, 90]), 8)
+    assert d.tolist() == [[1, M_, M_, 4, M_, M_, M_],                  # block_0
+                          [1, M_, 70, 4, M_, M_, M_],                  # B
+                          [1, M_, M_, 4, M_, 80, M_],                  # D
+                          [1, M_, 70, 4, M_, 80, M_],                  # B + D
+                          [1, 60, M_, 4, M_, M_, M_],                  # the third
+                          [1, 60, 70, 4, M_, 80, M_],                  # top three
+                          [1, M_, M_, 4, M_, M_, 90],                  # the fourth
+                          [1, 60, 70, 4, M_, 80, 90]]                  # top four
+    d = o.speculative_drafts(block, np.array([2, 5, -1, -1]), np.array([70, 80, 0, 0]), 8)
+    assert d[4].tolist() == d[6].tolist() == block.tolist() and d[5].tolist() == d[7].tolist() == d[3].tolist()
+    rng = np.random.default_rng(3)
+    for _ in range(50):
+        block, cp, ct, *_ = _random_step_outputs(rng, 4)
+        assert np.array_equal(o.speculative_drafts(block, cp, ct, 4), o.accept_jump_drafts(block, cp, ct))
+        assert np.array_equal(o.speculative_drafts(block, cp, ct, 8)[:4], o.accept_jump_drafts(block, cp, ct))
+
+
+def test_speculative_jump_with_four_blocks_is_the_rule_of_accept_jump():
+    """Sec. 4.2.1 fixes the rule for B and D: on four blocks the eight-block rule must give exactly that."""
+    rng = np.random.default_rng(10)
+    seen = set()
+    for trial in range(1500):
+        block, cp, ct, drafts, conf, am, um = _random_step_outputs(rng, 4)
+        want = o.accept_jump(drafts, conf, am, um, cp, ct, M_)
+        got = o.speculative_jump(drafts, conf, am, um, cp, ct, M_, 4)
+        assert got[0] == want[0]
+        for g, w_ in zip(got[1:], want[1:]):
+            assert np.array_equal(g, w_)
+        seen.add(want[0])
+    assert seen == {0, 1, 2, 3}
+
+
+def test_speculative_jump_eight_blocks_by_hand():
+    block, cp, ct = [1, M_, M_, 4, M_, M_, M_, M_], [2, 5, 1, 6], [70, 80, 60, 90]
+
+    def run(accepts):
+        drafts = o.speculative_drafts(np.array(block, np.int32), np.array(cp), np.array(ct), 8)
+        conf, am, um = np.full((8, 8), 0.1), np.full((8, 8), 50, np.int32), np.zeros((8, 8), np.uint8)
+        conf[:, 7], conf[:, 4] = 0.3, 0.2                      # ranks the positions no draft touches
+        for s, p, t in accepts:
+            um[s, p], am[s, p] = 1, t
+        return o.speculative_jump(drafts, conf, am, um, np.array(cp), np.array(ct), M_, 8)
+
+    B_, D_, C_, E_ = (2, 70), (5, 80), (1, 60), (6, 90)         # (position, token) of the four candidates
+    assert run([])[0] == 0
+    assert run([(0, *C_)])[0] == 4                               # only the third verified: its own block
+    assert run([(0, *E_)])[0] == 6
+    assert run([(0, *C_), (0, *E_)])[0] == 4                     # two single-candidate blocks tie: the lower number
+    assert run([(0, *B_), (0, *C_)])[0] == 1                     # {B, third} is no block: B's, nothing more there
+    assert run([(0, *B_), (0, *D_), (0, *C_)])[0] == 5           # top three at once
+    assert run([(0, *B_), (0, *D_), (0, *C_), (0, *E_)])[0] == 7
+    assert run([(0, *B_), (0, *D_), (0, *E_)])[0] == 3           # {B, D, fourth} is no block: B + D
+    assert run([(0, *B_), (1, *D_), (3, *C_), (5, *E_)])[0] == 7     # one candidate at a time, four jumps
+    assert run([(0, *B_), (1, *D_), (3, *E_)])[0] == 3               # the chain stops where no block fits
+    assert run([(0, *D_), (2, *B_), (2, *C_)])[0] == 5               # from D's block straight to the top three
+    assert run([(0, *C_), (4, *B_), (4, *D_)])[0] == 5               # from the third's block too
+    assert run([(0, 2, 71)])[0] == 0                                  # another token than the speculated one
+    assert run([(1, *D_)])[0] == 0                                    # what a block that is never reached verifies is ignored
+    ch, nb, pos, tok, nd = run([(0, *B_), (0, *D_), (3, 1, 33)])
+    assert ch == 3 and nb.tolist() == [1, 33, 70, 4, M_, 80, M_, M_]
+    assert pos.tolist() == [7, 4, 6, -1] and tok.tolist() == [50, 50, 50, 0]
+    assert np.array_equal(nd, o.speculative_drafts(nb, pos, tok, 8))
+
+
+def test_speculative_jump_invariants_on_random_inputs():
+    """Brute force: the adopted block is the end of the only chain the rule allows, found by trying all paths."""
+    rng = np.random.default_rng(11)
+    seen = set()
+    for trial in range(1500):
+        block, cp, ct, drafts, conf, am, um = _random_step_outputs(rng, 8)
+        ch, nb, pos, tok, nd = o.speculative_jump(drafts, conf, am, um, cp, ct, M_, 8)
+        ok = lambda s, c: cp[c] >= 0 and drafts[s, cp[c]] == M_ and um[s, cp[c]] == 1 and am[s, cp[c]] == ct[c]
+        sets = [frozenset(x) for x in o.SPEC_SETS]
+        cur, hops = 0, 0
+        while True:
+            ver = sets[cur] | {c for c in range(4) if ok(cur, c)}
+            reach = [s for s in range(8) if sets[cur] < sets[s] <= ver]
+            if not reach:
+                break
+            size = max(len(sets[s]) for s in reach)
+            cur = min(s for s in reach if len(sets[s]) == size)
+            hops += 1
+        assert ch == cur and hops <= 4
+        seen.add(ch)
+        # every candidate of the adopted block was verified in some block of the chain, so the new block holds it
+        for c in o.SPEC_SETS[ch]:
+            assert nb[cp[c]] == ct[c]
+        assert np.array_equal(nb[um[ch] == 0], drafts[ch][um[ch] == 0]) and np.array_equal(nb[um[ch] == 1], am[ch][um[ch] == 1])
+        still = np.flatnonzero(nb == M_)
+        assert (pos >= 0).sum() == min(4, still.size) and len(set(pos[pos >= 0].tolist())) == (pos >= 0).sum()
+        ranked = sorted(still, key=lambda i: (-conf[ch][i], i))[:4]
+        assert pos[pos >= 0].tolist() == ranked and all(tok[j] == am[ch][pos[j]] for j in range(4) if pos[j] >= 0)
+        assert np.array_equal(nd, o.speculative_drafts(nb, pos, tok, 8))
+    assert seen == set(range(8))
+
+
 def test_accept_jump_next_drafts_and_invariants_on_random_inputs():
     """Properties that any input must satisfy, and an independent restatement of the branch rule."""
     rng = np.random.default_rng(9)
@@ -855,6 +976,66 @@ def test_generate_accept_jump_invariants_and_stage_switch():
                 blk = prev_ev["tokens"][ev["block_off"]:ev["block_off"] + ev["block_len"]]
                 assert (ev["kind"] == "shared") == (int((blk != MICRO.mask_id).sum()) >= 5)
     assert seen - {0}, "no speculative draft was ever adopted: the case does not exercise the controller"
+
+
+def test_generate_eight_blocks_in_the_decoded_share_stage():
+    """n_drafts = 8: until the switch point the run is the four-draft accept-jump run, position for position; in
+    the decoded-share stage a step forwards b + 7 * masked rows, and one such step is redone here from the
+    primitives (eight blocks from the four ranked candidates, the shared-K/V forward, the jump rule)."""
+    seen = set()
+    for seed in (23, 34, 35):
+        w, prompt = _gen_setup(seed=seed, gain=8.0)
+        P, R, b = len(prompt), 16, 8
+        four = o.GenParams(block_len=b, n_drafts=4, tau=0.85, share_from=b + 1)
+        t4, s4, e4 = o.generate(MICRO, w, prompt, R, four)
+        t8, s8, e8 = o.generate(MICRO, w, prompt, R, dataclasses_replace(four, n_drafts=8))
+        assert np.array_equal(t4, t8) and s4 == s8 and len(e4) == len(e8)
+        for a4, a8 in zip(e4, e8):
+            assert a4["chosen"] == a8["chosen"] and np.array_equal(a4["tokens"], a8["tokens"])
+            assert np.array_equal(a4["cand_pos"], a8["cand_pos"][:2]) and a8["cand_pos"].shape == (4,)
+        p8 = o.GenParams(block_len=b, n_drafts=8, tau=0.85, share_from=2)
+        tokens, stats, events = o.generate(MICRO, w, prompt, R, p8)
+        assert not (tokens == MICRO.mask_id).any() and stats["n_step_shared"] > 0
+        rows = 0
+        redone = False
+        for prev_ev, ev in zip(events, events[1:]):
+            if ev["kind"] == "refresh":
+                continue
+            off, bb = ev["block_off"], ev["block_len"]
+            blk = prev_ev["tokens"][off:off + bb]
+            nm = int((blk == MICRO.mask_id).sum())
+            assert (ev["kind"] == "shared") == (bb - nm >= 2)
+            rows += bb + 7 * nm if ev["kind"] == "shared" else 4 * bb
+            seen.add((ev["kind"], ev["chosen"]))
+            if ev["kind"] == "shared" and not redone:
+                # the cycle's cache: the refresh ran on the sequence as it stood when the block cycle began
+                cyc = [x for x in events[:events.index(ev)] if x["kind"] == "refresh"][-1]
+                before = events[events.index(cyc) - 1]["tokens"] if events.index(cyc) else \
+                    np.concatenate([prompt, np.full(R, MICRO.mask_id, np.int32)])
+                cache, _, _ = o.prefill(MICRO, w, before, resp_off=P)
+                drafts = o.speculative_drafts(blk, prev_ev["cand_pos"], prev_ev["cand_tok"], 8)
+                out = o.block_step_shared(MICRO, w, cache, drafts, off, 0.85)
+                ch, nb, pos, tok, _ = o.speculative_jump(drafts, *out, prev_ev["cand_pos"], prev_ev["cand_tok"],
+                                                         MICRO.mask_id, 8)
+                assert ch == ev["chosen"] and np.array_equal(nb, ev["tokens"][off:off + bb])
+                assert np.array_equal(pos, ev["cand_pos"]) and np.array_equal(tok, ev["cand_tok"])
+                redone = True
+        assert rows == stats["step_rows"] and redone
+    assert {c for k, c in seen if k == "shared"} - {0, 1, 2, 3}, "none of the four extra blocks was ever adopted"
+
+
+def test_generate_stops_when_the_greedy_token_is_mask():
+    """Untrained weights may attempt the MASK token itself at the forced position: the block's MASK count then
+    stays as it was and the loop reports it instead of spinning (LM head row of MASK made dominant here)."""
+    w, prompt = _gen_setup(seed=21, gain=8.0)
+    lm = w.f64(o.T_LM).copy()
+    lm[MICRO.mask_id] = 40.0 * lm.std()          # every hidden state with a positive mean now prefers MASK ...
+    lm[:MICRO.mask_id] = 0.0                     # ... and nothing competes
+    w.set_values(o.T_LM, 0, lm)
+    w.set_values(o.T_EMBED, 0, np.abs(w.f64(o.T_EMBED)))
+    for nd, sf in ((1, None), (4, None), (8, 0)):
+        with pytest.raises(RuntimeError):
+            o.generate(MICRO, w, prompt, 8, o.GenParams(block_len=4, n_drafts=nd, tau=0.5, share_from=sf))
 
 
 def dataclasses_replace(p, **kw):
