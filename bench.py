@@ -93,16 +93,17 @@ def cpu_baseline_step(shape, wl, seed, std):
 def bench_generate(args, model, shape, B, W, np, torch):
     """Whole generations (ODB-dLLM Sec. 2.1 with Sec. 4.2 on): 256 prompt tokens, 256 response positions in
     blocks of 32, at the 8B shape.  Random weights never reach tau = 0.9, so the final norm gain is raised to
-    8 (as in the parity tests' peaked variants): confidences then straddle the threshold.  Three decoders are
+    8 (as in the parity tests' peaked variants): confidences then straddle the threshold.  Four decoders are
     timed on the same prompt: threshold only, accept-jump, accept-jump with the decoded-share stage from 16
-    decoded positions on.  No [EOS] is defined for synthetic weights, so length prediction stays off."""
+    decoded positions on, and the same with eight blocks in that stage (Sec. 4.2.2's four extra candidates).
+    No [EOS] is defined for synthetic weights, so length prediction stays off."""
     P, R, b = 256, 256, 32
     B.odb_model_set_tensor(model, B.T_GF, 0, np.full(shape["d_model"], 0x4100, np.uint16))     # bf16(8.0)
     rng = np.random.default_rng(W.WEIGHT_SEED + 31)
     prompt = torch.from_numpy(rng.integers(0, shape["vocab"] - 1, P).astype(np.int32)).cuda()
     cache = B.odb_cache_create(model, 1, P + R)
     modes = {"threshold": dict(n_drafts=1), "accept_jump": dict(n_drafts=4),
-             "jump_share": dict(n_drafts=4, share_from=16)}
+             "jump_share": dict(n_drafts=4, share_from=16), "jump_share8": dict(n_drafts=8, share_from=16)}
     res = {}
     for mode, kw in modes.items():
         runs = []
@@ -124,13 +125,15 @@ def bench_generate(args, model, shape, B, W, np, torch):
                      "refresh_ms": float(np.mean([r["refresh_ms"] for r in runs])),
                      "step_ms": float(np.mean([r["step_ms"] for r in runs])),
                      "refresh_share_of_time": float(np.mean([r["refresh_ms"] / r["total_ms"] for r in runs]))}
-    best = res["jump_share"]
+    best = min((res["jump_share"], res["jump_share8"]), key=lambda r: r["ms_per_generation"])
+    best_name = "jump_share" if best is res["jump_share"] else "jump_share8"
     out = {"metric": "generated positions/s, whole block-wise generation (8B shape, peaked synthetic weights)",
            "value": best["positions_per_s"], "unit": "positions/s", "n_gpus": 1, "steps": args.steps,
            "warmup": args.warmup, "ms_per_step": best["ms_per_generation"], "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": "f16", "data": "synthetic",
            "config": {"workload": "generate: %d prompt + %d response positions, blocks of %d, tau 0.9, final norm gain 8; "
-                                  "value is the accept-jump + decoded-share decoder" % (P, R, b), "decoders": res},
+                                  "value is the faster accept-jump + decoded-share decoder (%s)" % (P, R, b, best_name),
+                      "decoders": res},
            "roofline": None, "cpu_baseline": None}
     print(json.dumps(out))
     B.odb_cache_destroy(cache)

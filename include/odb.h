@@ -254,10 +254,36 @@ int odb_accept_jump(const odb_model *m, const int32_t *drafts_dev, const float *
                     int32_t *chosen_dev, int32_t *new_drafts_dev, int32_t *new_cand_pos_dev,
                     int32_t *new_cand_tok_dev, void *stream);
 
+/* The jump rule over the S = 4 or 8 blocks of a step (ODB-dLLM Sec. 4.2.1, carried over to the
+ * eight blocks of Sec. 4.2.2; the paper states the rule for the two candidates B and D only).
+ * With the candidates ranked by confidence, block s holds the block with these candidates
+ * unmasked beforehand: s = 0 none, 1 {B}, 2 {D}, 3 {B, D}, 4 {third}, 5 {B, D, third},
+ * 6 {fourth}, 7 {all four}.  The walk starts at block_0.  At a block with candidate set X the
+ * verified set is X plus every other candidate whose position this block's own step unmasks
+ * with exactly the speculated token; the block whose set lies strictly above X inside the
+ * verified set and holds the most candidates (the lowest number among equals) is visited
+ * next, and the block at which no such block exists is adopted.  For S = 4 this is the rule
+ * of odb_accept_jump.  The adopted block plus every position its own step unmasked is
+ * new_drafts[.,0]; the n_next / 2 most confident positions still MASK there (lower index
+ * first on equal confidence; -1 / token 0 where fewer remain, and in the entries behind
+ * n_next / 2) are the next candidates and new_drafts[.,1 .. n_next) the blocks built on them.
+ *   drafts_dev, argmax_dev  device int32 [batch, S, b]; conf_dev float, unmask_dev uint8, same shape
+ *   cand_pos_dev, cand_tok_dev  device int32 [batch, 4] (the first S / 2 are read)
+ *   chosen_dev device int32 [batch], new_drafts_dev device int32 [batch, n_next, b],
+ *   new_cand_pos_dev, new_cand_tok_dev device int32 [batch, 4]                 written
+ * Output buffers must not overlap input buffers.  Asynchronous on `stream`; all buffers are
+ * the caller's.  Errors: ODB_E_INVALID_ARG for NULL pointers, batch < 1, b < 1, S or n_next
+ * other than 4 and 8. */
+int odb_speculative_jump(const odb_model *m, const int32_t *drafts_dev, const float *conf_dev,
+                         const int32_t *argmax_dev, const uint8_t *unmask_dev,
+                         const int32_t *cand_pos_dev, const int32_t *cand_tok_dev, int batch, int b,
+                         int S, int n_next, int32_t *chosen_dev, int32_t *new_drafts_dev,
+                         int32_t *new_cand_pos_dev, int32_t *new_cand_tok_dev, void *stream);
+
 /* Block-wise generation of one response (ODB-dLLM Sec. 2.1, with the adaptive length
  * prediction of Sec. 4.1 and the jump-share decoding of Sec. 4.2 switched on by the
  * parameters).  The host loop is the library's; every decision is taken by kernels and the
- * host reads back eight words per forward.
+ * host reads back sixteen words per forward.
  *
  * The response starts as resp_len MASK tokens behind the prompt and is decoded block by
  * block, front to back.  A block cycle opens with a refresh (odb_prefill over the whole
@@ -272,7 +298,12 @@ int odb_accept_jump(const odb_model *m, const int32_t *drafts_dev, const float *
  *      the block alone.  n_drafts = 4: the four accept-jump drafts and odb_accept_jump (the
  *      first candidates are the two most confident positions the refresh left MASKed); once
  *      share_from positions of the block are decoded the step is odb_block_step_shared
- *      on the same four drafts.
+ *      on the same four drafts.  n_drafts = 8 (needs share_from >= 0): as n_drafts = 4 until
+ *      share_from positions are decoded, then odb_block_step_shared on eight blocks - the four
+ *      most confident positions left MASKed are the candidates (Sec. 4.2.2: the third, the top
+ *      three, the fourth and the top four join B, D and B + D) - and odb_speculative_jump.
+ *      A step that leaves the block's MASK count unchanged (an untrained model may attempt
+ *      the MASK token itself) ends the call with ODB_E_HIP rather than repeating for ever.
  * Generation ends when the next block would start at or behind the end of the sequence.
  * None of the parameter values is printed in the paper.
  *
@@ -289,14 +320,16 @@ int odb_accept_jump(const odb_model *m, const int32_t *drafts_dev, const float *
  * once per forward.  Working buffers come from the model's allocator and are released
  * before returning.  Errors: ODB_E_INVALID_ARG for NULL handles / tokens / params / stats,
  * prompt_len < 1, resp_len < 1, a cache of batch != 1 or too short, block_len outside
- * [1, 256] (or > 64 with share_from >= 0), n_drafts other than 1 and 4, eos_id >= vocab or
+ * [1, 256] (or > 64 with share_from >= 0), n_drafts other than 1, 4 and 8 (or 8 with
+ * share_from < 0), eos_id >= vocab or
  * equal to the MASK id; more than max_events forwards stop being recorded (stats.n_events
  * still counts them).  On an error of an inner call its code is returned and tokens_dev is
  * left partly decoded. */
 enum { ODB_EV_REFRESH = 0, ODB_EV_STEP = 1, ODB_EV_STEP_SHARED = 2 };
 typedef struct {
     int block_len;        /* positions per block (32 in the paper's runs) */
-    int n_drafts;         /* 1: threshold decoding; 4: accept-jump (Sec. 4.2.1) */
+    int n_drafts;         /* 1: threshold decoding; 4: accept-jump (Sec. 4.2.1); 8: accept-jump, then
+                             eight blocks in the decoded-share stage (Sec. 4.2.2) */
     float tau;            /* acceptance threshold */
     int eos_id;           /* < 0: no length prediction */
     float truncate_thr;   /* Sec. 4.1 */
@@ -309,7 +342,8 @@ typedef struct {
     int block_off, block_len;   /* block_len 0: the cut fell into what was already decoded */
     int chosen;           /* adopted draft (0 for a refresh and for n_drafts = 1) */
     int n_masked;         /* MASK positions left in the block */
-    int cand_pos[2], cand_tok[2];   /* the candidates handed to the next step */
+    int cand_pos[4], cand_tok[4];   /* the candidates handed to the next step, best first (-1 / 0:
+                                       none; n_drafts < 8 uses two) */
 } odb_generate_event;
 typedef struct {
     int n_refresh, n_step, n_step_shared, final_len, n_events;

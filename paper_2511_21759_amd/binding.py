@@ -24,6 +24,7 @@ SYMBOLS = (
     "odb_last_error", "odb_profile_begin", "odb_profile_end", "odb_set_step_mode", "odb_model_status",
     "odb_debug_step_trace", "odb_predict_length", "odb_accept_jump", "odb_block_step_shared",
     "odb_block_step_shared_rows", "odb_block_step_shared_logits", "odb_cache_truncate", "odb_generate",
+    "odb_speculative_jump",
 )
 
 KERNEL_CLASSES = ("gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "rmsnorm",
@@ -51,7 +52,7 @@ class odb_generate_params(ctypes.Structure):
 class odb_generate_event(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int), ("length", ctypes.c_int), ("block_off", ctypes.c_int),
                 ("block_len", ctypes.c_int), ("chosen", ctypes.c_int), ("n_masked", ctypes.c_int),
-                ("cand_pos", ctypes.c_int * 2), ("cand_tok", ctypes.c_int * 2)]
+                ("cand_pos", ctypes.c_int * 4), ("cand_tok", ctypes.c_int * 4)]
 
 
 class odb_generate_stats(ctypes.Structure):
@@ -100,6 +101,7 @@ def lib() -> ctypes.CDLL:
     L.odb_cache_truncate.argtypes = [vp, ci]
     L.odb_generate.argtypes = [vp, vp, vp, ci, ci, vp, vp, vp, vp, ci, vp]
     L.odb_accept_jump.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, vp, vp, vp, vp, vp]
+    L.odb_speculative_jump.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, vp, vp, vp, vp, vp]
     L.odb_block_step_shared.argtypes = [vp, vp, vp, ci, ci, ci, ci, cf, vp, vp, vp, vp]
     L.odb_block_step_shared_rows.argtypes = [ci, ci, ci, ci]
     L.odb_block_step_shared_logits.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp, vp]
@@ -238,7 +240,8 @@ def odb_generate(model: int, cache: int, tokens, prompt_len: int, block_len: int
                  eos_id: int = -1, truncate_thr: float = 0.9, share_from: int = -1, max_events: int = 0,
                  event_tokens: bool = False):
     """tokens: int32 CUDA tensor [prompt_len + resp_len] whose first prompt_len entries hold the prompt; decoded
-    in place.  -> (stats dict, events list of dicts, event_tokens int32 CUDA tensor [n, L0] or None)."""
+    in place.  -> (stats dict, events list of dicts, event_tokens int32 CUDA tensor [n, L0] or None).
+    An event's cand_pos / cand_tok hold the candidates in use: four with n_drafts = 8, else two."""
     import torch
     if tokens.dtype != torch.int32 or tokens.dim() != 1 or not tokens.is_contiguous() or not tokens.is_cuda:
         raise TypeError("tokens must be a contiguous 1-D int32 CUDA tensor")
@@ -252,9 +255,10 @@ def odb_generate(model: int, cache: int, tokens, prompt_len: int, block_len: int
                               snap.data_ptr() if snap is not None else None, max_events, _stream()))
     stats = {name: getattr(st, name) for name, _ in odb_generate_stats._fields_}
     n = min(st.n_events, max_events)
+    nc = 4 if n_drafts == 8 else 2
     events = [dict(kind=EVENT_KINDS[e.kind], L=e.length, block_off=e.block_off, block_len=e.block_len, chosen=e.chosen,
-                   n_masked=e.n_masked, cand_pos=np.array(list(e.cand_pos), np.int32),
-                   cand_tok=np.array(list(e.cand_tok), np.int32)) for e in (ev[i] for i in range(n))]
+                   n_masked=e.n_masked, cand_pos=np.array(list(e.cand_pos)[:nc], np.int32),
+                   cand_tok=np.array(list(e.cand_tok)[:nc], np.int32)) for e in (ev[i] for i in range(n))]
     return stats, events, (snap[:n] if snap is not None else None)
 
 
@@ -277,6 +281,26 @@ def odb_accept_jump(model: int, drafts, conf, argmax, unmask, cand_pos, cand_tok
     _check(lib().odb_accept_jump(model, drafts.data_ptr(), conf.data_ptr(), argmax.data_ptr(), unmask.data_ptr(),
                                  cand_pos.data_ptr(), cand_tok.data_ptr(), B, b, chosen.data_ptr(), new_drafts.data_ptr(),
                                  new_pos.data_ptr(), new_tok.data_ptr(), _stream()))
+    return chosen, new_drafts, new_pos, new_tok
+
+
+def odb_speculative_jump(model: int, drafts, conf, argmax, unmask, cand_pos, cand_tok, n_next: int):
+    """drafts/argmax int32, conf f32, unmask uint8: CUDA tensors [B, S, b], S = 4 or 8; cand_pos/cand_tok int32 [B, 4]
+    -> (chosen int32 [B], new_drafts int32 [B, n_next, b], new_cand_pos int32 [B, 4], new_cand_tok int32 [B, 4])."""
+    import torch
+    B, S, b = drafts.shape
+    want = {"drafts": (drafts, torch.int32, (B, S, b)), "conf": (conf, torch.float32, (B, S, b)),
+            "argmax": (argmax, torch.int32, (B, S, b)), "unmask": (unmask, torch.uint8, (B, S, b)),
+            "cand_pos": (cand_pos, torch.int32, (B, 4)), "cand_tok": (cand_tok, torch.int32, (B, 4))}
+    for name, (t, dt, shp) in want.items():
+        if t.dtype != dt or tuple(t.shape) != shp or not t.is_contiguous() or not t.is_cuda:
+            raise TypeError("%s must be a contiguous CUDA tensor of dtype %s and shape %s" % (name, dt, shp))
+    chosen = torch.empty((B,), dtype=torch.int32, device=drafts.device)
+    new_drafts = torch.empty((B, max(int(n_next), 1), b), dtype=torch.int32, device=drafts.device)
+    new_pos, new_tok = torch.empty_like(cand_pos), torch.empty_like(cand_tok)
+    _check(lib().odb_speculative_jump(model, drafts.data_ptr(), conf.data_ptr(), argmax.data_ptr(), unmask.data_ptr(),
+                                      cand_pos.data_ptr(), cand_tok.data_ptr(), B, b, S, n_next, chosen.data_ptr(),
+                                      new_drafts.data_ptr(), new_pos.data_ptr(), new_tok.data_ptr(), _stream()))
     return chosen, new_drafts, new_pos, new_tok
 
 

@@ -802,6 +802,24 @@ int odb_accept_jump(const odb_model *mh, const int32_t *drafts, const float *con
     return ODB_OK;
 }
 
+int odb_speculative_jump(const odb_model *mh, const int32_t *drafts, const float *conf, const int32_t *argmax,
+                         const uint8_t *unmask, const int32_t *cand_pos, const int32_t *cand_tok, int batch, int b, int S,
+                         int n_next, int32_t *chosen, int32_t *new_drafts, int32_t *new_cand_pos, int32_t *new_cand_tok,
+                         void *stream) {
+    if (!mh || !drafts || !conf || !argmax || !unmask || !cand_pos || !cand_tok || !chosen || !new_drafts || !new_cand_pos ||
+        !new_cand_tok)
+        return fail(ODB_E_INVALID_ARG, "speculative_jump: NULL argument");
+    if (batch < 1 || b < 1) return fail(ODB_E_INVALID_ARG, "speculative_jump: batch=%d, b=%d", batch, b);
+    if ((S != 4 && S != 8) || (n_next != 4 && n_next != 8))
+        return fail(ODB_E_INVALID_ARG, "speculative_jump: S=%d, n_next=%d (4 or 8)", S, n_next);
+    const Model &m = mh->m;
+    HIP_TRY(hipSetDevice(m.device));
+    launch_spec_jump(drafts, conf, argmax, unmask, cand_pos, cand_tok, batch, S, n_next, b, m.cfg.mask_id, chosen, new_drafts,
+                     new_cand_pos, new_cand_tok, (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return ODB_OK;
+}
+
 int odb_predict_length(const odb_model *mh, const int32_t *tokens, const float *conf, const int32_t *argmax, int batch,
                        int L, int resp_off, int eos_id, float truncate_thr, int32_t *new_len, void *stream) {
     if (!mh || !tokens || !conf || !argmax || !new_len) return fail(ODB_E_INVALID_ARG, "predict_length: NULL argument");
@@ -818,7 +836,7 @@ int odb_predict_length(const odb_model *mh, const int32_t *tokens, const float *
 }
 
 // The generation loop (ODB-dLLM Sec. 2.1 + 4.1 + 4.2): see odb.h for the order of events.  Every decision is
-// a kernel's; the host reads eight words back per forward to learn the length, the block's MASK count (loop
+// a kernel's; the host reads sixteen words back per forward to learn the length, the block's MASK count (loop
 // exit, row bound of the decoded-share step) and what to record.
 int odb_generate(odb_model *mh, odb_cache *ch, int32_t *tokens, int prompt_len, int resp_len,
                  const odb_generate_params *gp, odb_generate_stats *st, odb_generate_event *events,
@@ -832,8 +850,10 @@ int odb_generate(odb_model *mh, odb_cache *ch, int32_t *tokens, int prompt_len, 
     if (c.batch != 1 || c.max_len < P + R)
         return fail(ODB_E_INVALID_ARG, "generate: needs a cache of batch 1 and max_len >= %d (has batch %d, max_len %d)",
                     P + R, c.batch, c.max_len);
-    if (gp->n_drafts != 1 && gp->n_drafts != 4) return fail(ODB_E_INVALID_ARG, "generate: n_drafts=%d", gp->n_drafts);
-    const bool share = gp->n_drafts == 4 && gp->share_from >= 0;
+    const int nd = gp->n_drafts;
+    if ((nd != 1 && nd != 4 && nd != 8) || (nd == 8 && gp->share_from < 0))
+        return fail(ODB_E_INVALID_ARG, "generate: n_drafts=%d, share_from=%d", nd, gp->share_from);
+    const bool share = nd >= 4 && gp->share_from >= 0;
     if (b < 1 || b > 256 || (share && b > 64)) return fail(ODB_E_INVALID_ARG, "generate: block_len=%d", b);
     if (gp->eos_id >= m.cfg.vocab || gp->eos_id == mask_id) return fail(ODB_E_INVALID_ARG, "generate: eos_id=%d", gp->eos_id);
     if (max_events < 0 || ((events || event_tokens) && max_events < 1))
@@ -844,7 +864,7 @@ int odb_generate(odb_model *mh, odb_cache *ch, int32_t *tokens, int prompt_len, 
 
     // working buffers: the refresh's attempt, two sets of drafts and candidates (the controller reads one and
     // writes the other), one step's outputs, the words for the host
-    const size_t nb = (size_t)4 * b;
+    const size_t nb = (size_t)(nd == 8 ? 8 : 4) * b;
     const size_t bytes = align_up((size_t)R * 4, 256) * 2 + align_up(nb * 4, 256) * 4 + align_up(nb, 256) + 256 * 4;
     char *buf = (char *)dev_alloc(m, bytes);
     int32_t *host_ctl = nullptr;
@@ -861,7 +881,7 @@ int odb_generate(odb_model *mh, odb_cache *ch, int32_t *tokens, int prompt_len, 
     float *conf = (float *)take(nb * 4);
     int32_t *am = (int32_t *)take(nb * 4);
     uint8_t *um = (uint8_t *)take(nb);
-    int32_t *cand[2] = {(int32_t *)take(16), (int32_t *)take(16)};
+    int32_t *cand[2] = {(int32_t *)take(32), (int32_t *)take(32)};          // four positions, then four tokens
     int32_t *chosen = (int32_t *)take(4), *ctl = (int32_t *)take(64);     // ctl[0..8) for the host, ctl[8] the predicted length
 
     using clk = std::chrono::steady_clock;
@@ -872,13 +892,14 @@ int odb_generate(odb_model *mh, odb_cache *ch, int32_t *tokens, int prompt_len, 
     auto read_back = [&](int kind) -> int {      // ctl -> host, one record; the only synchronisation of a forward
         if (event_tokens && st->n_events < max_events)
             HIP_TRY(hipMemcpyAsync(event_tokens + (size_t)st->n_events * L0, tokens, (size_t)L0 * 4, hipMemcpyDeviceToDevice, s));
-        HIP_TRY(hipMemcpyAsync(host_ctl, ctl, 32, hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipMemcpyAsync(host_ctl, ctl, 64, hipMemcpyDeviceToHost, s));
         HIP_TRY(hipStreamSynchronize(s));
         if (events && st->n_events < max_events) {
             odb_generate_event &e = events[st->n_events];
             e.kind = kind; e.length = host_ctl[0]; e.block_off = off; e.block_len = host_ctl[7]; e.chosen = host_ctl[2];
             e.n_masked = host_ctl[1];
             e.cand_pos[0] = host_ctl[3]; e.cand_pos[1] = host_ctl[4]; e.cand_tok[0] = host_ctl[5]; e.cand_tok[1] = host_ctl[6];
+            e.cand_pos[2] = host_ctl[9]; e.cand_pos[3] = host_ctl[10]; e.cand_tok[2] = host_ctl[11]; e.cand_tok[3] = host_ctl[12];
         }
         st->n_events++;
         return ODB_OK;
@@ -894,7 +915,7 @@ int odb_generate(odb_model *mh, odb_cache *ch, int32_t *tokens, int prompt_len, 
         if (gp->eos_id >= 0)
             launch_predict_length(tokens, att_conf, att_am, 1, L, P, mask_id, gp->eos_id, gp->truncate_thr, ctl + 8, s);
         launch_gen_adopt(tokens, off, b, gp->eos_id >= 0 ? ctl + 8 : nullptr, L, att_conf + (off - P), att_am + (off - P),
-                         nullptr, mask_id, gp->tau, gp->n_drafts == 4 ? drafts[cur] : nullptr, cand[cur], ctl, s);
+                         nullptr, mask_id, gp->tau, nd >= 4 ? drafts[cur] : nullptr, nd, cand[cur], ctl, s);
         if ((rc = read_back(ODB_EV_REFRESH))) break;
         st->refresh_ms += ms_since(t0);
         L = host_ctl[0];
@@ -909,21 +930,24 @@ int odb_generate(odb_model *mh, odb_cache *ch, int32_t *tokens, int prompt_len, 
             if (gp->n_drafts == 1) {
                 rc = step_impl(mh, ch, tokens + off, off, bb, 1, gp->tau, conf, am, um, nullptr, stream);
                 if (rc) break;
-                launch_gen_adopt(tokens, off, bb, nullptr, L, conf, am, um, mask_id, gp->tau, nullptr, cand[cur], ctl, s);
+                launch_gen_adopt(tokens, off, bb, nullptr, L, conf, am, um, mask_id, gp->tau, nullptr, 0, cand[cur], ctl, s);
                 st->step_rows += bb;
             } else {
+                // (the first four of eight blocks are the accept-jump drafts: the steps before the switch use those)
+                int S = 4;
                 if (share && bb - n_masked >= gp->share_from) {
                     kind = ODB_EV_STEP_SHARED;
-                    rc = step_shared_impl(mh, ch, drafts[cur], off, bb, 4, n_masked, gp->tau, conf, am, um, nullptr, nullptr, stream);
-                    st->step_rows += bb + 3 * n_masked;
+                    S = nd;
+                    rc = step_shared_impl(mh, ch, drafts[cur], off, bb, S, n_masked, gp->tau, conf, am, um, nullptr, nullptr, stream);
+                    st->step_rows += bb + (S - 1) * n_masked;
                     st->n_step_shared++;
                 } else {
                     rc = step_impl(mh, ch, drafts[cur], off, bb, 4, gp->tau, conf, am, um, nullptr, stream);
                     st->step_rows += 4 * bb;
                 }
                 if (rc) break;
-                launch_accept_jump(drafts[cur], conf, am, um, cand[cur], cand[cur] + 2, 1, bb, mask_id, chosen, drafts[cur ^ 1],
-                                   cand[cur ^ 1], cand[cur ^ 1] + 2, s);
+                launch_spec_jump(drafts[cur], conf, am, um, cand[cur], cand[cur] + 4, 1, S, nd, bb, mask_id, chosen,
+                                 drafts[cur ^ 1], cand[cur ^ 1], cand[cur ^ 1] + 4, s);
                 cur ^= 1;
                 launch_gen_commit(tokens, off, bb, L, drafts[cur], chosen, cand[cur], mask_id, ctl, s);
             }

@@ -84,10 +84,15 @@ void launch_rmsnorm(const float *h, const float *gain, float eps, int d, RowMap 
 void launch_accept_jump(const int32_t *drafts, const float *conf, const int32_t *argmax, const uint8_t *unmask,
                         const int32_t *cand_pos, const int32_t *cand_tok, int batch, int b, int mask_id, int32_t *chosen,
                         int32_t *new_drafts, int32_t *new_cand_pos, int32_t *new_cand_tok, hipStream_t s);
+// the jump rule over S = 4 or 8 blocks (cand_pos / cand_tok: four entries per sequence); builds n_next blocks
+void launch_spec_jump(const int32_t *drafts, const float *conf, const int32_t *argmax, const uint8_t *unmask,
+                      const int32_t *cand_pos, const int32_t *cand_tok, int batch, int S, int n_next, int b, int mask_id,
+                      int32_t *chosen, int32_t *new_drafts, int32_t *new_cand_pos, int32_t *new_cand_tok, hipStream_t s);
 // generation loop bookkeeping (see rows.hip): adoption of a forward's attempt at the current block, and the
-// write-back after the accept-jump controller; both pack ctl[0..8) for the host.  cand = {pos B, pos D, token B, token D}
+// write-back after the jump controller; both pack ctl[0..13) for the host.  cand = four candidate positions, then
+// their four tokens; n_build = blocks written to drafts (4 or 8)
 void launch_gen_adopt(int32_t *tokens, int off, int b, const int32_t *len_ptr, int len, const float *conf,
-                      const int32_t *argmax, const uint8_t *unmask, int mask_id, float tau, int32_t *drafts,
+                      const int32_t *argmax, const uint8_t *unmask, int mask_id, float tau, int32_t *drafts, int n_build,
                       int32_t *cand, int32_t *ctl, hipStream_t s);
 void launch_gen_commit(int32_t *tokens, int off, int bb, int len, const int32_t *new_drafts, const int32_t *chosen,
                        const int32_t *cand, int mask_id, int32_t *ctl, hipStream_t s);

@@ -278,25 +278,129 @@ __global__ __launch_bounds__(64) void accept_jump_kernel(const int32_t *drafts, 
     }
 }
 
+// The k <= 4 most confident positions of blk[0 .. bb) that hold MASK, best first, lower index first on equal
+// confidence; -1 where fewer are left.  One wave; every lane ends with the same q.  (A lane only reads the
+// positions lane, lane + 64, ... of blk: the ones it may have written itself just before.)
+__device__ inline void top_masked(const int32_t *blk, const float *conf, int bb, int mask_id, int k, int (&q)[4]) {
+    const int lane = threadIdx.x;
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+        q[r] = -1;
+        if (r < k) {
+            Cand best{-INFINITY, 0x7fffffff};
+            for (int i = lane; i < bb; i += 64) {
+                bool taken = false;
+#pragma unroll
+                for (int j = 0; j < 4; j++) taken = taken || (j < r && q[j] == i);
+                const Cand y{conf[i], i};
+                if (!taken && blk[i] == mask_id && cand_better(y, best)) best = y;
+            }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                const Cand y{__shfl_xor(best.c, o), __shfl_xor(best.i, o)};
+                if (cand_better(y, best)) best = y;
+            }
+            q[r] = best.i != 0x7fffffff ? best.i : -1;
+        }
+    }
+}
+
+// Candidate sets of the up to eight blocks of a step as bit masks over the ranked candidates (ODB-dLLM
+// Sec. 4.2.1: block_0, B, D, B + D; Sec. 4.2.2: the third, the top three, the fourth, the top four).
+__device__ __constant__ int kSpecSets[8] = {0, 1, 2, 3, 4, 7, 8, 15};
+
+// block s of the next step: the block with the candidates of its set unmasked beforehand
+__device__ inline int spec_token(int s, int i, int t, const int (&q)[4], const int (&u)[4]) {
+#pragma unroll
+    for (int c = 0; c < 4; c++)
+        if (((kSpecSets[s] >> c) & 1) && q[c] == i) t = u[c];
+    return t;
+}
+
+// The jump rule over S = 4 or 8 blocks, one wave per sequence.  From block_0: at a block with candidate set X the
+// verified set is X plus the candidates that this block's own step unmasks with the speculated token; the block
+// whose set lies strictly above X inside the verified set and holds the most candidates (lowest number among
+// equals) is next, and the walk ends where there is none.  For S = 4 this is the rule of Sec. 4.2.1 (the paper
+// states none for eight blocks).  The adopted block plus its step's unmaskings is the new block; its n_next / 2
+// most confident still-masked positions become the candidates of the n_next blocks written to new_drafts.
+__global__ __launch_bounds__(64) void spec_jump_kernel(const int32_t *drafts, const float *conf, const int32_t *argmax,
+                                                       const uint8_t *unmask, const int32_t *cand_pos,
+                                                       const int32_t *cand_tok, int S, int n_next, int b, int mask_id,
+                                                       int32_t *chosen_out, int32_t *new_drafts, int32_t *new_cand_pos,
+                                                       int32_t *new_cand_tok) {
+    const int seq = blockIdx.x, lane = threadIdx.x;
+    const size_t base = (size_t)seq * S * b;
+    const int32_t *dr = drafts + base, *am = argmax + base;
+    const float *cf = conf + base;
+    const uint8_t *um = unmask + base;
+    const int n_cand = S / 2;
+    int p[4], t[4];
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+        p[c] = c < n_cand ? cand_pos[seq * 4 + c] : -1;
+        t[c] = c < n_cand ? cand_tok[seq * 4 + c] : 0;
+    }
+    int ch = 0;
+    for (int hop = 0; hop < 4; hop++) {
+        const int X = kSpecSets[ch];
+        int V = X;
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+            const int pc = p[c];
+            if (!((X >> c) & 1) && pc >= 0 && pc < b && dr[ch * b + pc] == mask_id && um[ch * b + pc] != 0 &&
+                am[ch * b + pc] == t[c])
+                V |= 1 << c;
+        }
+        int best = -1, best_n = __popc(X);
+        for (int s = 0; s < S; s++) {
+            const int m = kSpecSets[s];
+            if ((m & ~V) == 0 && (m & X) == X && m != X && __popc(m) > best_n) { best = s; best_n = __popc(m); }
+        }
+        if (best < 0) break;
+        ch = best;
+    }
+
+    int32_t *nd = new_drafts + (size_t)seq * n_next * b;
+    for (int i = lane; i < b; i += 64) nd[i] = um[ch * b + i] ? am[ch * b + i] : dr[ch * b + i];
+    int q[4], u[4];
+    top_masked(nd, cf + ch * b, b, mask_id, n_next / 2, q);
+#pragma unroll
+    for (int c = 0; c < 4; c++) u[c] = q[c] >= 0 ? am[ch * b + q[c]] : 0;
+    if (lane == 0) {
+        chosen_out[seq] = ch;
+#pragma unroll
+        for (int c = 0; c < 4; c++) { new_cand_pos[seq * 4 + c] = q[c]; new_cand_tok[seq * 4 + c] = u[c]; }
+    }
+    for (int i = lane; i < b; i += 64) {
+        const int tk = nd[i];
+        for (int s = 1; s < n_next; s++) nd[s * b + i] = spec_token(s, i, tk, q, u);
+    }
+}
+
 // ---- generation loop bookkeeping (ODB-dLLM Sec. 2.1 / 4.1 / 4.2.1), one wave ------------------------
 // ctl words written for the host: [0] sequence length, [1] MASK positions left in the block, [2] adopted
-// draft, [3..4] candidate positions, [5..6] candidate tokens, [7] length of the block.
+// draft, [3..4] positions of candidates B and D, [5..6] their tokens, [7] length of the block, [9..10] positions
+// of the third and fourth candidate, [11..12] their tokens ([8] belongs to the length prediction).
 //
 // Adoption of one forward's attempt at the current block.  The block is tokens[off .. off+bb) with
 // bb = min(b, len - off), len read from len_ptr (the length prediction's output) when given.  Position i
 // takes argmax[i] if unmask[i] (a step's own decision) or, without an unmask array (a refresh), if it holds
 // MASK and its confidence exceeds tau or is the largest among the block's MASK positions (lower index on
-// ties).  The two most confident positions still MASK afterwards become the candidates, and with drafts
-// given the block and its three speculative variants (candidate B, D, both) are written there.
+// ties).  The two (n_build = 8: four) most confident positions still MASK afterwards become the candidates
+// (cand: four positions, then four tokens), and with drafts given the block and its n_build - 1 speculative
+// variants are written there.
 __global__ __launch_bounds__(64) void gen_adopt_kernel(int32_t *tokens, int off, int b, const int32_t *len_ptr, int len,
                                                        const float *conf, const int32_t *argmax, const uint8_t *unmask,
-                                                       int mask_id, float tau, int32_t *drafts, int32_t *cand,
+                                                       int mask_id, float tau, int32_t *drafts, int n_build, int32_t *cand,
                                                        int32_t *ctl) {
     const int lane = threadIdx.x;
     if (len_ptr) len = *len_ptr;
     const int bb = min(b, len - off);
     if (bb <= 0) {
-        if (lane == 0) { ctl[0] = len; ctl[1] = 0; ctl[2] = 0; ctl[3] = ctl[4] = -1; ctl[5] = ctl[6] = 0; ctl[7] = 0; }
+        if (lane == 0) {
+            ctl[0] = len; ctl[1] = 0; ctl[2] = 0; ctl[3] = ctl[4] = -1; ctl[5] = ctl[6] = 0; ctl[7] = 0;
+            ctl[9] = ctl[10] = -1; ctl[11] = ctl[12] = 0;
+        }
         return;
     }
     int32_t *blk = tokens + off;
@@ -310,35 +414,31 @@ __global__ __launch_bounds__(64) void gen_adopt_kernel(int32_t *tokens, int off,
         for (int o = 32; o > 0; o >>= 1) cand_push(f, f1, Cand{__shfl_xor(f.c, o), __shfl_xor(f.i, o)});
         forced = f.i;
     }
-    Cand x0 = none, x1 = none;
     int left = 0;
     for (int i = lane; i < bb; i += 64) {
         const int t0 = blk[i];
         const bool take = unmask ? unmask[i] != 0 : (t0 == mask_id && (conf[i] > tau || i == forced));
         const int t = take ? argmax[i] : t0;
         blk[i] = t;
-        if (t == mask_id) { cand_push(x0, x1, Cand{conf[i], i}); left++; }
+        left += t == mask_id;
     }
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        Cand y0{__shfl_xor(x0.c, o), __shfl_xor(x0.i, o)}, y1{__shfl_xor(x1.c, o), __shfl_xor(x1.i, o)};
-        cand_push(x0, x1, y0);
-        cand_push(x0, x1, y1);
-        left += __shfl_xor(left, o);
-    }
-    const int q0 = x0.i != 0x7fffffff ? x0.i : -1, q1 = x1.i != 0x7fffffff ? x1.i : -1;
-    const int u0 = q0 >= 0 ? argmax[q0] : 0, u1 = q1 >= 0 ? argmax[q1] : 0;
+    for (int o = 32; o > 0; o >>= 1) left += __shfl_xor(left, o);
+    int q[4], u[4];
+    top_masked(blk, conf, bb, mask_id, n_build == 8 ? 4 : 2, q);
+#pragma unroll
+    for (int c = 0; c < 4; c++) u[c] = q[c] >= 0 ? argmax[q[c]] : 0;
     if (lane == 0) {
-        ctl[0] = len; ctl[1] = left; ctl[2] = 0; ctl[3] = q0; ctl[4] = q1; ctl[5] = u0; ctl[6] = u1; ctl[7] = bb;
-        if (cand) { cand[0] = q0; cand[1] = q1; cand[2] = u0; cand[3] = u1; }
+        ctl[0] = len; ctl[1] = left; ctl[2] = 0; ctl[3] = q[0]; ctl[4] = q[1]; ctl[5] = u[0]; ctl[6] = u[1]; ctl[7] = bb;
+        ctl[9] = q[2]; ctl[10] = q[3]; ctl[11] = u[2]; ctl[12] = u[3];
+        if (cand)
+#pragma unroll
+            for (int c = 0; c < 4; c++) { cand[c] = q[c]; cand[4 + c] = u[c]; }
     }
     if (drafts)     // each lane re-reads only the positions it wrote itself
         for (int i = lane; i < bb; i += 64) {
             const int t = blk[i];
-            drafts[i] = t;
-            drafts[bb + i] = i == q0 ? u0 : t;
-            drafts[2 * bb + i] = i == q1 ? u1 : t;
-            drafts[3 * bb + i] = i == q0 ? u0 : (i == q1 ? u1 : t);
+            for (int s = 0; s < n_build; s++) drafts[s * bb + i] = spec_token(s, i, t, q, u);
         }
 }
 
@@ -358,14 +458,23 @@ __global__ __launch_bounds__(64) void gen_commit_kernel(int32_t *tokens, int off
     for (int o = 32; o > 0; o >>= 1) left += __shfl_xor(left, o);
     if (lane == 0) {
         ctl[0] = len; ctl[1] = left; ctl[2] = chosen[0];
-        ctl[3] = cand[0]; ctl[4] = cand[1]; ctl[5] = cand[2]; ctl[6] = cand[3]; ctl[7] = bb;
+        ctl[3] = cand[0]; ctl[4] = cand[1]; ctl[5] = cand[4]; ctl[6] = cand[5]; ctl[7] = bb;
+        ctl[9] = cand[2]; ctl[10] = cand[3]; ctl[11] = cand[6]; ctl[12] = cand[7];
     }
 }
 
 void launch_gen_adopt(int32_t *tokens, int off, int b, const int32_t *len_ptr, int len, const float *conf,
-                      const int32_t *argmax, const uint8_t *unmask, int mask_id, float tau, int32_t *drafts,
+                      const int32_t *argmax, const uint8_t *unmask, int mask_id, float tau, int32_t *drafts, int n_build,
                       int32_t *cand, int32_t *ctl, hipStream_t s) {
-    gen_adopt_kernel<<<1, 64, 0, s>>>(tokens, off, b, len_ptr, len, conf, argmax, unmask, mask_id, tau, drafts, cand, ctl);
+    gen_adopt_kernel<<<1, 64, 0, s>>>(tokens, off, b, len_ptr, len, conf, argmax, unmask, mask_id, tau, drafts, n_build, cand,
+                                      ctl);
+}
+
+void launch_spec_jump(const int32_t *drafts, const float *conf, const int32_t *argmax, const uint8_t *unmask,
+                      const int32_t *cand_pos, const int32_t *cand_tok, int batch, int S, int n_next, int b, int mask_id,
+                      int32_t *chosen, int32_t *new_drafts, int32_t *new_cand_pos, int32_t *new_cand_tok, hipStream_t s) {
+    spec_jump_kernel<<<dim3(batch), 64, 0, s>>>(drafts, conf, argmax, unmask, cand_pos, cand_tok, S, n_next, b, mask_id, chosen,
+                                                new_drafts, new_cand_pos, new_cand_tok);
 }
 
 void launch_gen_commit(int32_t *tokens, int off, int bb, int len, const int32_t *new_drafts, const int32_t *chosen,

@@ -64,6 +64,7 @@ def replay(p, prompt, R, gp, events, snaps, err):
     cfg, w, mask = p.cfg, p.w, p.cfg.mask_id
     P, b, tau = len(prompt), gp["block_len"], gp["tau"]
     eos = gp.get("eos_id", -1)
+    n_cand = 4 if gp["n_drafts"] == 8 else 2
     pre = np.concatenate([prompt, np.full(R, mask, np.int32)])
     L, cp, ct, cache = P + R, None, None, None
     n_clear = n_cmp = n_dec = 0
@@ -96,18 +97,19 @@ def replay(p, prompt, R, gp, events, snaps, err):
             blk, c_b, a_b = pre[off:off + bb], conf[off - P:off - P + bb], am[off - P:off - P + bb]
             um = o.threshold_unmask(blk, c_b, tau, mask)
             new = np.where(um == 1, a_b, blk).astype(np.int32)
-            pos, tok = o.speculative_candidates(new, c_b, a_b, mask)
+            pos, tok = o.speculative_candidates(new, c_b, a_b, mask, k=n_cand)
             ok = draft_clear(blk, z[off - P:off - P + bb], c_b, tau, mask, err)
             want_chosen, chosen_clear, c_ch = 0, True, c_b
         else:
             blk = pre[off:off + bb]
             m = blk == mask
-            share = gp["n_drafts"] == 4 and gp.get("share_from", -1) >= 0 and int((~m).sum()) >= gp["share_from"]
+            share = gp["n_drafts"] >= 4 and gp.get("share_from", -1) >= 0 and int((~m).sum()) >= gp["share_from"]
             assert e["kind"] == ("shared" if share else "step") and e["L"] == L and bb == min(b, L - off), tag
-            drafts = blk[None] if gp["n_drafts"] == 1 else o.accept_jump_drafts(blk, cp, ct)
+            # (eight blocks only in the decoded-share stage; the steps before it forward the first four)
+            drafts = blk[None] if gp["n_drafts"] == 1 else o.speculative_drafts(blk, cp, ct, gp["n_drafts"] if share else 4)
             if share:
                 conf, am, um, zs = o.block_step_shared(cfg, w, cache, drafts, off, tau, return_logits=True)
-                rows = [np.arange(bb)] + [np.flatnonzero(m)] * 3
+                rows = [np.arange(bb)] + [np.flatnonzero(m)] * (len(drafts) - 1)
             else:
                 conf, am, um, zs = o.block_step(cfg, w, cache, drafts, off, tau, return_logits=True)
                 rows = [np.arange(bb)] * len(drafts)
@@ -120,21 +122,27 @@ def replay(p, prompt, R, gp, events, snaps, err):
                 want_chosen, chosen_clear = 0, True
                 new = np.where(um[0] == 1, am[0], blk).astype(np.int32)
                 pos, tok = o.speculative_candidates(new, conf[0], am[0], mask)
-            else:
+            elif gp["n_drafts"] == 4:
                 want_chosen, new, pos, tok, _ = o.accept_jump(drafts, conf, am, um, cp, ct, mask)
                 # the controller looks at candidate B in block_0 and block_2, at candidate D in block_0 and block_1
                 looks = [(0, cp[0]), (2, cp[0]), (0, cp[1]), (1, cp[1])]
                 chosen_clear = all(oks[s][q] for s, q in looks if q >= 0)
+            else:
+                want_chosen, new, pos, tok, _ = o.speculative_jump(drafts, conf, am, um, cp, ct, mask, 8)
+                # the walk may look at any candidate in any block that does not hold it already
+                chosen_clear = all(oks[s][q] for s in range(len(drafts)) for q in cp[:len(drafts) // 2] if q >= 0)
             ok, c_ch = oks[want_chosen], conf[want_chosen]
         # invariants, whatever the margins
         got = post[off:off + bb]
         assert np.array_equal(post[:off], pre[:off]) and np.array_equal(post[off + bb:L], pre[off + bb:L]), tag
         assert np.array_equal(got[blk != mask], blk[blk != mask]), "%s: a decoded position changed" % tag
         assert e["n_masked"] == int((got == mask).sum()) < int((blk == mask).sum()), "%s: no progress" % tag
-        for j in range(2):
+        assert len(e["cand_pos"]) == n_cand, tag
+        for j in range(n_cand):
             q = e["cand_pos"][j]
             assert q == -1 or (0 <= q < bb and got[q] == mask), "%s: candidate on a decoded position" % tag
-        assert e["cand_pos"][0] != e["cand_pos"][1] or e["cand_pos"][0] == -1, tag
+        real = [q for q in e["cand_pos"] if q >= 0]
+        assert len(set(real)) == len(real) == min(n_cand, e["n_masked"]), tag
         # decisions, where they are clear of the error band
         n_dec += int((blk == mask).sum())
         if chosen_clear:
@@ -143,7 +151,7 @@ def replay(p, prompt, R, gp, events, snaps, err):
             sel = ok & (blk == mask)
             assert np.array_equal(got[sel], new[sel]), "%s: block after the forward" % tag
             n_cmp += int(sel.sum())
-            if ok.all() and ranking_clear(c_ch[new == mask], 2, err):
+            if ok.all() and ranking_clear(c_ch[new == mask], n_cand, err):
                 assert np.array_equal(e["cand_pos"], pos) and np.array_equal(e["cand_tok"], tok), "%s: candidates" % tag
                 n_clear += all_clear and chosen_clear
         pre, cp, ct = post.copy(), e["cand_pos"], e["cand_tok"]
@@ -209,6 +217,10 @@ CASES = [
     (5, 40, 70, dict(block_len=48, n_drafts=1, tau=0.7), (20, 60)),
     (6, 32, 128, dict(block_len=64, n_drafts=4, tau=0.9, share_from=32), None),      # the largest block the shared step takes
     (7, 20, 130, dict(block_len=128, n_drafts=4, tau=0.85), None),                    # blocks longer than a wave, a two-position tail
+    # eight blocks in the decoded-share stage (Sec. 4.2.2's four extra candidates), after four-draft steps / from the start
+    (8, 48, 96, dict(block_len=32, n_drafts=8, tau=0.9, share_from=8), None),
+    (9, 40, 80, dict(block_len=32, n_drafts=8, tau=0.85, share_from=0), (30, 70)),
+    (10, 24, 128, dict(block_len=64, n_drafts=8, tau=0.9, share_from=24), None),
 ]
 
 
@@ -234,7 +246,8 @@ def test_generate_errors_and_truncate():
     try:
         cache = p.cache(1, 96)
         tok = torch.zeros(96, dtype=torch.int32, device="cuda")
-        for kw in (dict(block_len=0), dict(block_len=300), dict(block_len=16, n_drafts=2),
+        for kw in (dict(block_len=0), dict(block_len=300), dict(block_len=16, n_drafts=2), dict(block_len=16, n_drafts=8),
+                   dict(block_len=128, n_drafts=8, share_from=4),
                    dict(block_len=128, n_drafts=4, share_from=4), dict(block_len=16, eos_id=p.cfg.mask_id),
                    dict(block_len=16, eos_id=p.cfg.vocab)):
             with pytest.raises(B.OdbError):
@@ -278,11 +291,13 @@ def test_truncated_cache_equals_the_oracle_on_the_kept_keys():
         p.close()
 
 
-def test_generate_at_full_width_equals_the_composed_calls():
+@pytest.mark.parametrize("ND", [4, 8])
+def test_generate_at_full_width_equals_the_composed_calls(ND):
     """8B width (d = 4096, F = 12288, V = 126464; 2 layers), where the oracle is too slow to replay a run: every
     forward of odb_generate must equal, bit for bit, what the separately tested entry points give on the state
-    before it (odb_prefill / odb_block_step / odb_block_step_shared / odb_accept_jump, and the acceptance rule and
-    candidate choice restated on the host from the library's own confidences)."""
+    before it (odb_prefill / odb_block_step / odb_block_step_shared / odb_accept_jump or, with eight blocks,
+    odb_speculative_jump, and the acceptance rule and candidate choice restated on the host from the library's
+    own confidences)."""
     shape = dict(W.MODEL_SHAPES["8b"], n_layers=2)
     model = B.odb_model_create(shape)
     try:
@@ -299,7 +314,7 @@ def test_generate_at_full_width_equals_the_composed_calls():
         late = [i for i in range(90, 130) if a0[i] not in a0[:90]]           # attempted nowhere earlier
         q = max(late, key=lambda i: c0[i])
         eos, thr = int(a0[q]), float(c0[q]) * 0.9
-        stats, events, snaps = B.odb_generate(model, cache, tokens, P, block_len=b, n_drafts=4, tau=tau, eos_id=eos,
+        stats, events, snaps = B.odb_generate(model, cache, tokens, P, block_len=b, n_drafts=ND, tau=tau, eos_id=eos,
                                               truncate_thr=thr, share_from=SHARE, max_events=400, event_tokens=True)
         snaps = snaps.cpu().numpy()
         assert stats["n_events"] == len(events) and stats["final_len"] < P + R
@@ -323,26 +338,29 @@ def test_generate_at_full_width_equals_the_composed_calls():
                     continue
                 blk, c_b, a_b = pre[off:off + bb], conf[off - P:off - P + bb], am[off - P:off - P + bb]
                 new = np.where(o.threshold_unmask(blk, c_b, np.float32(tau), mask) == 1, a_b, blk).astype(np.int32)
-                pos, tok = o.speculative_candidates(new, c_b, a_b, mask)
+                pos, tok = o.speculative_candidates(new, c_b, a_b, mask, k=ND // 2)
                 chosen = 0
             else:
                 blk = pre[off:off + bb]
                 share = int((blk != mask).sum()) >= SHARE
                 assert e["kind"] == ("shared" if share else "step"), tag
-                drafts = cuda_i32(o.accept_jump_drafts(blk, cp, ct)[None])
+                drafts = cuda_i32(o.speculative_drafts(blk, cp, ct, ND if share else 4)[None])
                 if share:
                     out = B.odb_block_step_shared(model, cache, drafts, off, int((blk == mask).sum()), tau)
                 else:
                     out = B.odb_block_step(model, cache, drafts, off, tau)
-                ch, nd, npos, ntok = B.odb_accept_jump(model, drafts, *out, cuda_i32(cp[None]), cuda_i32(ct[None]))
+                if ND == 4:
+                    ch, nd, npos, ntok = B.odb_accept_jump(model, drafts, *out, cuda_i32(cp[None]), cuda_i32(ct[None]))
+                else:
+                    ch, nd, npos, ntok = B.odb_speculative_jump(model, drafts, *out, cuda_i32(cp[None]), cuda_i32(ct[None]), 8)
                 chosen, new = int(ch.cpu().numpy()[0]), nd.cpu().numpy()[0, 0]
                 pos, tok = npos.cpu().numpy()[0], ntok.cpu().numpy()[0]
             assert e["chosen"] == chosen and np.array_equal(post[off:off + bb], new), tag
             assert np.array_equal(e["cand_pos"], pos) and np.array_equal(e["cand_tok"], tok), tag
             assert np.array_equal(post[:off], pre[:off]) and np.array_equal(post[off + bb:L], pre[off + bb:L]), tag
             pre, cp, ct = post.copy(), e["cand_pos"], e["cand_tok"]
-        print("\nfull-width generate: %d refreshes + %d steps (%d shared), final length %d of %d, adopted %s" % (
-            stats["n_refresh"], stats["n_step"], stats["n_step_shared"], stats["final_len"], P + R,
+        print("\nfull-width generate (%d blocks): %d refreshes + %d steps (%d shared), final length %d of %d, adopted %s" % (
+            ND, stats["n_refresh"], stats["n_step"], stats["n_step_shared"], stats["final_len"], P + R,
             sorted(set(e["chosen"] for e in events))))
         assert kinds == {"refresh", "step", "shared"}, "the case must run all three kinds of forward (ran %s)" % kinds
         B.odb_cache_destroy(cache)

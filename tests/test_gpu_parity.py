@@ -448,6 +448,57 @@ def test_accept_jump_bit_exact_on_random_step_outputs(tiny):
     assert set(np.unique(got[0])) <= {0, 1, 2, 3}
 
 
+def test_speculative_jump_bit_exact_on_random_step_outputs(tiny):
+    """The jump rule over four and eight blocks (Sec. 4.2.1 / 4.2.2): adopted block, next blocks and next candidates
+    equal the oracle's exactly, for either number of blocks to build."""
+    rng = np.random.default_rng(22)
+    mask_id, V = tiny.cfg.mask_id, tiny.cfg.vocab
+    seen = {4: set(), 8: set()}
+    for S in (4, 8):
+        for Bn, b in [(1, 1), (1, 3), (3, 16), (2, 32), (4, 64), (2, 100), (1, 257)]:
+            for trial in range(8):
+                n_next = (4, 8)[trial % 2]
+                block = rng.integers(0, V - 1, (Bn, b)).astype(np.int32)
+                block[rng.random((Bn, b)) < [0.0, 0.1, 0.3, 0.5, 0.7, 0.8, 0.9, 1.0][trial]] = mask_id
+                cp = np.full((Bn, 4), -1, np.int32)
+                ct = rng.integers(0, V - 1, (Bn, 4)).astype(np.int32)
+                drafts = np.empty((Bn, S, b), np.int32)
+                for i in range(Bn):
+                    masked = np.flatnonzero(block[i] == mask_id)
+                    k = min(S // 2, masked.size, int(rng.integers(0, S // 2 + 1)))
+                    cp[i, :k] = rng.permutation(masked)[:k]
+                    drafts[i] = o.speculative_drafts(block[i], cp[i], ct[i], S)
+                conf = rng.random((Bn, S, b)).astype(np.float32)
+                conf[rng.random((Bn, S, b)) < 0.3] = np.float32(0.5)          # ties in the candidate ranking
+                am = rng.integers(0, V - 1, (Bn, S, b)).astype(np.int32)
+                for i in range(Bn):
+                    for c in range(S // 2):
+                        if cp[i, c] >= 0:
+                            am[i, :, cp[i, c]] = np.where(rng.random(S) < 0.75, ct[i, c], am[i, :, cp[i, c]])
+                um = ((rng.random((Bn, S, b)) < 0.5) & (drafts == mask_id)).astype(np.uint8)
+                res = B.odb_speculative_jump(tiny.model, cuda_i32(drafts), torch.from_numpy(conf).cuda(), cuda_i32(am),
+                                             torch.from_numpy(um).cuda(), cuda_i32(cp), cuda_i32(ct), n_next)
+                got = tuple(t.cpu().numpy() for t in res)
+                for i in range(Bn):
+                    ch, nb, pos, tok, nd = o.speculative_jump(drafts[i], conf[i], am[i], um[i], cp[i, :S // 2], ct[i, :S // 2],
+                                                              mask_id, n_next)
+                    k = n_next // 2
+                    assert got[0][i] == ch and np.array_equal(got[1][i], nd), (S, Bn, b, trial, i)
+                    assert np.array_equal(got[2][i][:k], pos) and np.array_equal(got[3][i][:k], tok), (S, Bn, b, trial, i)
+                    assert np.all(got[2][i][k:] == -1) and np.all(got[3][i][k:] == 0), (S, Bn, b, trial, i)
+                    seen[S].add(int(ch))
+    assert seen[4] == {0, 1, 2, 3} and seen[8] == set(range(8))
+    x = cuda_i32(np.zeros((1, 4, 8), np.int32))
+    f, u8, c4 = torch.zeros((1, 4, 8), device="cuda"), torch.zeros((1, 4, 8), dtype=torch.uint8, device="cuda"), \
+        cuda_i32(np.zeros((1, 4), np.int32))
+    with pytest.raises(B.OdbError):
+        B.odb_speculative_jump(tiny.model, x, f, x, u8, c4, c4, 6)
+    x6 = cuda_i32(np.zeros((1, 6, 8), np.int32))
+    with pytest.raises(B.OdbError):
+        B.odb_speculative_jump(tiny.model, x6, torch.zeros((1, 6, 8), device="cuda"), x6,
+                               torch.zeros((1, 6, 8), dtype=torch.uint8, device="cuda"), c4, c4, 4)
+
+
 def test_accept_jump_decoding_loop_on_the_peaked_model():
     """A block decoded by repeated [4-draft step -> accept-jump] on the GPU.  In every iteration the controller
     is compared bit-exactly with the oracle's on the same step outputs, and the step outputs themselves with
