@@ -178,7 +178,7 @@ int run_stack(Model &m, const Cache &c, const Plan &pl, const StackIO &io, hipSt
     const size_t seq_elems = (size_t)H * c.lmax32 * dh;
     const int fresh32 = ru(io.rm.rpu_pad, 32);
     const int n_ssq = d / 16;
-    const Workspace ws{(float *)(base + pl.part), kPartialBytes};
+    const Workspace ws{(float *)(base + pl.part), kPartialBytes, m.counters + 1024};
     const NormIn ni = io.fused_norm ? NormIn{ssq, n_ssq, cfg.rms_eps} : NormIn{nullptr, 0, 0.f};
 
     for (int l = 0; l < cfg.n_layers; l++) {
@@ -265,7 +265,7 @@ int run_head(Model &m, const Plan &pl, RowMap rm, int skip, bool fused_norm, con
     float *h = (float *)(base + pl.h);
     u16 *xa = (u16 *)(base + pl.xa);
     float *stats = (float *)(base + pl.stats);
-    const Workspace ws{(float *)(base + pl.part), kPartialBytes};
+    const Workspace ws{(float *)(base + pl.part), kPartialBytes, m.counters + 1024};
     const int rows = rm.units * (rm.valid - skip);
     int lm_mt, rpu_pad, valid;
     NormIn ni{nullptr, 0, 0.f};
@@ -666,7 +666,7 @@ static int step_shared_impl(odb_model *mh, const odb_cache *ch, const int32_t *d
     if (rc) return rc;
     // final norm (fused) + LM head on all rows, then the per-unit finish
     u16 *xa = (u16 *)(base + pl.xa);
-    const Workspace ws{(float *)(base + pl.part), kPartialBytes};
+    const Workspace ws{(float *)(base + pl.part), kPartialBytes, m.counters + 1024};
     const NormIn ni{(float *)(base + pl.ssq), cfg.d_model / 16, cfg.rms_eps};
     const GemmShape sh{rows_pad / 16, cfg.vocab / 16, cfg.d_model / 32};
     if (logits) {

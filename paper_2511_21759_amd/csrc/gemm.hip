@@ -12,6 +12,68 @@ __global__ __launch_bounds__(64 * WKT) void gemm_stream_kernel(GemmArgs g, Epi e
 
 constexpr int kStreamWGs = 256;      // one workgroup per compute unit
 
+// The streaming kernel with K split over KS workgroups per block of n-tiles, for projections whose activations
+// are long (the down projection: every workgroup of the plain kernel reads all 32 x 12288 of them through L2,
+// which costs as much as a third of its weight stream).  Workgroup (n-block, ks) adds k-slice ks for NG n-tiles
+// and leaves its sums in partial[ks]; each workgroup then bumps the block's arrival counter, and the one that
+// arrives last adds the KS partial sums in slice order (so the result does not depend on who was last) and runs
+// the epilogue.  Nobody waits: the other workgroups simply exit.  Partial sums and counter travel as
+// device-coherent accesses, ordered by a wait for the stores' completion before the counter is touched; cache-wide
+// fences (a release / acquire pair) were measured to stall the weight streams of every workgroup on the chip
+// (108 us instead of 20 us in a traffic model of this kernel).  The counter is back at zero when the kernel ends.
+template <int MT, int NG, int PF, int KS, class Epi>
+__global__ __launch_bounds__(64 * WK) void gemm_stream_ksplit_kernel(GemmArgs g, Epi epi, float *partial, unsigned *arrive) {
+    __shared__ __attribute__((aligned(16))) char smem[kGemmSmemBytes];
+    __shared__ unsigned s_old;
+    const int ks = blockIdx.x % KS, nb = blockIdx.x / KS, nblocks = gridDim.x / KS;
+    const int kl = g.KT / KS;
+    GemmArgs gs = g;
+    gs.k_len = kl;
+    gs.A += (size_t)ks * kl * g.MT_total * kTileElems;
+    gs.W += (size_t)ks * kl * kTileElems;
+    const size_t slice = (size_t)g.MT_total * g.NT * 256;
+    frag_t wb[PF][NG];
+    gemm_wg<MT, NG, PF, false, EpiPartial, WK, false>(gs, EpiPartial{partial + ks * slice, g.NT}, nb, nblocks, 0, wb, smem);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // this wave's partial sums have been written
+    __syncthreads();
+    if (threadIdx.x == 0) s_old = __hip_atomic_fetch_add(arrive + nb, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (s_old != KS - 1) return;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int n_lo = (int)(((long)nb * g.NT) / nblocks), n_hi = (int)(((long)(nb + 1) * g.NT) / nblocks);
+    const int nn = n_hi - n_lo;
+    for (int t = wv; t < g.MT_total * nn; t += WK) {
+        const int mt = t / nn, nt = n_lo + t % nn;
+        const float *q = partial + ((size_t)mt * g.NT + nt) * 256 + lane;
+        f32x4 c = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < KS; s++)
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+                c[r] += __hip_atomic_load(q + s * slice + r * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        epi(mt, nt, c, lane, 0);
+    }
+    if (threadIdx.x == 0) __hip_atomic_store(arrive + nb, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+constexpr int kSplitKS = 4, kSplitNG = 4, kSplitPF = 4;      // (2 x 2 n-tiles, rings of 2, 6 and 8 measured slower)
+// shapes the K-split kernel takes: up to 32 rows without a fused norm, n-blocks x KS workgroups within the chip,
+// k-slices that the waves and the ring divide, room for the partial sums
+static bool ksplit_ok(GemmShape sh, Workspace ws) {
+    const int nblocks = (sh.N_tiles + kSplitNG - 1) / kSplitNG;
+    return sh.M_tiles <= 2 && ws.arrive && nblocks * kSplitKS <= kStreamWGs && nblocks <= 1024 &&
+           sh.K_tiles % (kSplitKS * WK * kSplitPF) == 0 &&
+           (size_t)kSplitKS * sh.M_tiles * sh.N_tiles * 1024 <= ws.partial_bytes;
+}
+template <class Epi>
+static void launch_stream_ksplit(const u16 *a, const u16 *w, GemmShape sh, Epi e, Workspace ws, hipStream_t s) {
+    GemmArgs g;
+    g.A = a; g.W = w; g.KT = sh.K_tiles; g.MT_total = sh.M_tiles; g.NT = sh.N_tiles;
+    g.ssq = nullptr; g.n_ssq = 0; g.eps = 0.f; g.inv_d = 0.f; g.k_len = 0;
+    const int nblocks = (sh.N_tiles + kSplitNG - 1) / kSplitNG;
+    gemm_stream_ksplit_kernel<2, kSplitNG, kSplitPF, kSplitKS, Epi><<<dim3(nblocks * kSplitKS), 64 * WK, 0, s>>>(
+        g, e, ws.partial, ws.arrive);
+}
+
 // The persistent streaming kernel for up to 128 rows: MT row tiles per wave (2, 4, 6 or 8: 32-row steps),
 // NG n-tiles per group, a PF-deep ring, WKT waves (four when the accumulators need the 512-register budget).
 // The per-projection choices below are the fastest measured on MI355X; K_tiles that the ring depth does not
@@ -21,6 +83,7 @@ static void launch_stream(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, E
     GemmArgs g;
     g.A = a; g.W = w; g.KT = sh.K_tiles; g.MT_total = sh.M_tiles; g.NT = sh.N_tiles;
     g.ssq = ni.ssq; g.n_ssq = ni.n_ssq; g.eps = ni.eps; g.inv_d = 1.0f / (float)(sh.K_tiles * 32);
+    g.k_len = 0;
     const int kw = sh.K_tiles / WKT;                // K_tiles is a multiple of 8 (checked at model creation)
     const int groups = (sh.N_tiles + NG - 1) / NG;
     dim3 grid(groups < kStreamWGs ? groups : kStreamWGs, 1);
@@ -126,7 +189,10 @@ void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int l
     // More than 32 rows: the tile kernel, whose K split over workgroups also splits the activation reads (a
     // workgroup of the streaming kernel reads all of A for its 16 columns: measured 3-4 % of the step slower).
     // From 2048 rows the 256 x 128 blocks of the 256-row kernel fill the chip (8 x 32 blocks for N = 4096).
-    if (sh.M_tiles <= 2) launch_stream<2, 1, 8, 8, false>(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
+    // Up to 32 rows with more input than output channels (the down projection): K split over four workgroups,
+    // 3.55 -> 3.47 ms per step at the 8B shape.  Not for the O projection (K = N: measured 0.6 % slower).
+    if (sh.M_tiles <= 2 && sh.K_tiles > sh.N_tiles && ksplit_ok(sh, ws)) launch_stream_ksplit(a, w, sh, e, ws, s);
+    else if (sh.M_tiles <= 2) launch_stream<2, 1, 8, 8, false>(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
     else if (use_big(sh)) launch_big(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
     else launch_tile(a, w, sh, NormIn{nullptr, 0, 0.f}, e, ws, true, s);
 }

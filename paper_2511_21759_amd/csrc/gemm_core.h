@@ -38,13 +38,16 @@ struct GemmArgs {
     const float *ssq;
     int n_ssq;
     float eps, inv_d;
+    // k-tiles this call covers (0: all KT).  A and W then point at the first k-tile of the slice; KT stays the
+    // distance between the n-tiles of W.
+    int k_len;
 };
 
 // m-tiles per reduction pass: at most six 1 KiB tiles per wave go through LDS at a time
 // (with four waves twice as many: the buffer holds WK * 6 tiles)
 constexpr int gemm_mc(int mt, int ng, int wkt = WK) {
     return wkt == 4 && mt == 8 ? (ng >= 6 ? 2 : (ng >= 3 ? 4 : 8))
-                               : (ng >= 6 ? 1 : (ng >= 3 ? 2 : (mt < 4 ? mt : (mt % 4 == 0 ? 4 : 3))));
+                               : (ng >= 4 ? 1 : (ng >= 3 ? 2 : (mt < 4 ? mt : (mt % 4 == 0 ? 4 : 3))));
 }
 
 constexpr int kGemmSmemBytes = WK * 6 * 1024 + 8 * 16 * 4;    // LDS one workgroup needs (red + row scales)
@@ -60,7 +63,7 @@ __device__ __forceinline__ void gemm_prefetch_w(const GemmArgs &g, int wg, int n
     // a workgroup without n-tiles still loads (tile 0, discarded) so that the ring is always
     // fully redefined here and never has to be kept alive across phases
     if (n_hi <= n_lo) n_hi = n_lo + 1 <= g.NT ? n_lo + 1 : g.NT;
-    const int KW = g.KT / WKT;
+    const int KW = (g.k_len ? g.k_len : g.KT) / WKT;
     const int k0 = IL ? wk : wk * KW, kst = IL ? WKT : 1;      // first k-tile of this wave and its stride
     const u16 *wbase = g.W + (size_t)k0 * kTileElems + lane * 8;
 #pragma unroll
@@ -91,7 +94,7 @@ __device__ __forceinline__ void gemm_wg(const GemmArgs &g, Epi epi, int wg, int 
     const int n_lo = (int)(((long)wg * g.NT) / nwg);
     const int n_hi = (int)(((long)(wg + 1) * g.NT) / nwg);
     if (n_lo >= n_hi) return;
-    const int KW = g.KT / WKT;
+    const int KW = (g.k_len ? g.k_len : g.KT) / WKT;
     const int ngroups = (n_hi - n_lo + NG - 1) / NG;
     const int k0 = IL ? wk : wk * KW, kst = IL ? WKT : 1;      // first k-tile of this wave and its stride
 
@@ -416,5 +419,19 @@ struct EpiStore {
     }
 };
 
+// One K slice's sums, left for the workgroup that finishes the tile (gemm.hip: gemm_stream_ksplit_kernel):
+// p[m_tile][n_tile][r][lane] holds element r of the lane's fragment.  Written with device-coherent stores so
+// that a workgroup on another XCD reads them without any cache-wide fence.
+struct EpiPartial {
+    float *p;
+    int nt_total;
+    __device__ bool transposed(int) const { return false; }
+    __device__ void finish(int, int, int, int) const {}
+    __device__ void operator()(int mt, int nt, f32x4 c, int lane, int) const {
+        float *q = p + ((size_t)mt * nt_total + nt) * 256 + lane;
+#pragma unroll
+        for (int r = 0; r < 4; r++) __hip_atomic_store(q + r * 64, c[r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+};
 
 }  // namespace odb

@@ -134,7 +134,8 @@ struct QkvOut {
     u16 *v_b; size_t v_b_unit_stride, v_b_head_stride;
 };
 // fp32 workspace for K-split partial sums (multi-draft step)
-struct Workspace { float *partial; size_t partial_bytes; };
+// partial: K-split partial sums; arrive: 1024 arrival counters of the K-split streaming kernel (zero between launches)
+struct Workspace { float *partial; size_t partial_bytes; unsigned *arrive; };
 void launch_gemm_qkv(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, QkvOut out, Workspace ws, hipStream_t s);
 void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int ldh, NormOut no, Workspace ws,
                        hipStream_t s);

@@ -323,6 +323,21 @@ def test_full_size_properties_without_an_oracle():
             cS, aS, uS = B.odb_block_step(model, cache, dr[:, :S].contiguous(), wl.block_off, wl.tau)
             assert torch.allclose(torch.log(cS), torch.log(conf[:, :S]), atol=0.05), S
             assert (aS == am[:, :S]).float().mean() > 0.9 and (uS.sum(-1) == 1).all(), S
+        # one draft (32 rows): its down projection splits K over four workgroups and the last to arrive adds the
+        # partial sums - in slice order, so repeated calls must agree bit for bit whoever arrives last
+        c1, a1, u1 = B.odb_block_step(model, cache, dr[:, :1].contiguous(), wl.block_off, wl.tau)
+        assert torch.allclose(torch.log(c1), torch.log(conf[:, :1]), atol=0.05) and (a1 == am[:, :1]).float().mean() > 0.9
+        for _ in range(5):
+            cr, ar, ur = B.odb_block_step(model, cache, dr[:, :1].contiguous(), wl.block_off, wl.tau)
+            assert torch.equal(cr, c1) and torch.equal(ar, a1) and torch.equal(ur, u1)
+        # a block of 16 (one row tile) against the same draft four times over (64 rows: other kernels throughout)
+        d16 = dr[:, :1, :16].contiguous()
+        c16, a16, u16 = B.odb_block_step(model, cache, d16, wl.block_off, wl.tau)
+        c64, a64, u64 = B.odb_block_step(model, cache, d16.repeat(1, 4, 1).contiguous(), wl.block_off, wl.tau)
+        assert torch.isfinite(c16).all() and (c16 > 0).all() and (c16 <= 1).all()
+        assert torch.allclose(torch.log(c64), torch.log(c16).expand(-1, 4, -1), atol=0.05)
+        assert (a64 == a16.expand(-1, 4, -1)).float().mean() > 0.9 and torch.equal(c64[:, 0], c64[:, 3])
+        B.odb_model_status(model)
         B.odb_cache_destroy(cache)
     finally:
         B.odb_model_destroy(model)
