@@ -56,11 +56,11 @@ __global__ __launch_bounds__(64 * WK) void gemm_stream_ksplit_kernel(GemmArgs g,
 }
 
 constexpr int kSplitKS = 4, kSplitNG = 4, kSplitPF = 4;      // (2 x 2 n-tiles, rings of 2, 6 and 8 measured slower)
-// shapes the K-split kernel takes: up to 32 rows without a fused norm, n-blocks x KS workgroups within the chip,
+// shapes the K-split kernel takes: up to 96 rows without a fused norm, n-blocks x KS workgroups within the chip,
 // k-slices that the waves and the ring divide, room for the partial sums
 static bool ksplit_ok(GemmShape sh, Workspace ws) {
     const int nblocks = (sh.N_tiles + kSplitNG - 1) / kSplitNG;
-    return sh.M_tiles <= 2 && ws.arrive && nblocks * kSplitKS <= kStreamWGs && nblocks <= 1024 &&
+    return sh.M_tiles <= 6 && ws.arrive && nblocks * kSplitKS <= kStreamWGs && nblocks <= 1024 &&
            sh.K_tiles % (kSplitKS * WK * kSplitPF) == 0 &&
            (size_t)kSplitKS * sh.M_tiles * sh.N_tiles * 1024 <= ws.partial_bytes;
 }
@@ -70,8 +70,10 @@ static void launch_stream_ksplit(const u16 *a, const u16 *w, GemmShape sh, Epi e
     g.A = a; g.W = w; g.KT = sh.K_tiles; g.MT_total = sh.M_tiles; g.NT = sh.N_tiles;
     g.ssq = nullptr; g.n_ssq = 0; g.eps = 0.f; g.inv_d = 0.f; g.k_len = 0;
     const int nblocks = (sh.N_tiles + kSplitNG - 1) / kSplitNG;
-    gemm_stream_ksplit_kernel<2, kSplitNG, kSplitPF, kSplitKS, Epi><<<dim3(nblocks * kSplitKS), 64 * WK, 0, s>>>(
-        g, e, ws.partial, ws.arrive);
+    const dim3 grid(nblocks * kSplitKS);
+    if (sh.M_tiles <= 2) gemm_stream_ksplit_kernel<2, kSplitNG, kSplitPF, kSplitKS, Epi><<<grid, 64 * WK, 0, s>>>(g, e, ws.partial, ws.arrive);
+    else if (sh.M_tiles <= 4) gemm_stream_ksplit_kernel<4, kSplitNG, 4, kSplitKS, Epi><<<grid, 64 * WK, 0, s>>>(g, e, ws.partial, ws.arrive);
+    else gemm_stream_ksplit_kernel<6, kSplitNG, 2, kSplitKS, Epi><<<grid, 64 * WK, 0, s>>>(g, e, ws.partial, ws.arrive);
 }
 
 // The persistent streaming kernel for up to 128 rows: MT row tiles per wave (2, 4, 6 or 8: 32-row steps),
@@ -186,12 +188,17 @@ void launch_gemm_qkv(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, QkvOu
 void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int ldh, NormOut no, Workspace ws,
                        hipStream_t s) {
     EpiResid e{h, ldh, no, sh.M_tiles};
-    // More than 32 rows: the tile kernel, whose K split over workgroups also splits the activation reads (a
-    // workgroup of the streaming kernel reads all of A for its 16 columns: measured 3-4 % of the step slower).
-    // From 2048 rows the 256 x 128 blocks of the 256-row kernel fill the chip (8 x 32 blocks for N = 4096).
-    // Up to 32 rows with more input than output channels (the down projection): K split over four workgroups,
-    // 3.55 -> 3.47 ms per step at the 8B shape.  Not for the O projection (K = N: measured 0.6 % slower).
-    if (sh.M_tiles <= 2 && sh.K_tiles > sh.N_tiles && ksplit_ok(sh, ws)) launch_stream_ksplit(a, w, sh, e, ws, s);
+    // K split over four workgroups with the in-kernel reduction (gemm_stream_ksplit_kernel) where it measured
+    // faster at the 8B shape: the down projection (more input than output channels) up to 96 rows and the O
+    // projection from 33 to 96 rows.  Per step: 3.55 -> 3.47 ms at 32 rows, 4.25 -> 4.03 at 64, 4.77 -> 4.71 at 96.
+    // (At 32 rows the O projection is 0.6 % slower that way than with the plain streaming kernel; at 96 rows either
+    // projection alone measured 1 % slower and only both together faster; at 128 rows, where the ring is down to
+    // two stages, every combination loses 1-1.5 % to the tile kernel.)
+    // Otherwise, more than 32 rows: the tile kernel, whose K split over workgroups also splits the activation
+    // reads, with a separate pass that adds the partial sums.  From 2048 rows the 256 x 128 blocks of the 256-row
+    // kernel fill the chip (8 x 32 blocks for N = 4096).
+    const bool long_k = sh.K_tiles > sh.N_tiles;
+    if (sh.M_tiles <= 6 && (long_k || sh.M_tiles > 2) && ksplit_ok(sh, ws)) launch_stream_ksplit(a, w, sh, e, ws, s);
     else if (sh.M_tiles <= 2) launch_stream<2, 1, 8, 8, false>(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
     else if (use_big(sh)) launch_big(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
     else launch_tile(a, w, sh, NormIn{nullptr, 0, 0.f}, e, ws, true, s);

@@ -323,6 +323,8 @@ def test_full_size_properties_without_an_oracle():
             cS, aS, uS = B.odb_block_step(model, cache, dr[:, :S].contiguous(), wl.block_off, wl.tau)
             assert torch.allclose(torch.log(cS), torch.log(conf[:, :S]), atol=0.05), S
             assert (aS == am[:, :S]).float().mean() > 0.9 and (uS.sum(-1) == 1).all(), S
+            cR, aR, uR = B.odb_block_step(model, cache, dr[:, :S].contiguous(), wl.block_off, wl.tau)
+            assert torch.equal(cR, cS) and torch.equal(aR, aS) and torch.equal(uR, uS), S      # K-split projections: fixed order
         # one draft (32 rows): its down projection splits K over four workgroups and the last to arrive adds the
         # partial sums - in slice order, so repeated calls must agree bit for bit whoever arrives last
         c1, a1, u1 = B.odb_block_step(model, cache, dr[:, :1].contiguous(), wl.block_off, wl.tau)
