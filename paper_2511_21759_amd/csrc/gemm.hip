@@ -193,7 +193,8 @@ void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int l
     // projection from 33 to 96 rows.  Per step: 3.55 -> 3.47 ms at 32 rows, 4.25 -> 4.03 at 64, 4.77 -> 4.71 at 96.
     // (At 32 rows the O projection is 0.6 % slower that way than with the plain streaming kernel; at 96 rows either
     // projection alone measured 1 % slower and only both together faster; at 128 rows, where the ring is down to
-    // two stages, every combination loses 1-1.5 % to the tile kernel.)
+    // two stages, every combination loses 1-1.5 % to the tile kernel, and a four-wave variant with a ring of
+    // four loses 4 %.)
     // Otherwise, more than 32 rows: the tile kernel, whose K split over workgroups also splits the activation
     // reads, with a separate pass that adds the partial sums.  From 2048 rows the 256 x 128 blocks of the 256-row
     // kernel fill the chip (8 x 32 blocks for N = 4096).
