@@ -56,6 +56,13 @@ __device__ inline frag_t ld_frag(const u16 *p) {
     return *reinterpret_cast<const frag_t *>(p);
 }
 
+// The same load marked non-temporal, for data that is read once per kernel (weight tiles): the plain streaming
+// read of 8 GiB measures 5.9-6.25 TB/s on MI355X with ordinary loads and 6.6-7.1 TB/s with these.
+__device__ inline frag_t ld_frag_stream(const u16 *p) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    return __builtin_bit_cast(frag_t, __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p)));
+}
+
 __device__ inline f32x4 mfma16(const frag_t &x, const frag_t &y, f32x4 acc) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(
         __builtin_bit_cast(f16x8, x), __builtin_bit_cast(f16x8, y), acc, 0, 0, 0);

@@ -117,7 +117,9 @@ static void launch_tile(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi
     // (8 waves x 1 n-tile, ring of 8) for the multi-draft step, (8 x 2, ring of 4) for compute-bound shapes:
     // the best of the shapes tried on MI355X (4-wave workgroups, 4 n-tiles per wave and 2 or 4 k-tiles
     // per barrier were all slower - occupancy beats wider tiles here)
-    if (c.ngw == 1) gemm_tile_kernel<8, 1, 1, 8, Epi><<<grid, 512, 0, s>>>(g, e);
+    // (a single block of rows: every weight tile is read once, non-temporally)
+    if (c.ngw == 1 && m_blocks == 1) gemm_tile_kernel<8, 1, 1, 8, Epi, true><<<grid, 512, 0, s>>>(g, e);
+    else if (c.ngw == 1) gemm_tile_kernel<8, 1, 1, 8, Epi><<<grid, 512, 0, s>>>(g, e);
     else gemm_tile_kernel<8, 2, 1, 4, Epi><<<grid, 512, 0, s>>>(g, e);
     if (ks > 1) {
         if constexpr (!is_row_stats<Epi>::value)

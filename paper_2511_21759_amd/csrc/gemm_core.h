@@ -72,7 +72,7 @@ __device__ __forceinline__ void gemm_prefetch_w(const GemmArgs &g, int wg, int n
         for (int n = 0; n < NG; n++) {
             int nt = n_lo + n;
             nt = nt < n_hi ? nt : n_hi - 1;
-            wb[s][n] = ld_frag(wbase + ((size_t)nt * g.KT + s * kst) * kTileElems);
+            wb[s][n] = ld_frag_stream(wbase + ((size_t)nt * g.KT + s * kst) * kTileElems);
         }
 }
 
@@ -113,7 +113,7 @@ __device__ __forceinline__ void gemm_wg(const GemmArgs &g, Epi epi, int wg, int 
         for (int n = 0; n < NG; n++) {
             int nt = n_lo + grp * NG + n;
             nt = nt < n_hi ? nt : n_hi - 1;
-            wb[slot][n] = ld_frag(wbase + ((size_t)nt * g.KT + kk * kst) * kTileElems);
+            wb[slot][n] = ld_frag_stream(wbase + ((size_t)nt * g.KT + kk * kst) * kTileElems);
         }
 #pragma unroll
         for (int m = 0; m < MT; m++) ab[slot][m] = ld_frag(ap[m] + kk * a_step);

@@ -45,7 +45,8 @@ __device__ __forceinline__ void merge_stat(float &m, float &s, int &a, float om,
 // pipeline is a chunk of KC k-tiles (one barrier per chunk); PF chunks are in flight.
 constexpr int tile_smem_bytes(int kc) { return 2 * kc * 8 * 1024 + 8 * 1024 + 128 * 4; }
 
-template <int NW, int NGW, int KC, int PF, class Epi>
+// SW: the weight tiles are read by one workgroup only (a single block of rows), so they are loaded non-temporally.
+template <int NW, int NGW, int KC, int PF, class Epi, bool SW = false>
 __global__ __launch_bounds__(64 * NW) void gemm_tile_kernel(TileArgs g, Epi epi) {
     constexpr int AW = 8 / NW;                 // A tiles (per k-tile) of the slab each wave fetches
     static_assert(NW == 4 || NW == 8, "waves per workgroup");
@@ -125,7 +126,8 @@ __global__ __launch_bounds__(64 * NW) void gemm_tile_kernel(TileArgs g, Epi epi)
 #pragma unroll
             for (int i = 0; i < AW; i++) ar[slot][kk][i] = ld_frag(ap[i] + k * a_step);
 #pragma unroll
-            for (int j = 0; j < NGW; j++) wr[slot][kk][j] = ld_frag(wp[j] + (size_t)k * kTileElems);
+            for (int j = 0; j < NGW; j++)
+                wr[slot][kk][j] = SW ? ld_frag_stream(wp[j] + (size_t)k * kTileElems) : ld_frag(wp[j] + (size_t)k * kTileElems);
         }
     };
 #pragma unroll
