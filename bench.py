@@ -94,8 +94,10 @@ def bench_generate(args, model, shape, B, W, np, torch):
     """Whole generations (ODB-dLLM Sec. 2.1 with Sec. 4.2 on): 256 prompt tokens, 256 response positions in
     blocks of 32, at the 8B shape.  Random weights never reach tau = 0.9, so the final norm gain is raised to
     8 (as in the parity tests' peaked variants): confidences then straddle the threshold.  Four decoders are
-    timed on the same prompt: threshold only, accept-jump, accept-jump with the decoded-share stage from 16
-    decoded positions on, and the same with eight blocks in that stage (Sec. 4.2.2's four extra candidates).
+    timed on the same prompt: threshold only, accept-jump, accept-jump with the decoded-share stage from 20
+    decoded positions on, and the same with eight blocks in that stage (Sec. 4.2.2's four extra candidates; from
+    20 decoded positions on an eight-block step has at most 32 + 7 * 12 = 116 rows and stays within the kernels
+    for up to 128 rows).
     No [EOS] is defined for synthetic weights, so length prediction stays off."""
     P, R, b = 256, 256, 32
     B.odb_model_set_tensor(model, B.T_GF, 0, np.full(shape["d_model"], 0x4100, np.uint16))     # bf16(8.0)
@@ -103,7 +105,7 @@ def bench_generate(args, model, shape, B, W, np, torch):
     prompt = torch.from_numpy(rng.integers(0, shape["vocab"] - 1, P).astype(np.int32)).cuda()
     cache = B.odb_cache_create(model, 1, P + R)
     modes = {"threshold": dict(n_drafts=1), "accept_jump": dict(n_drafts=4),
-             "jump_share": dict(n_drafts=4, share_from=16), "jump_share8": dict(n_drafts=8, share_from=16)}
+             "jump_share": dict(n_drafts=4, share_from=20), "jump_share8": dict(n_drafts=8, share_from=20)}
     res = {}
     for mode, kw in modes.items():
         runs = []
