@@ -9,8 +9,9 @@
  *     block, followed by the confidence-threshold acceptance
  *     (Sec. 3 Observation 3; Sec. 4.2 and Fig. 8 for the drafts);
  * and, built on those two, the paper's controllers: odb_predict_length (Sec. 4.1),
- * odb_accept_jump (Sec. 4.2.1), odb_block_step_shared (Sec. 4.2.2) and the whole
- * block-wise loop, odb_generate (Sec. 2.1).
+ * odb_accept_jump (Sec. 4.2.1) and its form for eight blocks, odb_speculative_jump,
+ * odb_block_step_shared (Sec. 4.2.2) and the whole block-wise loop, odb_generate
+ * (Sec. 2.1).
  *
  * Conventions
  *   - "dev" pointers are device (HBM) addresses on the current HIP device,
