@@ -402,6 +402,39 @@ def test_refresh_then_length_prediction_matches_the_oracle_chain(tiny):
         tokens = tokens[:, :got].copy()
 
 
+# Shapes between the tiny and the 8B model that reach the kernels the tiny model is too narrow for: the K split
+# with the in-kernel reduction takes projections whose K is a multiple of 4096.  "long down": F = 4096 into
+# d = 1024 (the down projection's form: more input than output channels, split at every row count up to 96);
+# "square O": d = 4096 (the O projection's form, split from 33 to 96 rows).
+MID_SHAPES = {
+    "long down": dict(n_layers=2, d_model=1024, n_heads=8, head_dim=128, d_ff=4096, vocab=2048, rope_base=10000.0,
+                      rms_eps=1e-5, mask_id=2047),
+    "square O": dict(n_layers=2, d_model=4096, n_heads=32, head_dim=128, d_ff=1024, vocab=2048, rope_base=10000.0,
+                     rms_eps=1e-5, mask_id=2047),
+}
+
+
+@pytest.mark.parametrize("name", sorted(MID_SHAPES))
+def test_k_split_projections_against_the_oracle(name):
+    """Element-wise parity of whole steps whose O / down projections run through the K-split streaming kernel, at
+    16, 32, 64 and 96 rows (one to six row tiles), and bit-identical results when a call is repeated (the partial
+    sums are added in slice order whichever workgroup arrives last)."""
+    p = Pair(MID_SHAPES[name], gf=8.0)
+    try:
+        wl = W.decode_workload(p.shape, 40, 56, 32, 3, W.WEIGHT_SEED + 33)
+        cache, oc = run_prefill_case(p, wl.tokens, wl.resp_off, name + " prefill")
+        for S, b in ((1, 16), (1, 32), (2, 32), (3, 32)):
+            drafts = np.ascontiguousarray(wl.drafts[:, :S, :b])
+            run_step_case(p, cache, oc, drafts, wl.block_off, 0.9, "%s step %d x %d" % (name, S, b))
+            d = cuda_i32(drafts)
+            first = B.odb_block_step(p.model, cache, d, wl.block_off, 0.9)
+            for _ in range(3):
+                again = B.odb_block_step(p.model, cache, d, wl.block_off, 0.9)
+                assert all(torch.equal(x, y) for x, y in zip(first, again)), (name, S, b)
+    finally:
+        p.close()
+
+
 # ------------------------------------------------------------------ accept-jump controller (Sec. 4.2.1)
 
 def _oracle_accept_jump_batch(drafts, conf, am, um, cp, ct, mask_id):
