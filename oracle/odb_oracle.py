@@ -627,6 +627,10 @@ class GenParams:
     truncate_thr: float = 0.9           # Sec. 4.1
     share_from: Optional[int] = None    # decoded positions of the block from which steps run in the
                                         # decoded-share stage (Sec. 4.2.2); None: never (n_drafts = 8 needs it)
+    row_budget: Optional[int] = None    # n_drafts = 8: a decoded-share step forwards eight blocks only if its
+                                        # b + 7 * masked rows fit the budget, else the four accept-jump blocks
+                                        # (Sec. 4.2: the step has to stay in the memory-bound region; Sec. 4.2.2:
+                                        # the shrinking blocks make room for the extra candidates); None: always eight
 
 
 def truncate_cache(cache: Cache, new_len: int) -> Cache:
@@ -652,7 +656,8 @@ def generate(cfg: Config, w: Weights, prompt: np.ndarray, resp_len: int, p: GenP
         left masked).  Once share_from positions of the block are decoded the step runs in the
         decoded-share stage, with the same four drafts; with n_drafts = 8 that stage forwards eight
         blocks (the four most confident positions left masked are the candidates, SPEC_SETS) and the
-        jump rule runs over all of them (speculative_jump), the steps before it stay four-draft ones.
+        jump rule runs over all of them (speculative_jump), the steps before it stay four-draft ones -
+        and so do the steps of that stage whose eight blocks would exceed row_budget rows.
     The block's tokens are written back and the next block cycle begins; generation ends when the
     block start reaches the (possibly shortened) end of the sequence.
 
@@ -705,9 +710,12 @@ def generate(cfg: Config, w: Weights, prompt: np.ndarray, resp_len: int, p: GenP
             else:
                 n_masked = int((block == mask_id).sum())
                 if p.share_from is not None and bb - n_masked >= p.share_from:
-                    drafts = speculative_drafts(block, cp, ct, p.n_drafts)
+                    S = p.n_drafts
+                    if S == 8 and p.row_budget is not None and bb + 7 * n_masked > p.row_budget:
+                        S = 4
+                    drafts = speculative_drafts(block, cp, ct, S)
                     conf_s, am_s, um_s = block_step_shared(cfg, w, cache, drafts, off, p.tau)
-                    kind, rows = "shared", bb + (p.n_drafts - 1) * n_masked
+                    kind, rows = "shared", bb + (S - 1) * n_masked
                     stats["n_step_shared"] += 1
                 else:
                     drafts = speculative_drafts(block, cp, ct, 4)

@@ -1022,6 +1022,28 @@ def test_generate_eight_blocks_in_the_decoded_share_stage():
                 redone = True
         assert rows == stats["step_rows"] and redone
     assert {c for k, c in seen if k == "shared"} - {0, 1, 2, 3}, "none of the four extra blocks was ever adopted"
+    # the row budget: eight blocks only where b + 7 * masked rows fit; a budget nothing exceeds changes nothing,
+    # one that nothing fits gives the four-block run with the same switch point
+    w, prompt = _gen_setup(seed=23, gain=8.0)
+    p8 = o.GenParams(block_len=8, n_drafts=8, tau=0.85, share_from=2)
+    ref8 = o.generate(MICRO, w, prompt, 16, p8)
+    big = o.generate(MICRO, w, prompt, 16, dataclasses_replace(p8, row_budget=8 + 7 * 8))
+    assert np.array_equal(ref8[0], big[0]) and ref8[1] == big[1]
+    none = o.generate(MICRO, w, prompt, 16, dataclasses_replace(p8, row_budget=0))
+    ref4 = o.generate(MICRO, w, prompt, 16, dataclasses_replace(p8, n_drafts=4))
+    assert np.array_equal(none[0], ref4[0]) and none[1] == ref4[1]
+    mid = o.generate(MICRO, w, prompt, 16, dataclasses_replace(p8, row_budget=8 + 7 * 3))
+    rows, n8 = 0, 0
+    for prev_ev, ev in zip(mid[2], mid[2][1:]):
+        if ev["kind"] == "refresh":
+            continue
+        blk = prev_ev["tokens"][ev["block_off"]:ev["block_off"] + ev["block_len"]]
+        nm = int((blk == MICRO.mask_id).sum())
+        eight = ev["kind"] == "shared" and nm <= 3
+        n8 += eight
+        rows += (ev["block_len"] + (7 if eight else 3) * nm) if ev["kind"] == "shared" else 4 * ev["block_len"]
+        assert ev["chosen"] < (8 if eight else 4)
+    assert rows == mid[1]["step_rows"] and n8 > 0
 
 
 def test_generate_stops_when_the_greedy_token_is_mask():
