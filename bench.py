@@ -105,7 +105,7 @@ def bench_generate(args, model, shape, B, W, np, torch):
     prompt = torch.from_numpy(rng.integers(0, shape["vocab"] - 1, P).astype(np.int32)).cuda()
     cache = B.odb_cache_create(model, 1, P + R)
     modes = {"threshold": dict(n_drafts=1), "accept_jump": dict(n_drafts=4),
-             "jump_share": dict(n_drafts=4, share_from=20), "jump_share8": dict(n_drafts=8, share_from=20)}
+             "jump_share": dict(n_drafts=4, share_from=20), "jump_share8": dict(n_drafts=8, share_from=20, row_budget=128)}
     res = {}
     for mode, kw in modes.items():
         runs = []

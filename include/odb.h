@@ -302,7 +302,9 @@ int odb_speculative_jump(const odb_model *m, const int32_t *drafts_dev, const fl
  *      on the same four drafts.  n_drafts = 8 (needs share_from >= 0): as n_drafts = 4 until
  *      share_from positions are decoded, then odb_block_step_shared on eight blocks - the four
  *      most confident positions left MASKed are the candidates (Sec. 4.2.2: the third, the top
- *      three, the fourth and the top four join B, D and B + D) - and odb_speculative_jump.
+ *      three, the fourth and the top four join B, D and B + D) - and odb_speculative_jump;
+ *      with row_budget > 0 a step of that stage whose eight blocks would come to more rows
+ *      runs on the four accept-jump blocks instead.
  *      A step that leaves the block's MASK count unchanged (an untrained model may attempt
  *      the MASK token itself) ends the call with ODB_E_HIP rather than repeating for ever.
  * Generation ends when the next block would start at or behind the end of the sequence.
@@ -336,6 +338,10 @@ typedef struct {
     float truncate_thr;   /* Sec. 4.1 */
     int share_from;       /* decoded positions of the block from which steps run in the
                              decoded-share stage (Sec. 4.2.2); < 0: never */
+    int row_budget;       /* n_drafts = 8: a decoded-share step forwards eight blocks only if its
+                             block_len + 7 * masked rows fit this budget, else the four accept-jump
+                             blocks (Sec. 4.2: the step has to stay memory-bound; Sec. 4.2.2: the
+                             shrinking blocks make room for the extra candidates); <= 0: always eight */
 } odb_generate_params;
 typedef struct {
     int kind;             /* ODB_EV_* */

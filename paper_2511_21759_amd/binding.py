@@ -46,7 +46,8 @@ class odb_config(ctypes.Structure):
 
 class odb_generate_params(ctypes.Structure):
     _fields_ = [("block_len", ctypes.c_int), ("n_drafts", ctypes.c_int), ("tau", ctypes.c_float),
-                ("eos_id", ctypes.c_int), ("truncate_thr", ctypes.c_float), ("share_from", ctypes.c_int)]
+                ("eos_id", ctypes.c_int), ("truncate_thr", ctypes.c_float), ("share_from", ctypes.c_int),
+                ("row_budget", ctypes.c_int)]
 
 
 class odb_generate_event(ctypes.Structure):
@@ -237,8 +238,8 @@ def odb_cache_truncate(cache: int, new_len: int) -> None:
 
 
 def odb_generate(model: int, cache: int, tokens, prompt_len: int, block_len: int, n_drafts: int = 1, tau: float = 0.9,
-                 eos_id: int = -1, truncate_thr: float = 0.9, share_from: int = -1, max_events: int = 0,
-                 event_tokens: bool = False):
+                 eos_id: int = -1, truncate_thr: float = 0.9, share_from: int = -1, row_budget: int = 0,
+                 max_events: int = 0, event_tokens: bool = False):
     """tokens: int32 CUDA tensor [prompt_len + resp_len] whose first prompt_len entries hold the prompt; decoded
     in place.  -> (stats dict, events list of dicts, event_tokens int32 CUDA tensor [n, L0] or None).
     An event's cand_pos / cand_tok hold the candidates in use: four with n_drafts = 8, else two."""
@@ -246,7 +247,7 @@ def odb_generate(model: int, cache: int, tokens, prompt_len: int, block_len: int
     if tokens.dtype != torch.int32 or tokens.dim() != 1 or not tokens.is_contiguous() or not tokens.is_cuda:
         raise TypeError("tokens must be a contiguous 1-D int32 CUDA tensor")
     L0 = tokens.shape[0]
-    gp = odb_generate_params(block_len, n_drafts, tau, eos_id, truncate_thr, share_from)
+    gp = odb_generate_params(block_len, n_drafts, tau, eos_id, truncate_thr, share_from, row_budget)
     st = odb_generate_stats()
     ev = (odb_generate_event * max_events)() if max_events > 0 else None
     snap = torch.empty((max_events, L0), dtype=torch.int32, device=tokens.device) if event_tokens and max_events > 0 else None

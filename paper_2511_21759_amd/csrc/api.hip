@@ -937,7 +937,7 @@ int odb_generate(odb_model *mh, odb_cache *ch, int32_t *tokens, int prompt_len, 
                 int S = 4;
                 if (share && bb - n_masked >= gp->share_from) {
                     kind = ODB_EV_STEP_SHARED;
-                    S = nd;
+                    S = nd == 8 && gp->row_budget > 0 && bb + 7 * n_masked > gp->row_budget ? 4 : nd;
                     rc = step_shared_impl(mh, ch, drafts[cur], off, bb, S, n_masked, gp->tau, conf, am, um, nullptr, nullptr, stream);
                     st->step_rows += bb + (S - 1) * n_masked;
                     st->n_step_shared++;

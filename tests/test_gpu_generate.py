@@ -106,7 +106,10 @@ def replay(p, prompt, R, gp, events, snaps, err):
             share = gp["n_drafts"] >= 4 and gp.get("share_from", -1) >= 0 and int((~m).sum()) >= gp["share_from"]
             assert e["kind"] == ("shared" if share else "step") and e["L"] == L and bb == min(b, L - off), tag
             # (eight blocks only in the decoded-share stage; the steps before it forward the first four)
-            drafts = blk[None] if gp["n_drafts"] == 1 else o.speculative_drafts(blk, cp, ct, gp["n_drafts"] if share else 4)
+            S_step = gp["n_drafts"] if share else 4
+            if share and S_step == 8 and gp.get("row_budget", 0) > 0 and bb + 7 * int(m.sum()) > gp["row_budget"]:
+                S_step = 4                                  # eight blocks would not fit the row budget
+            drafts = blk[None] if gp["n_drafts"] == 1 else o.speculative_drafts(blk, cp, ct, S_step)
             if share:
                 conf, am, um, zs = o.block_step_shared(cfg, w, cache, drafts, off, tau, return_logits=True)
                 rows = [np.arange(bb)] + [np.flatnonzero(m)] * (len(drafts) - 1)
@@ -193,7 +196,8 @@ def run_case(p, seed, P, R, gp, pick_eos=None):
     og = o.GenParams(block_len=gp["block_len"], n_drafts=gp["n_drafts"], tau=gp["tau"],
                      eos_id=gp["eos_id"] if gp.get("eos_id", -1) >= 0 else None,
                      truncate_thr=gp.get("truncate_thr", 0.9),
-                     share_from=gp["share_from"] if gp.get("share_from", -1) >= 0 else None)
+                     share_from=gp["share_from"] if gp.get("share_from", -1) >= 0 else None,
+                     row_budget=gp["row_budget"] if gp.get("row_budget", 0) > 0 else None)
     if n_clear == len(events):
         t_o, s_o, e_o = o.generate(cfg, p.w, prompt, R, og)
         assert np.array_equal(final, t_o), "every forward was clear of the error band, yet the runs differ"
@@ -221,6 +225,7 @@ CASES = [
     (8, 48, 96, dict(block_len=32, n_drafts=8, tau=0.9, share_from=8), None),
     (9, 40, 80, dict(block_len=32, n_drafts=8, tau=0.85, share_from=0), (30, 70)),
     (10, 24, 128, dict(block_len=64, n_drafts=8, tau=0.9, share_from=24), None),
+    (11, 40, 96, dict(block_len=32, n_drafts=8, tau=0.9, share_from=4, row_budget=128), None),       # eight blocks once they fit 128 rows
 ]
 
 
