@@ -45,8 +45,10 @@ def check_rows(logits, conf, am, g, prefix, tag, same_gemm=True):
     gap = top[..., -1] - top[..., -2]
     strict = gap > band
     assert np.array_equal(am[strict], am_o[strict]), "%s: argmax outside the error band" % tag
-    second = g[prefix + "_top_ids"][..., -2]
-    assert np.all((am[~strict] == am_o[~strict]) | (am[~strict] == second[~strict])), "%s: argmax not in top-2" % tag
+    # inside the band: any of the stored eight best tokens whose oracle logit is within the band of the largest
+    ids = g[prefix + "_top_ids"]
+    ok = ((ids == am[..., None]) & (top >= top[..., -1:] - band)).any(-1)
+    assert np.all(ok[~strict]), "%s: argmax outside the error band" % tag
     if same_gemm:
         # the fused statistics agree with the unfused logits when the same kernels produced both
         assert np.array_equal(am, logits.argmax(-1)), "%s: fused argmax vs stored logits" % tag
@@ -222,7 +224,8 @@ def test_decoded_share_step_against_stored_oracle():
                 assert am[s_, i_] == g["step_argmax"][s_, i_], (s_, i_)
                 n_strict += 1
             else:
-                assert am[s_, i_] in (g["step_argmax"][s_, i_], g["step_top_ids"][s_, i_][-2]), (s_, i_)
+                ids = g["step_top_ids"][s_, i_]
+                assert ((ids == am[s_, i_]) & (top >= top[-1] - band)).any(), (s_, i_)
         # positions that are not computed read as the call documents; random weights: only forced picks
         nc = ~computed
         assert np.all(conf[nc] == 0) and np.array_equal(am[nc], wl.drafts[0][nc]) and not um[nc].any()

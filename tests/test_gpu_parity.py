@@ -76,17 +76,19 @@ def check_decisions(conf_g, am_g, conf_o, am_o, z_o, err, tag):
     conf = exp(z_max - logsumexp z) and both terms are 1-Lipschitz in the max norm,
     so |log conf_gpu - log conf_oracle| <= 2 err must hold exactly.
     argmax must be bit-exact on every row whose top-2 logit gap exceeds 2 err (no
-    admissible perturbation can flip it); rows with a top-2 probability margin above
-    1e-2 whose gap is inside that band may only flip to the oracle's runner-up.
+    admissible perturbation can flip it); on the other rows it must be a token whose
+    oracle logit lies within 2 err of the row's largest.
     Returns the number of rows with margin > 1e-2 that were checked bit-exactly."""
     assert np.all(np.abs(np.log(conf_g) - np.log(conf_o)) <= 2 * err + 1e-5), "%s: confidence" % tag
     part = np.partition(z_o, -2, axis=-1)
     gap = part[..., -1] - part[..., -2]
     strict = gap > 2 * err
     assert np.array_equal(am_g[strict], am_o[strict]), "%s: argmax differs outside the error band" % tag
-    second = np.argsort(z_o, axis=-1)[..., -2]
+    # inside the band the library may pick any token whose oracle logit is within 2 err of the largest (with
+    # three logits that close it need not be one of the oracle's two best)
     loose = ~strict
-    assert np.all((am_g[loose] == am_o[loose]) | (am_g[loose] == second[loose])), "%s: argmax not in top-2" % tag
+    picked = np.take_along_axis(z_o, am_g[..., None].astype(np.int64), axis=-1)[..., 0]
+    assert np.all(picked[loose] >= part[..., -1][loose] - 2 * err - 1e-9), "%s: argmax outside the error band" % tag
     clear = top2_margin(z_o) > MARGIN
     return int((clear & strict).sum()), int(clear.sum())
 
@@ -594,6 +596,7 @@ def _shared_workload(shape, P_len, R_len, b, S, seed, batch, frac_decoded, block
     (1, 64, 32, 32, 2, 0.0, 0),      # nothing decoded: the plain step
     (2, 33, 31, 16, 5, 1.0, 0),      # everything decoded: the speculative blocks are empty
     (1, 128, 64, 48, 8, 0.9, 3),     # few masked positions left
+    (2, 37, 161, 64, 7, 0.2, 2),     # 864 rows: the 256-row GEMM blocks under the decoded-share row map
 ])
 def test_decoded_share_step_against_the_oracle(tiny, Bn, P, R, b, S, frac, slack):
     tokens, drafts, off, ro = _shared_workload(tiny.shape, P, R, b, S, 1000 + b + S, Bn, frac)
