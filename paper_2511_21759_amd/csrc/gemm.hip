@@ -127,51 +127,69 @@ static void launch_tile(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi
     }
 }
 
-// 256 rows and more: 256-row blocks through LDS (gemm_big.h), 64 * WN columns wide
-template <int WN, class Epi, int NWV = 8>
+// 256 rows and more: blocks of MBT x 16 rows through LDS (gemm_big.h), 64 * WN columns wide
+template <int WN, class Epi, int MBT = 16>
 static void launch_big_wn(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi e, hipStream_t s) {
     BigArgs g;
     g.A = a; g.W = w; g.KT = sh.K_tiles; g.MT_total = sh.M_tiles; g.NT = sh.N_tiles;
     g.ssq = ni.ssq; g.n_ssq = ni.n_ssq; g.eps = ni.eps; g.inv_d = 1.0f / (float)(sh.K_tiles * 32);
-    g.m_blocks = (sh.M_tiles + 15) / 16;
+    g.m_blocks = (sh.M_tiles + MBT - 1) / MBT;
     g.n_blocks = (sh.N_tiles + 4 * WN - 1) / (4 * WN);
     static bool attr_set = false;           // once per instantiation: the ring needs more than the default 64 KiB
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_big_kernel<WN, Epi, NWV>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_big_kernel<WN, Epi, 8, MBT>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, big_smem_bytes(WN));
         attr_set = true;
     }
     dim3 grid(8 * g.m_blocks * ((g.n_blocks + 7) / 8));
-    gemm_big_kernel<WN, Epi, NWV><<<grid, 64 * NWV, big_smem_bytes(WN), s>>>(g, e);
+    gemm_big_kernel<WN, Epi, 8, MBT><<<grid, 64 * 8, big_smem_bytes(WN), s>>>(g, e);
 }
 
-// Block width for the 256-row kernel, or 0 when the tile kernel should run instead.  With T blocks on 256
-// compute units a launch takes ceil(T / 256) block-times, and a block-time shrinks more slowly than the
-// block: measured on one GPU at 1024 and 2048 rows, a 192-column block takes 0.87 and a 128-column block
-// 0.68 of the time of a 256-column one (the k-step is bound by its barrier and operand delivery as much as
-// by its MFMAs).  The width with the smallest rounds x block-time wins among those whose block slots are at
-// least 70 % useful (a ragged last row block counts by its real rows); below 70 % for every width the
-// 128-row tile kernel wins (measured at 640 rows).  The O and down projections (N = 4096) stay with the
-// tile kernel.
-static int big_width(GemmShape sh) {
-    if (sh.M_tiles < 16 || sh.N_tiles < 32) return 0;
-    const double rel[5] = {0, 0, 0.68, 0.87, 1.0};
-    int best = 0;
+// Block shape for the LDS-ring kernel - MBT 16-row tiles by 64 * WN columns - or wn = 0 when the tile kernel
+// should run instead.  With T blocks on 256 compute units a launch takes ceil(T / 256) block-times, and a
+// block-time shrinks more slowly than the block (the k-step is bound by its barrier and operand delivery as
+// much as by its MFMAs).  Measured on one GPU at K = 4096, in units of the 256 x 256 block (110 us): 256-row
+// blocks of 192 / 128 columns 0.87 / 0.68; 128-row blocks of 256 / 192 / 128 columns 0.66 / 0.60 / 0.46.  The
+// shape with the smallest rounds x block-time wins among those whose block slots are at least 70 % useful (a
+// ragged last block counts by its real rows); below 70 % for every shape the 128-row tile kernel wins
+// (measured at 640 rows).  The 128-row blocks serve shapes that would leave compute units idle: QKV at 512 rows
+// (256 blocks of 128 x 192 instead of 192 of 256 x 128: 83 -> 69 us), every wide projection at 640 rows (five row
+// blocks that fit exactly: refresh 14.7 -> 13.0 ms), the 256-row step (7.6 -> 7.2 ms).
+struct BigChoice { int mbt, wn; };
+static BigChoice big_choice(GemmShape sh) {
+    BigChoice best{16, 0};
+    if (sh.M_tiles < 16 || sh.N_tiles < 32) return best;
+    const double rel16[5] = {0, 0, 0.68, 0.87, 1.0}, rel8[5] = {0, 0, 0.46, 0.60, 0.66};
     double best_cost = 0;
-    for (int wn = 4; wn >= 2; wn--) {
-        const int blocks = ((sh.M_tiles + 15) / 16) * ((sh.N_tiles + 4 * wn - 1) / (4 * wn));
-        const int rounds = (blocks + kStreamWGs - 1) / kStreamWGs;
-        const double useful = (sh.M_tiles / 16.0) * (sh.N_tiles / (4.0 * wn)) / ((double)rounds * kStreamWGs);
-        const double cost = rounds * rel[wn];
-        if (useful >= 0.7 && (best == 0 || cost < best_cost - 1e-9)) { best = wn; best_cost = cost; }
-    }
+    for (int mbt = 16; mbt >= 8; mbt -= 8)
+        for (int wn = 4; wn >= 2; wn--) {
+            const int blocks = ((sh.M_tiles + mbt - 1) / mbt) * ((sh.N_tiles + 4 * wn - 1) / (4 * wn));
+            const int rounds = (blocks + kStreamWGs - 1) / kStreamWGs;
+            const double useful = (sh.M_tiles / (double)mbt) * (sh.N_tiles / (4.0 * wn)) / ((double)rounds * kStreamWGs);
+            const double cost = rounds * (mbt == 16 ? rel16[wn] : rel8[wn]);
+            // (a 128-row shape has to promise 5 % over the best 256-row one: the unit times are measurements)
+            if (useful >= 0.7 && (best.wn == 0 || cost < best_cost * (mbt == 8 && best.mbt == 16 ? 0.95 : 1.0) - 1e-9)) {
+                best = BigChoice{mbt, wn};
+                best_cost = cost;
+            }
+        }
     return best;
 }
+static int big_width(GemmShape sh) { return big_choice(sh).wn; }
 static bool use_big(GemmShape sh) { return big_width(sh) != 0; }
 
 template <class Epi>
 static void launch_big(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi e, hipStream_t s) {
-    switch (big_width(sh)) {
+    const BigChoice c = big_choice(sh);
+    if (c.mbt == 8) {
+        switch (c.wn) {
+            case 2: launch_big_wn<2, Epi, 8>(a, w, sh, ni, e, s); break;
+            case 3: launch_big_wn<3, Epi, 8>(a, w, sh, ni, e, s); break;
+            default: launch_big_wn<4, Epi, 8>(a, w, sh, ni, e, s); break;
+        }
+        return;
+    }
+    switch (c.wn) {
         case 2: launch_big_wn<2>(a, w, sh, ni, e, s); break;
         case 3: launch_big_wn<3>(a, w, sh, ni, e, s); break;
         default: launch_big_wn<4>(a, w, sh, ni, e, s); break;
@@ -203,7 +221,10 @@ void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int l
     const bool long_k = sh.K_tiles > sh.N_tiles;
     if (sh.M_tiles <= 6 && (long_k || sh.M_tiles > 2) && ksplit_ok(sh, ws)) launch_stream_ksplit(a, w, sh, e, ws, s);
     else if (sh.M_tiles <= 2) launch_stream<2, 1, 8, 8, false>(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
-    else if (use_big(sh)) launch_big(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
+    // (128-row blocks only for the O projection: at 1024 rows 256 blocks of 128 x 128 take 57 us against 64 us for the
+    // tile kernel and its reduction pass; the down projection, three times as long in K, measured 4 % slower that way)
+    else if (use_big(sh) && (big_choice(sh).mbt == 16 || sh.K_tiles <= sh.N_tiles))
+        launch_big(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
     else launch_tile(a, w, sh, NormIn{nullptr, 0, 0.f}, e, ws, true, s);
 }
 void launch_gemm_swiglu(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, u16 *act, Workspace ws, hipStream_t s) {

@@ -4,7 +4,8 @@
 //
 // A workgroup of eight waves computes a 256 x (64 WN) block of C over all of K, WN = 4, 3 or 2 (256, 192 or
 // 128 columns: the narrower blocks exist for shapes whose count of 256-wide blocks fills the compute units
-// badly).  Per k-tile it needs sixteen 1 KiB tiles of A and 4 WN of W; they are copied from global memory straight into LDS
+// badly), or with MBT = 8 a 128 x (64 WN) block (each wave half as many row tiles; the description below is
+// for 256 rows).  Per k-tile it needs sixteen 1 KiB tiles of A and 4 WN of W; they are copied from global memory straight into LDS
 // (global_load ... lds, no registers in between) into a ring of four stages, three k-tiles ahead of
 // the MFMAs, so one barrier per k-tile is the only synchronisation.  The waves form a 2 x 4 grid,
 // each owning 8 x WN output tiles: per k-tile a wave reads 8 + WN operand tiles from LDS for 8 WN MFMAs,
@@ -36,12 +37,16 @@ struct BigArgs {
 
 // NWV = 4 (four waves of 128 x 32 WN columns each, accumulators in the AGPR half of the register file) halves the
 // LDS reads per MFMA but measured 20 % slower than eight waves on MI355X; only NWV = 8 is instantiated.
-template <int WN, class Epi, int NWV = 8>
+// MBT: 16-row tiles per block, 16 (256 rows) or 8 (128 rows: twice the blocks for shapes that leave compute
+// units idle otherwise; per flop it needs 1.4 x the operand bytes of the 256-row block).
+template <int WN, class Epi, int NWV = 8, int MBT = 16>
 __global__ __launch_bounds__(64 * NWV) void gemm_big_kernel(BigArgs g, Epi epi) {
     static_assert(WN >= 2 && WN <= 4, "block width in units of 64 columns");
     static_assert(NWV == 8 || NWV == 4, "waves per workgroup");
+    static_assert(MBT == 16 || MBT == 8, "rows per block");
     constexpr int CW = NWV / 2;                 // waves side by side; two rows of them
     constexpr int WT = 4 * WN / CW;             // 16-column tiles per wave
+    constexpr int MW = MBT / 2;                 // 16-row tiles per wave
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int NS = big_stages(WN);
     typedef frag_t stage_t[32][64];                                          // tiles 0..15: A, 16..16+4*WN-1: W
@@ -57,10 +62,10 @@ __global__ __launch_bounds__(64 * NWV) void gemm_big_kernel(BigArgs g, Epi epi) 
     const int xcd = blockIdx.x % 8, jx = blockIdx.x / 8;
     const int nb = (jx / g.m_blocks) * 8 + xcd, mb = jx % g.m_blocks;
     if (nb >= g.n_blocks) return;
-    const int mt0 = mb * 16, nt0 = nb * 4 * WN;
+    const int mt0 = mb * MBT, nt0 = nb * 4 * WN;
 
-    // the first half of the waves copies the sixteen tiles of A into every stage, the second half the 4 WN of W
-    constexpr int PA = 16 / CW, PW = 4 * WN / CW, PMAX = PA > PW ? PA : PW;
+    // the first half of the waves copies the MBT tiles of A into every stage, the second half the 4 WN of W
+    constexpr int PA = MBT / CW, PW = 4 * WN / CW, PMAX = PA > PW ? PA : PW;
     const u16 *src[PMAX];
     size_t kstride;
     const int per = w < CW ? PA : PW, slot0 = w < CW ? PA * w : 16 + (w - CW) * PW;
@@ -106,7 +111,7 @@ __global__ __launch_bounds__(64 * NWV) void gemm_big_kernel(BigArgs g, Epi epi) 
         // (32 KiB from the start of the last slot: for the narrower blocks this runs on into the per-wave
         // scratch behind the ring, which is not in use yet, and ends before the row scales)
         static_assert(big_stage_bytes(WN) + 8 * 1024 >= NWV * 16 * 64 * 4, "room for the row-scale scratch");
-        constexpr int RW = 256 / NWV;           // rows per wave
+        constexpr int RW = MBT * 16 / NWV;      // rows per wave
         float *tmp = reinterpret_cast<float *>(&ring[NS - 1][0][0]) + w * (16 * 64);
         const int si = 4 * lane, sic = si < g.n_ssq - 4 ? si : g.n_ssq - 4;
 #pragma unroll
@@ -139,12 +144,12 @@ __global__ __launch_bounds__(64 * NWV) void gemm_big_kernel(BigArgs g, Epi epi) 
             if (lane < 16) s_rstd[w * RW + half * 16 + lane] = 1.0f / sqrtf(t * g.inv_d + g.eps);
         }
     } else {
-        for (int r = lane; r < 256 / NWV; r += 64) s_rstd[w * (256 / NWV) + r] = 1.0f;
+        for (int r = lane; r < MBT * 16 / NWV; r += 64) s_rstd[w * (MBT * 16 / NWV) + r] = 1.0f;
     }
 
-    f32x4 acc[8][WT];
+    f32x4 acc[MW][WT];
 #pragma unroll
-    for (int m = 0; m < 8; m++)
+    for (int m = 0; m < MW; m++)
 #pragma unroll
         for (int j = 0; j < WT; j++) acc[m][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
@@ -153,19 +158,19 @@ __global__ __launch_bounds__(64 * NWV) void gemm_big_kernel(BigArgs g, Epi epi) 
     // all waves run under the MFMAs instead of in a phase of their own after each barrier.  Stage k+NS-1
     // is requested from global memory in iteration k, into the slot whose tiles fed the MFMAs of k-1.
     static_assert(NS >= 3 && (NS - 2) * PMAX <= 16, "slot arithmetic and counted waits below");
-    frag_t a[2][8], b[2][WT];
+    frag_t a[2][MW], b[2][WT];
     auto fetch = [&](auto P, int k) __attribute__((always_inline)) {
         constexpr int p = decltype(P)::value;
         const stage_t &st = ring[k % NS];
 #pragma unroll
         for (int j = 0; j < WT; j++) b[p][j] = st[16 + wn * WT + j][lane];
 #pragma unroll
-        for (int m = 0; m < 8; m++) a[p][m] = st[wm * 8 + m][lane];
+        for (int m = 0; m < MW; m++) a[p][m] = st[wm * MW + m][lane];
     };
     auto mfmas = [&](auto P) __attribute__((always_inline)) {
         constexpr int p = decltype(P)::value;
 #pragma unroll
-        for (int m = 0; m < 8; m++)
+        for (int m = 0; m < MW; m++)
 #pragma unroll
             for (int j = 0; j < WT; j++) acc[m][j] = mfma16(b[p][j], a[p][m], acc[m][j]);
     };
@@ -181,7 +186,7 @@ __global__ __launch_bounds__(64 * NWV) void gemm_big_kernel(BigArgs g, Epi epi) 
         }
         __builtin_amdgcn_s_barrier();
         if (k + NS - 1 < nk) issue((k + NS - 1) % NS, k + NS - 1);
-        if constexpr (WN == 4 && NWV == 8) {
+        if constexpr (WN == 4 && NWV == 8 && MBT == 16) {
             // widest block: every register is taken, the reads of stage k+1 go ahead of the MFMAs of stage k
             // (measured 5 % faster than the interleaved order, which needs more live registers)
             fetch(std::integral_constant<int, 1 - p>{}, k + 1);
@@ -193,7 +198,7 @@ __global__ __launch_bounds__(64 * NWV) void gemm_big_kernel(BigArgs g, Epi epi) 
             // the MFMAs instead of being waited for ahead of them (2 % faster at 192 columns).
             mfmas(P);
             fetch(std::integral_constant<int, 1 - p>{}, k + 1);
-            constexpr int NR = 8 + WT, NM = 8 * WT, MPR = NM / NR;
+            constexpr int NR = MW + WT, NM = MW * WT, MPR = NM / NR;
 #pragma unroll
             for (int i = 0; i < NR; i++) {
                 __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);       // MPR MFMAs
@@ -227,8 +232,8 @@ __global__ __launch_bounds__(64 * NWV) void gemm_big_kernel(BigArgs g, Epi epi) 
         int *st_a = reinterpret_cast<int *>(st_s + CW * 256);
         const int mi = lane & 15, gq = lane >> 4;
 #pragma unroll
-        for (int m = 0; m < 8; m++) {
-            const int r = wm * 128 + m * 16 + mi;
+        for (int m = 0; m < MW; m++) {
+            const int r = wm * MW * 16 + m * 16 + mi;
             float rm = -INFINITY, rs = 0.f;
             int ra = 0x7fffffff;
 #pragma unroll
@@ -260,7 +265,7 @@ __global__ __launch_bounds__(64 * NWV) void gemm_big_kernel(BigArgs g, Epi epi) 
             }
         }
         __syncthreads();
-        for (int r = threadIdx.x; r < 256; r += 64 * NWV) {
+        for (int r = threadIdx.x; r < MBT * 16; r += 64 * NWV) {
             const int row = mt0 * 16 + r;
             float rm = st_m[r], rs = st_s[r];
             int ra = st_a[r];
@@ -275,12 +280,12 @@ __global__ __launch_bounds__(64 * NWV) void gemm_big_kernel(BigArgs g, Epi epi) 
         }
     } else {
 #pragma unroll
-        for (int m = 0; m < 8; m++)
+        for (int m = 0; m < MW; m++)
 #pragma unroll
             for (int j = 0; j < WT; j++) {
-                const int mt = mt0 + wm * 8 + m, nt = nt0 + wn * WT + j;
+                const int mt = mt0 + wm * MW + m, nt = nt0 + wn * WT + j;
                 if (mt < g.MT_total && nt < g.NT) {
-                    const float *rsd = s_rstd + (wm * 8 + m) * 16;
+                    const float *rsd = s_rstd + (wm * MW + m) * 16;
                     f32x4 c;
                     if (!epi.transposed(nt)) {
                         c = acc[m][j] * rsd[lane & 15];
