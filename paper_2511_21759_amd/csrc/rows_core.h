@@ -55,37 +55,98 @@ __device__ __forceinline__ void embed_row(int r, const u16 *embed, const int32_t
 // the 16 vocabulary columns of part.  Merging keeps the lowest id on equal maxima.
 struct Stat { float m, s; int a; };
 
-__device__ inline Stat merge(Stat x, Stat y) {
-    Stat o;
-    o.m = fmaxf(x.m, y.m);
-    // equal maxima (including two empty -inf partials) must not evaluate inf - inf
-    float ex = x.m == o.m ? 1.f : expf(x.m - o.m);
-    float ey = y.m == o.m ? 1.f : expf(y.m - o.m);
-    o.s = x.s * ex + y.s * ey;
-    o.a = x.m > y.m ? x.a : (y.m > x.m ? y.a : (x.a < y.a ? x.a : y.a));
-    return o;
+// UN independent partials per lane, loaded back to back, folded into the lane's running (max, sum, argmax):
+// one exponential per partial (against the maximum of the pass) plus one for the running sum.
+template <int UN>
+__device__ __forceinline__ Stat merge_partials_pass(const float *p, int q0, int n_part, int lane, Stat acc) {
+    Stat t[UN];
+    float mp = acc.m;
+#pragma unroll
+    for (int j = 0; j < UN; j++) {
+        int q = q0 + lane + 64 * j;
+        if (q < n_part) t[j] = Stat{p[q * 3], p[q * 3 + 1], __float_as_int(p[q * 3 + 2])};
+        else t[j] = Stat{-INFINITY, 0.f, 0x7fffffff};
+        mp = fmaxf(mp, t[j].m);
+    }
+    // equal maxima (including empty -inf partials) must not evaluate inf - inf
+    float sum = acc.m == mp ? acc.s : acc.s * expf(acc.m - mp);
+    int a = acc.m == mp ? acc.a : 0x7fffffff;
+#pragma unroll
+    for (int j = 0; j < UN; j++) {
+        sum += t[j].m == mp ? t[j].s : t[j].s * expf(t[j].m - mp);
+        a = t[j].m == mp && t[j].a < a ? t[j].a : a;         // lowest token id among equal maxima
+    }
+    return Stat{mp, sum, a};
 }
 
-// the whole wave merges the n_part partials of one row (p = first partial of the row); every lane gets the result
+// The same for groups of four partials (48 contiguous bytes: three 16-byte loads per lane instead of twelve
+// 4-byte loads at a 12-byte stride, which the address unit of the one compute unit this kernel runs on serves
+// at a fraction of the rate).  p must be 16-byte aligned.
+template <int UG>
+__device__ __forceinline__ Stat merge_partials_pass4(const float *p, int g0, int n_grp, int lane, Stat acc) {
+    f32x4 v[UG][3];
+#pragma unroll
+    for (int j = 0; j < UG; j++) {
+        const int g = g0 + lane + 64 * j;
+        if (g < n_grp) {
+            const f32x4 *q = reinterpret_cast<const f32x4 *>(p + (size_t)g * 12);
+            v[j][0] = q[0]; v[j][1] = q[1]; v[j][2] = q[2];
+        } else {
+            const float e = __int_as_float(0x7fffffff);          // empty partials: (-inf, 0, no id)
+            v[j][0] = f32x4{-INFINITY, 0.f, e, -INFINITY};
+            v[j][1] = f32x4{0.f, e, -INFINITY, 0.f};
+            v[j][2] = f32x4{e, -INFINITY, 0.f, e};
+        }
+    }
+    Stat t[UG * 4];
+    float mp = acc.m;
+#pragma unroll
+    for (int j = 0; j < UG; j++) {
+        t[4 * j + 0] = Stat{v[j][0][0], v[j][0][1], __float_as_int(v[j][0][2])};
+        t[4 * j + 1] = Stat{v[j][0][3], v[j][1][0], __float_as_int(v[j][1][1])};
+        t[4 * j + 2] = Stat{v[j][1][2], v[j][1][3], __float_as_int(v[j][2][0])};
+        t[4 * j + 3] = Stat{v[j][2][1], v[j][2][2], __float_as_int(v[j][2][3])};
+#pragma unroll
+        for (int k = 0; k < 4; k++) mp = fmaxf(mp, t[4 * j + k].m);
+    }
+    float sum = acc.m == mp ? acc.s : acc.s * expf(acc.m - mp);
+    int a = acc.m == mp ? acc.a : 0x7fffffff;
+#pragma unroll
+    for (int j = 0; j < UG * 4; j++) {
+        sum += t[j].m == mp ? t[j].s : t[j].s * expf(t[j].m - mp);
+        a = t[j].m == mp && t[j].a < a ? t[j].a : a;
+    }
+    return Stat{mp, sum, a};
+}
+
+// the whole wave merges the n_part partials of one row (p = first partial of the row); every lane gets the result.
+// Each lane folds its partials against their common maximum (the pairwise merge costs two exponentials in a
+// dependent chain per partial, and a 1536-partial row of the few-row LM head made this kernel take 22 us on its
+// single compute unit); the 64 lane results are combined the same way: wave maximum, one rescale, butterfly sum.
 __device__ __forceinline__ Stat merge_row_partials(const float *p, int n_part, int lane) {
     Stat acc = {-INFINITY, 0.f, 0x7fffffff};
-    for (int q0 = 0; q0 < n_part; q0 += 64 * 8) {            // eight independent partials per lane and pass
-        Stat t[8];
-#pragma unroll
-        for (int j = 0; j < 8; j++) {
-            int q = q0 + lane + 64 * j;
-            if (q < n_part) t[j] = Stat{p[q * 3], p[q * 3 + 1], __float_as_int(p[q * 3 + 2])};
-            else t[j] = Stat{-INFINITY, 0.f, 0x7fffffff};
-        }
-#pragma unroll
-        for (int j = 0; j < 8; j++) acc = merge(acc, t[j]);
+    if (n_part % 4 == 0 && (reinterpret_cast<uintptr_t>(p) & 15) == 0) {
+        const int n_grp = n_part / 4;
+        int g0 = 0;
+        for (; n_grp - g0 > 64 * 2; g0 += 64 * 6) acc = merge_partials_pass4<6>(p, g0, n_grp, lane, acc);
+        if (g0 < n_grp) acc = merge_partials_pass4<2>(p, g0, n_grp, lane, acc);
+    } else {
+        int q0 = 0;
+        for (; n_part - q0 > 64 * 8; q0 += 64 * 24) acc = merge_partials_pass<24>(p, q0, n_part, lane, acc);
+        if (q0 < n_part) acc = merge_partials_pass<8>(p, q0, n_part, lane, acc);
     }
+    float wm = acc.m;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) wm = fmaxf(wm, __shfl_xor(wm, o));
+    float sum = acc.m == wm ? acc.s : acc.s * expf(acc.m - wm);
+    int a = acc.m == wm ? acc.a : 0x7fffffff;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
-        Stat t = {__shfl_xor(acc.m, o), __shfl_xor(acc.s, o), __shfl_xor(acc.a, o)};
-        acc = merge(acc, t);
+        sum += __shfl_xor(sum, o);                              // commutative: every lane ends with the same bits
+        const int oa = __shfl_xor(a, o);
+        a = oa < a ? oa : a;
     }
-    return acc;
+    return Stat{wm, sum, a};
 }
 
 // One workgroup finishes unit u: merges the partial statistics of its rpu rows, then applies the
