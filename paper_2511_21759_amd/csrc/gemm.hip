@@ -11,6 +11,12 @@ __global__ __launch_bounds__(64 * WKT) void gemm_stream_kernel(GemmArgs g, Epi e
 }
 
 constexpr int kStreamWGs = 256;      // one workgroup per compute unit
+// Every workgroup of the streaming kernels reads the same activation tiles; started at the same k-tile they ask the
+// same L2 channels for them at the same time.  Workgroup wg starts kKRot * wg k-tiles further on and wraps round
+// (7 is coprime to the 12 and 16 k-tiles per wave of the 8B shape; of 1, 3, 5 and 7 the multipliers 3 and 7 leave the
+// 32-row gate/up kernel at its 33.0 us, 1 and 5 cost it 0.6 us): the down projection 22.5 -> 20.7 us at 32 rows,
+// gate/up 49.0 -> 47.4 us at 128 rows; the order of a workgroup's fp32 sums depends on its index, not on the run.
+constexpr int kKRot = 7;
 
 // The streaming kernel with K split over KS workgroups per block of n-tiles, for projections whose activations
 // are long (the down projection: every workgroup of the plain kernel reads all 32 x 12288 of them through L2,
@@ -68,7 +74,7 @@ template <class Epi>
 static void launch_stream_ksplit(const u16 *a, const u16 *w, GemmShape sh, Epi e, Workspace ws, hipStream_t s) {
     GemmArgs g;
     g.A = a; g.W = w; g.KT = sh.K_tiles; g.MT_total = sh.M_tiles; g.NT = sh.N_tiles;
-    g.ssq = nullptr; g.n_ssq = 0; g.eps = 0.f; g.inv_d = 0.f; g.k_len = 0;
+    g.ssq = nullptr; g.n_ssq = 0; g.eps = 0.f; g.inv_d = 0.f; g.k_len = 0; g.k_rot = kKRot;
     const int nblocks = (sh.N_tiles + kSplitNG - 1) / kSplitNG;
     const dim3 grid(nblocks * kSplitKS);
     if (sh.M_tiles <= 2) gemm_stream_ksplit_kernel<2, kSplitNG, kSplitPF, kSplitKS, Epi><<<grid, 64 * WK, 0, s>>>(g, e, ws.partial, ws.arrive);
@@ -85,7 +91,7 @@ static void launch_stream(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, E
     GemmArgs g;
     g.A = a; g.W = w; g.KT = sh.K_tiles; g.MT_total = sh.M_tiles; g.NT = sh.N_tiles;
     g.ssq = ni.ssq; g.n_ssq = ni.n_ssq; g.eps = ni.eps; g.inv_d = 1.0f / (float)(sh.K_tiles * 32);
-    g.k_len = 0;
+    g.k_len = 0; g.k_rot = kKRot;
     const int kw = sh.K_tiles / WKT;                // K_tiles is a multiple of 8 (checked at model creation)
     const int groups = (sh.N_tiles + NG - 1) / NG;
     dim3 grid(groups < kStreamWGs ? groups : kStreamWGs, 1);
@@ -201,11 +207,12 @@ void launch_gemm_qkv(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, QkvOu
     // (Up to 96 rows a ring of ONE stage is the fastest since the weight tiles are loaded non-temporally - 2048 waves
     // with one group of tiles each in flight keep the HBM stream full, and fewer outstanding weight loads per
     // compute unit leave the activation loads less to queue behind: 1.9 % per step at 32 rows for this and the
-    // gate/up projection together, 1.5 % at 64 rows, 0.5 % at 96; at 128 rows the deeper rings still win.)
+    // gate/up projection together, 1.5 % at 64 rows, 0.5 % at 96; the 128-row gate/up keeps its four waves and deeper ring.)
     if (sh.M_tiles <= 2) launch_stream<2, 3, 1, 8, true>(xa, w, sh, ni, e, s);
     else if (sh.M_tiles <= 4) launch_stream<4, 3, 1, 8, true>(xa, w, sh, ni, e, s);          // 33..64 rows: still eight waves
     else if (sh.M_tiles <= 6) launch_stream<6, 3, 1, 8, true>(xa, w, sh, ni, e, s);          // 65..96 rows
-    else if (sh.M_tiles <= 8) launch_stream<8, 3, 4, 4, false>(xa, w, sh, ni, e, s);     // four waves: 24 accumulator tiles + the ring need the 512-register budget
+    // (128 rows: eight waves and a ring of one fit 256 registers - 36.5 -> 35.3 us against four waves with a ring of four)
+    else if (sh.M_tiles <= 8) launch_stream<8, 3, 1, 8, false>(xa, w, sh, ni, e, s);
     else if (use_big(sh)) launch_big(xa, w, sh, ni, e, s);
     else launch_tile(xa, w, sh, ni, e, ws, true, s);
 }

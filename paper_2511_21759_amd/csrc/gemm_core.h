@@ -41,6 +41,9 @@ struct GemmArgs {
     // k-tiles this call covers (0: all KT).  A and W then point at the first k-tile of the slice; KT stays the
     // distance between the n-tiles of W.
     int k_len;
+    // > 0: workgroup wg walks its k-tiles starting at (wg * k_rot) % (k-tiles per wave) and wraps round, so that the
+    // workgroups, which all read the same activation tiles, do not ask the same L2 channels for them at the same time
+    int k_rot;
 };
 
 // m-tiles per reduction pass: at most six 1 KiB tiles per wave go through LDS at a time
@@ -108,7 +111,10 @@ __device__ __forceinline__ void gemm_wg(const GemmArgs &g, Epi epi, int wg, int 
     const size_t a_step = (size_t)g.MT_total * kTileElems * kst;
 
     frag_t ab[PF][MT];
-    auto load_stage = [&](int slot, int grp, int kk) __attribute__((always_inline)) {
+    const int rot = g.k_rot > 0 ? (int)(((unsigned)wg * (unsigned)g.k_rot) % (unsigned)KW) : 0;
+    auto load_stage = [&](int slot, int grp, int k_seq) __attribute__((always_inline)) {
+        int kk = k_seq + rot;
+        kk = kk >= KW ? kk - KW : kk;
 #pragma unroll
         for (int n = 0; n < NG; n++) {
             int nt = n_lo + grp * NG + n;
