@@ -31,6 +31,8 @@ static void launch_rows(AttnArgs a, float sc, hipStream_t s) {
     const int tiles_per_seq = a.units_per_seq * a.tiles_per_unit;
     const int chunks = (tiles_per_seq + NW * QTW - 1) / (NW * QTW);
     dim3 grid((a.units / a.units_per_seq) * chunks, a.H);
+    // (flattened: the kernel then maps all row chunks of a head to one XCD - 38.9 -> 38.2 us at 1024 rows)
+    if (a.H % 8 == 0 && grid.x > 1) grid = dim3(grid.x * grid.y, 1);
     attn_rows_kernel<DH, NW, QTW, NS, PIPE, DUAL><<<grid, 64 * NW, attn_rows_smem_bytes<DH, NS>(), s>>>(a, sc);
 }
 

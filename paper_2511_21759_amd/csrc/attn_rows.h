@@ -32,11 +32,20 @@ __global__ __launch_bounds__(64 * NW) void attn_rows_kernel(AttnArgs a, float sc
     typedef frag_t stage_t[FR][64];
     stage_t *ring = reinterpret_cast<stage_t *>(smem);
 
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, hd = blockIdx.y;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int tiles_per_seq = a.units_per_seq * a.tiles_per_unit;
     const int chunks = (tiles_per_seq + NW * QTW - 1) / (NW * QTW);
-    const int seq = blockIdx.x / chunks;
-    const int ts0 = (blockIdx.x % chunks) * (NW * QTW) + w * QTW;      // this wave's first tile within the sequence
+    // One-dimensional grid (gridDim.y == 1 although the heads are a multiple of 8): workgroup ids go round-robin over the XCDs, and
+    // id = xcd + 8 * (item + items * (head / 8)) with head = xcd + 8 * (head / 8) keeps all row chunks of a head
+    // (they read the same K/V) on one XCD, whose L2 then holds the K/V of its own heads only.
+    int hd = blockIdx.y, item = blockIdx.x;
+    if (gridDim.y == 1 && (a.H & 7) == 0) {
+        const int items = gridDim.x / a.H, j = blockIdx.x >> 3;
+        hd = (blockIdx.x & 7) + 8 * (j / items);
+        item = j % items;
+    }
+    const int seq = item / chunks;
+    const int ts0 = (item % chunks) * (NW * QTW) + w * QTW;      // this wave's first tile within the sequence
     const bool wave_live = ts0 < tiles_per_seq;
     const int unit = seq * a.units_per_seq + (wave_live ? ts0 : tiles_per_seq - 1) / a.tiles_per_unit;
 
