@@ -254,6 +254,28 @@ def test_step_edge_shapes(tiny, Bn, P, R, b, S, blk):
     run_step_case(tiny, cache, oc, wl.drafts, wl.block_off, 0.9, "edge step")
 
 
+WIDE_HEADS = dict(n_layers=2, d_model=1024, n_heads=8, head_dim=128, d_ff=2048, vocab=2048, rope_base=10000.0,
+                  rms_eps=1e-5, mask_id=2047)
+
+
+@pytest.mark.parametrize("Bn,P,R,b,S,blk", [
+    (1, 160, 96, 32, 1, 1),    # 32 step rows: both row tiles of a head on one XCD; 256 prefill rows: the flattened many-row grid
+    (1, 96, 64, 32, 16, 0),    # 16 drafts of two row tiles: the two-tile workgroups, the drafts of a head on one XCD
+    (2, 60, 36, 16, 3, 1),     # one row tile per draft, batch 2: six work items per head
+])
+def test_eight_heads_of_128_channels(Bn, P, R, b, S, blk):
+    """Heads of 128 channels in a multiple of eight take the attention launches whose workgroup ids are mapped
+    so that the work items of a head share an XCD (the tiny model's four heads of 64 channels do not); eight
+    k-tiles per wave also stagger the k-loops of the down projection.  Element by element against the oracle."""
+    p = Pair(WIDE_HEADS)
+    try:
+        wl = W.decode_workload(p.shape, P, R, b, S, 300 + P, batch=Bn, block_index=blk)
+        cache, oc = run_prefill_case(p, wl.tokens, wl.resp_off, "wide-head prefill")
+        run_step_case(p, cache, oc, wl.drafts, wl.block_off, 0.9, "wide-head step")
+    finally:
+        p.close()
+
+
 def test_gpu_structural_properties(tiny):
     """Sec. 4.2: drafts are mutually invisible; Sec. 2.1: a step on the unchanged
     block reproduces the refresh; the step leaves the cache untouched."""
