@@ -206,6 +206,7 @@ int run_stack(Model &m, const Cache &c, const Plan &pl, const StackIO &io, hipSt
             qo.k_b = kf + spec_off; qo.k_b_head_stride = (size_t)mp32 * dh; qo.k_b_unit_stride = (size_t)H * mp32 * dh;
             qo.v_b = vf + spec_off; qo.v_b_head_stride = (size_t)mp32 * dh; qo.v_b_unit_stride = (size_t)H * mp32 * dh;
         }
+        qo.set_divisors();
         {
             ProfScope ps(m, ODB_K_GEMM_QKV, s);
             launch_gemm_qkv(xa, w.qkv, GemmShape{mt, 3 * d / 16, d / 32}, ni, qo, ws, s);
@@ -369,6 +370,7 @@ int step_impl(odb_model *mh, const odb_cache *ch, const int32_t *drafts, int blo
         qo.tiles_per_unit = bp / 16; qo.pos_off = block_off; qo.H = H; qo.dh = dh; qo.d = d;
         qo.k = (u16 *)(base + pl.kf); qo.k_head_stride = (size_t)bp32 * dh; qo.k_unit_stride = (size_t)H * bp32 * dh;
         qo.v = (u16 *)(base + pl.vf); qo.v_head_stride = (size_t)bp32 * dh; qo.v_unit_stride = (size_t)H * bp32 * dh;
+        qo.set_divisors();
         AttnArgs &at = a.attn;
         at.q = qo.q; at.kc = c.k; at.vc = c.v;
         at.kc_seq_stride = seq_elems; at.kc_head_stride = (size_t)c.lmax32 * dh;

@@ -278,12 +278,13 @@ struct EpiQKV {
         // unit and tile inside the unit; in the decoded-share step the speculative units have their own size and K/V area
         const bool spec = o.split_tile > 0 && mt >= o.split_tile;
         const int tpu = pick(spec, o.tiles_per_unit_b, o.tiles_per_unit), mtu = pick(spec, mt - o.split_tile, mt);
-        const int unit = mtu / tpu, tu = mtu % tpu;
+        const int unit = pick(spec, o.fd_tpu_b, o.fd_tpu).quot(mtu), tu = mtu - unit * tpu;
         u16 *kdst = pick(spec, o.k_b, o.k) + unit * pick(spec, o.k_b_unit_stride, o.k_unit_stride);
         u16 *vdst = pick(spec, o.v_b, o.v) + unit * pick(spec, o.v_b_unit_stride, o.v_unit_stride);
         const size_t khs = pick(spec, o.k_b_head_stride, o.k_head_stride), vhs = pick(spec, o.v_b_head_stride, o.v_head_stride);
-        const int n = nt * 16, sec = n / o.d, rr = n % o.d;
-        const int hd = rr / o.dh, p0 = rr % o.dh;            // p0 is a multiple of 16
+        // (index arithmetic on tiles with precomputed multipliers: it sits in the serial tail of the kernel)
+        const int sec = o.fd_d.quot(nt), rt = nt - sec * (o.d >> 4);
+        const int hd = o.fd_dh.quot(rt), p0 = (rt - hd * (o.dh >> 4)) * 16;            // p0 is a multiple of 16
         if (sec < 2) {
             // physical channel 2j is logical j, 2j+1 is j + dh/2: each adjacent pair is a RoPE pair
             const int pos = o.rowpos ? o.rowpos[mt * 16 + mi] : o.pos_off + tu * 16 + mi;

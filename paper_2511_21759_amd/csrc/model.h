@@ -120,12 +120,30 @@ void launch_lm_finish_shared(const float *stats, int n_part, SharedMap sm, int m
 
 // ---- gemm.hip ---------------------------------------------------------------
 struct GemmShape { int M_tiles, N_tiles, K_tiles; };
+// Division by a run-time constant below 2^16 for dividends below 2^16: q = (x * mul) >> 32 with
+// mul = floor(2^32 / div) + 1 is exact there (the error term x * (mul * div - 2^32) stays below 2^32).
+struct FastDiv {
+    unsigned mul, div;
+    __host__ __device__ static FastDiv make(int d) {
+        FastDiv f;
+        f.div = d > 0 ? (unsigned)d : 1u;
+        f.mul = (unsigned)(0x100000000ull / f.div) + 1u;       // (div = 1: wraps to 1 - handled in quot)
+        return f;
+    }
+    __device__ __forceinline__ int quot(int x) const { return div == 1u ? x : (int)__umulhi((unsigned)x, mul); }
+};
+
 struct QkvOut {
     u16 *q;                    // [H][mt_total][dh/32][512]
     u16 *k; size_t k_unit_stride, k_head_stride;   // tiles [pos/16][dh/32]
     u16 *v; size_t v_unit_stride, v_head_stride;   // tiles [pos/32][dh/16], keys permuted inside
     const float *rope;         // (cos,sin) table
     int tiles_per_unit, pos_off, H, dh, d;
+    FastDiv fd_d, fd_dh, fd_tpu, fd_tpu_b;     // by d / 16, dh / 16, tiles_per_unit, tiles_per_unit_b: set_divisors()
+    void set_divisors() {
+        fd_d = FastDiv::make(d / 16); fd_dh = FastDiv::make(dh / 16);
+        fd_tpu = FastDiv::make(tiles_per_unit); fd_tpu_b = FastDiv::make(tiles_per_unit_b);
+    }
     // Decoded-share step (rowpos != nullptr): row r sits at absolute position rowpos[r]; m-tiles from
     // split_tile on belong to the speculative units (tiles_per_unit_b each), whose fresh K/V go to k_b / v_b.
     const int32_t *rowpos;
