@@ -248,7 +248,7 @@ __global__ __launch_bounds__(64 * NWV) void gemm_big_kernel(BigArgs g, Epi epi) 
                         if (c[x] > cm) { cm = c[x]; ca = nt * 16 + 4 * gq + x; }
                     float cs = 0.f;
 #pragma unroll
-                    for (int x = 0; x < 4; x++) cs += expf(c[x] - cm);
+                    for (int x = 0; x < 4; x++) cs += __expf(c[x] - cm);
                     merge_stat(rm, rs, ra, cm, cs, ca);
                 }
             }

@@ -359,6 +359,8 @@ struct EpiSwiGLU {
 // (max, sum exp(z - max), argmax) per row and slot in registers and writes ONE partial per row and
 // slot at the end: stats[row][part], part = workgroup * NG + n-slot.  Ties keep the lowest token id.
 // PASSES = slots per wave (see gemm_wg).
+// (Exponentials are the hardware instruction, relative error about 1e-6 at the arguments that matter: they sit between
+// the groups of the weight stream, and a confidence is compared with the oracle's to the logit error, 1e-3.)
 template <int PASSES>
 struct EpiLMStats {
     float *stats;
@@ -379,12 +381,12 @@ struct EpiLMStats {
             if (c[r] > m) { m = c[r]; a = nt * 16 + 4 * g + r; }
         float s = 0.f;
 #pragma unroll
-        for (int r = 0; r < 4; r++) s += expf(c[r] - m);
+        for (int r = 0; r < 4; r++) s += __expf(c[r] - m);
 #pragma unroll
         for (int p = 0; p < PASSES; p++)
             if (p == pass) {
                 float nm = fmaxf(rm[p], m);
-                rs[p] = rs[p] * (rm[p] == nm ? 1.f : expf(rm[p] - nm)) + s * (m == nm ? 1.f : expf(m - nm));
+                rs[p] = rs[p] * (rm[p] == nm ? 1.f : __expf(rm[p] - nm)) + s * (m == nm ? 1.f : __expf(m - nm));
                 ra[p] = rm[p] > m ? ra[p] : (m > rm[p] ? a : (ra[p] < a ? ra[p] : a));
                 rm[p] = nm;
             }
@@ -401,7 +403,7 @@ struct EpiLMStats {
             float om = __shfl_xor(m, o), os = __shfl_xor(s, o);
             int oa = __shfl_xor(a, o);
             float nm = fmaxf(m, om);
-            s = s * (m == nm ? 1.f : expf(m - nm)) + os * (om == nm ? 1.f : expf(om - nm));
+            s = s * (m == nm ? 1.f : __expf(m - nm)) + os * (om == nm ? 1.f : __expf(om - nm));
             a = m > om ? a : (om > m ? oa : (a < oa ? a : oa));
             m = nm;
         }

@@ -36,7 +36,7 @@ template <> struct is_row_stats<TileLMStats> { static constexpr bool value = tru
 
 __device__ __forceinline__ void merge_stat(float &m, float &s, int &a, float om, float os, int oa) {
     float nm = fmaxf(m, om);
-    s = s * (m == nm ? 1.f : expf(m - nm)) + os * (om == nm ? 1.f : expf(om - nm));
+    s = s * (m == nm ? 1.f : __expf(m - nm)) + os * (om == nm ? 1.f : __expf(om - nm));
     a = m > om ? a : (om > m ? oa : (a < oa ? a : oa));
     m = nm;
 }
@@ -201,7 +201,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_tile_kernel(TileArgs g, Epi epi)
                         if (c[r] > cm) { cm = c[r]; ca = (nt0 + j) * 16 + 4 * gq + r; }
                     float cs = 0.f;
 #pragma unroll
-                    for (int r = 0; r < 4; r++) cs += expf(c[r] - cm);
+                    for (int r = 0; r < 4; r++) cs += __expf(c[r] - cm);
                     merge_stat(rm, rs, ra, cm, cs, ca);
                 }
             }

@@ -69,11 +69,11 @@ __device__ __forceinline__ Stat merge_partials_pass(const float *p, int q0, int 
         mp = fmaxf(mp, t[j].m);
     }
     // equal maxima (including empty -inf partials) must not evaluate inf - inf
-    float sum = acc.m == mp ? acc.s : acc.s * expf(acc.m - mp);
+    float sum = acc.m == mp ? acc.s : acc.s * __expf(acc.m - mp);
     int a = acc.m == mp ? acc.a : 0x7fffffff;
 #pragma unroll
     for (int j = 0; j < UN; j++) {
-        sum += t[j].m == mp ? t[j].s : t[j].s * expf(t[j].m - mp);
+        sum += t[j].m == mp ? t[j].s : t[j].s * __expf(t[j].m - mp);
         a = t[j].m == mp && t[j].a < a ? t[j].a : a;         // lowest token id among equal maxima
     }
     return Stat{mp, sum, a};
@@ -109,11 +109,11 @@ __device__ __forceinline__ Stat merge_partials_pass4(const float *p, int g0, int
 #pragma unroll
         for (int k = 0; k < 4; k++) mp = fmaxf(mp, t[4 * j + k].m);
     }
-    float sum = acc.m == mp ? acc.s : acc.s * expf(acc.m - mp);
+    float sum = acc.m == mp ? acc.s : acc.s * __expf(acc.m - mp);
     int a = acc.m == mp ? acc.a : 0x7fffffff;
 #pragma unroll
     for (int j = 0; j < UG * 4; j++) {
-        sum += t[j].m == mp ? t[j].s : t[j].s * expf(t[j].m - mp);
+        sum += t[j].m == mp ? t[j].s : t[j].s * __expf(t[j].m - mp);
         a = t[j].m == mp && t[j].a < a ? t[j].a : a;
     }
     return Stat{mp, sum, a};
@@ -138,7 +138,7 @@ __device__ __forceinline__ Stat merge_row_partials(const float *p, int n_part, i
     float wm = acc.m;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) wm = fmaxf(wm, __shfl_xor(wm, o));
-    float sum = acc.m == wm ? acc.s : acc.s * expf(acc.m - wm);
+    float sum = acc.m == wm ? acc.s : acc.s * __expf(acc.m - wm);
     int a = acc.m == wm ? acc.a : 0x7fffffff;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
