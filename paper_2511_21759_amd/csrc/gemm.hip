@@ -46,7 +46,7 @@ __global__ __launch_bounds__(64 * WK) void gemm_stream_ksplit_kernel(GemmArgs g,
     __syncthreads();
     if (s_old != KS - 1) return;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int n_lo = (int)(((long)nb * g.NT) / nblocks), n_hi = (int)(((long)(nb + 1) * g.NT) / nblocks);
+    const int n_lo = (int)((unsigned)nb * (unsigned)g.NT / (unsigned)nblocks), n_hi = (int)((unsigned)(nb + 1) * (unsigned)g.NT / (unsigned)nblocks);
     const int nn = n_hi - n_lo;
     for (int t = wv; t < g.MT_total * nn; t += WK) {
         const int mt = t / nn, nt = n_lo + t % nn;

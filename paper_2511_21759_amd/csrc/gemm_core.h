@@ -61,8 +61,8 @@ constexpr int kGemmSmemBytes = WK * 6 * 1024 + 8 * 16 * 4;    // LDS one workgro
 template <int NG, int PF, int WKT = WK, bool IL = false>
 __device__ __forceinline__ void gemm_prefetch_w(const GemmArgs &g, int wg, int nwg, frag_t (&wb)[PF][NG]) {
     const int lane = threadIdx.x & 63, wk = threadIdx.x >> 6;
-    const int n_lo = (int)(((long)wg * g.NT) / nwg);
-    int n_hi = (int)(((long)(wg + 1) * g.NT) / nwg);
+    const int n_lo = (int)((unsigned)wg * (unsigned)g.NT / (unsigned)nwg);      // (32-bit: wg * NT stays far below 2^32)
+    int n_hi = (int)((unsigned)(wg + 1) * (unsigned)g.NT / (unsigned)nwg);
     // a workgroup without n-tiles still loads (tile 0, discarded) so that the ring is always
     // fully redefined here and never has to be kept alive across phases
     if (n_hi <= n_lo) n_hi = n_lo + 1 <= g.NT ? n_lo + 1 : g.NT;
@@ -94,8 +94,8 @@ __device__ __forceinline__ void gemm_wg(const GemmArgs &g, Epi epi, int wg, int 
     float *s_rstd = reinterpret_cast<float *>(smem + WK * 6 * 1024);
 
     const int lane = threadIdx.x & 63, wk = threadIdx.x >> 6;
-    const int n_lo = (int)(((long)wg * g.NT) / nwg);
-    const int n_hi = (int)(((long)(wg + 1) * g.NT) / nwg);
+    const int n_lo = (int)((unsigned)wg * (unsigned)g.NT / (unsigned)nwg);      // (32-bit: wg * NT stays far below 2^32)
+    const int n_hi = (int)((unsigned)(wg + 1) * (unsigned)g.NT / (unsigned)nwg);
     if (n_lo >= n_hi) return;
     const int KW = (g.k_len ? g.k_len : g.KT) / WKT;
     const int ngroups = (n_hi - n_lo + NG - 1) / NG;

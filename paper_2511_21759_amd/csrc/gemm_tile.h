@@ -60,7 +60,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_tile_kernel(TileArgs g, Epi epi)
     // one or two k-slices of A instead of reading all of it into every L2; 22.0 -> 21.6 us at 128 rows)
     const int nb = blockIdx.x / g.KS, ks = blockIdx.x % g.KS;
     const int mt0 = blockIdx.y * 8;
-    const int k_lo = (int)(((long)ks * g.KT) / g.KS), k_hi = (int)(((long)(ks + 1) * g.KT) / g.KS);
+    const int k_lo = (int)((unsigned)ks * (unsigned)g.KT / (unsigned)g.KS), k_hi = (int)((unsigned)(ks + 1) * (unsigned)g.KT / (unsigned)g.KS);
     const int nk = k_hi - k_lo;                 // k-tiles of this slice
     const int nc = (nk + KC - 1) / KC;          // chunks
     const int nt0 = (nb * NW + w) * NGW;
