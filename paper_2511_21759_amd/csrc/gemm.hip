@@ -51,12 +51,13 @@ __global__ __launch_bounds__(64 * WK) void gemm_stream_ksplit_kernel(GemmArgs g,
     for (int t = wv; t < g.MT_total * nn; t += WK) {
         const int mt = t / nn, nt = n_lo + t % nn;
         const float *q = partial + ((size_t)mt * g.NT + nt) * 256 + lane;
+        const auto pre = epi_preload(epi, mt, nt, lane);
         f32x4 c = f32x4{0.f, 0.f, 0.f, 0.f};
         for (int s = 0; s < KS; s++)
 #pragma unroll
             for (int r = 0; r < 4; r++)
                 c[r] += __hip_atomic_load(q + s * slice + r * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        epi(mt, nt, c, lane, 0);
+        epi_apply(epi, mt, nt, c, lane, 0, pre);
     }
     if (threadIdx.x == 0) __hip_atomic_store(arrive + nb, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }

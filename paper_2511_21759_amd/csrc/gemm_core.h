@@ -79,6 +79,15 @@ __device__ __forceinline__ void gemm_prefetch_w(const GemmArgs &g, int wg, int n
         }
 }
 
+// Hooks for epilogues that read global memory (the residual tile, the RoPE table): epi_preload issues those loads
+// before the partial sums go through LDS, epi_apply hands their result to the epilogue, so that their latency runs
+// under the reduction instead of in the tail of the kernel.  Default: nothing to preload.
+struct NoPre {};
+template <class Epi>
+__device__ __forceinline__ NoPre epi_preload(const Epi &, int, int, int) { return NoPre{}; }
+template <class Epi>
+__device__ __forceinline__ void epi_apply(Epi &epi, int mt, int nt, f32x4 c, int lane, int slot, NoPre) { epi(mt, nt, c, lane, slot); }
+
 // One workgroup's share of the GEMM: n-tiles [wg*NT/nwg, (wg+1)*NT/nwg), m-tiles mt0 .. mt0+MT-1.
 // HAVE_W: wb already holds (or is receiving) the tiles gemm_prefetch_w loads.
 // The epilogue is called as epi(mt, nt, c, lane, slot): slot numbers the (m-chunk, tile) pairs that
@@ -206,12 +215,22 @@ __device__ __forceinline__ void gemm_wg(const GemmArgs &g, Epi epi, int wg, int 
         // add the eight K-slices through LDS, MC m-tiles at a time; the wave that owns a tile runs its epilogue
 #pragma unroll
         for (int mc = 0; mc < MT; mc += MC) {
+            decltype(epi_preload(epi, 0, 0, 0)) pre[SPW];
+#pragma unroll
+            for (int u = 0; u < SPW; u++) {
+                const int t = wk + u * WKT, m = t / NG, n = t % NG;
+                const int mt = mt0 + mc + m, nt = n_lo + grp * NG + n;
+                if (t < MC * NG && mt < g.MT_total && nt < n_hi) pre[u] = epi_preload(epi, mt, nt, lane);
+            }
 #pragma unroll
             for (int m = 0; m < MC; m++)
 #pragma unroll
                 for (int n = 0; n < NG; n++) red[wk][m * NG + n][lane] = acc[mc + m][n];
             __syncthreads();
-            for (int t = wk; t < MC * NG; t += WKT) {
+#pragma unroll
+            for (int u = 0; u < SPW; u++) {
+                const int t = wk + u * WKT;
+                if (t >= MC * NG) break;
                 const int m = t / NG, n = t % NG;
                 const int mt = mt0 + mc + m, nt = n_lo + grp * NG + n;
                 if (mt < g.MT_total && nt < n_hi) {
@@ -235,7 +254,7 @@ __device__ __forceinline__ void gemm_wg(const GemmArgs &g, Epi epi, int wg, int 
                             c[r] = v * s_rstd[(mc + m) * 16 + 4 * gq + r];
                         }
                     }
-                    epi(mt, nt, c, lane, (mc / MC) * SPW + t / WKT);
+                    epi_apply(epi, mt, nt, c, lane, (mc / MC) * SPW + u, pre[u]);
                 }
             }
             __syncthreads();
@@ -317,10 +336,15 @@ struct EpiResid {
     int mt_total;
     __device__ bool transposed(int) const { return false; }
     __device__ void finish(int, int, int, int) const {}
-    __device__ void operator()(int mt, int nt, f32x4 c, int lane, int) const {
+    __device__ f32x4 preload(int mt, int nt, int lane) const {
+        const int mi = lane & 15, g = lane >> 4, row = mt * 16 + mi, col = nt * 16 + 4 * g;
+        return *reinterpret_cast<const f32x4 *>(h + (size_t)row * ld + col);
+    }
+    __device__ void operator()(int mt, int nt, f32x4 c, int lane, int) const { apply(mt, nt, c, lane, preload(mt, nt, lane)); }
+    __device__ void apply(int mt, int nt, f32x4 c, int lane, f32x4 hv) const {
         const int mi = lane & 15, g = lane >> 4, row = mt * 16 + mi, col = nt * 16 + 4 * g;
         float *p = h + (size_t)row * ld + col;
-        f32x4 v = *reinterpret_cast<f32x4 *>(p) + c;
+        f32x4 v = hv + c;
         *reinterpret_cast<f32x4 *>(p) = v;
         if (no.hb) {
             f32x4 gn = *reinterpret_cast<const f32x4 *>(no.gain + col);
@@ -334,6 +358,9 @@ struct EpiResid {
         }
     }
 };
+
+__device__ __forceinline__ f32x4 epi_preload(const EpiResid &e, int mt, int nt, int lane) { return e.preload(mt, nt, lane); }
+__device__ __forceinline__ void epi_apply(EpiResid &e, int mt, int nt, f32x4 c, int lane, int, f32x4 hv) { e.apply(mt, nt, c, lane, hv); }
 
 // W_gu interleaves the rows of W_gate and W_up (physical row 2j = gate j, 2j+1 = up j)
 struct EpiSwiGLU {
