@@ -387,7 +387,7 @@ struct EpiSwiGLU {
 // slot at the end: stats[row][part], part = workgroup * NG + n-slot.  Ties keep the lowest token id.
 // PASSES = slots per wave (see gemm_wg).
 // (Exponentials are the hardware instruction, relative error about 1e-6 at the arguments that matter: they sit between
-// the groups of the weight stream, and a confidence is compared with the oracle's to the logit error, 1e-3.)
+// the groups of the weight stream, and the error of a confidence is dominated by that of the logits, about 1e-3.)
 template <int PASSES>
 struct EpiLMStats {
     float *stats;
