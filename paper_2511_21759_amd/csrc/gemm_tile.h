@@ -283,6 +283,7 @@ __global__ __launch_bounds__(512) void tile_epilogue_kernel(TileArgs g, Epi epi)
     }
     __syncthreads();
     if (nt >= g.NT) return;
+    const auto pre = epi_preload(epi, mt, nt, lane);       // (the residual tile: requested with the partial sums, not after them)
     f32x4 c = f32x4{0.f, 0.f, 0.f, 0.f};
     if (!epi.transposed(nt)) {
         for (int s = 0; s < g.KS; s++) {
@@ -301,7 +302,7 @@ __global__ __launch_bounds__(512) void tile_epilogue_kernel(TileArgs g, Epi epi)
 #pragma unroll
         for (int r = 0; r < 4; r++) c[r] *= s_rstd[4 * gq + r];
     }
-    epi(mt, nt, c, lane, 0);
+    epi_apply(epi, mt, nt, c, lane, 0, pre);
 }
 
 }  // namespace odb
