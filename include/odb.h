@@ -44,6 +44,7 @@ extern "C" {
 #define ODB_E_NOMEM (-2)
 #define ODB_E_HIP (-3)
 #define ODB_E_UNSUPPORTED (-4)
+#define ODB_E_NO_PROGRESS (-5)   /* odb_generate: a decode step left the block's MASK count unchanged */
 
 typedef struct odb_model odb_model;
 typedef struct odb_cache odb_cache;
@@ -101,7 +102,9 @@ int odb_model_init_random(odb_model *m, uint64_t seed, double std, void *stream)
  * Synchronous.  Inside the library the projection matrices are held as IEEE
  * binary16, which represents every bf16 value of magnitude 2^-16 .. 65504
  * exactly; smaller magnitudes are rounded to a multiple of 2^-24 (an absolute
- * error below 3e-8), larger ones saturate. */
+ * error below 3e-8).  A projection matrix with an element beyond that range (or
+ * a NaN) is rejected with ODB_E_UNSUPPORTED and the model is left unchanged; the
+ * embedding table and the gains are kept as given (bf16 / float). */
 int odb_model_set_tensor(odb_model *m, int tensor_id, int layer,
                          const uint16_t *host_bf16, size_t n);
 int odb_model_get_tensor(const odb_model *m, int tensor_id, int layer,
@@ -145,26 +148,27 @@ int odb_block_step(odb_model *m, const odb_cache *c, const int32_t *drafts_dev,
                    int block_off, int b, int S, float tau, float *conf_dev,
                    int32_t *argmax_dev, uint8_t *unmask_dev, void *stream);
 
-/* How odb_block_step runs.  ODB_STEP_KERNELS (default): one kernel per
- * projection / attention.  ODB_STEP_FUSED: one persistent kernel for the whole
- * step whenever it has at most 128 rows (batch*S*ceil16(b)); same results bit
- * for bit.  On MI355X the grid barriers of the fused kernel currently cost more
- * than kernel boundaries, so it is the slower of the two and stays opt-in. */
-#define ODB_STEP_FUSED 0
-#define ODB_STEP_KERNELS 1
-int odb_set_step_mode(odb_model *m, int mode);
+/* Run-time switches of a model.
+ *   ODB_OPT_KSPLIT_REDUCE (default 1): projections with few rows and a long K may run on the
+ *     streaming kernel that splits K over four workgroups, which exchange their partial sums
+ *     through device-scope stores and an arrival counter inside the one launch (the last
+ *     workgroup to arrive adds them in slice order, so results do not depend on timing).
+ *     0 routes those projections to the kernels that exchange nothing inside a launch (the
+ *     plain streaming kernel, or the tile kernel with a separate reduction pass).
+ * Errors: ODB_E_INVALID_ARG for a NULL model, an unknown option or a value outside its range. */
+enum { ODB_OPT_KSPLIT_REDUCE = 0 };
+int odb_set_option(odb_model *m, int option, int value);
 
-/* Synchronises the device and returns ODB_OK, or ODB_E_HIP if a fused step
- * kernel gave up waiting at one of its grid barriers (its outputs are then
- * invalid); clears the condition. */
+/* Synchronises the device, reads the model's status word and clears it.  Returns ODB_OK, or
+ *   ODB_E_UNSUPPORTED  an activation left the binary16 range since the last check.  Between the
+ *       kernels activations travel as binary16: Q, K, V, the SwiGLU output and, because the
+ *       RMSNorm is folded into its neighbours, the un-normalised residual stream times the
+ *       norm's gain, h[i] * g[i].  All of them must stay within +-65504 (for h * g that is a
+ *       bound on the residual stream of the model, about 3e3 times what the 8B-shaped synthetic
+ *       weights reach); a value beyond is clamped and flagged, as is a NaN.  Outputs of the
+ *       calls since the last check are then not to be trusted;
+ *   ODB_E_INVALID_ARG  odb_block_step_shared met a block with more MASK positions than n_masked. */
 int odb_model_status(odb_model *m);
-
-/* Debug aid: while dev_u64 is non-NULL the fused step kernel stores, for every
- * workgroup w, the 100 MHz wall-clock time at which it arrives at and leaves each
- * of its grid barriers into dev_u64[w*stride + 2*i], [.. + 2*i + 1] (dev uint64,
- * number of workgroups = number of compute units, stride >= 2*(2 + 5*n_layers)).
- * NULL switches it off. */
-int odb_debug_step_trace(odb_model *m, void *dev_u64, int stride);
 
 /* Test-only variants that materialise the logits (dev float, row-major
  * [batch, L-resp_off, vocab] resp. [batch, S, b, vocab]) through an unfused
@@ -284,7 +288,7 @@ int odb_speculative_jump(const odb_model *m, const int32_t *drafts_dev, const fl
 /* Block-wise generation of one response (ODB-dLLM Sec. 2.1, with the adaptive length
  * prediction of Sec. 4.1 and the jump-share decoding of Sec. 4.2 switched on by the
  * parameters).  The host loop is the library's; every decision is taken by kernels and the
- * host reads back sixteen words per forward.
+ * host reads back sixteen 32-bit words per forward.
  *
  * The response starts as resp_len MASK tokens behind the prompt and is decoded block by
  * block, front to back.  A block cycle opens with a refresh (odb_prefill over the whole
@@ -306,7 +310,7 @@ int odb_speculative_jump(const odb_model *m, const int32_t *drafts_dev, const fl
  *      with row_budget > 0 a step of that stage whose eight blocks would come to more rows
  *      runs on the four accept-jump blocks instead.
  *      A step that leaves the block's MASK count unchanged (an untrained model may attempt
- *      the MASK token itself) ends the call with ODB_E_HIP rather than repeating for ever.
+ *      the MASK token itself) ends the call with ODB_E_NO_PROGRESS rather than repeating for ever.
  * Generation ends when the next block would start at or behind the end of the sequence.
  * None of the parameter values is printed in the paper.
  *
@@ -383,7 +387,7 @@ int odb_cache_read(const odb_cache *c, int layer, int kv, int batch_index,
  * enabled. */
 enum {
     ODB_K_GEMM_QKV = 0, ODB_K_ATTENTION, ODB_K_GEMM_O, ODB_K_GEMM_GATE_UP,
-    ODB_K_GEMM_DOWN, ODB_K_GEMM_LM_HEAD, ODB_K_RMSNORM, ODB_K_STEP_FUSED, ODB_K_COUNT
+    ODB_K_GEMM_DOWN, ODB_K_GEMM_LM_HEAD, ODB_K_RMSNORM, ODB_K_COUNT
 };
 int odb_profile_begin(odb_model *m, int kernel_class, int max_launches);
 int odb_profile_end(odb_model *m, int *n_launches, float *total_ms, float *empty_pairs_ms);

@@ -21,15 +21,14 @@ SYMBOLS = (
     "odb_model_create", "odb_model_destroy", "odb_model_init_random", "odb_model_set_tensor",
     "odb_model_get_tensor", "odb_cache_create", "odb_cache_destroy", "odb_cache_length", "odb_prefill",
     "odb_block_step", "odb_prefill_logits", "odb_block_step_logits", "odb_cache_read", "odb_strerror",
-    "odb_last_error", "odb_profile_begin", "odb_profile_end", "odb_set_step_mode", "odb_model_status",
-    "odb_debug_step_trace", "odb_predict_length", "odb_accept_jump", "odb_block_step_shared",
+    "odb_last_error", "odb_profile_begin", "odb_profile_end", "odb_set_option", "odb_model_status",
+    "odb_predict_length", "odb_accept_jump", "odb_block_step_shared",
     "odb_block_step_shared_rows", "odb_block_step_shared_logits", "odb_cache_truncate", "odb_generate",
     "odb_speculative_jump",
 )
 
-KERNEL_CLASSES = ("gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "rmsnorm",
-                  "step_fused")
-STEP_FUSED, STEP_KERNELS = 0, 1
+KERNEL_CLASSES = ("gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "rmsnorm")
+OPT_KSPLIT_REDUCE = 0
 
 T_EMBED, T_WQ, T_WK, T_WV, T_WO, T_WG, T_WU, T_WD, T_LM, T_G1, T_G2, T_GF = range(12)
 
@@ -42,6 +41,14 @@ class odb_config(ctypes.Structure):
     _fields_ = [("n_layers", ctypes.c_int), ("d_model", ctypes.c_int), ("n_heads", ctypes.c_int),
                 ("head_dim", ctypes.c_int), ("d_ff", ctypes.c_int), ("vocab", ctypes.c_int),
                 ("rope_base", ctypes.c_float), ("rms_eps", ctypes.c_float), ("mask_id", ctypes.c_int)]
+
+
+_ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
+_FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
+
+
+class odb_allocator(ctypes.Structure):
+    _fields_ = [("alloc", _ALLOC_FN), ("free", _FREE_FN), ("user", ctypes.c_void_p)]
 
 
 class odb_generate_params(ctypes.Structure):
@@ -81,7 +88,7 @@ def lib() -> ctypes.CDLL:
     import torch  # noqa: F401
     L = ctypes.CDLL(LIB_PATH)
     vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
-    L.odb_model_create.argtypes = [ctypes.POINTER(odb_config), vp, ctypes.POINTER(vp)]
+    L.odb_model_create.argtypes = [ctypes.POINTER(odb_config), ctypes.POINTER(odb_allocator), ctypes.POINTER(vp)]
     L.odb_model_destroy.argtypes = [vp]
     L.odb_model_destroy.restype = None
     L.odb_model_init_random.argtypes = [vp, ctypes.c_uint64, ctypes.c_double, vp]
@@ -106,9 +113,8 @@ def lib() -> ctypes.CDLL:
     L.odb_block_step_shared.argtypes = [vp, vp, vp, ci, ci, ci, ci, cf, vp, vp, vp, vp]
     L.odb_block_step_shared_rows.argtypes = [ci, ci, ci, ci]
     L.odb_block_step_shared_logits.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp, vp]
-    L.odb_set_step_mode.argtypes = [vp, ci]
+    L.odb_set_option.argtypes = [vp, ci, ci]
     L.odb_model_status.argtypes = [vp]
-    L.odb_debug_step_trace.argtypes = [vp, vp, ci]
     L.odb_strerror.argtypes = [ci]
     L.odb_strerror.restype = ctypes.c_char_p
     L.odb_last_error.restype = ctypes.c_char_p
@@ -136,15 +142,48 @@ def _dev_i32(t):
 
 # ---- one function per C entry point ---------------------------------------------------------
 
-def odb_model_create(shape: Dict) -> int:
+class _TorchAllocator:
+    """odb_allocator backed by torch.empty(dtype=uint8, device="cuda"): PyTorch stays the one owner of device
+    memory (weights, caches, scratch and the working buffers of odb_generate all come from its caching allocator).
+    The tensors are kept alive here, by address, until the library frees them."""
+
+    def __init__(self):
+        import torch
+        self.live = {}
+
+        def alloc(nbytes, _user):
+            try:
+                t = torch.empty(max(int(nbytes), 1), dtype=torch.uint8, device="cuda")
+            except RuntimeError:           # out of memory: the library reports ODB_E_NOMEM
+                return None
+            self.live[t.data_ptr()] = t    # (torch's blocks are aligned to 512 bytes)
+            return t.data_ptr()
+
+        def free(ptr, _user):
+            self.live.pop(ptr, None)
+
+        self._alloc, self._free = _ALLOC_FN(alloc), _FREE_FN(free)      # the callbacks must outlive the model
+        self.struct = odb_allocator(self._alloc, self._free, None)
+
+
+_allocators: Dict[int, _TorchAllocator] = {}
+
+
+def odb_model_create(shape: Dict, torch_allocator: bool = True) -> int:
+    """torch_allocator: hand the library an odb_allocator backed by torch (default); False = allocator NULL, the
+    library then calls hipMalloc / hipFree itself."""
     cfg = odb_config(**{k: shape[k] for k, _ in odb_config._fields_})
     out = ctypes.c_void_p()
-    _check(lib().odb_model_create(ctypes.byref(cfg), None, ctypes.byref(out)))
+    al = _TorchAllocator() if torch_allocator else None
+    _check(lib().odb_model_create(ctypes.byref(cfg), ctypes.byref(al.struct) if al else None, ctypes.byref(out)))
+    if al:
+        _allocators[out.value] = al
     return out.value
 
 
 def odb_model_destroy(model: int) -> None:
     lib().odb_model_destroy(model)
+    _allocators.pop(model, None)
 
 
 def odb_model_init_random(model: int, seed: int, std: float) -> None:
@@ -344,17 +383,12 @@ def odb_cache_read(cache: int, layer: int, kv: int, batch_index: int, pos0: int,
     return out
 
 
-def odb_set_step_mode(model: int, mode: int) -> None:
-    _check(lib().odb_set_step_mode(model, mode))
+def odb_set_option(model: int, option: int, value: int) -> None:
+    _check(lib().odb_set_option(model, option, value))
 
 
 def odb_model_status(model: int) -> None:
     _check(lib().odb_model_status(model))
-
-
-def odb_debug_step_trace(model: int, buf, stride: int) -> None:
-    """buf: int64 CUDA tensor [n_workgroups, stride] or None."""
-    _check(lib().odb_debug_step_trace(model, buf.data_ptr() if buf is not None else None, stride))
 
 
 def odb_profile_begin(model: int, kernel_class: int, max_launches: int) -> None:

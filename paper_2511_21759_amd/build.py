@@ -14,7 +14,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libodb.so")
-SOURCES = ["api.hip", "weights.hip", "rows.hip", "gemm.hip", "attn.hip", "step.hip"]
+SOURCES = ["api.hip", "weights.hip", "rows.hip", "gemm.hip", "attn.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          # MFMA results may stay in ordinary vector registers: without this the four-wave kernels (accumulators

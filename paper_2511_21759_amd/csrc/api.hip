@@ -5,6 +5,7 @@
 #include <string.h>
 
 #include <chrono>
+#include <mutex>
 #include <new>
 
 #include "model.h"
@@ -49,15 +50,18 @@ void dev_free(const Model &m, void *p) {
     else (void)hipFree(p);
 }
 
-constexpr int kCounters = 1 << 12;     // grid-barrier / arrival counters
+constexpr int kCounters = 1 << 12;     // status word and arrival counters
 constexpr size_t kPartialBytes = 32u << 20;   // K-split partial sums of the tile GEMM
 
-// byte offsets of the per-call buffers inside the model's scratch allocation
+// byte offsets of the per-call buffers inside the scratch area of a call
 struct Plan {
     size_t h, xa, q, kf, vf, ao, act, ssq, stats, part, extra, total;
+    size_t part_bytes;
 };
 
-Plan make_plan(const odb_config &c, int rows_pad, int fresh_rows, int lm_rows_pad, bool need_stats, size_t extra_bytes = 0) {
+// part_bytes: room for K-split partial sums (the GEMM launchers split K only as far as it allows)
+Plan make_plan(const odb_config &c, int rows_pad, int fresh_rows, int lm_rows_pad, bool need_stats, size_t extra_bytes = 0,
+               size_t part_bytes = kPartialBytes) {
     Plan p;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
@@ -70,8 +74,10 @@ Plan make_plan(const odb_config &c, int rows_pad, int fresh_rows, int lm_rows_pa
     p.ao = take((size_t)rows_pad * d * 2);
     p.act = take((size_t)rows_pad * c.d_ff * 2);
     p.ssq = take((size_t)rows_pad * (d / 16) * 4);
-    p.stats = take(need_stats ? (size_t)lm_rows_pad * 256 * 6 * 3 * 4 : 0);      // room for any launch variant
-    p.part = take(kPartialBytes);
+    // one (max, sum exp, argmax) partial per row and part, as many parts as the LM-head launch for these rows writes
+    p.stats = take(need_stats ? (size_t)lm_rows_pad * lm_stats_parts(c.vocab / 16, lm_rows_pad / 16) * 3 * 4 : 0);
+    p.part = take(part_bytes);
+    p.part_bytes = part_bytes;
     p.extra = take(extra_bytes);
     p.total = off;
     return p;
@@ -163,9 +169,12 @@ struct StackIO {
     const SharedMap *shared;    // decoded-share step: ragged units (see model.h), else nullptr
 };
 
-int run_stack(Model &m, const Cache &c, const Plan &pl, const StackIO &io, hipStream_t s) {
+Workspace workspace(const Model &m, char *base, const Plan &pl) {
+    return Workspace{(float *)(base + pl.part), pl.part_bytes, m.ksplit_reduce ? m.counters + 1024 : nullptr};
+}
+
+int run_stack(Model &m, const Cache &c, char *base, const Plan &pl, const StackIO &io, hipStream_t s) {
     const odb_config &cfg = m.cfg;
-    char *base = (char *)m.scratch;
     float *h = (float *)(base + pl.h), *ssq = (float *)(base + pl.ssq);
     u16 *xa = (u16 *)(base + pl.xa), *q = (u16 *)(base + pl.q), *kf = (u16 *)(base + pl.kf),
         *vf = (u16 *)(base + pl.vf), *ao = (u16 *)(base + pl.ao), *act = (u16 *)(base + pl.act);
@@ -178,18 +187,20 @@ int run_stack(Model &m, const Cache &c, const Plan &pl, const StackIO &io, hipSt
     const size_t seq_elems = (size_t)H * c.lmax32 * dh;
     const int fresh32 = ru(io.rm.rpu_pad, 32);
     const int n_ssq = d / 16;
-    const Workspace ws{(float *)(base + pl.part), kPartialBytes, m.counters + 1024};
+    const Workspace ws = workspace(m, base, pl);
+    unsigned *status = m.counters;
     const NormIn ni = io.fused_norm ? NormIn{ssq, n_ssq, cfg.rms_eps} : NormIn{nullptr, 0, 0.f};
 
     for (int l = 0; l < cfg.n_layers; l++) {
         LayerPtrs w = layer_ptrs(m, l);
         if (!io.fused_norm) {
             ProfScope ps(m, ODB_K_RMSNORM, s);
-            launch_rmsnorm(h, w.g1, cfg.rms_eps, d, io.rm, 0, false, mt, xa, s);
+            launch_rmsnorm(h, w.g1, cfg.rms_eps, d, io.rm, 0, false, mt, xa, status, s);
         }
         QkvOut qo{};
         qo.q = q;
         qo.rope = c.rope;
+        qo.status = status;
         qo.tiles_per_unit = tpu; qo.pos_off = io.pos_off; qo.H = H; qo.dh = dh; qo.d = d;
         u16 *kc = c.k + (size_t)l * c.layer_elems, *vc = c.v + (size_t)l * c.layer_elems;
         if (io.to_cache) {
@@ -235,19 +246,19 @@ int run_stack(Model &m, const Cache &c, const Plan &pl, const StackIO &io, hipSt
         }
         // the residual epilogues prepare the norm that follows them
         const float *g_after_mlp = l + 1 < cfg.n_layers ? m.g1 + (size_t)(l + 1) * d : m.gf;
-        NormOut no_attn = io.fused_norm ? NormOut{xa, ssq, w.g2, n_ssq} : NormOut{nullptr, nullptr, nullptr, 0};
-        NormOut no_mlp = io.fused_norm ? NormOut{xa, ssq, g_after_mlp, n_ssq} : NormOut{nullptr, nullptr, nullptr, 0};
+        NormOut no_attn = io.fused_norm ? NormOut{xa, ssq, w.g2, n_ssq, status} : NormOut{nullptr, nullptr, nullptr, 0, nullptr};
+        NormOut no_mlp = io.fused_norm ? NormOut{xa, ssq, g_after_mlp, n_ssq, status} : NormOut{nullptr, nullptr, nullptr, 0, nullptr};
         {
             ProfScope ps(m, ODB_K_GEMM_O, s);
             launch_gemm_resid(ao, w.o, GemmShape{mt, d / 16, d / 32}, h, d, no_attn, ws, s);
         }
         if (!io.fused_norm) {
             ProfScope ps(m, ODB_K_RMSNORM, s);
-            launch_rmsnorm(h, w.g2, cfg.rms_eps, d, io.rm, 0, false, mt, xa, s);
+            launch_rmsnorm(h, w.g2, cfg.rms_eps, d, io.rm, 0, false, mt, xa, status, s);
         }
         {
             ProfScope ps(m, ODB_K_GEMM_GATE_UP, s);
-            launch_gemm_swiglu(xa, w.gu, GemmShape{mt, 2 * F / 16, d / 32}, ni, act, ws, s);
+            launch_gemm_swiglu(xa, w.gu, GemmShape{mt, 2 * F / 16, d / 32}, ni, act, status, ws, s);
         }
         {
             ProfScope ps(m, ODB_K_GEMM_DOWN, s);
@@ -259,14 +270,13 @@ int run_stack(Model &m, const Cache &c, const Plan &pl, const StackIO &io, hipSt
 
 // final norm + LM head.  Fused mode: on the padded rows, straight from hb/ssq.
 // Otherwise on the compacted rows (unit u, i >= skip) through the RMSNorm kernel.
-int run_head(Model &m, const Plan &pl, RowMap rm, int skip, bool fused_norm, const int32_t *tokens, int rpu_out,
+int run_head(Model &m, char *base, const Plan &pl, RowMap rm, int skip, bool fused_norm, const int32_t *tokens, int rpu_out,
              float tau, float *conf, int32_t *argmax, uint8_t *unmask, float *logits, hipStream_t s) {
     const odb_config &cfg = m.cfg;
-    char *base = (char *)m.scratch;
     float *h = (float *)(base + pl.h);
     u16 *xa = (u16 *)(base + pl.xa);
     float *stats = (float *)(base + pl.stats);
-    const Workspace ws{(float *)(base + pl.part), kPartialBytes, m.counters + 1024};
+    const Workspace ws = workspace(m, base, pl);
     const int rows = rm.units * (rm.valid - skip);
     int lm_mt, rpu_pad, valid;
     NormIn ni{nullptr, 0, 0.f};
@@ -278,7 +288,7 @@ int run_head(Model &m, const Plan &pl, RowMap rm, int skip, bool fused_norm, con
     } else {
         lm_mt = (rows + 15) / 16;
         rpu_pad = valid = rpu_out;
-        launch_rmsnorm(h, m.gf, cfg.rms_eps, cfg.d_model, rm, skip, true, lm_mt, xa, s);
+        launch_rmsnorm(h, m.gf, cfg.rms_eps, cfg.d_model, rm, skip, true, lm_mt, xa, m.counters, s);
     }
     GemmShape sh{lm_mt, cfg.vocab / 16, cfg.d_model / 32};
     if (logits) {
@@ -315,15 +325,18 @@ int prefill_impl(odb_model *mh, odb_cache *ch, const int32_t *tokens, int L, int
     c.length = L;
     char *base = (char *)m.scratch;
     launch_embed(m, tokens, rm, (float *)(base + pl.h),
-                 NormOut{(u16 *)(base + pl.xa), (float *)(base + pl.ssq), m.g1, m.cfg.d_model / 16}, s);
+                 NormOut{(u16 *)(base + pl.xa), (float *)(base + pl.ssq), m.g1, m.cfg.d_model / 16, m.counters}, s);
     StackIO io{rm, 0, true, 0, 0, 0, 1, true};
-    rc = run_stack(m, c, pl, io, s);
+    rc = run_stack(m, c, base, pl, io, s);
     if (rc) return rc;
-    return run_head(m, pl, rm, resp_off, false, nullptr, 64, 0.f, conf, argmax, nullptr, logits, s);
+    return run_head(m, base, pl, rm, resp_off, false, nullptr, 64, 0.f, conf, argmax, nullptr, logits, s);
 }
 
+// scratch_base == nullptr: the model's own scratch, grown on demand.  Otherwise the call runs in the given area of
+// scratch_bytes bytes and allocates nothing.
 int step_impl(odb_model *mh, const odb_cache *ch, const int32_t *drafts, int block_off, int b, int S, float tau,
-              float *conf, int32_t *argmax, uint8_t *unmask, float *logits, void *stream) {
+              float *conf, int32_t *argmax, uint8_t *unmask, float *logits, void *stream, char *scratch_base = nullptr,
+              size_t scratch_bytes = 0) {
     if (!mh || !ch || !drafts) return fail(ODB_E_INVALID_ARG, "block_step: NULL handle or drafts");
     Model &m = mh->m;
     const Cache &c = ch->c;
@@ -339,62 +352,33 @@ int step_impl(odb_model *mh, const odb_cache *ch, const int32_t *drafts, int blo
     HIP_TRY(hipSetDevice(m.device));
     const odb_config &cfg = m.cfg;
     const int bp = ru(b, 16), bp32 = ru(b, 32), units = c.batch * S, rows_pad = units * bp;
-    Plan pl = make_plan(cfg, rows_pad, units * bp32, rows_pad, logits == nullptr);
-    int rc = ensure_scratch(m, pl.total, s);
-    if (rc) return rc;
-    RowMap rm{units, bp, b};
-    char *base = (char *)m.scratch;
-    launch_embed(m, drafts, rm, (float *)(base + pl.h),
-                 NormOut{(u16 *)(base + pl.xa), (float *)(base + pl.ssq), m.g1, cfg.d_model / 16}, s);
-    if (b % 32)   // slots of padded keys must hold finite values: they meet zero probabilities in the P*V product
-        launch_fill_f32((float *)((char *)m.scratch + pl.vf), 0.f, (size_t)units * bp32 * cfg.d_model / 2, s);
-    StackIO io{rm, block_off, false, block_off, block_off + b, b, S, true};
-    if (!logits && m.step_mode == ODB_STEP_FUSED && rows_pad <= 128) {
-        // the whole step as one persistent kernel
-        StepArgs a;
-        memset(&a, 0, sizeof(a));
-        const int d = cfg.d_model, H = cfg.n_heads, dh = cfg.head_dim;
-        a.embed = m.w[PK_EMBED]; a.wqkv = m.w[PK_QKV]; a.wo = m.w[PK_O]; a.wgu = m.w[PK_GU]; a.wd = m.w[PK_D];
-        a.wlm = m.w[PK_LM];
-        a.qkv_stride = m.layer_elems[PK_QKV]; a.o_stride = m.layer_elems[PK_O]; a.gu_stride = m.layer_elems[PK_GU];
-        a.d_stride = m.layer_elems[PK_D];
-        a.g1 = m.g1; a.g2 = m.g2; a.gf = m.gf;
-        a.n_layers = cfg.n_layers; a.d = d; a.H = H; a.dh = dh; a.F = cfg.d_ff; a.V = cfg.vocab; a.mask_id = cfg.mask_id;
-        a.eps = cfg.rms_eps; a.tau = tau;
-        a.tokens = drafts; a.rm = rm; a.mt_total = rows_pad / 16;
-        a.h = (float *)(base + pl.h); a.ssq = (float *)(base + pl.ssq); a.stats = (float *)(base + pl.stats);
-        a.hb = (u16 *)(base + pl.xa); a.ao = (u16 *)(base + pl.ao); a.act = (u16 *)(base + pl.act);
-        const size_t seq_elems = (size_t)H * c.lmax32 * dh;
-        QkvOut &qo = a.qo;
-        qo.q = (u16 *)(base + pl.q); qo.rope = c.rope;
-        qo.tiles_per_unit = bp / 16; qo.pos_off = block_off; qo.H = H; qo.dh = dh; qo.d = d;
-        qo.k = (u16 *)(base + pl.kf); qo.k_head_stride = (size_t)bp32 * dh; qo.k_unit_stride = (size_t)H * bp32 * dh;
-        qo.v = (u16 *)(base + pl.vf); qo.v_head_stride = (size_t)bp32 * dh; qo.v_unit_stride = (size_t)H * bp32 * dh;
-        qo.set_divisors();
-        AttnArgs &at = a.attn;
-        at.q = qo.q; at.kc = c.k; at.vc = c.v;
-        at.kc_seq_stride = seq_elems; at.kc_head_stride = (size_t)c.lmax32 * dh;
-        at.vc_seq_stride = seq_elems; at.vc_head_stride = (size_t)c.lmax32 * dh;
-        at.kf = qo.k; at.vf = qo.v;
-        at.kf_unit_stride = qo.k_unit_stride; at.kf_head_stride = qo.k_head_stride;
-        at.vf_unit_stride = qo.v_unit_stride; at.vf_head_stride = qo.v_head_stride;
-        at.out = a.ao;
-        at.H = H; at.dh = dh; at.mt_total = a.mt_total; at.tiles_per_unit = bp / 16; at.units = units;
-        at.units_per_seq = S; at.L = c.length; at.blk_lo = block_off; at.blk_hi = block_off + b; at.fresh = b;
-        a.cache_layer_stride = c.layer_elems;
-        a.conf = conf; a.argmax = argmax; a.unmask = unmask;
-        a.trace = m.trace; a.trace_stride = m.trace_stride;
-        a.barrier = m.counters + 64; a.status = m.counters; a.barrier_base = m.barrier_epoch;
-        {
-            ProfScope ps(m, ODB_K_STEP_FUSED, s);
-            HIP_TRY(launch_step_kernel(a, m.n_cu, s));
-        }
-        m.barrier_epoch += step_kernel_barriers(cfg.n_layers);
-        return ODB_OK;
+    Plan pl;
+    char *base;
+    if (scratch_base) {
+        // everything but the K-split partial sums first; they get what is left of the fixed area (the GEMM launchers
+        // split K only as far as the room allows), at most what the growing scratch would give them
+        pl = make_plan(cfg, rows_pad, units * bp32, rows_pad, true, 0, 0);
+        if (pl.total + (1u << 20) > scratch_bytes)
+            return fail(ODB_E_UNSUPPORTED, "block_step: %d rows of this model need %zu bytes of scratch, the fixed "
+                        "area holds %zu", rows_pad, pl.total + (1u << 20), scratch_bytes);
+        size_t part = (scratch_bytes - pl.total) / 256 * 256;
+        pl = make_plan(cfg, rows_pad, units * bp32, rows_pad, true, 0, part < kPartialBytes ? part : kPartialBytes);
+        base = scratch_base;
+    } else {
+        pl = make_plan(cfg, rows_pad, units * bp32, rows_pad, logits == nullptr);
+        int rc = ensure_scratch(m, pl.total, s);
+        if (rc) return rc;
+        base = (char *)m.scratch;
     }
-    rc = run_stack(m, c, pl, io, s);
+    RowMap rm{units, bp, b};
+    launch_embed(m, drafts, rm, (float *)(base + pl.h),
+                 NormOut{(u16 *)(base + pl.xa), (float *)(base + pl.ssq), m.g1, cfg.d_model / 16, m.counters}, s);
+    if (b % 32)   // slots of padded keys must hold finite values: they meet zero probabilities in the P*V product
+        launch_fill_f32((float *)(base + pl.vf), 0.f, (size_t)units * bp32 * cfg.d_model / 2, s);
+    StackIO io{rm, block_off, false, block_off, block_off + b, b, S, true};
+    int rc = run_stack(m, c, base, pl, io, s);
     if (rc) return rc;
-    return run_head(m, pl, rm, 0, true, drafts, b, tau, conf, argmax, unmask, logits, s);
+    return run_head(m, base, pl, rm, 0, true, drafts, b, tau, conf, argmax, unmask, logits, s);
 }
 
 }  // namespace
@@ -409,7 +393,8 @@ const char *odb_strerror(int code) {
     case ODB_E_INVALID_ARG: return "invalid argument";
     case ODB_E_NOMEM: return "out of device memory";
     case ODB_E_HIP: return "HIP runtime error";
-    case ODB_E_UNSUPPORTED: return "unsupported configuration or device";
+    case ODB_E_UNSUPPORTED: return "unsupported configuration, device or value range";
+    case ODB_E_NO_PROGRESS: return "a decode step unmasked nothing";
     default: return "unknown error";
     }
 }
@@ -435,7 +420,7 @@ int odb_model_create(const odb_config *cfg, const odb_allocator *allocator, odb_
     m.device = dev;
     m.prof_class = -1;
     m.n_cu = prop.multiProcessorCount;
-    m.step_mode = ODB_STEP_KERNELS;
+    m.ksplit_reduce = true;
     if (allocator) { m.alloc = *allocator; m.has_alloc = true; }
     const size_t d = cfg->d_model, f = cfg->d_ff, v = cfg->vocab, nl = cfg->n_layers;
     m.layer_elems[PK_QKV] = 3 * d * d;
@@ -512,6 +497,13 @@ static int tensor_io(Model &m, int tensor_id, int layer, uint16_t *host, size_t 
         m.staging = (u16 *)dev_alloc(m, n * 2);
         if (!m.staging) return fail(ODB_E_NOMEM, "tensor staging of %zu bytes", n * 2);
         m.staging_bytes = n * 2;
+    }
+    if (to_model && tensor_id != ODB_T_EMBED && tensor_id < ODB_T_G1) {
+        // projection matrices are held as binary16: a bf16 value beyond its range (or a NaN) would be clamped silently
+        for (size_t i = 0; i < n; i++)
+            if ((host[i] & 0x7fffu) > 0x477fu)          // |x| > 65280, the largest bf16 value that binary16 holds
+                return fail(ODB_E_UNSUPPORTED, "set_tensor: element %zu of tensor %d (bf16 bits 0x%04x) lies outside the "
+                            "binary16 range the projection matrices are stored in", i, tensor_id, host[i]);
     }
     if (to_model) HIP_TRY(hipMemcpy(m.staging, host, n * 2, hipMemcpyHostToDevice));
     if (tensor_id >= ODB_T_G1) {
@@ -659,16 +651,16 @@ static int step_shared_impl(odb_model *mh, const odb_cache *ch, const int32_t *d
     launch_shared_setup(drafts, sm, block_off, cfg.mask_id, n_masked, conf, argmax, unmask, m.counters, s);
     // rows are embedded through the token-per-row table: every row is its own unit of one
     launch_embed(m, sm.rowtok, RowMap{rows_pad, 1, 1}, (float *)(base + pl.h),
-                 NormOut{(u16 *)(base + pl.xa), (float *)(base + pl.ssq), m.g1, cfg.d_model / 16}, s);
+                 NormOut{(u16 *)(base + pl.xa), (float *)(base + pl.ssq), m.g1, cfg.d_model / 16, m.counters}, s);
     // slots of padded keys must hold finite values: they meet zero probabilities in the P*V product
     launch_fill_f32((float *)(base + pl.vf), 0.f, (size_t)fresh_rows * cfg.d_model / 2, s);
     RowMap rm{c.batch, sm.bp, b};
     StackIO io{rm, block_off, false, block_off, block_off + b, b, 1, true, &sm};
-    rc = run_stack(m, c, pl, io, s);
+    rc = run_stack(m, c, base, pl, io, s);
     if (rc) return rc;
     // final norm (fused) + LM head on all rows, then the per-unit finish
     u16 *xa = (u16 *)(base + pl.xa);
-    const Workspace ws{(float *)(base + pl.part), kPartialBytes, m.counters + 1024};
+    const Workspace ws = workspace(m, base, pl);
     const NormIn ni{(float *)(base + pl.ssq), cfg.d_model / 16, cfg.rms_eps};
     const GemmShape sh{rows_pad / 16, cfg.vocab / 16, cfg.d_model / 32};
     if (logits) {
@@ -706,20 +698,16 @@ int odb_block_step_shared_logits(odb_model *m, const odb_cache *c, const int32_t
                             rowout_dev, stream);
 }
 
-int odb_set_step_mode(odb_model *mh, int mode) {
-    if (!mh) return fail(ODB_E_INVALID_ARG, "set_step_mode: model is NULL");
-    if (mode != ODB_STEP_FUSED && mode != ODB_STEP_KERNELS) return fail(ODB_E_INVALID_ARG, "set_step_mode: mode %d", mode);
-    mh->m.step_mode = mode;
-    return ODB_OK;
-}
-
-int odb_debug_step_trace(odb_model *mh, void *dev_u64, int stride) {
-    if (!mh) return fail(ODB_E_INVALID_ARG, "debug_step_trace: model is NULL");
-    if (dev_u64 && stride < 2 * (int)step_kernel_barriers(mh->m.cfg.n_layers))
-        return fail(ODB_E_INVALID_ARG, "debug_step_trace: stride %d too small", stride);
-    mh->m.trace = (unsigned long long *)dev_u64;
-    mh->m.trace_stride = stride;
-    return ODB_OK;
+int odb_set_option(odb_model *mh, int option, int value) {
+    if (!mh) return fail(ODB_E_INVALID_ARG, "set_option: model is NULL");
+    switch (option) {
+    case ODB_OPT_KSPLIT_REDUCE:
+        if (value != 0 && value != 1) return fail(ODB_E_INVALID_ARG, "set_option: KSPLIT_REDUCE takes 0 or 1");
+        mh->m.ksplit_reduce = value != 0;
+        return ODB_OK;
+    default:
+        return fail(ODB_E_INVALID_ARG, "set_option: unknown option %d", option);
+    }
 }
 
 int odb_model_status(odb_model *mh) {
@@ -731,10 +719,14 @@ int odb_model_status(odb_model *mh) {
     HIP_TRY(hipMemcpy(&host, m.counters, sizeof(host), hipMemcpyDeviceToHost));
     if (host != 0) {
         // bring flags, epoch and status back to a clean state
-        HIP_TRY(hipMemset(m.counters, 0, kCounters * sizeof(unsigned)));
-        m.barrier_epoch = 0;
-        if (host & ~2u) return fail(ODB_E_HIP, "a fused step kernel timed out at a grid barrier");
-        return fail(ODB_E_INVALID_ARG, "block_step_shared: a block held more MASK positions than n_masked");
+        // back to a clean state (only the status word: the arrival counters are zero between launches anyway)
+        HIP_TRY(hipMemset(m.counters, 0, sizeof(unsigned)));
+        if (host & kStatusSaturated)
+            return fail(ODB_E_UNSUPPORTED, "an activation left the binary16 range (|x| > 65504, or not a number) and was "
+                        "clamped: the outputs of the calls since the last status check are not to be trusted");
+        if (host & kStatusSharedOverflow)
+            return fail(ODB_E_INVALID_ARG, "block_step_shared: a block held more MASK positions than n_masked");
+        return fail(ODB_E_HIP, "unknown status bits 0x%x", host);
     }
     return ODB_OK;
 }
@@ -838,7 +830,7 @@ int odb_predict_length(const odb_model *mh, const int32_t *tokens, const float *
 }
 
 // The generation loop (ODB-dLLM Sec. 2.1 + 4.1 + 4.2): see odb.h for the order of events.  Every decision is
-// a kernel's; the host reads sixteen words back per forward to learn the length, the block's MASK count (loop
+// a kernel's; the host reads sixteen words (64 bytes) back per forward to learn the length, the block's MASK count (loop
 // exit, row bound of the decoded-share step) and what to record.
 int odb_generate(odb_model *mh, odb_cache *ch, int32_t *tokens, int prompt_len, int resp_len,
                  const odb_generate_params *gp, odb_generate_stats *st, odb_generate_event *events,
@@ -957,7 +949,7 @@ int odb_generate(odb_model *mh, odb_cache *ch, int32_t *tokens, int prompt_len, 
             if ((rc = read_back(kind))) break;
             st->step_ms += ms_since(t0);
             if (host_ctl[1] >= n_masked) {           // forced progress makes this impossible; never spin on it
-                rc = fail(ODB_E_HIP, "generate: a step left %d of %d positions masked", host_ctl[1], n_masked);
+                rc = fail(ODB_E_NO_PROGRESS, "generate: a step left %d of %d positions masked", host_ctl[1], n_masked);
                 break;
             }
             n_masked = host_ctl[1];

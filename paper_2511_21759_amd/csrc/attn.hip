@@ -1,4 +1,6 @@
 // Stand-alone launches of the attention core (see attn_core.h).
+#include <mutex>
+
 #include "attn_rows.h"
 
 namespace odb {
@@ -22,12 +24,11 @@ __global__ __launch_bounds__(64 * NW) void attn_xcd_kernel(AttnArgs a, float sc,
 // Many rows per (sequence, head): K/V tiles shared through LDS by all rows of a workgroup (attn_rows.h)
 template <int DH, int NW, int QTW, int NS, bool PIPE, bool DUAL>
 static void launch_rows(AttnArgs a, float sc, hipStream_t s) {
-    static bool attr_set = false;           // once per instantiation: the ring may need more than the default LDS limit
-    if (!attr_set) {
+    static std::once_flag attr_once;        // once per instantiation: the ring may need more than the default LDS limit
+    std::call_once(attr_once, [] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_rows_kernel<DH, NW, QTW, NS, PIPE, DUAL>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, attn_rows_smem_bytes<DH, NS>());
-        attr_set = true;
-    }
+    });
     const int tiles_per_seq = a.units_per_seq * a.tiles_per_unit;
     const int chunks = (tiles_per_seq + NW * QTW - 1) / (NW * QTW);
     dim3 grid((a.units / a.units_per_seq) * chunks, a.H);

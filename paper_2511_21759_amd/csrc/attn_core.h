@@ -1,4 +1,4 @@
-// Device-side core of the attention kernels (attn.hip) and of the fused step kernel (step.hip).
+// Device-side core of the attention kernels (attn.hip).
 //
 // Bidirectional attention of a group of query rows against the K/V cache plus,
 // in the decode step, the fresh K/V of the rows' own draft.

@@ -25,7 +25,7 @@ typedef unsigned short u16;
 
 constexpr int kTileRows = 16;
 constexpr int kTileK = 32;
-constexpr int kTileElems = 512;   // 1 KiB of bf16
+constexpr int kTileElems = 512;   // 1 KiB of binary16
 constexpr int kWave = 64;
 
 struct __attribute__((aligned(16))) frag_t { uint32_t w[4]; };   // 8 binary16
@@ -44,6 +44,14 @@ __device__ inline float bf2f(u16 b) {
 __device__ inline u16 f2h(float x) {           // binary16, round to nearest even, saturating
     x = fminf(fmaxf(x, -65504.f), 65504.f);
     return __builtin_bit_cast(u16, (_Float16)x);
+}
+// Conversions to binary16 saturate silently; a kernel that rounds activations calls this beside them so that a value
+// beyond the binary16 range (or a NaN) is reported instead: bit kStatusSaturated of the model's status word is set
+// and odb_model_status turns it into an error.  Rare path: one compare per four values otherwise.
+constexpr unsigned kStatusSharedOverflow = 2u, kStatusSaturated = 4u;
+__device__ __forceinline__ void note_saturation(unsigned *status, float a, float b, float c, float d) {
+    const float m = fmaxf(fmaxf(fabsf(a), fabsf(b)), fmaxf(fabsf(c), fabsf(d)));
+    if (status && !(m <= 65504.f)) atomicOr(status, kStatusSaturated);
 }
 __device__ inline float h2f(u16 b) {
     return (float)__builtin_bit_cast(_Float16, b);

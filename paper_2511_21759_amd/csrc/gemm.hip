@@ -1,4 +1,6 @@
 // Stand-alone launches of the weight-streaming GEMM (see gemm_core.h).
+#include <mutex>
+
 #include "gemm_big.h"
 
 namespace odb {
@@ -142,12 +144,11 @@ static void launch_big_wn(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, E
     g.ssq = ni.ssq; g.n_ssq = ni.n_ssq; g.eps = ni.eps; g.inv_d = 1.0f / (float)(sh.K_tiles * 32);
     g.m_blocks = (sh.M_tiles + MBT - 1) / MBT;
     g.n_blocks = (sh.N_tiles + 4 * WN - 1) / (4 * WN);
-    static bool attr_set = false;           // once per instantiation: the ring needs more than the default 64 KiB
-    if (!attr_set) {
+    static std::once_flag attr_once;        // once per instantiation: the ring needs more than the default 64 KiB
+    std::call_once(attr_once, [] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_big_kernel<WN, Epi, 8, MBT>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, big_smem_bytes(WN));
-        attr_set = true;
-    }
+    });
     dim3 grid(8 * g.m_blocks * ((g.n_blocks + 7) / 8));
     gemm_big_kernel<WN, Epi, 8, MBT><<<grid, 64 * 8, big_smem_bytes(WN), s>>>(g, e);
 }
@@ -239,8 +240,9 @@ void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int l
         launch_big(a, w, sh, NormIn{nullptr, 0, 0.f}, e, s);
     else launch_tile(a, w, sh, NormIn{nullptr, 0, 0.f}, e, ws, true, s);
 }
-void launch_gemm_swiglu(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, u16 *act, Workspace ws, hipStream_t s) {
-    EpiSwiGLU e{act, sh.M_tiles};
+void launch_gemm_swiglu(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, u16 *act, unsigned *status, Workspace ws,
+                        hipStream_t s) {
+    EpiSwiGLU e{act, sh.M_tiles, status};
     if (sh.M_tiles <= 2) launch_stream<2, 6, 1, 8, true>(xa, w, sh, ni, e, s);
     else if (sh.M_tiles <= 4) launch_stream<4, 6, 1, 8, true>(xa, w, sh, ni, e, s);
     else if (sh.M_tiles <= 6) launch_stream<6, 6, 1, 8, true>(xa, w, sh, ni, e, s);

@@ -1,6 +1,5 @@
-// Device-side core of the weight-streaming bf16 MFMA GEMM  C[M,N] = A[M,K] * W[N,K]^T
-// for few rows, shared by the stand-alone GEMM kernels (gemm.hip) and the fused
-// decode-step kernel (step.hip).
+// Device-side core of the weight-streaming binary16 MFMA GEMM  C[M,N] = A[M,K] * W[N,K]^T
+// for few rows (launched from gemm.hip).
 //
 // A (activations) is tile-major [k_tile][m_tile][512], W is [n_tile][k_tile][512]
 // (see common.h for the tile).  The work is persistent in spirit: nwg workgroups
@@ -33,7 +32,7 @@ constexpr int WK = 8;    // waves per workgroup = K slices
 struct GemmArgs {
     const u16 *A, *W;
     int KT, MT_total, NT;
-    // fused RMSNorm of the input rows: A holds bf16(x * gain) and ssq[row][0..n_ssq) partial sums
+    // fused RMSNorm of the input rows: A holds binary16(x * gain) and ssq[row][0..n_ssq) partial sums
     // of x^2; the result rows are scaled by 1/sqrt(sum/d + eps).  ssq == nullptr: A is used as is.
     const float *ssq;
     int n_ssq;
@@ -275,7 +274,7 @@ __device__ __forceinline__ void gemm_wg(const GemmArgs &g, Epi epi, int wg, int 
 // Default:    lane l holds C[row = 16*mt + (l&15)][col = 16*nt + 4*(l>>4) + r], r = 0..3.
 // Transposed: lane l holds C[row = 16*mt + 4*(l>>4) + r][col = 16*nt + (l&15)].
 
-__device__ inline void st_bf16x4(u16 *p, float a, float b, float c, float d) {
+__device__ inline void st_f16x4(u16 *p, float a, float b, float c, float d) {
     uint2 v;
     v.x = pack2(a, b);
     v.y = pack2(c, d);
@@ -318,16 +317,18 @@ struct EpiQKV {
             float y2 = c[2] * cs1.x - c[3] * cs1.y;
             float y3 = c[3] * cs1.x + c[2] * cs1.y;
             const int kk = (p0 & 16) + 4 * g;                 // k-element of y0 inside the 32-wide tile
-            st_bf16x4(dst + ((kk >> 3) * 16 + mi) * 8 + (kk & 7), y0, y1, y2, y3);
+            note_saturation(o.status, y0, y1, y2, y3);
+            st_f16x4(dst + ((kk >> 3) * 16 + mi) * 8 + (kk & 7), y0, y1, y2, y3);
         } else {
             // V^T tile: row = channel, the 32 keys of a tile sit in k-slot 8*g + 4*half + r
             u16 *dst = vdst + hd * vhs + ((size_t)(tu >> 1) * (o.dh / 16) + p0 / 16) * kTileElems + lane * 8 + 4 * (tu & 1);
-            st_bf16x4(dst, c[0], c[1], c[2], c[3]);
+            note_saturation(o.status, c[0], c[1], c[2], c[3]);
+            st_f16x4(dst, c[0], c[1], c[2], c[3]);
         }
     }
 };
 
-// h += C.  With a NormOut it also prepares the next RMSNorm: hb = bf16(h * gain) in the
+// h += C.  With a NormOut it also prepares the next RMSNorm: hb = binary16(h * gain) in the
 // operand layout and the sum of squares of this tile's 16 columns per row.
 struct EpiResid {
     float *h;
@@ -349,8 +350,10 @@ struct EpiResid {
         if (no.hb) {
             f32x4 gn = *reinterpret_cast<const f32x4 *>(no.gain + col);
             const int kk = (nt & 1) * 16 + 4 * g;
-            st_bf16x4(no.hb + ((size_t)(nt >> 1) * mt_total + mt) * kTileElems + ((kk >> 3) * 16 + mi) * 8 + (kk & 7),
-                      v[0] * gn[0], v[1] * gn[1], v[2] * gn[2], v[3] * gn[3]);
+            const f32x4 y = v * gn;
+            note_saturation(no.status, y[0], y[1], y[2], y[3]);
+            st_f16x4(no.hb + ((size_t)(nt >> 1) * mt_total + mt) * kTileElems + ((kk >> 3) * 16 + mi) * 8 + (kk & 7),
+                     y[0], y[1], y[2], y[3]);
             float q = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
             q += __shfl_xor(q, 16);
             q += __shfl_xor(q, 32);
@@ -366,6 +369,7 @@ __device__ __forceinline__ void epi_apply(EpiResid &e, int mt, int nt, f32x4 c, 
 struct EpiSwiGLU {
     u16 *act;
     int mt_total;
+    unsigned *status;
     __device__ bool transposed(int) const { return false; }
     __device__ void finish(int, int, int, int) const {}
     __device__ void operator()(int mt, int nt, f32x4 c, int lane, int) const {
@@ -376,6 +380,7 @@ struct EpiSwiGLU {
         float y0 = c[0] * __builtin_amdgcn_rcpf(1.0f + __expf(-c[0])) * c[1];
         float y1 = c[2] * __builtin_amdgcn_rcpf(1.0f + __expf(-c[2])) * c[3];
         const int kk = j & 31;
+        note_saturation(status, y0, y1, 0.f, 0.f);
         u16 *dst = act + ((size_t)(j >> 5) * mt_total + mt) * kTileElems + ((kk >> 3) * 16 + mi) * 8 + (kk & 7);
         *reinterpret_cast<uint32_t *>(dst) = pack2(y0, y1);
     }

@@ -1,4 +1,4 @@
-// bf16 MFMA GEMM  C[M,N] = A[M,K] * W[N,K]^T  for 33 rows and more (the multi-draft step,
+// binary16 MFMA GEMM  C[M,N] = A[M,K] * W[N,K]^T  for 33 rows and more (the multi-draft step,
 // the prefill, the long-context step).  Same operand layouts and epilogues as gemm_core.h.
 //
 // A workgroup computes a 128-row block x (8*NGW n-tiles) x one slice of K.  Its eight waves split

@@ -32,11 +32,8 @@ struct Model {
     // scratch, grown on demand (see api.hip)
     void *scratch;
     size_t scratch_bytes;
-    unsigned *counters;        // [0] status word of the fused step kernel, [64..] its per-workgroup barrier flags
-    unsigned barrier_epoch;    // barrier epoch reached once all launched step kernels have finished
-    unsigned long long *trace; // debug: barrier timestamps of the fused step kernel (device memory of the caller)
-    int trace_stride;
-    int step_mode;             // 0: fused persistent kernel when the shape allows, 1: separate kernels
+    unsigned *counters;        // [0] status word (kStatus* bits), [1024..2048) arrival counters of the K-split GEMM
+    bool ksplit_reduce;        // the K-split streaming GEMM with its in-kernel reduction may be used (ODB_OPT_KSPLIT_REDUCE)
     int n_cu;
     u16 *staging;              // set/get tensor staging
     size_t staging_bytes;
@@ -63,11 +60,12 @@ void launch_fill_i32(int32_t *p, int32_t v, size_t n, hipStream_t s);
 void launch_rope_table(float *table, int n_pos, int dh, double base, hipStream_t s);
 void launch_cache_read(const Cache &c, int layer, int kv, int batch_index, int pos0, int n, float *out, hipStream_t s);
 
-// Fused RMSNorm.  NormIn: the GEMM input holds bf16(x * gain) and ssq[row][0..n_ssq) are partial
+// Fused RMSNorm.  NormIn: the GEMM input holds binary16(x * gain) and ssq[row][0..n_ssq) are partial
 // sums of x^2 over the row; output rows are scaled by 1/sqrt(sum/d + eps) (ssq == nullptr: off).
-// NormOut: the residual epilogue also emits that pair for the next norm (hb == nullptr: off).
+// NormOut: the residual epilogue also emits that pair for the next norm (hb == nullptr: off);
+// status: the model's status word, where a value beyond the binary16 range is reported (may be nullptr).
 struct NormIn { const float *ssq; int n_ssq; float eps; };
-struct NormOut { u16 *hb; float *ssq; const float *gain; int n_ssq; };
+struct NormOut { u16 *hb; float *ssq; const float *gain; int n_ssq; unsigned *status; };
 
 // ---- rows.hip ---------------------------------------------------------------
 // Row bookkeeping.  Rows are grouped in "units" (a draft in the step, a
@@ -79,7 +77,7 @@ void launch_embed(const Model &m, const int32_t *tokens, RowMap rm, float *h, No
 // xa = bf16(rmsnorm(h) * gain) in tile-major [d/32][mt_total][512]; if `compact`, destination
 // row j = u*(valid-skip) + (i-skip) for source row (u, i >= skip), else the same row.
 void launch_rmsnorm(const float *h, const float *gain, float eps, int d, RowMap rm, int skip, bool compact,
-                    int dst_mt_total, u16 *xa, hipStream_t s);
+                    int dst_mt_total, u16 *xa, unsigned *status, hipStream_t s);
 // stats rows come in units of rpu_pad rows of which the first rpu are real; the `rows` outputs are compact
 void launch_accept_jump(const int32_t *drafts, const float *conf, const int32_t *argmax, const uint8_t *unmask,
                         const int32_t *cand_pos, const int32_t *cand_tok, int batch, int b, int mask_id, int32_t *chosen,
@@ -138,6 +136,7 @@ struct QkvOut {
     u16 *k; size_t k_unit_stride, k_head_stride;   // tiles [pos/16][dh/32]
     u16 *v; size_t v_unit_stride, v_head_stride;   // tiles [pos/32][dh/16], keys permuted inside
     const float *rope;         // (cos,sin) table
+    unsigned *status;          // the model's status word (saturation of a binary16 conversion), may be nullptr
     int tiles_per_unit, pos_off, H, dh, d;
     FastDiv fd_d, fd_dh, fd_tpu, fd_tpu_b;     // by d / 16, dh / 16, tiles_per_unit, tiles_per_unit_b: set_divisors()
     void set_divisors() {
@@ -157,7 +156,8 @@ struct Workspace { float *partial; size_t partial_bytes; unsigned *arrive; };
 void launch_gemm_qkv(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, QkvOut out, Workspace ws, hipStream_t s);
 void launch_gemm_resid(const u16 *a, const u16 *w, GemmShape sh, float *h, int ldh, NormOut no, Workspace ws,
                        hipStream_t s);
-void launch_gemm_swiglu(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, u16 *act, Workspace ws, hipStream_t s);
+void launch_gemm_swiglu(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, u16 *act, unsigned *status, Workspace ws,
+                        hipStream_t s);
 // stats[row][lm_stats_parts(N_tiles, M_tiles)][3]: one partial (max, sum exp, argmax) per row and (workgroup, n-slot)
 int lm_stats_parts(int n_tiles, int m_tiles);
 void launch_gemm_lmstats(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, float *stats, Workspace ws,
@@ -190,35 +190,5 @@ struct AttnArgs {
     const unsigned long long *dmask;
 };
 void launch_attention(AttnArgs a, hipStream_t s);
-
-// ---- step.hip ---------------------------------------------------------------
-// Everything the fused decode-step kernel needs (pointers into the model, the cache and the
-// scratch of one call).
-struct StepArgs {
-    const u16 *embed, *wqkv, *wo, *wgu, *wd, *wlm;      // layer 0 of each kind
-    size_t qkv_stride, o_stride, gu_stride, d_stride;   // elements per layer
-    const float *g1, *g2, *gf;
-    int n_layers, d, H, dh, F, V, mask_id;
-    float eps, tau;
-    const int32_t *tokens;
-    RowMap rm;
-    int mt_total;
-    float *h, *ssq, *stats;
-    u16 *hb, *ao, *act;
-    QkvOut qo;                 // q / fresh K / fresh V destinations
-    AttnArgs attn;             // kc, vc point at layer 0
-    size_t cache_layer_stride;
-    float *conf;
-    int32_t *argmax;
-    uint8_t *unmask;
-    unsigned *barrier, *status;
-    unsigned barrier_base;
-    unsigned long long *trace;  // optional [nwg][trace_stride] timestamps, two per barrier
-    int trace_stride;
-};
-bool step_kernel_supports(const StepArgs &a);
-size_t step_kernel_max_wgs(int device);
-hipError_t launch_step_kernel(const StepArgs &a, int nwg, hipStream_t s);
-inline unsigned step_kernel_barriers(int n_layers) { return 2u + 5u * (unsigned)n_layers; }
 
 }  // namespace odb

@@ -24,7 +24,8 @@ __device__ inline float wave_sum(float v) {
 
 // One wave per destination row.  xa tile (kt, mt) holds rows 16*mt.., k 32*kt.. .
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *h, const float *gain, float eps, int d, RowMap rm,
-                                                      int skip, int compact, int dst_rows, int dst_mt_total, u16 *xa) {
+                                                      int skip, int compact, int dst_rows, int dst_mt_total, u16 *xa,
+                                                      unsigned *status) {
     int lane = threadIdx.x & 63;
     int j = blockIdx.x * 4 + (threadIdx.x >> 6);          // destination row
     if (j >= dst_mt_total * 16) return;
@@ -54,6 +55,8 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *h, const floa
             float4 b = *reinterpret_cast<const float4 *>(x + q * 8 + 4);
             float4 ga = *reinterpret_cast<const float4 *>(gain + q * 8);
             float4 gb = *reinterpret_cast<const float4 *>(gain + q * 8 + 4);
+            note_saturation(status, a.x * rstd * ga.x, a.y * rstd * ga.y, a.z * rstd * ga.z, a.w * rstd * ga.w);
+            note_saturation(status, b.x * rstd * gb.x, b.y * rstd * gb.y, b.z * rstd * gb.z, b.w * rstd * gb.w);
             f.w[0] = pack2(a.x * rstd * ga.x, a.y * rstd * ga.y);
             f.w[1] = pack2(a.z * rstd * ga.z, a.w * rstd * ga.w);
             f.w[2] = pack2(b.x * rstd * gb.x, b.y * rstd * gb.y);
@@ -65,11 +68,11 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *h, const floa
 }
 
 void launch_rmsnorm(const float *h, const float *gain, float eps, int d, RowMap rm, int skip, bool compact,
-                    int dst_mt_total, u16 *xa, hipStream_t s) {
+                    int dst_mt_total, u16 *xa, unsigned *status, hipStream_t s) {
     int dst_rows = compact ? rm.units * (rm.valid - skip) : rm.units * rm.rpu_pad;
     int padded = dst_mt_total * 16;
     rmsnorm_kernel<<<dim3((padded + 3) / 4), 256, 0, s>>>(h, gain, eps, d, rm, skip, compact ? 1 : 0, dst_rows,
-                                                          dst_mt_total, xa);
+                                                          dst_mt_total, xa, status);
 }
 
 __global__ __launch_bounds__(1024) void lm_finish_kernel(const float *stats, int n_part, int rows, int rpu, int rpu_pad,

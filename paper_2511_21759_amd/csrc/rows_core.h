@@ -1,4 +1,4 @@
-// Row-wise device functions shared by rows.hip and the fused step kernel (step.hip):
+// Row-wise device functions of rows.hip:
 // embedding gather and the final reduction of the LM-head statistics with the
 // threshold unmask.
 #pragma once
@@ -39,9 +39,11 @@ __device__ __forceinline__ void embed_row(int r, const u16 *embed, const int32_t
             for (int half = 0; half < 2; half++) {
                 frag_t f;
 #pragma unroll
-                for (int j = 0; j < 4; j++)
-                    f.w[j] = pack2(x[half * 8 + 2 * j] * gn[half * 8 + 2 * j],
-                                     x[half * 8 + 2 * j + 1] * gn[half * 8 + 2 * j + 1]);
+                for (int j = 0; j < 4; j++) {
+                    const float y0 = x[half * 8 + 2 * j] * gn[half * 8 + 2 * j], y1 = x[half * 8 + 2 * j + 1] * gn[half * 8 + 2 * j + 1];
+                    note_saturation(no.status, y0, y1, 0.f, 0.f);
+                    f.w[j] = pack2(y0, y1);
+                }
                 const int chunk = (nt & 1) * 2 + half;
                 *reinterpret_cast<frag_t *>(no.hb + ((size_t)(nt >> 1) * mt_total + (r >> 4)) * kTileElems +
                                             (chunk * 16 + (r & 15)) * 8) = f;

@@ -18,7 +18,30 @@ from paper_2511_21759_amd import workloads as W
 pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
-LOGIT_TOL, KV_TOL = 2e-2, 1e-2
+LOGIT_TOL, KV_TOL, MARGIN, TAU_BAND = 2e-2, 1e-2, 1e-2, 1e-3
+LITERAL = {"argmax_rows": 0, "unmask_positions": 0}     # rows on which the bar was asserted as stated
+
+
+def check_unmask_literal(um, drafts, g, prefix, tau, mask_id, tag):
+    """Acceptance flags against the stored oracle's wherever the bar as stated binds: MASK positions whose top-2
+    probability margin exceeds 1e-2 and whose confidence is further than 1e-3 from tau; a position below tau is
+    flagged only as the forced pick, compared where the most confident MASK position leads by more than 1e-2."""
+    conf_o, ref = g[prefix + "_conf"], g[prefix + "_unmask"]
+    top = g[prefix + "_top_logits"].astype(np.float64)
+    margin = conf_o * (1.0 - np.exp(top[..., -2] - top[..., -1]))
+    for s in range(drafts.shape[0]):
+        masked = drafts[s] == mask_id
+        if not masked.any():
+            continue
+        cm = np.sort(conf_o[s][masked])[::-1]
+        forced_clear = cm.size < 2 or cm[0] - cm[1] > MARGIN
+        for i in np.flatnonzero(masked):
+            if not (margin[s][i] > MARGIN and abs(conf_o[s][i] - tau) > TAU_BAND):
+                continue
+            if not conf_o[s][i] > tau and not forced_clear and conf_o[s][i] >= cm[0] - MARGIN:
+                continue
+            assert um[s][i] == ref[s][i], "%s: unmask[%d][%d]" % (tag, s, i)
+            LITERAL["unmask_positions"] += 1
 
 
 def cuda_i32(a):
@@ -49,6 +72,14 @@ def check_rows(logits, conf, am, g, prefix, tag, same_gemm=True):
     ids = g[prefix + "_top_ids"]
     ok = ((ids == am[..., None]) & (top >= top[..., -1:] - band)).any(-1)
     assert np.all(ok[~strict]), "%s: argmax outside the error band" % tag
+    # the bar as stated: no mismatch on any row whose two largest probabilities differ by more than 1e-2
+    # (p1 = conf, p2 = conf * exp(z2 - z1), from the stored eight largest logits)
+    margin = conf_o * (1.0 - np.exp(top[..., -2] - top[..., -1]))
+    clear = margin > MARGIN
+    bad = clear & (am != am_o)
+    assert not bad.any(), "%s: argmax differs on %d of %d rows with top-2 probability margin > 1e-2" % (
+        tag, int(bad.sum()), int(clear.sum()))
+    LITERAL["argmax_rows"] += int(clear.sum())
     if same_gemm:
         # the fused statistics agree with the unfused logits when the same kernels produced both
         assert np.array_equal(am, logits.argmax(-1)), "%s: fused argmax vs stored logits" % tag
@@ -84,19 +115,16 @@ def test_configs_1_and_2_against_stored_oracle(fname):
         # config 2 (S = 4); its draft 0 is config 1
         d = cuda_i32(wl.drafts)
         z = B.odb_block_step_logits(model, cache, d, wl.block_off, shape["vocab"]).cpu().numpy()[0]
-        for mode in (B.STEP_KERNELS, B.STEP_FUSED):
-            B.odb_set_step_mode(model, mode)
-            conf, am, um = (t.cpu().numpy()[0] for t in B.odb_block_step(model, cache, d, wl.block_off, float(g["tau"])))
-            B.odb_model_status(model)
-            e, rel, ns, n = check_rows(z, conf, am, g, "step", fname + " step", same_gemm=mode == B.STEP_KERNELS)
-            assert np.array_equal(um, g["step_unmask"]), "unmask (tau = 0.9 is far from every confidence here)"
-            d1 = cuda_i32(W.config1().drafts)
-            c1, a1, u1 = (t.cpu().numpy()[0] for t in B.odb_block_step(model, cache, d1, wl.block_off, float(g["tau"])))
-            # S = 1 and S = 4 run different GEMM kernels (other summation orders): same forced pick, confidences within bf16 noise
-            assert np.array_equal(u1[0], um[0]) and np.allclose(c1[0], conf[0], rtol=5e-2)
-            assert (a1[0] == am[0]).mean() >= 0.9
+        conf, am, um = (t.cpu().numpy()[0] for t in B.odb_block_step(model, cache, d, wl.block_off, float(g["tau"])))
+        B.odb_model_status(model)
+        e, rel, ns, n = check_rows(z, conf, am, g, "step", fname + " step")
+        assert np.array_equal(um, g["step_unmask"]), "unmask (tau = 0.9 is far from every confidence here)"
+        d1 = cuda_i32(W.config1().drafts)
+        c1, a1, u1 = (t.cpu().numpy()[0] for t in B.odb_block_step(model, cache, d1, wl.block_off, float(g["tau"])))
+        # S = 1 and S = 4 run different GEMM kernels (other summation orders): same forced pick, confidences within binary16 noise
+        assert np.array_equal(u1[0], um[0]) and np.allclose(c1[0], conf[0], rtol=5e-2)
+        assert (a1[0] == am[0]).mean() >= 0.9
         print("%s step: max sampled logit err %.4f (rel %.2e), %d/%d rows bit-exact-checked" % (fname, e, rel, ns, n))
-        B.odb_set_step_mode(model, B.STEP_KERNELS)
         B.odb_cache_destroy(cache)
     finally:
         B.odb_model_destroy(model)
@@ -143,14 +171,16 @@ def test_batch4_long_block_against_stored_oracle():
         B.odb_model_destroy(model)
 
 
-@pytest.mark.parametrize("resp", [512, 128])
+@pytest.mark.parametrize("resp", [512, 256, 128])
 def test_config3_prefill_against_stored_oracle(resp):
-    """Config 3's refreshes (512 prompt + 512 / 128 MASK positions: 1024 and 640 rows, the shapes bench.py times)
-    at the full 8B width with two layers against stored oracle outputs: the 256-row GEMM blocks in their 192-column
-    form at 1024 rows, the 128-row tile kernel at 640 rows, the K/V-sharing attention kernel over a thousand keys."""
-    path = os.path.join(GOLDEN, "config3_oracle_2L.npz")
+    """Config 3's refreshes (512 prompt + 512 / 256 / 128 MASK positions: 1024, 768 and 640 rows, the lengths the
+    adaptive length prediction shrinks the refresh to) at the full 8B width with two layers against stored oracle
+    outputs: each length picks its own GEMM block shapes, and the K/V-sharing attention kernel runs over up to a
+    thousand keys."""
+    fname = "config3_r256_oracle_2L.npz" if resp == 256 else "config3_oracle_2L.npz"
+    path = os.path.join(GOLDEN, fname)
     if not os.path.exists(path):
-        pytest.skip("config3_oracle_2L.npz has not been generated (tests/golden/make_8b_golden.py prefill)")
+        pytest.skip("%s has not been generated (tests/golden/make_8b_golden.py prefill / prefill256)" % fname)
     g = np.load(path)
     tag = "r%d_" % resp
     view = {k[len(tag):]: g[k] for k in g.files if k.startswith(tag)}
@@ -343,6 +373,101 @@ def test_full_size_properties_without_an_oracle():
         assert torch.allclose(torch.log(c64), torch.log(c16).expand(-1, 4, -1), atol=0.05)
         assert (a64 == a16.expand(-1, 4, -1)).float().mean() > 0.9 and torch.equal(c64[:, 0], c64[:, 3])
         B.odb_model_status(model)
+        B.odb_cache_destroy(cache)
+    finally:
+        B.odb_model_destroy(model)
+
+
+def test_config4_at_its_real_lengths_against_stored_oracle():
+    """Config 4 as bench.py times it (batch 4, 2048 prompt + 1024 response positions, block of 64, S = 8: 2048 step
+    rows against 3008 cached keys per sequence) at the full 8B width with two layers.  Sequences and drafts are
+    independent, so the stored oracle outputs of the refresh of sequences 0 and 3 (K/V at sampled positions) and
+    of drafts 0 and 7 of sequence 0 and draft 3 of sequence 3 pin the whole call."""
+    path = os.path.join(GOLDEN, "config4_oracle_2L.npz")
+    if not os.path.exists(path):
+        pytest.skip("config4_oracle_2L.npz has not been generated (tests/golden/make_8b_golden.py config4)")
+    g = np.load(path)
+    shape = dict(W.MODEL_SHAPES["8b"], n_layers=int(g["n_layers"]))
+    wl = W.config4()
+    assert wl.block_off == int(g["block_off"])
+    model = B.odb_model_create(shape)
+    try:
+        B.odb_model_init_random(model, W.WEIGHT_SEED, W.WEIGHT_STD)
+        Bn, L = wl.tokens.shape
+        cache = B.odb_cache_create(model, Bn, L)
+        B.odb_prefill(model, cache, cuda_i32(wl.tokens), L - 64)
+        for bi in g["seqs"]:
+            for layer in range(shape["n_layers"]):
+                for kv, name in ((0, "k"), (1, "v")):
+                    got = B.odb_cache_read(cache, layer, kv, int(bi), 0, L, 32, 128)[g["kv_pos"]]
+                    err = np.abs(got - g["%s_sample_%d" % (name, bi)][layer]).max() / g["%s_absmax_%d" % (name, bi)][layer]
+                    assert err <= KV_TOL, "config4: cache seq %d layer %d %s: %.3g" % (bi, layer, name, err)
+        d = cuda_i32(wl.drafts)
+        tau = float(g["tau"])
+        z_all = B.odb_block_step_logits(model, cache, d, wl.block_off, shape["vocab"])
+        conf, am, um = (t.cpu().numpy() for t in B.odb_block_step(model, cache, d, wl.block_off, tau))
+        B.odb_model_status(model)
+        for i, (bi, s_) in enumerate(g["picks"]):
+            view = {k[len("p%d_" % i):]: g[k] for k in g.files if k.startswith("p%d_" % i)}
+            view = {"step_" + k: v for k, v in view.items()}
+            view["step_logit_cols"] = g["logit_cols"]
+            z = z_all[bi, s_].cpu().numpy()
+            e, rel, ns, n = check_rows(z, conf[bi, s_], am[bi, s_], view, "step", "config4 seq %d draft %d" % (bi, s_))
+            assert np.array_equal(um[bi, s_], view["step_unmask"]), "unmask of sequence %d draft %d" % (bi, s_)
+            print("\nconfig4 seq %d draft %d: logit err rel %.2e (%d/%d rows strict)" % (bi, s_, rel, ns, n))
+        # the other drafts and sequences: finite, one forced pick each (random weights never reach tau)
+        assert np.isfinite(conf).all() and (conf > 0).all() and (um.sum(-1) == (wl.drafts == shape["mask_id"]).any(-1)).all()
+        del z_all
+        B.odb_cache_destroy(cache)
+    finally:
+        B.odb_model_destroy(model)
+
+
+@pytest.mark.parametrize("gain", [8, 16])
+def test_peaked_configs_1_and_2_assert_the_decision_bar_as_stated(gain):
+    """Configs 1 and 2 at the full 8B width (two layers) with the final-norm gain at 8 / 16, where confidences
+    straddle tau = 0.9 and most rows have a top-2 probability margin above 1e-2: argmax and unmask are asserted
+    against the stored oracle on every such row, literally, in the refresh, the four-draft step and the one-draft
+    step, and the counts of rows the bar bound on must not be zero."""
+    path = os.path.join(GOLDEN, "config12_peaked_oracle_2L.npz")
+    if not os.path.exists(path):
+        pytest.skip("config12_peaked_oracle_2L.npz has not been generated (tests/golden/make_8b_golden.py peaked)")
+    g0 = np.load(path)
+    tag = "g%d_" % gain
+    g = {k[len(tag):]: g0[k] for k in g0.files if k.startswith(tag)}
+    g["step_logit_cols"] = g0["step_logit_cols"]
+    shape = dict(W.MODEL_SHAPES["8b"], n_layers=int(g0["n_layers"]))
+    wl = W.config2()
+    tau = float(g0["tau"])
+    model = B.odb_model_create(shape)
+    LITERAL.update(argmax_rows=0, unmask_positions=0)
+    try:
+        B.odb_model_init_random(model, W.WEIGHT_SEED, W.WEIGHT_STD)
+        B.odb_model_set_tensor(model, B.T_GF, 0, np.full(shape["d_model"], {8: 0x4100, 16: 0x4180}[gain], np.uint16))
+        cache = B.odb_cache_create(model, 1, wl.tokens.shape[1])
+        tok = cuda_i32(wl.tokens)
+        zp = B.odb_prefill_logits(model, cache, tok, wl.resp_off, shape["vocab"]).cpu().numpy()[0]
+        conf_p, am_p = (t.cpu().numpy()[0] for t in B.odb_prefill(model, cache, tok, wl.resp_off))
+        check_rows(zp, conf_p, am_p, g, "prefill", "peaked %d refresh" % gain)
+        n_refresh = LITERAL["argmax_rows"]
+        d = cuda_i32(wl.drafts)
+        z = B.odb_block_step_logits(model, cache, d, wl.block_off, shape["vocab"]).cpu().numpy()[0]
+        conf, am, um = (t.cpu().numpy()[0] for t in B.odb_block_step(model, cache, d, wl.block_off, tau))
+        e, rel, ns, n = check_rows(z, conf, am, g, "step", "peaked %d step" % gain)
+        check_unmask_literal(um, wl.drafts[0], g, "step", tau, shape["mask_id"], "peaked %d step" % gain)
+        n_step = LITERAL["argmax_rows"] - n_refresh
+        # config 1: draft 0 alone (32 rows: the few-row kernels)
+        z1 = B.odb_block_step_logits(model, cache, d[:, :1].contiguous(), wl.block_off, shape["vocab"]).cpu().numpy()[0]
+        c1, a1, u1 = (t.cpu().numpy()[0] for t in B.odb_block_step(model, cache, d[:, :1].contiguous(), wl.block_off, tau))
+        g1 = {k: (v[:1] if k.startswith("step_") and getattr(v, "ndim", 0) >= 2 else v) for k, v in g.items()}
+        check_rows(z1, c1, a1, g1, "step", "peaked %d one-draft step" % gain)
+        check_unmask_literal(u1, wl.drafts[0][:1], g1, "step", tau, shape["mask_id"], "peaked %d one-draft step" % gain)
+        B.odb_model_status(model)
+        print("\npeaked gain %d: logit err rel %.2e; decision bar asserted as stated on %d refresh rows, %d + %d step rows, "
+              "%d unmask positions; oracle step confidences %.3g .. %.3g" % (
+                  gain, rel, n_refresh, n_step, LITERAL["argmax_rows"] - n_refresh - n_step, LITERAL["unmask_positions"],
+                  g["step_conf"].min(), g["step_conf"].max()))
+        assert n_refresh > 0 and n_step > 0 and LITERAL["unmask_positions"] > 0
         B.odb_cache_destroy(cache)
     finally:
         B.odb_model_destroy(model)
