@@ -170,6 +170,22 @@ int odb_set_option(odb_model *m, int option, int value);
  *   ODB_E_INVALID_ARG  odb_block_step_shared met a block with more MASK positions than n_masked. */
 int odb_model_status(odb_model *m);
 
+/* odb_block_step for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and same results as odb_block_step, but every intermediate buffer lives in a fixed
+ * area of ODB_STATIC_SCRATCH_BYTES bytes that is part of the loaded library (one per GPU,
+ * held until the process ends); the call itself allocates and frees nothing.
+ * A step whose rows need more than that area is rejected with ODB_E_UNSUPPORTED before
+ * anything is launched (at the 8B shape of the paper's models, d = 4096, d_ff = 12288,
+ * vocab = 126464, the area holds steps of up to 128 rows).  All models on one GPU share the
+ * area and every call overwrites what the last one left there: calls on one GPU that overlap
+ * in time, on whatever streams or models, race; issue them one after the other on one
+ * stream.  Other errors as odb_block_step. */
+#define ODB_STATIC_SCRATCH_BYTES (32u << 20)
+int odb_block_step_static(odb_model *m, const odb_cache *c, const int32_t *drafts_dev,
+                          int block_off, int b, int S, float tau, float *conf_dev,
+                          int32_t *argmax_dev, uint8_t *unmask_dev, void *stream);
+
 /* Test-only variants that materialise the logits (dev float, row-major
  * [batch, L-resp_off, vocab] resp. [batch, S, b, vocab]) through an unfused
  * store instead of the fused confidence/argmax reduction. */

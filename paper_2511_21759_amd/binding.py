@@ -22,13 +22,14 @@ SYMBOLS = (
     "odb_model_get_tensor", "odb_cache_create", "odb_cache_destroy", "odb_cache_length", "odb_prefill",
     "odb_block_step", "odb_prefill_logits", "odb_block_step_logits", "odb_cache_read", "odb_strerror",
     "odb_last_error", "odb_profile_begin", "odb_profile_end", "odb_set_option", "odb_model_status",
-    "odb_predict_length", "odb_accept_jump", "odb_block_step_shared",
+    "odb_predict_length", "odb_accept_jump", "odb_block_step_shared", "odb_block_step_static",
     "odb_block_step_shared_rows", "odb_block_step_shared_logits", "odb_cache_truncate", "odb_generate",
     "odb_speculative_jump",
 )
 
 KERNEL_CLASSES = ("gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "rmsnorm")
 OPT_KSPLIT_REDUCE = 0
+STATIC_SCRATCH_BYTES = 32 << 20
 
 T_EMBED, T_WQ, T_WK, T_WV, T_WO, T_WG, T_WU, T_WD, T_LM, T_G1, T_G2, T_GF = range(12)
 
@@ -115,6 +116,7 @@ def lib() -> ctypes.CDLL:
     L.odb_block_step_shared_logits.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp, vp]
     L.odb_set_option.argtypes = [vp, ci, ci]
     L.odb_model_status.argtypes = [vp]
+    L.odb_block_step_static.argtypes = [vp, vp, vp, ci, ci, ci, cf, vp, vp, vp, vp]
     L.odb_strerror.argtypes = [ci]
     L.odb_strerror.restype = ctypes.c_char_p
     L.odb_last_error.restype = ctypes.c_char_p
@@ -356,6 +358,15 @@ def odb_block_step(model: int, cache: int, drafts, block_off: int, tau: float, c
         unmask = torch.empty((B, S, b), dtype=torch.uint8, device=drafts.device)
     _check(lib().odb_block_step(model, cache, _dev_i32(drafts), block_off, b, S, tau, conf.data_ptr(),
                                 argmax.data_ptr(), unmask.data_ptr(), _stream()))
+    return conf, argmax, unmask
+
+
+def odb_block_step_static(model: int, cache: int, drafts, block_off: int, tau: float, conf, argmax, unmask):
+    """odb_block_step in the library's fixed scratch area; the caller brings every output tensor (nothing is
+    allocated on the way, here or in the library)."""
+    B, S, b = drafts.shape
+    _check(lib().odb_block_step_static(model, cache, _dev_i32(drafts), block_off, b, S, tau, conf.data_ptr(),
+                                       argmax.data_ptr(), unmask.data_ptr(), _stream()))
     return conf, argmax, unmask
 
 

@@ -332,6 +332,16 @@ int prefill_impl(odb_model *mh, odb_cache *ch, const int32_t *tokens, int L, int
     return run_head(m, base, pl, rm, resp_off, false, nullptr, 64, 0.f, conf, argmax, nullptr, logits, s);
 }
 
+// The library's fixed scratch area for callers that cannot allocate (odb_block_step_static): one array per GPU,
+// held from the moment the library is loaded until the process ends.  Host code never uses the array's name as
+// an address: static_scratch_ptr() asks the runtime for this device's copy once and keeps the pointer.
+constexpr size_t kStaticScratchBytes = ODB_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+char *g_static_scratch[kMaxDevices];
+std::mutex g_static_scratch_mutex;
+
+int static_scratch_ptr(int device, char **out);      // defined behind the array, at the end of this file
+
 // scratch_base == nullptr: the model's own scratch, grown on demand.  Otherwise the call runs in the given area of
 // scratch_bytes bytes and allocates nothing.
 int step_impl(odb_model *mh, const odb_cache *ch, const int32_t *drafts, int block_off, int b, int S, float tau,
@@ -359,7 +369,7 @@ int step_impl(odb_model *mh, const odb_cache *ch, const int32_t *drafts, int blo
         // split K only as far as the room allows), at most what the growing scratch would give them
         pl = make_plan(cfg, rows_pad, units * bp32, rows_pad, true, 0, 0);
         if (pl.total + (1u << 20) > scratch_bytes)
-            return fail(ODB_E_UNSUPPORTED, "block_step: %d rows of this model need %zu bytes of scratch, the fixed "
+            return fail(ODB_E_UNSUPPORTED, "block_step_static: %d rows of this model need %zu bytes of scratch, the fixed "
                         "area holds %zu", rows_pad, pl.total + (1u << 20), scratch_bytes);
         size_t part = (scratch_bytes - pl.total) / 256 * 256;
         pl = make_plan(cfg, rows_pad, units * bp32, rows_pad, true, 0, part < kPartialBytes ? part : kPartialBytes);
@@ -421,6 +431,11 @@ int odb_model_create(const odb_config *cfg, const odb_allocator *allocator, odb_
     m.prof_class = -1;
     m.n_cu = prop.multiProcessorCount;
     m.ksplit_reduce = true;
+    {
+        char *fixed = nullptr;          // this device's copy of the fixed scratch area: looked up once, here
+        rc = static_scratch_ptr(dev, &fixed);
+        if (rc) { delete mh; return rc; }
+    }
     if (allocator) { m.alloc = *allocator; m.has_alloc = true; }
     const size_t d = cfg->d_model, f = cfg->d_ff, v = cfg->vocab, nl = cfg->n_layers;
     m.layer_elems[PK_QKV] = 3 * d * d;
@@ -989,4 +1004,40 @@ int odb_cache_read(const odb_cache *ch, int layer, int kv, int batch_index, int 
     return ODB_OK;
 }
 
+int odb_block_step_static(odb_model *m, const odb_cache *c, const int32_t *drafts_dev, int block_off, int b, int S,
+                          float tau, float *conf_dev, int32_t *argmax_dev, uint8_t *unmask_dev, void *stream) {
+    if (!m) return fail(ODB_E_INVALID_ARG, "block_step_static: model is NULL");
+    if (!conf_dev || !argmax_dev || !unmask_dev) return fail(ODB_E_INVALID_ARG, "block_step_static: NULL output");
+    char *base = nullptr;
+    int rc = static_scratch_ptr(m->m.device, &base);      // a table look-up after model creation
+    if (rc) return rc;
+    return step_impl(m, c, drafts_dev, block_off, b, S, tau, conf_dev, argmax_dev, unmask_dev, nullptr, stream, base,
+                     kStaticScratchBytes);
+}
+
 }  // extern "C"
+
+// ---- the fixed scratch area ---------------------------------------------------------------------------------
+// Device memory that exists without any allocation call: every GPU the library runs on holds its own copy of
+// this array at its own address.  In host code the name `scratch` is only a handle for hipGetSymbolAddress;
+// the address it yields (per device, with that device current) is what kernels and copies are given.
+static __device__ __align__(256) unsigned char scratch[ODB_STATIC_SCRATCH_BYTES];
+
+namespace {
+int static_scratch_ptr(int device, char **out) {
+    if (device < 0 || device >= kMaxDevices) return fail(ODB_E_UNSUPPORTED, "device index %d", device);
+    std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+    if (!g_static_scratch[device]) {
+        int cur = -1;
+        HIP_TRY(hipGetDevice(&cur));
+        if (cur != device) HIP_TRY(hipSetDevice(device));
+        void *p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (cur != device && cur >= 0) (void)hipSetDevice(cur);
+        if (e != hipSuccess || !p) return fail(ODB_E_HIP, "hipGetSymbolAddress(scratch) on device %d: %s", device, hipGetErrorString(e));
+        g_static_scratch[device] = (char *)p;
+    }
+    *out = g_static_scratch[device];
+    return ODB_OK;
+}
+}  // namespace
