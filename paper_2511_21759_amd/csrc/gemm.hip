@@ -262,7 +262,11 @@ static int lm_ng(int n_tiles, int m_tiles) {
     const int per = (n_tiles + kStreamWGs - 1) / kStreamWGs;
     return (per + 3) / 4 * 4 < (per + kLmNG - 1) / kLmNG * kLmNG ? 4 : kLmNG;
 }
+// From 33 to 128 rows the LM head runs on the tile kernel with four n-tiles per wave (see launch_gemm_lmstats)
+constexpr int kLmTileNGW = 4;
+static bool lm_tile(int m_tiles) { return m_tiles > 2 && m_tiles <= 8; }
 int lm_stats_parts(int n_tiles, int m_tiles) {
+    if (lm_tile(m_tiles)) return (n_tiles + 8 * kLmTileNGW - 1) / (8 * kLmTileNGW);
     if (m_tiles <= 8) {
         const int ng = lm_ng(n_tiles, m_tiles);
         const int groups = (n_tiles + ng - 1) / ng;
@@ -278,9 +282,20 @@ void launch_gemm_lmstats(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, f
     const int parts = lm_stats_parts(sh.N_tiles, sh.M_tiles);
     if (sh.M_tiles <= 2 && lm_ng(sh.N_tiles, sh.M_tiles) == 4) launch_stream<2, 4, 4, 8, true>(xa, w, sh, ni, EpiLMStats<2>(stats, parts), s);
     else if (sh.M_tiles <= 2) launch_stream<2, kLmNG, 4, 8, true>(xa, w, sh, ni, EpiLMStats<2>(stats, parts), s);
-    else if (sh.M_tiles <= 4) launch_stream<4, kLmNG, 2, 8, true>(xa, w, sh, ni, EpiLMStats<4>(stats, parts), s);
-    else if (sh.M_tiles <= 6) launch_stream<6, kLmNG, 1, 8, true>(xa, w, sh, ni, EpiLMStats<6>(stats, parts), s);
-    else if (sh.M_tiles <= 8) launch_stream<8, kLmNG, 2, 4, true>(xa, w, sh, ni, EpiLMStats<16>(stats, parts), s);
+    else if (lm_tile(sh.M_tiles)) {
+        // 33..128 rows.  A streaming workgroup reads all activation rows once per group of six n-tiles, and with 31
+        // n-tiles per workgroup that is five to six times [rows x d] through each compute unit's vector-memory path,
+        // more than its weights: at 128 rows the kernel was bound by that path (244 us, 4.2 TB/s).  The tile kernel
+        // shares the activation slab between eight waves through LDS, so with four n-tiles per wave a workgroup reads
+        // the activations once for 32 n-tiles; the vocabulary gives 247 such workgroups, one round on the chip:
+        // 167 us at 128 rows (6.2 TB/s), and the finishing kernel merges 247 partials per row instead of 1536.
+        TileArgs g;
+        g.A = xa; g.W = w; g.KT = sh.K_tiles; g.MT_total = sh.M_tiles; g.NT = sh.N_tiles;
+        g.ssq = ni.ssq; g.n_ssq = ni.n_ssq; g.eps = ni.eps; g.inv_d = 1.0f / (float)(sh.K_tiles * 32);
+        g.partial = nullptr; g.KS = 1;
+        g.n_blocks = parts;
+        gemm_tile_kernel<8, kLmTileNGW, 1, 4, TileLMStats, true><<<dim3(g.n_blocks, 1), 512, 0, s>>>(g, TileLMStats{stats, parts});
+    }
     else if (use_big(sh)) launch_big(xa, w, sh, ni, TileLMStats{stats, parts}, s);
     else launch_tile(xa, w, sh, ni, TileLMStats{stats, parts}, ws, false, s);
 }
