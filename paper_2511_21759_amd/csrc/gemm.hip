@@ -124,12 +124,12 @@ static void launch_tile(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, Epi
     g.KS = ks;
     dim3 grid(g.n_blocks * ks, m_blocks);
     // (8 waves x 1 n-tile, ring of 8) for the multi-draft step, (8 x 2, ring of 4) for compute-bound shapes:
-    // the best of the shapes tried on MI355X (4-wave workgroups, 4 n-tiles per wave and 2 or 4 k-tiles
-    // per barrier were all slower - occupancy beats wider tiles here)
+    // the best of the shapes tried on MI355X (4-wave workgroups of 1, 2 or 4 n-tiles per wave, 8 x 2 with a ring of 8
+    // and 2 or 4 k-tiles per barrier were all slower or equal - occupancy beats wider tiles here; 8 x 4 spills)
     // (a single block of rows: every weight tile is read once, non-temporally)
-    if (c.ngw == 1 && m_blocks == 1) gemm_tile_kernel<8, 1, 1, 8, Epi, true><<<grid, 512, 0, s>>>(g, e);
-    else if (c.ngw == 1) gemm_tile_kernel<8, 1, 1, 8, Epi><<<grid, 512, 0, s>>>(g, e);
-    else gemm_tile_kernel<8, 2, 1, 4, Epi><<<grid, 512, 0, s>>>(g, e);
+    if (c.ngw == 1 && m_blocks == 1) gemm_tile_kernel<8, 1, 8, Epi, true><<<grid, 512, 0, s>>>(g, e);
+    else if (c.ngw == 1) gemm_tile_kernel<8, 1, 8, Epi><<<grid, 512, 0, s>>>(g, e);
+    else gemm_tile_kernel<8, 2, 4, Epi><<<grid, 512, 0, s>>>(g, e);
     if (ks > 1) {
         if constexpr (!is_row_stats<Epi>::value)
             tile_epilogue_kernel<Epi><<<dim3((sh.N_tiles + 7) / 8, sh.M_tiles), 512, 0, s>>>(g, e);
@@ -294,7 +294,7 @@ void launch_gemm_lmstats(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, f
         g.ssq = ni.ssq; g.n_ssq = ni.n_ssq; g.eps = ni.eps; g.inv_d = 1.0f / (float)(sh.K_tiles * 32);
         g.partial = nullptr; g.KS = 1;
         g.n_blocks = parts;
-        gemm_tile_kernel<8, kLmTileNGW, 1, 4, TileLMStats, true><<<dim3(g.n_blocks, 1), 512, 0, s>>>(g, TileLMStats{stats, parts});
+        gemm_tile_kernel<8, kLmTileNGW, 4, TileLMStats, true><<<dim3(g.n_blocks, 1), 512, 0, s>>>(g, TileLMStats{stats, parts});
     }
     else if (use_big(sh)) launch_big(xa, w, sh, ni, TileLMStats{stats, parts}, s);
     else launch_tile(xa, w, sh, ni, TileLMStats{stats, parts}, ws, false, s);

@@ -3,8 +3,8 @@
 //
 // A workgroup computes a 128-row block x (8*NGW n-tiles) x one slice of K.  Its eight waves split
 // the n-tiles; the 128 x 32 slab of A that a k-step needs is shared through LDS: every wave fetches
-// one of the slab's eight 16-row tiles PF steps ahead into registers and drops it into a two-slot LDS
-// buffer when its turn comes, so A is read from L2 once per workgroup while every wave streams its
+// one of the slab's eight 16-row tiles PF steps ahead into registers and drops it into a ring of LDS
+// slots when its turn comes, so A is read from L2 once per workgroup while every wave streams its
 // own weight tiles from HBM straight into MFMA operand registers.  With a K split (grid.x =
 // n-blocks x KS) the partial sums go to an fp32 workspace in MFMA fragment order and
 // tile_epilogue_kernel adds them in a fixed order and runs the epilogue.
@@ -41,19 +41,22 @@ __device__ __forceinline__ void merge_stat(float &m, float &s, int &a, float om,
     m = nm;
 }
 
-// NW waves per workgroup, each NGW n-tiles wide: the workgroup covers NW*NGW n-tiles.  A stage of the
-// pipeline is a chunk of KC k-tiles (one barrier per chunk); PF chunks are in flight.
-constexpr int tile_smem_bytes(int kc) { return 2 * kc * 8 * 1024 + 8 * 1024 + 128 * 4; }
+// NW waves per workgroup, each NGW n-tiles wide: the workgroup covers NW*NGW n-tiles.  One k-tile per barrier; every
+// wave keeps PF k-tiles (its share of the A slab and its own weight tiles) in flight.  The A slab goes through a ring
+// of kTileSlots LDS slots (a slot is rewritten four barriers after its last reader asked for it).
+constexpr int kTileSlots = 4;
+constexpr int tile_smem_bytes() { return kTileSlots * 8 * 1024 + 8 * 1024 + 128 * 4; }
 
 // SW: the weight tiles are read by one workgroup only (a single block of rows), so they are loaded non-temporally.
-template <int NW, int NGW, int KC, int PF, class Epi, bool SW = false>
+template <int NW, int NGW, int PF, class Epi, bool SW = false>
 __global__ __launch_bounds__(64 * NW) void gemm_tile_kernel(TileArgs g, Epi epi) {
     constexpr int AW = 8 / NW;                 // A tiles (per k-tile) of the slab each wave fetches
     static_assert(NW == 4 || NW == 8, "waves per workgroup");
-    __shared__ __attribute__((aligned(16))) char smem[tile_smem_bytes(KC)];
-    frag_t (*a_lds)[KC][8][64] = reinterpret_cast<frag_t (*)[KC][8][64]>(smem);         // [2][KC][8 m-tiles][64 lanes]
-    f32x4 (*scr)[64] = reinterpret_cast<f32x4 (*)[64]>(smem + 2 * KC * 8 * 1024);        // [8 waves][64]
-    float *s_rstd = reinterpret_cast<float *>(smem + 2 * KC * 8 * 1024 + 8 * 1024);
+    static_assert(PF % kTileSlots == 0, "ring slots and register buffers are indexed by the unrolled step");
+    __shared__ __attribute__((aligned(16))) char smem[tile_smem_bytes()];
+    frag_t (*a_lds)[8][64] = reinterpret_cast<frag_t (*)[8][64]>(smem);                    // [slots][8 m-tiles][64 lanes]
+    f32x4 (*scr)[64] = reinterpret_cast<f32x4 (*)[64]>(smem + kTileSlots * 8 * 1024);      // [8 waves][64]
+    float *s_rstd = reinterpret_cast<float *>(smem + kTileSlots * 8 * 1024 + 8 * 1024);
 
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     // (k-slice in the low bits of the id: workgroup ids go round-robin over the XCDs, so an XCD's workgroups then share
@@ -62,7 +65,6 @@ __global__ __launch_bounds__(64 * NW) void gemm_tile_kernel(TileArgs g, Epi epi)
     const int mt0 = blockIdx.y * 8;
     const int k_lo = (int)((unsigned)ks * (unsigned)g.KT / (unsigned)g.KS), k_hi = (int)((unsigned)(ks + 1) * (unsigned)g.KT / (unsigned)g.KS);
     const int nk = k_hi - k_lo;                 // k-tiles of this slice
-    const int nc = (nk + KC - 1) / KC;          // chunks
     const int nt0 = (nb * NW + w) * NGW;
 
     const u16 *wp[NGW];
@@ -118,49 +120,55 @@ __global__ __launch_bounds__(64 * NW) void gemm_tile_kernel(TileArgs g, Epi epi)
 #pragma unroll
         for (int j = 0; j < NGW; j++) acc[m][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // k-tiles past the end of the slice are clamped to its last tile and contribute nothing (see below)
-    frag_t wr[PF][KC][NGW], ar[PF][KC][AW];
-    auto load_chunk = [&](int slot, int c) __attribute__((always_inline)) {
+    // Loads past the end of the slice fetch its last tile again and are never used: the refills of the main loop
+    // are unconditional, so the order of the outstanding loads is fixed and every wait counts exactly.
+    frag_t wr[PF][NGW], ar[PF][AW];
+    auto load_step = [&](int slot, int c) __attribute__((always_inline)) {
+        const int k = c < nk ? c : nk - 1;
 #pragma unroll
-        for (int kk = 0; kk < KC; kk++) {
-            int k = c * KC + kk;
-            k = k < nk ? k : nk - 1;
+        for (int i = 0; i < AW; i++) ar[slot][i] = ld_frag(ap[i] + k * a_step);
 #pragma unroll
-            for (int i = 0; i < AW; i++) ar[slot][kk][i] = ld_frag(ap[i] + k * a_step);
-#pragma unroll
-            for (int j = 0; j < NGW; j++)
-                wr[slot][kk][j] = SW ? ld_frag_stream(wp[j] + (size_t)k * kTileElems) : ld_frag(wp[j] + (size_t)k * kTileElems);
-        }
+        for (int j = 0; j < NGW; j++)
+            wr[slot][j] = SW ? ld_frag_stream(wp[j] + (size_t)k * kTileElems) : ld_frag(wp[j] + (size_t)k * kTileElems);
     };
 #pragma unroll
-    for (int s = 0; s < PF; s++)
-        if (s < nc) load_chunk(s, s);
+    for (int s = 0; s < PF; s++) load_step(s, s);
 
-    for (int cb = 0; cb < nc; cb += PF) {
+    // PIPE (up to two n-tiles per wave): step c stores the slab of step c+1, and after the barrier reads it into a second
+    // set of registers while the MFMAs of step c run on the set read one step earlier.  Wider waves have no registers
+    // for the second set: they store, wait and read the slab of step c itself.
+    constexpr bool PIPE = NGW <= 2;
+    frag_t a[PIPE ? 2 : 1][8];
+    if constexpr (PIPE) {
 #pragma unroll
-        for (int s = 0; s < PF; s++) {
-            const int c = cb + s;
-            if (c < nc) {
+        for (int i = 0; i < AW; i++) a_lds[0][w * AW + i][lane] = ar[0][i];
+        __syncthreads();
 #pragma unroll
-                for (int kk = 0; kk < KC; kk++)
+        for (int m = 0; m < 8; m++) a[0][m] = a_lds[0][m][lane];
+    }
+    auto step = [&](int s, int c) __attribute__((always_inline)) {
+        constexpr int nxt = PIPE ? 1 : 0;
 #pragma unroll
-                    for (int i = 0; i < AW; i++) a_lds[c & 1][kk][w * AW + i][lane] = ar[s][kk][i];
-                __syncthreads();
+        for (int i = 0; i < AW; i++) a_lds[(s + nxt) % kTileSlots][w * AW + i][lane] = ar[(s + nxt) % PF][i];
+        __syncthreads();
 #pragma unroll
-                for (int kk = 0; kk < KC; kk++) {
-                    if (c * KC + kk < nk) {
-                        frag_t a[8];
+        for (int m = 0; m < 8; m++) a[(s + nxt) & nxt][m] = a_lds[(s + nxt) % kTileSlots][m][lane];
 #pragma unroll
-                        for (int m = 0; m < 8; m++) a[m] = a_lds[c & 1][kk][m][lane];
+        for (int m = 0; m < 8; m++)
 #pragma unroll
-                        for (int m = 0; m < 8; m++)
+            for (int j = 0; j < NGW; j++) acc[m][j] = mfma16(wr[s][j], a[s & nxt][m], acc[m][j]);
+        load_step(s, c + PF);
+    };
+    int cb = 0;
+    for (; cb + PF <= nk; cb += PF) {
 #pragma unroll
-                            for (int j = 0; j < NGW; j++) acc[m][j] = mfma16(wr[s][kk][j], a[m], acc[m][j]);
-                    }
-                }
-                if (c + PF < nc) load_chunk(s, c + PF);
-            }
-        }
+        for (int s = 0; s < PF; s++) step(s, cb + s);
+    }
+    {
+        const int rest = nk - cb;                // uniform over the workgroup
+#pragma unroll
+        for (int s = 0; s < PF - 1; s++)
+            if (s < rest) step(s, cb + s);
     }
     __syncthreads();
 
