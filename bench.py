@@ -70,8 +70,8 @@ def profile_figures(name):
         except ValueError:
             continue
         # (the gate/up kernel of the timed steps is the row with the most launches; the set-up's refresh has its own)
-        if len(cells) == 7 and nums[0] > best_calls:          # kernel | calls | avg us | min | max | total ms | %
-            best_calls, avg_us = nums[0], nums[1]
+        if len(cells) == 8 and nums[1] > best_calls:          # kernel | workgroups | calls | avg us | min | max | total ms | %
+            best_calls, avg_us = nums[1], nums[2]
         elif len(cells) == 6 and nums[0] > best_disp:         # kernel | dispatches | fetch KiB | write KiB | read MB | write MB
             best_disp, traffic = nums[0], (nums[3] + nums[4]) * 1e6
     return avg_us, traffic, rel
