@@ -22,11 +22,11 @@ __global__ __launch_bounds__(64 * NW) void attn_xcd_kernel(AttnArgs a, float sc,
 }
 
 // Many rows per (sequence, head): K/V tiles shared through LDS by all rows of a workgroup (attn_rows.h)
-template <int DH, int NW, int QTW, int NS, bool PIPE, bool DUAL>
+template <int DH, int NW, int QTW, int NS>
 static void launch_rows(AttnArgs a, float sc, hipStream_t s) {
     static std::once_flag attr_once;        // once per instantiation: the ring may need more than the default LDS limit
     std::call_once(attr_once, [] {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_rows_kernel<DH, NW, QTW, NS, PIPE, DUAL>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_rows_kernel<DH, NW, QTW, NS>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, attn_rows_smem_bytes<DH, NS>());
     });
     const int tiles_per_seq = a.units_per_seq * a.tiles_per_unit;
@@ -34,7 +34,7 @@ static void launch_rows(AttnArgs a, float sc, hipStream_t s) {
     dim3 grid((a.units / a.units_per_seq) * chunks, a.H);
     // (flattened: the kernel then maps all row chunks of a head to one XCD - 38.9 -> 38.2 us at 1024 rows)
     if (a.H % 8 == 0 && grid.x > 1) grid = dim3(grid.x * grid.y, 1);
-    attn_rows_kernel<DH, NW, QTW, NS, PIPE, DUAL><<<grid, 64 * NW, attn_rows_smem_bytes<DH, NS>(), s>>>(a, sc);
+    attn_rows_kernel<DH, NW, QTW, NS><<<grid, 64 * NW, attn_rows_smem_bytes<DH, NS>(), s>>>(a, sc);
 }
 
 void launch_attention(AttnArgs a, hipStream_t s) {
@@ -52,11 +52,11 @@ void launch_attention(AttnArgs a, hipStream_t s) {
         // 256 rows per workgroup when that still gives every compute unit a workgroup, else 128
         const int wgs8 = (a.units / a.units_per_seq) * ((tiles_per_seq + 15) / 16) * a.H;
         if (a.dh == 128) {
-            if (wgs8 >= 256) launch_rows<128, 8, 2, 8, true, false>(a, sc, s);
-            else launch_rows<128, 4, 2, 4, true, true>(a, sc, s);
+            if (wgs8 >= 256) launch_rows<128, 8, 2, 8>(a, sc, s);
+            else launch_rows<128, 4, 2, 6>(a, sc, s);
         } else {
-            if (wgs8 >= 256) launch_rows<64, 8, 2, 8, true, true>(a, sc, s);
-            else launch_rows<64, 4, 2, 4, true, true>(a, sc, s);
+            if (wgs8 >= 256) launch_rows<64, 8, 2, 8>(a, sc, s);
+            else launch_rows<64, 4, 2, 6>(a, sc, s);
         }
         return;
     }

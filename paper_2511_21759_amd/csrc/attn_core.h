@@ -138,6 +138,84 @@ __device__ __forceinline__ void attn_scores(const AttnArgs &a, float sc, int key
     }
 }
 
+// Scores of one 32-key tile: st[t][s] = K_s Q_t^T (s: the two 16-key halves of the tile)
+template <int DH, int QT>
+__device__ __forceinline__ void attn_qk(const frag_t (&kf)[2][DH / 32], const frag_t (&q)[QT][DH / 32], f32x4 (&st)[QT][2]) {
+#pragma unroll
+    for (int t = 0; t < QT; t++)
+#pragma unroll
+        for (int s = 0; s < 2; s++) {
+            st[t][s] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int dt = 0; dt < DH / 32; dt++) st[t][s] = mfma16(kf[s][dt], q[t][dt], st[t][s]);
+        }
+}
+
+// The softmax half of attn_scores on scores st that are already there (cached keys only), followed by the score
+// MFMAs of the NEXT tile (K fragments kf_next -> st_next).  masked (wave-uniform): some keys of the tile are
+// invisible; their scores are set to -inf in a branch of its own, so that the common tile pays nothing for masks.
+// The rare raise of a row's reference (see attn_scores) is taken for all row tiles in one branch.
+template <int DH, int QT>
+__device__ __forceinline__ void attn_softmax_qk(const AttnArgs &a, float sc, int key0, bool masked, f32x4 (&st)[QT][2],
+                                                const frag_t (&kf_next)[2][DH / 32], const frag_t (&q)[QT][DH / 32],
+                                                f32x4 (&st_next)[QT][2], f32x4 (&o)[QT][DH / 16], float (&mrun)[QT],
+                                                float (&lrun)[QT], frag_t (&pf)[QT], int lane) {
+    constexpr int DT16 = DH / 16;
+    if (masked) {
+        const int g = lane >> 4;
+#pragma unroll
+        for (int s = 0; s < 2; s++)
+#pragma unroll
+            for (int rr = 0; rr < 4; rr++) {
+                const int key = key0 + s * 16 + 4 * g + rr;
+                const bool ok = key < a.L && !(key >= a.blk_lo && key < a.blk_hi);
+#pragma unroll
+                for (int t = 0; t < QT; t++) st[t][s][rr] = ok ? st[t][s][rr] : -INFINITY;
+            }
+    }
+    float tm[QT];
+    bool raise = false;
+#pragma unroll
+    for (int t = 0; t < QT; t++) {
+        tm[t] = fmaxf(fmaxf(fmaxf(st[t][0][0], st[t][0][1]), fmaxf(st[t][0][2], st[t][0][3])),
+                      fmaxf(fmaxf(st[t][1][0], st[t][1][1]), fmaxf(st[t][1][2], st[t][1][3])));
+        raise = raise || tm[t] * sc > mrun[t] + kAttnSlack;
+    }
+    if (__any(raise)) {
+#pragma unroll
+        for (int t = 0; t < QT; t++) {
+            if (__any(tm[t] * sc > mrun[t] + kAttnSlack)) {
+                float x = fmaxf(tm[t], __shfl_xor(tm[t], 16));
+                x = fmaxf(x, __shfl_xor(x, 32));
+                const float mnew = fmaxf(mrun[t], x * sc);
+                const float alpha = __builtin_amdgcn_exp2f(mrun[t] - (mnew == -INFINITY ? 0.f : mnew));
+                lrun[t] *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < DT16; dt++) o[t][dt] *= alpha;
+                mrun[t] = mnew;
+            }
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < QT; t++) {
+        const float mref = mrun[t] == -INFINITY ? 0.f : mrun[t];
+        float p[2][4], ps = 0.f;
+#pragma unroll
+        for (int s = 0; s < 2; s++)
+#pragma unroll
+            for (int rr = 0; rr < 4; rr++) {
+                p[s][rr] = __builtin_amdgcn_exp2f(__builtin_fmaf(st[t][s][rr], sc, -mref));
+                ps += p[s][rr];
+            }
+        lrun[t] += ps;
+        pf[t].w[0] = pack2(p[0][0], p[0][1]);
+        pf[t].w[1] = pack2(p[0][2], p[0][3]);
+        pf[t].w[2] = pack2(p[1][0], p[1][1]);
+        pf[t].w[3] = pack2(p[1][2], p[1][3]);
+    }
+    attn_qk<DH, QT>(kf_next, q, st_next);
+}
+
 // O^T += V^T P^T for QT row tiles
 template <int DH, int QT>
 __device__ __forceinline__ void attn_pv(const frag_t (&vf)[DH / 16], const frag_t (&pf)[QT], f32x4 (&o)[QT][DH / 16]) {

@@ -11,6 +11,7 @@
 // (decode step) are private to that draft's rows; each wave reads its own from global memory
 // after the shared loop.  Visibility is as in attn_core.h.
 #pragma once
+#include <type_traits>
 #include "attn_core.h"
 
 namespace odb {
@@ -19,10 +20,7 @@ template <int DH, int NS>
 constexpr int attn_rows_smem_bytes() { return NS * (2 * (DH / 32) + DH / 16) * 1024; }
 
 // Requires tiles_per_unit % QTW == 0 when there are fresh keys (a wave's tiles then belong to one draft).
-// PIPE: fetch K of tile i+1 from LDS while P*V of tile i is issued.
-// DUAL: a second code path without key masks for tiles whose 32 keys are all visible (fewer VALU operations;
-// with eight waves of dh = 128 the two paths together do not fit the register file without spilling).
-template <int DH, int NW, int QTW, int NS, bool PIPE, bool DUAL>
+template <int DH, int NW, int QTW, int NS>
 __global__ __launch_bounds__(64 * NW) void attn_rows_kernel(AttnArgs a, float sc) {
     constexpr int DT32 = DH / 32, DT16 = DH / 16;
     constexpr int FR = 2 * DT32 + DT16;              // 1 KiB fragments per 32-key tile: K then V^T
@@ -90,10 +88,15 @@ __global__ __launch_bounds__(64 * NW) void attn_rows_kernel(AttnArgs a, float sc
 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // q has arrived: the counted waits below see only the ring
     static_assert(PER * (NS - 2) <= 28 && (PER * (NS - 2) <= 16 || PER % 2 == 0), "wait_vmcnt covers these counts");
-    static_assert(NS >= 3, "two tiles are being read while the third is requested");
+    static_assert(NS >= 4, "tiles being read while the next is requested");
     // Copies of tiles 0 .. NS-2 are requested up front; in iteration i tile i+NS-1 follows, into the slot of
-    // tile i-1.  Within an iteration the LDS reads run under the MFMAs: V of tile i is fetched before the
-    // scores are computed, K of tile i+1 while P*V is issued (its registers are free by then).
+    // tile i-1.  A wave enters iteration i with the scores of tile i in registers and the K fragments of
+    // tile i+1 read; it fetches V of tile i, runs the softmax of tile i and the score MFMAs of tile i+1,
+    // fetches K of tile i+2 and issues P*V of tile i (the reads complete under it).  Past the last tile the
+    // "next" tiles are the last one again; what is computed from them is never used.
+    // (MFMAs and vector instructions hardly overlap on this chip - a wave that interleaves 16 MFMAs with 48
+    // independent fmas takes 85 % of the sum of the two alone, two waves of a SIMD that run one kind each take
+    // 80 % - so what the softmax costs is its instruction count: masks are applied on masked tiles only.)
     frag_t kf[2][DT32], vf[DT16], pf[QTW];
     const KeyVis kv{a.fresh, 0ull, 1, 0};
     auto read_k = [&](int i) __attribute__((always_inline)) {
@@ -111,28 +114,41 @@ __global__ __launch_bounds__(64 * NW) void attn_rows_kernel(AttnArgs a, float sc
 #pragma unroll
     for (int j = 0; j < NS - 1; j++)
         if (j < n_live) issue(j, j);
-    if (PIPE && n_live > 0) {
-        landed(0, NS - 2);
+    f32x4 sc_t[2][QTW][2];
+    if (n_live > 0) {
+        landed(n_live > 1 ? 1 : 0, NS - 2);
         __builtin_amdgcn_s_barrier();
-        if (wave_live) read_k(0);
+        if (wave_live) {
+            read_k(0);
+            attn_qk<DH, QTW>(kf, q, sc_t[0]);
+            read_k(n_live > 1 ? 1 : 0);
+        }
     }
-    for (int i = 0; i < n_live; i++) {
-        if (!PIPE) landed(i, i + NS - 2);
-        else if (i + 1 < n_live) landed(i + 1, i + NS - 2);
+    auto iter = [&](auto P, int i) __attribute__((always_inline)) {
+        constexpr int p = decltype(P)::value;
+        const int i2 = i + 2 < n_live ? i + 2 : n_live - 1;
+        landed(i2, i + NS - 2);
         __builtin_amdgcn_s_barrier();
-        // tile i (PIPE: i+1) is visible to every wave, and every wave is done with the slot of tile i-1
+        // tile i+2 is visible to every wave, and every wave is done with the slot of tile i-1
         if (i + NS - 1 < n_live) issue((i + NS - 1) % NS, i + NS - 1);
         if (wave_live) {
             const stage_t &st = ring[i % NS];
-            if (!PIPE) read_k(i);
 #pragma unroll
             for (int dt = 0; dt < DT16; dt++) vf[dt] = st[2 * DT32 + dt][lane];
             const int key0 = tile_of(i) * 32;
-            if (!DUAL || attn_tile_masked(a, key0, kKeysCached, 0)) attn_scores<DH, QTW, true>(a, sc, key0, kKeysCached, kv, kf, q, o, mrun, lrun, pf, lane);
-            else attn_scores<DH, QTW, false>(a, sc, key0, kKeysCached, kv, kf, q, o, mrun, lrun, pf, lane);
-            if (PIPE && i + 1 < n_live) read_k(i + 1);
+            attn_softmax_qk<DH, QTW>(a, sc, key0, attn_tile_masked(a, key0, kKeysCached, 0), sc_t[p], kf, q, sc_t[1 - p], o,
+                                     mrun, lrun, pf, lane);
+            read_k(i2);
             attn_pv<DH, QTW>(vf, pf, o);
         }
+    };
+    {
+        int i = 0;
+        for (; i + 1 < n_live; i += 2) {
+            iter(std::integral_constant<int, 0>{}, i);
+            iter(std::integral_constant<int, 1>{}, i + 1);
+        }
+        if (i < n_live) iter(std::integral_constant<int, 0>{}, i);
     }
     if (!wave_live) return;
 
