@@ -166,7 +166,7 @@ static void launch_big_wn(const u16 *a, const u16 *w, GemmShape sh, NormIn ni, E
 struct BigChoice { int mbt, wn; };
 static BigChoice big_choice(GemmShape sh) {
     BigChoice best{16, 0};
-    if (sh.M_tiles < 16 || sh.N_tiles < 32) return best;
+    if (sh.M_tiles < 12 || sh.N_tiles < 32) return best;     // (192 rows fill three quarters of a 256-row block)
     const double rel16[5] = {0, 0, 0.68, 0.87, 1.0}, rel8[5] = {0, 0, 0.46, 0.60, 0.66};
     double best_cost = 0;
     for (int mbt = 16; mbt >= 8; mbt -= 8)
@@ -262,6 +262,10 @@ static int lm_ng(int n_tiles, int m_tiles) {
     const int per = (n_tiles + kStreamWGs - 1) / kStreamWGs;
     return (per + 3) / 4 * 4 < (per + kLmNG - 1) / kLmNG * kLmNG ? 4 : kLmNG;
 }
+// Beyond 128 rows the LM head of a long vocabulary always runs on the LDS-ring kernel, 256 columns wide where no other width is chosen
+// (129..191 rows leave part of a 256-row block empty, and still measure 283 us against 427 us on the tile kernel:
+// the vocabulary is long enough to be bound by the weight stream either way)
+static int lm_big_width(GemmShape sh) { const int wn = big_width(sh); return wn || sh.N_tiles < 32 ? wn : 4; }
 // From 33 to 128 rows the LM head runs on the tile kernel with four n-tiles per wave (see launch_gemm_lmstats)
 constexpr int kLmTileNGW = 4;
 static bool lm_tile(int m_tiles) { return m_tiles > 2 && m_tiles <= 8; }
@@ -272,7 +276,7 @@ int lm_stats_parts(int n_tiles, int m_tiles) {
         const int groups = (n_tiles + ng - 1) / ng;
         return (groups < kStreamWGs ? groups : kStreamWGs) * ng;
     }
-    if (const int wn = big_width(GemmShape{m_tiles, n_tiles, 0})) return (n_tiles + 4 * wn - 1) / (4 * wn);
+    if (const int wn = lm_big_width(GemmShape{m_tiles, n_tiles, 0})) return (n_tiles + 4 * wn - 1) / (4 * wn);
     const TileCfg c = tile_cfg(m_tiles);
     return (n_tiles + c.nw * c.ngw - 1) / (c.nw * c.ngw);
 }
@@ -297,6 +301,7 @@ void launch_gemm_lmstats(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, f
         gemm_tile_kernel<8, kLmTileNGW, 4, TileLMStats, true><<<dim3(g.n_blocks, 1), 512, 0, s>>>(g, TileLMStats{stats, parts});
     }
     else if (use_big(sh)) launch_big(xa, w, sh, ni, TileLMStats{stats, parts}, s);
+    else if (lm_big_width(sh)) launch_big_wn<4>(xa, w, sh, ni, TileLMStats{stats, parts}, s);
     else launch_tile(xa, w, sh, ni, TileLMStats{stats, parts}, ws, false, s);
 }
 void launch_gemm_store(const u16 *xa, const u16 *w, GemmShape sh, NormIn ni, float *out, int units, int rpu_pad,

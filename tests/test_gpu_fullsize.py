@@ -358,6 +358,13 @@ def test_full_size_properties_without_an_oracle():
             assert (aS == am[:, :S]).float().mean() > 0.9 and (uS.sum(-1) == 1).all(), S
             cR, aR, uR = B.odb_block_step(model, cache, dr[:, :S].contiguous(), wl.block_off, wl.tau)
             assert torch.equal(cR, cS) and torch.equal(aR, aS) and torch.equal(uR, uS), S      # K-split projections: fixed order
+        # five and six drafts (160 and 192 rows: two row blocks on the tile kernel, the LM head and, at 192 rows, the wide
+        # projections on the 256-row kernel with part of a block empty)
+        for pick in ([0, 1, 2, 3, 0], [0, 1, 2, 3, 0, 1]):
+            cS, aS, uS = B.odb_block_step(model, cache, dr[:, pick].contiguous(), wl.block_off, wl.tau)
+            assert torch.allclose(torch.log(cS), torch.log(conf[:, pick]), atol=0.05), len(pick)
+            assert (aS == am[:, pick]).float().mean() > 0.9 and (uS.sum(-1) == 1).all(), len(pick)
+            assert torch.equal(cS[:, 0], cS[:, 4]) and torch.equal(aS[:, 0], aS[:, 4]), len(pick)     # the same draft twice
         # one draft (32 rows): its down projection splits K over four workgroups and the last to arrive adds the
         # partial sums - in slice order, so repeated calls must agree bit for bit whoever arrives last
         c1, a1, u1 = B.odb_block_step(model, cache, dr[:, :1].contiguous(), wl.block_off, wl.tau)
