@@ -9,7 +9,7 @@ template <int MT, int NG, int PF, class Epi, int WKT = WK, bool IL = false>
 __global__ __launch_bounds__(64 * WKT) void gemm_stream_kernel(GemmArgs g, Epi epi) {
     __shared__ __attribute__((aligned(16))) char smem[kGemmSmemBytes];
     frag_t wb[PF][NG];
-    gemm_wg<MT, NG, PF, false, Epi, WKT, IL>(g, epi, blockIdx.x, gridDim.x, blockIdx.y * MT, wb, smem);
+    gemm_wg<MT, NG, PF, Epi, WKT, IL>(g, epi, blockIdx.x, gridDim.x, blockIdx.y * MT, wb, smem);
 }
 
 constexpr int kStreamWGs = 256;      // one workgroup per compute unit
@@ -41,7 +41,7 @@ __global__ __launch_bounds__(64 * WK) void gemm_stream_ksplit_kernel(GemmArgs g,
     gs.W += (size_t)ks * kl * kTileElems;
     const size_t slice = (size_t)g.MT_total * g.NT * 256;
     frag_t wb[PF][NG];
-    gemm_wg<MT, NG, PF, false, EpiPartial, WK, false>(gs, EpiPartial{partial + ks * slice, g.NT}, nb, nblocks, 0, wb, smem);
+    gemm_wg<MT, NG, PF, EpiPartial, WK, false>(gs, EpiPartial{partial + ks * slice, g.NT}, nb, nblocks, 0, wb, smem);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // this wave's partial sums have been written
     __syncthreads();
     if (threadIdx.x == 0) s_old = __hip_atomic_fetch_add(arrive + nb, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -54,30 +54,6 @@ constexpr int gemm_mc(int mt, int ng, int wkt = WK) {
 
 constexpr int kGemmSmemBytes = WK * 6 * 1024 + 8 * 16 * 4;    // LDS one workgroup needs (red + row scales)
 
-// Weight tiles of the first PF k-steps of workgroup `wg`'s first group of n-tiles.  Weights do not
-// depend on the previous kernel phase, so a caller may issue these loads early (before it waits
-// for its input rows) and hand the ring to gemm_wg<..., true>.
-template <int NG, int PF, int WKT = WK, bool IL = false>
-__device__ __forceinline__ void gemm_prefetch_w(const GemmArgs &g, int wg, int nwg, frag_t (&wb)[PF][NG]) {
-    const int lane = threadIdx.x & 63, wk = threadIdx.x >> 6;
-    const int n_lo = (int)((unsigned)wg * (unsigned)g.NT / (unsigned)nwg);      // (32-bit: wg * NT stays far below 2^32)
-    int n_hi = (int)((unsigned)(wg + 1) * (unsigned)g.NT / (unsigned)nwg);
-    // a workgroup without n-tiles still loads (tile 0, discarded) so that the ring is always
-    // fully redefined here and never has to be kept alive across phases
-    if (n_hi <= n_lo) n_hi = n_lo + 1 <= g.NT ? n_lo + 1 : g.NT;
-    const int KW = (g.k_len ? g.k_len : g.KT) / WKT;
-    const int k0 = IL ? wk : wk * KW, kst = IL ? WKT : 1;      // first k-tile of this wave and its stride
-    const u16 *wbase = g.W + (size_t)k0 * kTileElems + lane * 8;
-#pragma unroll
-    for (int s = 0; s < PF; s++)
-#pragma unroll
-        for (int n = 0; n < NG; n++) {
-            int nt = n_lo + n;
-            nt = nt < n_hi ? nt : n_hi - 1;
-            wb[s][n] = ld_frag_stream(wbase + ((size_t)nt * g.KT + s * kst) * kTileElems);
-        }
-}
-
 // Hooks for epilogues that read global memory (the residual tile, the RoPE table): epi_preload issues those loads
 // before the partial sums go through LDS, epi_apply hands their result to the epilogue, so that their latency runs
 // under the reduction instead of in the tail of the kernel.  Default: nothing to preload.
@@ -88,11 +64,10 @@ template <class Epi>
 __device__ __forceinline__ void epi_apply(Epi &epi, int mt, int nt, f32x4 c, int lane, int slot, NoPre) { epi(mt, nt, c, lane, slot); }
 
 // One workgroup's share of the GEMM: n-tiles [wg*NT/nwg, (wg+1)*NT/nwg), m-tiles mt0 .. mt0+MT-1.
-// HAVE_W: wb already holds (or is receiving) the tiles gemm_prefetch_w loads.
 // The epilogue is called as epi(mt, nt, c, lane, slot): slot numbers the (m-chunk, tile) pairs that
 // this wave serves, the same in every group of n-tiles, so a stateful epilogue can keep one
 // accumulator per slot; epi.finish(mt, part, lane, slot) follows once per slot at the end.
-template <int MT, int NG, int PF, bool HAVE_W, class Epi, int WKT = WK, bool IL = false>
+template <int MT, int NG, int PF, class Epi, int WKT = WK, bool IL = false>
 __device__ __forceinline__ void gemm_wg(const GemmArgs &g, Epi epi, int wg, int nwg, int mt0,
                                         frag_t (&wb)[PF][NG], char *smem) {
     constexpr int MC = gemm_mc(MT, NG, WKT);                // m-tiles reduced per pass through LDS (<= 48 KiB)
@@ -157,15 +132,8 @@ __device__ __forceinline__ void gemm_wg(const GemmArgs &g, Epi epi, int wg, int 
             sv[j] = *reinterpret_cast<const f32x4 *>(p + sic);
         }
     }
-    if (HAVE_W) {
 #pragma unroll
-        for (int s = 0; s < PF; s++)
-#pragma unroll
-            for (int m = 0; m < MT; m++) ab[s][m] = ld_frag(ap[m] + s * a_step);
-    } else {
-#pragma unroll
-        for (int s = 0; s < PF; s++) load_stage(s, 0, s);
-    }
+    for (int s = 0; s < PF; s++) load_stage(s, 0, s);
     if (g.ssq) {
         // 64 lane-partials per row -> one sum per row: transposed through LDS (row stride 65 floats keeps
         // the gather conflict-free), then lane l adds RPW of the partials of row l % RPW and the 64 / RPW
