@@ -298,6 +298,9 @@ struct EpiQKV {
 
 // h += C.  With a NormOut it also prepares the next RMSNorm: hb = binary16(h * gain) in the
 // operand layout and the sum of squares of this tile's 16 columns per row.
+// What EpiResid reads from global memory for one output tile: the residual values and (when the tile also feeds the
+// next RMSNorm) the norm's gain - both requested before the sums are there, not in a chain behind them.
+struct ResidPre { f32x4 hv, gn; };
 struct EpiResid {
     float *h;
     int ld;
@@ -305,20 +308,22 @@ struct EpiResid {
     int mt_total;
     __device__ bool transposed(int) const { return false; }
     __device__ void finish(int, int, int, int) const {}
-    __device__ f32x4 preload(int mt, int nt, int lane) const {
+    __device__ ResidPre preload(int mt, int nt, int lane) const {
         const int mi = lane & 15, g = lane >> 4, row = mt * 16 + mi, col = nt * 16 + 4 * g;
-        return *reinterpret_cast<const f32x4 *>(h + (size_t)row * ld + col);
+        ResidPre p;
+        p.hv = *reinterpret_cast<const f32x4 *>(h + (size_t)row * ld + col);
+        p.gn = no.hb ? *reinterpret_cast<const f32x4 *>(no.gain + col) : f32x4{0.f, 0.f, 0.f, 0.f};
+        return p;
     }
     __device__ void operator()(int mt, int nt, f32x4 c, int lane, int) const { apply(mt, nt, c, lane, preload(mt, nt, lane)); }
-    __device__ void apply(int mt, int nt, f32x4 c, int lane, f32x4 hv) const {
+    __device__ void apply(int mt, int nt, f32x4 c, int lane, const ResidPre &pre) const {
         const int mi = lane & 15, g = lane >> 4, row = mt * 16 + mi, col = nt * 16 + 4 * g;
         float *p = h + (size_t)row * ld + col;
-        f32x4 v = hv + c;
+        f32x4 v = pre.hv + c;
         *reinterpret_cast<f32x4 *>(p) = v;
         if (no.hb) {
-            f32x4 gn = *reinterpret_cast<const f32x4 *>(no.gain + col);
             const int kk = (nt & 1) * 16 + 4 * g;
-            const f32x4 y = v * gn;
+            const f32x4 y = v * pre.gn;
             note_saturation(no.status, y[0], y[1], y[2], y[3]);
             st_f16x4(no.hb + ((size_t)(nt >> 1) * mt_total + mt) * kTileElems + ((kk >> 3) * 16 + mi) * 8 + (kk & 7),
                      y[0], y[1], y[2], y[3]);
@@ -330,8 +335,8 @@ struct EpiResid {
     }
 };
 
-__device__ __forceinline__ f32x4 epi_preload(const EpiResid &e, int mt, int nt, int lane) { return e.preload(mt, nt, lane); }
-__device__ __forceinline__ void epi_apply(EpiResid &e, int mt, int nt, f32x4 c, int lane, int, f32x4 hv) { e.apply(mt, nt, c, lane, hv); }
+__device__ __forceinline__ ResidPre epi_preload(const EpiResid &e, int mt, int nt, int lane) { return e.preload(mt, nt, lane); }
+__device__ __forceinline__ void epi_apply(EpiResid &e, int mt, int nt, f32x4 c, int lane, int, const ResidPre &pre) { e.apply(mt, nt, c, lane, pre); }
 
 // W_gu interleaves the rows of W_gate and W_up (physical row 2j = gate j, 2j+1 = up j)
 struct EpiSwiGLU {

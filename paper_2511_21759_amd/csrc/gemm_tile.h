@@ -9,6 +9,7 @@
 // n-blocks x KS) the partial sums go to an fp32 workspace in MFMA fragment order and
 // tile_epilogue_kernel adds them in a fixed order and runs the epilogue.
 #pragma once
+#include <type_traits>
 #include "gemm_core.h"
 
 namespace odb {
@@ -292,20 +293,53 @@ __global__ __launch_bounds__(512) void tile_epilogue_kernel(TileArgs g, Epi epi)
     __syncthreads();
     if (nt >= g.NT) return;
     const auto pre = epi_preload(epi, mt, nt, lane);       // (the residual tile: requested with the partial sums, not after them)
+    // The KS partial sums of a tile are requested together and added in slice order: a loop that loads and adds one
+    // slice at a time is a chain of KS memory latencies (5.6 of the 6.4 us this kernel took at eight slices).
     f32x4 c = f32x4{0.f, 0.f, 0.f, 0.f};
+    const size_t slice = (size_t)g.MT_total * g.NT * 256;
+    const float *base = g.partial + ((size_t)mt * g.NT + nt) * 256;
     if (!epi.transposed(nt)) {
-        for (int s = 0; s < g.KS; s++) {
-            size_t tile = ((size_t)s * g.MT_total + mt) * g.NT + nt;
-            c += *reinterpret_cast<const f32x4 *>(g.partial + tile * 256 + lane * 4);
+        const float *p = base + lane * 4;
+        auto sum = [&](auto N) __attribute__((always_inline)) {
+            constexpr int n = decltype(N)::value;
+            f32x4 v[n];
+#pragma unroll
+            for (int s = 0; s < n; s++) v[s] = *reinterpret_cast<const f32x4 *>(p + s * slice);
+#pragma unroll
+            for (int s = 0; s < n; s++) c += v[s];
+        };
+        switch (g.KS) {
+            case 2: sum(std::integral_constant<int, 2>{}); break;
+            case 4: sum(std::integral_constant<int, 4>{}); break;
+            case 8: sum(std::integral_constant<int, 8>{}); break;
+            case 16: sum(std::integral_constant<int, 16>{}); break;
+            default:
+                for (int s = 0; s < g.KS; s++) c += *reinterpret_cast<const f32x4 *>(p + s * slice);
         }
         c *= s_rstd[lane & 15];
     } else {
         const int ni = lane & 15, gq = lane >> 4;
-        for (int s = 0; s < g.KS; s++) {
-            size_t tile = ((size_t)s * g.MT_total + mt) * g.NT + nt;
-            const float *base = g.partial + tile * 256;
+        const float *p = base + ((ni >> 2) * 16 + 4 * gq) * 4 + (ni & 3);
+        auto sum = [&](auto N) __attribute__((always_inline)) {
+            constexpr int n = decltype(N)::value;
+            float v[n][4];
 #pragma unroll
-            for (int r = 0; r < 4; r++) c[r] += base[((ni >> 2) * 16 + 4 * gq + r) * 4 + (ni & 3)];
+            for (int s = 0; s < n; s++)
+#pragma unroll
+                for (int r = 0; r < 4; r++) v[s][r] = p[s * slice + r * 4];
+#pragma unroll
+            for (int s = 0; s < n; s++)
+#pragma unroll
+                for (int r = 0; r < 4; r++) c[r] += v[s][r];
+        };
+        switch (g.KS) {
+            case 2: sum(std::integral_constant<int, 2>{}); break;
+            case 4: sum(std::integral_constant<int, 4>{}); break;
+            case 8: sum(std::integral_constant<int, 8>{}); break;
+            default:
+                for (int s = 0; s < g.KS; s++)
+#pragma unroll
+                    for (int r = 0; r < 4; r++) c[r] += p[s * slice + r * 4];
         }
 #pragma unroll
         for (int r = 0; r < 4; r++) c[r] *= s_rstd[4 * gq + r];
