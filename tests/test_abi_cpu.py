@@ -91,3 +91,16 @@ def test_workloads_are_seeded_and_shaped():
     c4 = workloads.config4()
     assert c4.tokens.shape == (4, 3072) and c4.drafts.shape == (4, 8, 64) and c4.block_off == 2048
     assert workloads.config3(256).shape == (1, 768)
+
+
+def test_bench_reads_the_gate_up_row_of_every_tracked_profile():
+    """bench.py quotes the kernel-trace average and the measured HBM bytes of the gate/up GEMM from the tracked
+    rocprofv3 summaries: every one of them must hold a row that its parser finds, with figures of a plausible size."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("odb_bench", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    for name, (lo_us, hi_us) in {"config1": (20, 60), "config2": (30, 80), "config3": (100, 300), "config4": (200, 600)}.items():
+        avg_us, traffic, rel = bench.profile_figures(name)
+        assert avg_us is not None and lo_us < avg_us < hi_us, (name, avg_us, rel)
+        assert traffic is not None and 1.9e8 < traffic < 2e9, (name, traffic, rel)
