@@ -379,6 +379,11 @@ def test_full_size_properties_without_an_oracle():
         assert torch.isfinite(c16).all() and (c16 > 0).all() and (c16 <= 1).all()
         assert torch.allclose(torch.log(c64), torch.log(c16).expand(-1, 4, -1), atol=0.05)
         assert (a64 == a16.expand(-1, 4, -1)).float().mean() > 0.9 and torch.equal(c64[:, 0], c64[:, 3])
+        # seven copies (112 rows: seven of the eight row tiles of the 128-row kernels, the last one a repeat of the seventh)
+        c112, a112, u112 = B.odb_block_step(model, cache, d16.repeat(1, 7, 1).contiguous(), wl.block_off, wl.tau)
+        assert torch.allclose(torch.log(c112), torch.log(c16).expand(-1, 7, -1), atol=0.05)
+        assert (a112 == a16.expand(-1, 7, -1)).float().mean() > 0.9 and torch.equal(c112[:, 0], c112[:, 6])
+        assert torch.equal(u112[:, 0], u112[:, 6])
         B.odb_model_status(model)
         B.odb_cache_destroy(cache)
     finally:
