@@ -131,10 +131,10 @@ __device__ __forceinline__ void attn_scores(const AttnArgs &a, float sc, int key
                 ps += p[s][rr];
             }
         lrun[t] += ps;
-        pf[t].w[0] = pack2(p[0][0], p[0][1]);
-        pf[t].w[1] = pack2(p[0][2], p[0][3]);
-        pf[t].w[2] = pack2(p[1][0], p[1][1]);
-        pf[t].w[3] = pack2(p[1][2], p[1][3]);
+        pf[t].w[0] = pack2_inrange(p[0][0], p[0][1]);
+        pf[t].w[1] = pack2_inrange(p[0][2], p[0][3]);
+        pf[t].w[2] = pack2_inrange(p[1][0], p[1][1]);
+        pf[t].w[3] = pack2_inrange(p[1][2], p[1][3]);
     }
 }
 
@@ -208,10 +208,10 @@ __device__ __forceinline__ void attn_softmax_qk(const AttnArgs &a, float sc, int
                 ps += p[s][rr];
             }
         lrun[t] += ps;
-        pf[t].w[0] = pack2(p[0][0], p[0][1]);
-        pf[t].w[1] = pack2(p[0][2], p[0][3]);
-        pf[t].w[2] = pack2(p[1][0], p[1][1]);
-        pf[t].w[3] = pack2(p[1][2], p[1][3]);
+        pf[t].w[0] = pack2_inrange(p[0][0], p[0][1]);
+        pf[t].w[1] = pack2_inrange(p[0][2], p[0][3]);
+        pf[t].w[2] = pack2_inrange(p[1][0], p[1][1]);
+        pf[t].w[3] = pack2_inrange(p[1][2], p[1][3]);
     }
     attn_qk<DH, QT>(kf_next, q, st_next);
 }

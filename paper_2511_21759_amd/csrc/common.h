@@ -60,6 +60,14 @@ __device__ inline uint32_t pack2(float lo, float hi) {      // two operand eleme
     return (uint32_t)f2h(lo) | ((uint32_t)f2h(hi) << 16);
 }
 
+// Two operand elements from values known to lie inside the binary16 range (attention probabilities, at most
+// 2^kAttnSlack): round to nearest even, no clamp - one packed conversion instead of two clamps, two conversions and a merge.
+__device__ inline uint32_t pack2_inrange(float lo, float hi) {
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{lo, hi}, f16x2_t));
+}
+
 __device__ inline frag_t ld_frag(const u16 *p) {
     return *reinterpret_cast<const frag_t *>(p);
 }
